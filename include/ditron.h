@@ -1,0 +1,225 @@
+/*
+ * ditron.h -- C ABI of the MI355X (gfx950) fused communication + GEMM kernels.
+ *
+ * One GPU's share of three tensor-parallel operators, with the other ranks' shards
+ * resident in the same GPU's memory and published, chunk by chunk with one int32 signal
+ * flag each, in the order the peer ranks would deliver them:
+ *
+ *   ditron_ag_gemm              AllGather-GEMM          (paper, Appendix "AllGather GEMM")
+ *   ditron_gemm_rs              GEMM-ReduceScatter      (paper, Appendix "GEMM Reduce-Scatter")
+ *   ditron_moe_ag_grouped_gemm  AllGather + grouped GEMM over local experts
+ *                               (paper, kernel list "ag_group_gemm"; Appendix "Swizzle", third listing)
+ *
+ * Conventions common to every entry point
+ *   - "device" pointers are GPU global memory (or pinned host memory mapped into the GPU),
+ *     "host" pointers are ordinary host memory read during the call.  All device buffers are
+ *     owned by the caller; the library allocates no device memory and keeps no state
+ *     between calls apart from the process-wide spin limit below.
+ *   - All device pointers must be 16-byte aligned.  Matrices are row-major and dense
+ *     (leading dimension = number of columns).  bf16 is the upper half of an IEEE binary32;
+ *     fp8 is OCP e4m3 (finite only, max 448).  The contraction length k must be a multiple
+ *     of 8 (bf16) or 16 (fp8), n a multiple of 8.
+ *   - Calls enqueue work on `stream` (a hipStream_t passed as void*, NULL = default stream)
+ *     and return; results are valid once the stream has been synchronised.
+ *   - Signals.  `signals` is a caller-allocated int32 array of ditron_signal_words(world)
+ *     words that the caller zero-fills once.  A flag "has arrived" when it equals `epoch`;
+ *     pass a value different from every earlier call on the same buffer (e.g. 1, 2, 3, ...)
+ *     so that no reset sits between calls.  Words beyond the flags are internal counters
+ *     which every call leaves at zero.
+ *   - `status` is a device int32[DITRON_STATUS_WORDS], zero-filled by the caller.  Kernels
+ *     never spin forever: a wait that exceeds the spin limit stores DITRON_ERR_TIMEOUT in
+ *     status[0] (and the flag index in status[1]) and the work-group carries on, so the
+ *     result is then undefined but the kernel terminates.
+ *   - Return value: DITRON_OK, or an error without any work having been enqueued.
+ *     INVALID_ARG: null / misaligned pointer, non-positive size, rank outside [0, world),
+ *     m not divisible by world, world > DITRON_MAX_WORLD, bad enum.  UNSUPPORTED: a
+ *     size rule above is violated or the layout/dtype combination has no kernel.
+ *     HIP: the launch failed.
+ */
+#ifndef DITRON_H
+#define DITRON_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  DITRON_OK = 0,
+  DITRON_ERR_INVALID_ARG = 1,
+  DITRON_ERR_UNSUPPORTED = 2,
+  DITRON_ERR_WORKSPACE = 3,
+  DITRON_ERR_HIP = 4,
+  DITRON_ERR_TIMEOUT = 5
+} ditron_status_t;
+
+typedef enum { DITRON_BF16 = 0, DITRON_FP8_E4M3 = 1 } ditron_dtype_t;
+
+/* Physical layout of the logical [k, n] right-hand matrix. */
+typedef enum {
+  DITRON_B_KN = 0, /* stored [k, n], n contiguous */
+  DITRON_B_NK = 1  /* stored [n, k], k contiguous: the weight layout of the paper's launchers */
+} ditron_blayout_t;
+
+enum {
+  DITRON_EMULATE_PRODUCER = 1u,  /* the call itself copies the shards and raises the flags */
+  DITRON_EXTERNAL_PRODUCER = 2u, /* somebody else fills the workspace and raises the flags   */
+  DITRON_DUMP_SCHEDULE = 8u      /* write the tile schedule to `schedule_out`                */
+};
+
+#define DITRON_MAX_WORLD 32
+#define DITRON_STATUS_WORDS 4
+#define DITRON_SCHEDULE_WORDS 4 /* int32 words per tile record in a schedule dump */
+
+/* Number of int32 words the `signals` array of any entry point must have for `world`
+ * ranks and `chunks` flags per rank (chunks = 1 except for ditron_gemm_rs). */
+size_t ditron_signal_words(int world, int chunks);
+
+/* Tile shape and ordering parameters the library will use for a problem, so that a test can
+ * evaluate the schedule independently.  op: 0 = ag_gemm, 1 = gemm_rs, 2 = moe grouped gemm.
+ * out[0]=BLOCK_M out[1]=BLOCK_N out[2]=GROUP_SIZE_M out[3]=chiplets used by the work-group
+ * remap (0 = no remap) out[4]=tiles per chiplet per block out[5]=number of tiles
+ * (ag_gemm / gemm_rs) out[6]=threads per work-group out[7]=producer work-groups. */
+ditron_status_t ditron_tile_config(int op, int m, int n, int k, int dtype, int out[8]);
+
+/*
+ * AllGather-GEMM:  C[world*m_per_rank, n] = concat_s(A_s) . B       (fp32 accumulate)
+ *
+ * Paper: host launcher `ag_gemm`, producer `cp_engine_producer_all_gather_full_mesh_pull`
+ * and consumer `kernel_consumer_gemm` of Appendix "AllGather GEMM".  Shard s lands at rows
+ * [s*m_per_rank, (s+1)*m_per_rank) of `workspace` and flag s is raised after it; a tile
+ * whose rows touch shards rank_beg..rank_end waits for exactly those flags; tile rows are
+ * visited starting at the rank's own shard.
+ *
+ *  a_shards      host array of `world` device pointers, each [m_per_rank, k] in `dtype`
+ *                (EMULATE_PRODUCER; ignored with EXTERNAL_PRODUCER)
+ *  b, b_layout   device, logical [k, n] in `dtype`, layout ditron_blayout_t
+ *  c             device out, [world*m_per_rank, n] bf16
+ *  a_scales      device float[world] (fp8: one scale per shard) or NULL
+ *  b_scales      device float[n]     (fp8: one scale per output column) or NULL
+ *                fp8 result is (sum_k a*b) * a_scales[row / m_per_rank] * b_scales[col]
+ *  workspace     device, [world*m_per_rank, k] in `dtype`: the gathered A (written by the
+ *                producer, read by the GEMM)
+ *  signals       device int32[ditron_signal_words(world, 1)]; flag s is word s
+ *  status        device int32[DITRON_STATUS_WORDS]
+ *  schedule_out  device int32[4 * tiles] or NULL; with DITRON_DUMP_SCHEDULE the GEMM
+ *                work-group with index w writes (pid_m, pid_n, rank_beg, rank_end) at 4*w
+ *  arrival_order host int[world] or NULL: the order in which the emulated producer delivers
+ *                shards; NULL = rank, rank+1, ... (mod world) as in the paper's producer
+ */
+ditron_status_t ditron_ag_gemm(const void* const* a_shards, const void* b, int b_layout, void* c,
+                               const float* a_scales, const float* b_scales, void* workspace,
+                               int32_t* signals, int32_t* status, int32_t* schedule_out,
+                               const int* arrival_order, int m_per_rank, int n, int k, int world,
+                               int rank, int dtype, int32_t epoch, unsigned flags, void* stream);
+
+/*
+ * GEMM-ReduceScatter:  out[m/world, n] = rows_rank( sum_s P_s ),  P_rank = A . B computed here.
+ *
+ * Paper: `gemm_rs_op`, `kernel_gemm_rs_producer` and the reduce-scatter launchers of Appendix
+ * "GEMM Reduce-Scatter".  The GEMM visits tile rows starting at the segment of rank+1 and
+ * ending with the rank's own; every tile adds one to the counter of each segment it touches
+ * and the tile that completes a segment raises that segment's flag.  The blocks the peers
+ * would push into this rank's scatter buffer are copied there (peer by peer, in the order
+ * rank-1, rank-2, ..., unless `arrival_order` says otherwise) with one flag per
+ * (peer, row chunk).  The reduction adds the `world` blocks in fp32, in slot order, and
+ * rounds once to bf16; a row chunk is reduced once its `world` flags are up.
+ *
+ *  a             device [m, k_local] bf16
+ *  b, b_layout   device, logical [k_local, n] bf16
+ *  gemm_out      device out [m, n] bf16: this rank's partial product
+ *  peer_partials host array of `world` device pointers; entry s != rank is the [m/world, n]
+ *                bf16 block that rank s contributes to this rank (entry `rank` is ignored:
+ *                the own block is rows rank*m/world.. of gemm_out)
+ *  scatter_buf   device [world, m/world, n] bf16: the destination slots (slot `rank` unused)
+ *  out           device out [m/world, n] bf16
+ *  signals       device int32[ditron_signal_words(world, chunks_per_slot)]:
+ *                words [0, world) are the GEMM's segment flags, words
+ *                [world, world + world*chunks_per_slot) the arrival flags (slot-major)
+ *  schedule_out  with DITRON_DUMP_SCHEDULE: (pid_m, pid_n, segment_start, segment_end) per
+ *                GEMM work-group
+ *  arrival_order host int[world-1] (peers in delivery order) or NULL
+ *  chunks_per_slot  row chunks per slot (>= 1, must divide m/world)
+ */
+ditron_status_t ditron_gemm_rs(const void* a, const void* b, int b_layout, void* gemm_out,
+                               const void* const* peer_partials, void* scatter_buf, void* out,
+                               int32_t* signals, int32_t* status, int32_t* schedule_out,
+                               const int* arrival_order, int m, int n, int k_local, int world,
+                               int rank, int chunks_per_slot, int32_t epoch, unsigned flags,
+                               void* stream);
+
+/*
+ * The reduction step of GEMM-ReduceScatter on its own: out = bf16( sum_s fp32(slots[s]) ),
+ * slot order 0..world-1.  slots: host array of `world` device pointers [rows, n] bf16.
+ * `signals` may be NULL (no gating); otherwise word s*chunks + c gates row chunk c of slot s.
+ */
+ditron_status_t ditron_reduce_slots(const void* const* slots, void* out, const int32_t* signals,
+                                    int32_t* status, int rows, int n, int world, int chunks,
+                                    int32_t epoch, void* stream);
+
+/*
+ * MoE: route -> (all-gathered) token rows grouped by expert -> grouped GEMM.
+ *
+ * Paper: "ag_group_gemm" in the kernel list; tile ordering from
+ * `threadblock_swizzle_ag_moe_kernel`.  Token t = s*tokens_per_rank + i lives in shard s;
+ * assignment f = t*top_k + j goes to expert topk_ids[f].  For the local experts
+ * [expert_begin, expert_begin + num_local_experts):
+ *   counts[s*num_experts + e]  assignments of shard s to expert e (all experts)
+ *   expert_offsets[j]          exclusive prefix sum of the local experts' totals; [E_l] = R
+ *   gather_idx[offset_j + q]   q-th smallest f routed to local expert j
+ *   y[p, :] = X[gather_idx[p] / top_k, :] . W_j   for p in the rows of expert j, fp32 accumulate
+ * Row tiles are ordered by (expert, arrival stage of the last shard they need) and each
+ * waits for the shard flags it needs.
+ *
+ *  x_shards      host array of `world` device pointers [tokens_per_rank, hidden] bf16
+ *  topk_ids      device int32 [world*tokens_per_rank, top_k]
+ *  w, w_layout   device, per expert logical [hidden, inter] bf16, experts contiguous;
+ *                layout as ditron_blayout_t (DITRON_B_NK = [E_l, inter, hidden])
+ *  y             device out [max_rows, inter] bf16; rows >= R are not written
+ *  counts        device out int32 [world * num_experts]
+ *  expert_offsets device out int32 [num_local_experts + 1]
+ *  gather_idx    device out int32 [max_rows]
+ *  tile_records  device out int32 [1 + 4*max_tiles]: ntiles, then (expert_id, tiled_m,
+ *                segment_start, segment_end) per tile, max_tiles =
+ *                ditron_moe_max_tiles(max_rows, num_local_experts)
+ *  workspace     device [world*tokens_per_rank, hidden] bf16 gathered tokens
+ *  signals       device int32[ditron_signal_words(world, 1)]
+ *  If R exceeds max_rows, status[0] = DITRON_ERR_WORKSPACE and no GEMM tile runs.
+ */
+ditron_status_t ditron_moe_ag_grouped_gemm(const void* const* x_shards, const int32_t* topk_ids,
+                                           const void* w, int w_layout, void* y, int32_t* counts,
+                                           int32_t* expert_offsets, int32_t* gather_idx,
+                                           int32_t* tile_records, void* workspace,
+                                           int32_t* signals, int32_t* status,
+                                           const int* arrival_order, int tokens_per_rank,
+                                           int hidden, int inter, int num_experts, int top_k,
+                                           int expert_begin, int num_local_experts, int max_rows,
+                                           int world, int rank, int32_t epoch, unsigned flags,
+                                           void* stream);
+
+/* Upper bound on the number of row tiles of the grouped GEMM. */
+int ditron_moe_max_tiles(int max_rows, int num_local_experts);
+
+/*
+ * Test / integration helper: an external producer.  Copies n chunks (dst[i] <- src[i],
+ * bytes[i] bytes, multiples of 16) in the given order on `stream`, raising
+ * signals[flag_index[i]] = epoch after each, optionally idling `delay_cycles` GPU clock
+ * ticks before each chunk.  All array arguments are host arrays of length n (n <= 64).
+ */
+ditron_status_t ditron_publish_chunks(void* const* dst, const void* const* src,
+                                      const size_t* bytes, const int* flag_index,
+                                      int32_t* signals, int n, int32_t epoch,
+                                      unsigned delay_cycles, void* stream);
+
+/* Process-wide bound on flag polls per wait (default 1<<20, of the order of a second).  A tiny value
+ * lets a test exercise the time-out path without hanging a kernel. */
+void ditron_set_spin_limit(unsigned polls);
+
+const char* ditron_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DITRON_H */

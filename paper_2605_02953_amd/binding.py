@@ -1,0 +1,142 @@
+"""ctypes binding of libditron.so: same names as the C ABI, argument marshalling only.
+
+Tensors are torch tensors used purely as device memory; nothing here computes.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libditron.so")
+
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_TIMEOUT = range(6)
+BF16, FP8_E4M3 = 0, 1
+B_KN, B_NK = 0, 1
+EMULATE_PRODUCER, EXTERNAL_PRODUCER, DUMP_SCHEDULE = 1, 2, 8
+MAX_WORLD = 32
+STATUS_WORDS = 4
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2605_02953_amd.build`")
+
+lib = ctypes.CDLL(LIB_PATH)
+
+_vp, _i, _u, _i32 = ctypes.c_void_p, ctypes.c_int, ctypes.c_uint, ctypes.c_int32
+_pp = ctypes.POINTER(ctypes.c_void_p)
+_ip = ctypes.POINTER(ctypes.c_int)
+
+lib.ditron_signal_words.restype = ctypes.c_size_t
+lib.ditron_signal_words.argtypes = [_i, _i]
+lib.ditron_tile_config.restype = _i
+lib.ditron_tile_config.argtypes = [_i, _i, _i, _i, _i, _ip]
+lib.ditron_set_spin_limit.restype = None
+lib.ditron_set_spin_limit.argtypes = [_u]
+lib.ditron_status_string.restype = ctypes.c_char_p
+lib.ditron_status_string.argtypes = [_i]
+lib.ditron_ag_gemm.restype = _i
+lib.ditron_ag_gemm.argtypes = [_pp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _ip,
+                               _i, _i, _i, _i, _i, _i, _i32, _u, _vp]
+lib.ditron_gemm_rs.restype = _i
+lib.ditron_gemm_rs.argtypes = [_vp, _vp, _i, _vp, _pp, _vp, _vp, _vp, _vp, _vp, _ip,
+                               _i, _i, _i, _i, _i, _i, _i32, _u, _vp]
+lib.ditron_reduce_slots.restype = _i
+lib.ditron_reduce_slots.argtypes = [_pp, _vp, _vp, _vp, _i, _i, _i, _i, _i32, _vp]
+lib.ditron_moe_ag_grouped_gemm.restype = _i
+lib.ditron_moe_ag_grouped_gemm.argtypes = [_pp, _vp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _ip,
+                                           _i, _i, _i, _i, _i, _i, _i, _i, _i, _i, _i32, _u, _vp]
+lib.ditron_moe_max_tiles.restype = _i
+lib.ditron_moe_max_tiles.argtypes = [_i, _i]
+lib.ditron_publish_chunks.restype = _i
+lib.ditron_publish_chunks.argtypes = [_pp, _pp, ctypes.POINTER(ctypes.c_size_t), _ip, _vp, _i, _i32, _u, _vp]
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return ctypes.c_void_p(t)
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _ptr_array(tensors):
+    if tensors is None:
+        return None
+    arr = (ctypes.c_void_p * len(tensors))()
+    for i, t in enumerate(tensors):
+        arr[i] = None if t is None else (t if isinstance(t, int) else t.data_ptr())
+    return arr
+
+
+def _int_array(v):
+    if v is None:
+        return None
+    return (ctypes.c_int * len(v))(*[int(x) for x in v])
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def status_string(code):
+    return lib.ditron_status_string(int(code)).decode()
+
+
+def signal_words(world, chunks=1):
+    return int(lib.ditron_signal_words(world, chunks))
+
+
+def set_spin_limit(polls):
+    lib.ditron_set_spin_limit(int(polls))
+
+
+def tile_config(op, m, n, k, dtype=BF16):
+    out = (ctypes.c_int * 8)()
+    st = lib.ditron_tile_config(op, m, n, k, dtype, out)
+    keys = ("block_m", "block_n", "group_m", "num_xcd", "per_xcd", "ntiles", "threads", "producers")
+    return st, dict(zip(keys, list(out)))
+
+
+def ag_gemm(a_shards, b, b_layout, c, a_scales, b_scales, workspace, signals, status, schedule_out,
+            arrival_order, m_per_rank, n, k, world, rank, dtype, epoch, flags, stream=None):
+    return lib.ditron_ag_gemm(_ptr_array(a_shards), _ptr(b), b_layout, _ptr(c), _ptr(a_scales), _ptr(b_scales),
+                              _ptr(workspace), _ptr(signals), _ptr(status), _ptr(schedule_out),
+                              _int_array(arrival_order), m_per_rank, n, k, world, rank, dtype, epoch, flags,
+                              _stream(stream))
+
+
+def gemm_rs(a, b, b_layout, gemm_out, peer_partials, scatter_buf, out, signals, status, schedule_out,
+            arrival_order, m, n, k_local, world, rank, chunks_per_slot, epoch, flags, stream=None):
+    return lib.ditron_gemm_rs(_ptr(a), _ptr(b), b_layout, _ptr(gemm_out), _ptr_array(peer_partials),
+                              _ptr(scatter_buf), _ptr(out), _ptr(signals), _ptr(status), _ptr(schedule_out),
+                              _int_array(arrival_order), m, n, k_local, world, rank, chunks_per_slot, epoch,
+                              flags, _stream(stream))
+
+
+def reduce_slots(slots, out, signals, status, rows, n, world, chunks, epoch, stream=None):
+    return lib.ditron_reduce_slots(_ptr_array(slots), _ptr(out), _ptr(signals), _ptr(status), rows, n, world,
+                                   chunks, epoch, _stream(stream))
+
+
+def moe_max_tiles(max_rows, num_local_experts):
+    return int(lib.ditron_moe_max_tiles(max_rows, num_local_experts))
+
+
+def moe_ag_grouped_gemm(x_shards, topk_ids, w, w_layout, y, counts, expert_offsets, gather_idx, tile_records,
+                        workspace, signals, status, arrival_order, tokens_per_rank, hidden, inter, num_experts,
+                        top_k, expert_begin, num_local_experts, max_rows, world, rank, epoch, flags, stream=None):
+    return lib.ditron_moe_ag_grouped_gemm(_ptr_array(x_shards), _ptr(topk_ids), _ptr(w), w_layout, _ptr(y),
+                                          _ptr(counts), _ptr(expert_offsets), _ptr(gather_idx),
+                                          _ptr(tile_records), _ptr(workspace), _ptr(signals), _ptr(status),
+                                          _int_array(arrival_order), tokens_per_rank, hidden, inter,
+                                          num_experts, top_k, expert_begin, num_local_experts, max_rows, world,
+                                          rank, epoch, flags, _stream(stream))
+
+
+def publish_chunks(dst, src, nbytes, flag_index, signals, epoch, delay_cycles=0, stream=None):
+    n = len(dst)
+    sizes = (ctypes.c_size_t * n)(*[int(x) for x in nbytes])
+    return lib.ditron_publish_chunks(_ptr_array(dst), _ptr_array(src), sizes, _int_array(flag_index),
+                                     _ptr(signals), n, epoch, delay_cycles, _stream(stream))

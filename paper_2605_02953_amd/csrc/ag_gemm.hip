@@ -1,0 +1,143 @@
+// AllGather-GEMM, one rank's share (paper, Appendix "AllGather GEMM").
+//
+// One launch holds both roles.  The first `num_producers` work-groups are the emulated
+// peers: shard by shard, in delivery order, they copy shard s into rows
+// [s*m_per_rank, (s+1)*m_per_rank) of the workspace and then raise flag s (the copy is
+// fused into the kernel rather than issued as separate memcpy calls).  Every other
+// work-group is one output tile of the consumer GEMM: it maps its index to a tile through
+// the chiplet remap, the grouped order and the rank rotation, waits for the flags of the
+// shards its rows touch, and only then reads the workspace.  Producer work-groups have the
+// lowest indices, so they are dispatched before any consumer can occupy a compute unit.
+#include "gemm_core.h"
+#include "launch.h"
+
+namespace ditron {
+
+struct AgGemmParams {
+  const void* shard[DITRON_MAX_WORLD];
+  int order[DITRON_MAX_WORLD];
+  char* workspace;
+  const char* b;
+  __bf16* c;
+  const float* a_scales;
+  const float* b_scales;
+  int32_t* flags;      // [world]
+  int32_t* arrivals;   // [world] producer arrival counters
+  int32_t* status;
+  int32_t* schedule;   // or null
+  int m_per_rank, m, n, k, world, rank;
+  int32_t epoch;
+  int num_producers;
+  unsigned spin_limit;
+  int group_m, num_xcd, per_xcd, npm, npn;
+};
+
+template <class T>
+__global__ __launch_bounds__(T::THREADS) void ag_gemm_kernel(const AgGemmParams p) {
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  if ((int)blockIdx.x < p.num_producers) {
+    const size_t shard_bytes = (size_t)p.m_per_rank * p.k * 2;
+    for (int i = 0; i < p.world; ++i) {
+      const int s = p.order[i];
+      copy_slice(p.workspace + (size_t)s * shard_bytes, p.shard[s], shard_bytes, blockIdx.x, p.num_producers);
+      publish_after_all(p.arrivals + s, p.num_producers, p.flags + s, p.epoch);
+    }
+    return;
+  }
+  const int wg = blockIdx.x - p.num_producers;
+  const int pid = xcd_remap(wg, p.npm * p.npn, p.num_xcd, p.per_xcd);
+  int pid_m, pid_n;
+  grouped_order(pid, p.npm, p.npn, p.group_m, pid_m, pid_n);
+  // start on the rows of the rank's own shard, then follow the ring
+  pid_m = (pid_m + cdiv(p.m_per_rank * p.rank, T::BM)) % p.npm;
+  const int m0 = pid_m * T::BM, n0 = pid_n * T::BN;
+  const int rank_beg = m0 / p.m_per_rank;
+  const int rank_end = (min(m0 + T::BM, p.m) - 1) / p.m_per_rank;
+  if (p.schedule && threadIdx.x == 0) {
+    int32_t* rec = p.schedule + 4 * (size_t)wg;
+    rec[0] = pid_m; rec[1] = pid_n; rec[2] = rank_beg; rec[3] = rank_end;
+  }
+  flag_wait_block(p.flags, rank_beg, rank_end - rank_beg + 1, p.epoch, p.spin_limit, p.status);
+
+  const size_t row_bytes = (size_t)p.k * 2;
+  const char* a_tile = p.workspace;
+  const char* b_tile = p.b;
+  const int M = p.m, N = p.n;
+  auto a_row = [=](int r) { return a_tile + (size_t)min(m0 + r, M - 1) * row_bytes; };
+  auto b_row = [=](int r) { return b_tile + (size_t)min(n0 + r, N - 1) * row_bytes; };
+  f32x16_t acc[T::NI][T::MI];
+  gemm_mainloop<T>(acc, a_row, b_row, p.k, lds);
+  store_tile_bf16<T>(acc, p.c, (size_t)p.n, m0, n0, M, N, p.a_scales, p.m_per_rank, p.b_scales);
+}
+
+template <class T>
+static ditron_status_t launch_ag(AgGemmParams& p, hipStream_t stream) {
+  p.npm = cdiv(p.m, T::BM);
+  p.npn = cdiv(p.n, T::BN);
+  auto kern = ag_gemm_kernel<T>;
+  if (!set_dynamic_lds((const void*)kern, T::LDS_BYTES)) return DITRON_ERR_HIP;
+  const unsigned grid = (unsigned)(p.num_producers + p.npm * p.npn);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(T::THREADS), T::LDS_BYTES, stream, p);
+  return hipGetLastError() == hipSuccess ? DITRON_OK : DITRON_ERR_HIP;
+}
+
+}  // namespace ditron
+
+using namespace ditron;
+
+extern "C" ditron_status_t ditron_ag_gemm(const void* const* a_shards, const void* b, int b_layout, void* c,
+                                          const float* a_scales, const float* b_scales, void* workspace,
+                                          int32_t* signals, int32_t* status, int32_t* schedule_out,
+                                          const int* arrival_order, int m_per_rank, int n, int k, int world,
+                                          int rank, int dtype, int32_t epoch, unsigned flags, void* stream) {
+  if (world < 1 || world > DITRON_MAX_WORLD || rank < 0 || rank >= world) return DITRON_ERR_INVALID_ARG;
+  if (m_per_rank <= 0 || n <= 0 || k <= 0) return DITRON_ERR_INVALID_ARG;
+  if (!b || !c || !workspace || !signals || !status) return DITRON_ERR_INVALID_ARG;
+  if (!aligned16(b) || !aligned16(c) || !aligned16(workspace) || !aligned16(signals)) return DITRON_ERR_INVALID_ARG;
+  const bool emulate = (flags & DITRON_EMULATE_PRODUCER) != 0;
+  const bool external = (flags & DITRON_EXTERNAL_PRODUCER) != 0;
+  if (emulate == external) return DITRON_ERR_INVALID_ARG;
+  if ((flags & DITRON_DUMP_SCHEDULE) && !schedule_out) return DITRON_ERR_INVALID_ARG;
+  if (b_layout != DITRON_B_KN && b_layout != DITRON_B_NK) return DITRON_ERR_INVALID_ARG;
+  if (dtype != DITRON_BF16 && dtype != DITRON_FP8_E4M3) return DITRON_ERR_INVALID_ARG;
+  if (emulate) {
+    if (!a_shards) return DITRON_ERR_INVALID_ARG;
+    for (int s = 0; s < world; ++s)
+      if (!a_shards[s] || !aligned16(a_shards[s])) return DITRON_ERR_INVALID_ARG;
+    if (arrival_order && !is_permutation(arrival_order, world)) return DITRON_ERR_INVALID_ARG;
+  }
+  if (dtype == DITRON_FP8_E4M3) return ditron_ag_gemm_fp8(a_shards, b, b_layout, c, a_scales, b_scales, workspace, signals, status,
+                                                          schedule_out, arrival_order, m_per_rank, n, k, world, rank, epoch, flags, stream);
+  if (b_layout != DITRON_B_NK) return DITRON_ERR_UNSUPPORTED;
+  if (k % 8 != 0 || n % 8 != 0) return DITRON_ERR_UNSUPPORTED;
+
+  AgGemmParams p{};
+  for (int i = 0; i < world; ++i) {
+    p.shard[i] = emulate ? a_shards[i] : nullptr;
+    p.order[i] = arrival_order ? arrival_order[i] : (rank + i) % world;
+  }
+  p.workspace = (char*)workspace;
+  p.b = (const char*)b;
+  p.c = (__bf16*)c;
+  p.a_scales = nullptr;
+  p.b_scales = nullptr;
+  p.flags = signals;
+  p.arrivals = signals + world;
+  p.status = status;
+  p.schedule = (flags & DITRON_DUMP_SCHEDULE) ? schedule_out : nullptr;
+  p.m_per_rank = m_per_rank;
+  p.m = m_per_rank * world;
+  p.n = n;
+  p.k = k;
+  p.world = world;
+  p.rank = rank;
+  p.epoch = epoch;
+  p.spin_limit = g_spin_limit;
+  TileChoice tc = choose_tile(p.m, n, k);
+  p.group_m = tc.group_m;
+  p.num_xcd = tc.num_xcd;
+  p.per_xcd = tc.per_xcd;
+  p.num_producers = emulate ? tc.producers : 0;
+  if (tc.big) return launch_ag<TileBig>(p, (hipStream_t)stream);
+  return launch_ag<TileSmall>(p, (hipStream_t)stream);
+}

@@ -1,0 +1,115 @@
+// Entry points that are not tied to one operator: sizes, tile choice, spin limit, status
+// strings, and the external chunk publisher used by tests and by integrations that bring
+// their own transport.
+#include "launch.h"
+
+namespace ditron {
+unsigned g_spin_limit = 1u << 20;
+
+struct PublishParams {
+  void* dst[64];
+  const void* src[64];
+  size_t bytes[64];
+  int flag_index[64];
+  int32_t* signals;
+  int n;
+  int32_t epoch;
+  unsigned delay_cycles;
+};
+
+// A single work-group walks the chunks in order: optional idle time, copy, then the flag.
+__global__ __launch_bounds__(1024) void publish_chunks_kernel(const PublishParams p) {
+  for (int i = 0; i < p.n; ++i) {
+    if (p.delay_cycles) {
+      const unsigned long long t0 = wall_clock64();
+      while (wall_clock64() - t0 < p.delay_cycles) __builtin_amdgcn_s_sleep(32);
+    }
+    copy_slice(p.dst[i], p.src[i], p.bytes[i], 0, 1);
+    __syncthreads();
+    if (threadIdx.x == 0) flag_raise(p.signals + p.flag_index[i], p.epoch);
+  }
+}
+}  // namespace ditron
+
+using namespace ditron;
+
+extern "C" size_t ditron_signal_words(int world, int chunks) {
+  if (world < 1 || chunks < 1) return 0;
+  // flags [world] + per-rank counters [world] + chunk flags [world*chunks] + chunk counters [world*chunks]
+  return (size_t)world * 2 + (size_t)world * chunks * 2;
+}
+
+extern "C" ditron_status_t ditron_tile_config(int op, int m, int n, int k, int dtype, int out[8]) {
+  if (!out || m <= 0 || n <= 0 || k <= 0 || op < 0 || op > 2) return DITRON_ERR_INVALID_ARG;
+  if (dtype != DITRON_BF16) return DITRON_ERR_UNSUPPORTED;
+  TileChoice t = choose_tile(m, n, k);
+  out[0] = t.block_m;
+  out[1] = t.block_n;
+  out[2] = t.group_m;
+  out[3] = t.num_xcd;
+  out[4] = t.per_xcd;
+  out[5] = cdiv(m, t.block_m) * cdiv(n, t.block_n);
+  out[6] = t.threads;
+  out[7] = t.producers;
+  return DITRON_OK;
+}
+
+extern "C" void ditron_set_spin_limit(unsigned polls) { g_spin_limit = polls ? polls : 1u; }
+
+extern "C" const char* ditron_status_string(int status) {
+  switch (status) {
+    case DITRON_OK: return "ok";
+    case DITRON_ERR_INVALID_ARG: return "invalid argument";
+    case DITRON_ERR_UNSUPPORTED: return "unsupported shape, layout or dtype";
+    case DITRON_ERR_WORKSPACE: return "workspace too small";
+    case DITRON_ERR_HIP: return "HIP launch failed";
+    case DITRON_ERR_TIMEOUT: return "signal wait timed out";
+    default: return "unknown status";
+  }
+}
+
+extern "C" ditron_status_t ditron_publish_chunks(void* const* dst, const void* const* src, const size_t* bytes,
+                                                 const int* flag_index, int32_t* signals, int n, int32_t epoch,
+                                                 unsigned delay_cycles, void* stream) {
+  if (n < 0 || n > 64 || !signals) return DITRON_ERR_INVALID_ARG;
+  if (n == 0) return DITRON_OK;
+  if (!dst || !src || !bytes || !flag_index) return DITRON_ERR_INVALID_ARG;
+  PublishParams p{};
+  for (int i = 0; i < n; ++i) {
+    if ((bytes[i] & 15u) || flag_index[i] < 0) return DITRON_ERR_INVALID_ARG;
+    if (bytes[i] && (!dst[i] || !src[i] || !aligned16(dst[i]) || !aligned16(src[i]))) return DITRON_ERR_INVALID_ARG;
+    p.dst[i] = dst[i];
+    p.src[i] = src[i];
+    p.bytes[i] = bytes[i];
+    p.flag_index[i] = flag_index[i];
+  }
+  p.signals = signals;
+  p.n = n;
+  p.epoch = epoch;
+  p.delay_cycles = delay_cycles;
+  hipLaunchKernelGGL(publish_chunks_kernel, dim3(1), dim3(1024), 0, (hipStream_t)stream, p);
+  return hipGetLastError() == hipSuccess ? DITRON_OK : DITRON_ERR_HIP;
+}
+
+// Placeholders until the operators land.
+extern "C" ditron_status_t ditron_ag_gemm_fp8(const void* const*, const void*, int, void*, const float*, const float*,
+                                              void*, int32_t*, int32_t*, int32_t*, const int*, int, int, int, int, int,
+                                              int32_t, unsigned, void*) {
+  return DITRON_ERR_UNSUPPORTED;
+}
+extern "C" ditron_status_t ditron_gemm_rs(const void*, const void*, int, void*, const void* const*, void*, void*,
+                                          int32_t*, int32_t*, int32_t*, const int*, int, int, int, int, int, int,
+                                          int32_t, unsigned, void*) {
+  return DITRON_ERR_UNSUPPORTED;
+}
+extern "C" ditron_status_t ditron_reduce_slots(const void* const*, void*, const int32_t*, int32_t*, int, int, int,
+                                               int, int32_t, void*) {
+  return DITRON_ERR_UNSUPPORTED;
+}
+extern "C" ditron_status_t ditron_moe_ag_grouped_gemm(const void* const*, const int32_t*, const void*, int, void*,
+                                                      int32_t*, int32_t*, int32_t*, int32_t*, void*, int32_t*,
+                                                      int32_t*, const int*, int, int, int, int, int, int, int, int,
+                                                      int, int, int32_t, unsigned, void*) {
+  return DITRON_ERR_UNSUPPORTED;
+}
+extern "C" int ditron_moe_max_tiles(int, int) { return 0; }

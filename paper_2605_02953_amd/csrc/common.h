@@ -1,0 +1,121 @@
+// Device-side helpers shared by the kernels: signal flags, chunk copies, small utilities.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/ditron.h"
+
+namespace ditron {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+#define DITRON_LDS(p) ((__attribute__((address_space(3))) void*)(p))
+
+__host__ __device__ inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+
+// ------------------------------------------------------------------ signal flags
+// A flag is raised with a release store at agent scope after the data it guards, and
+// observed with an acquire load at agent scope before the data is read (the paper's
+// `wait` + `consume_token` pair and its release `st`).  The eight chiplets have separate
+// L2 caches, so nothing weaker than agent scope orders a producer on one chiplet with a
+// consumer on another.
+__device__ inline void flag_raise(int32_t* flag, int32_t value) {
+  __hip_atomic_store(flag, value, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// One lane polls `count` consecutive flags until each equals `value`; gives up after
+// `spin_limit` polls per flag and records the time-out.  Returns with acquire ordering.
+__device__ inline void flag_wait_lane(const int32_t* flags, int first, int count, int32_t value,
+                                      unsigned spin_limit, int32_t* status) {
+  for (int i = 0; i < count; ++i) {
+    const int32_t* f = flags + first + i;
+    unsigned polls = 0;
+    while (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != value) {
+      if (++polls >= spin_limit) {
+        status[1] = first + i;
+        status[0] = DITRON_ERR_TIMEOUT;
+        break;
+      }
+      __builtin_amdgcn_s_sleep(8);
+    }
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+}
+
+// Whole work-group waits: lane 0 polls, the barrier hands the acquired view to the rest.
+__device__ inline void flag_wait_block(const int32_t* flags, int first, int count, int32_t value,
+                                       unsigned spin_limit, int32_t* status) {
+  if (threadIdx.x == 0) flag_wait_lane(flags, first, count, value, spin_limit, status);
+  __syncthreads();
+}
+
+// ------------------------------------------------------------------ chunk copy
+// Copy `bytes` (multiple of 16) from src to dst with 128-bit accesses, the calling
+// work-group being part `part` of `nparts` cooperating work-groups.
+__device__ inline void copy_slice(void* __restrict__ dst, const void* __restrict__ src, size_t bytes,
+                                  int part, int nparts) {
+  const size_t n16 = bytes >> 4;
+  const u32x4_t* s = (const u32x4_t*)src;
+  u32x4_t* d = (u32x4_t*)dst;
+  const size_t stride = (size_t)nparts * blockDim.x;
+  size_t i = (size_t)part * blockDim.x + threadIdx.x;
+  // four independent 16-byte loads in flight per lane
+  for (; i + 3 * stride < n16; i += 4 * stride) {
+    u32x4_t v0 = __builtin_nontemporal_load(s + i);
+    u32x4_t v1 = __builtin_nontemporal_load(s + i + stride);
+    u32x4_t v2 = __builtin_nontemporal_load(s + i + 2 * stride);
+    u32x4_t v3 = __builtin_nontemporal_load(s + i + 3 * stride);
+    d[i] = v0;
+    d[i + stride] = v1;
+    d[i + 2 * stride] = v2;
+    d[i + 3 * stride] = v3;
+  }
+  for (; i < n16; i += stride) d[i] = s[i];
+}
+
+// After every cooperating work-group has finished its slice of a chunk, the last one to
+// arrive raises the chunk's flag and leaves the arrival counter at zero for the next call.
+__device__ inline void publish_after_all(int32_t* counter, int nparts, int32_t* flag, int32_t value) {
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int old = __hip_atomic_fetch_add(counter, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    if (old == nparts - 1) {
+      __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      flag_raise(flag, value);
+    }
+  }
+}
+
+// ------------------------------------------------------------------ tile ordering
+// Linear tile id -> (pid_m, pid_n), tile rows in groups of group_m with the row index
+// running fastest inside a group (paper, first lines of the AllGather-GEMM consumer).
+__device__ inline void grouped_order(int pid, int npm, int npn, int group_m, int& pid_m, int& pid_n) {
+  const int in_group = group_m * npn;
+  const int first_m = (pid / in_group) * group_m;
+  const int size_m = min(npm - first_m, group_m);
+  const int r = pid % in_group;
+  pid_m = first_m + r % size_m;
+  pid_n = r / size_m;
+}
+
+// Work-group index -> linear tile id.  The dispatcher deals work-groups round-robin to the
+// chiplets; inside every block of num_xcd*per_xcd tiles, chiplet x receives a run of
+// consecutive tile ids, so tiles that share operand panels share an L2, while blocks stay in
+// schedule order.
+__device__ inline int xcd_remap(int wg, int ntiles, int num_xcd, int per_xcd) {
+  if (num_xcd <= 1) return wg;
+  const int block = num_xcd * per_xcd;
+  const int base = (wg / block) * block;
+  const int size = min(block, ntiles - base);
+  const int local = wg - base;
+  const int x = local % num_xcd, j = local / num_xcd;
+  const int q = size / num_xcd, rem = size % num_xcd;
+  // chiplets 0..rem-1 own q+1 work-groups of this block, the rest own q
+  const int start = x * q + min(x, rem);
+  return base + start + j;
+}
+
+}  // namespace ditron

@@ -1,0 +1,62 @@
+// Host-side helpers shared by the entry points: argument checks, tile choice, launch set-up.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/ditron.h"
+#include "gemm_core.h"
+
+namespace ditron {
+
+// 256x256 output tile, 8 waves as 2 (rows) x 4 (columns): 128x64 per wave, 128 KiB of LDS.
+typedef GemmTile<256, 256, 2, 4> TileBig;
+// 128x128 output tile, 4 waves as 2 x 2: 64x64 per wave, 64 KiB of LDS; for problems with
+// too few 256x256 tiles to fill the chip.
+typedef GemmTile<128, 128, 2, 2> TileSmall;
+
+struct TileChoice {
+  bool big;
+  int block_m, block_n, threads;
+  int group_m;    // GROUP_SIZE_M of the grouped tile order
+  int num_xcd;    // chiplets assumed by the work-group remap (0: no remap)
+  int per_xcd;    // consecutive tiles handed to one chiplet inside a remap block
+  int producers;  // work-groups that play the peers when the producer is emulated
+};
+
+inline TileChoice choose_tile(int m, int n, int /*k*/) {
+  TileChoice t{};
+  const long tiles_big = (long)cdiv(m, 256) * cdiv(n, 256);
+  t.big = tiles_big >= 192;
+  t.block_m = t.block_n = t.big ? 256 : 128;
+  t.threads = t.big ? TileBig::THREADS : TileSmall::THREADS;
+  t.group_m = 4;
+  t.num_xcd = 8;
+  t.per_xcd = 32;
+  t.producers = 16;
+  return t;
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline bool is_permutation(const int* v, int n) {
+  bool seen[DITRON_MAX_WORLD] = {false};
+  for (int i = 0; i < n; ++i) {
+    if (v[i] < 0 || v[i] >= n || seen[v[i]]) return false;
+    seen[v[i]] = true;
+  }
+  return true;
+}
+
+// Kernels with more than 64 KiB of dynamic LDS need the limit raised once per function.
+inline bool set_dynamic_lds(const void* func, int bytes) {
+  return hipFuncSetAttribute(func, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) == hipSuccess;
+}
+
+extern unsigned g_spin_limit;
+
+}  // namespace ditron
+
+extern "C" ditron_status_t ditron_ag_gemm_fp8(const void* const* a_shards, const void* b, int b_layout, void* c,
+                                              const float* a_scales, const float* b_scales, void* workspace,
+                                              int32_t* signals, int32_t* status, int32_t* schedule_out,
+                                              const int* arrival_order, int m_per_rank, int n, int k, int world,
+                                              int rank, int32_t epoch, unsigned flags, void* stream);

@@ -1,0 +1,48 @@
+"""Helpers for the GPU parity tests: move raw storage to the device, run one entry point
+through the C ABI, bring raw storage back.  No arithmetic happens here."""
+import numpy as np
+import torch
+
+
+def to_dev(arr):
+    """numpy raw storage (uint16 bf16 bits / uint8 fp8 bytes / int32 / float32) -> device tensor."""
+    a = np.ascontiguousarray(arr)
+    if a.dtype == np.uint16:
+        a = a.view(np.int16)
+    return torch.from_numpy(a).cuda()
+
+
+def bits(t):
+    """device tensor of bf16 storage (int16) -> numpy uint16."""
+    return t.cpu().numpy().view(np.uint16)
+
+
+def nk(b_kn):
+    """logical [k, n] storage -> physical [n, k] (k contiguous)."""
+    return np.ascontiguousarray(b_kn.T)
+
+
+class AgGemmRun:
+    """Buffers for repeated ditron_ag_gemm calls on one problem shape."""
+
+    def __init__(self, B, world, m_per_rank, n, k, esize=2):
+        self.B, self.world, self.m_per_rank, self.n, self.k = B, world, m_per_rank, n, k
+        m = world * m_per_rank
+        dt = torch.int16 if esize == 2 else torch.uint8
+        self.workspace = torch.zeros((m, k), dtype=dt, device="cuda")
+        self.c = torch.zeros((m, n), dtype=torch.int16, device="cuda")
+        self.signals = torch.zeros(B.signal_words(world, 1), dtype=torch.int32, device="cuda")
+        self.status = torch.zeros(B.STATUS_WORDS, dtype=torch.int32, device="cuda")
+        self.epoch = 0
+
+    def __call__(self, shards_dev, b_dev, rank, order=None, flags=None, schedule=None, b_layout=None,
+                 dtype=None, a_scales=None, b_scales=None, stream=None):
+        B = self.B
+        self.epoch += 1
+        flags = B.EMULATE_PRODUCER if flags is None else flags
+        if schedule is not None:
+            flags |= B.DUMP_SCHEDULE
+        st = B.ag_gemm(shards_dev, b_dev, B.B_NK if b_layout is None else b_layout, self.c, a_scales, b_scales,
+                       self.workspace, self.signals, self.status, schedule, order, self.m_per_rank, self.n,
+                       self.k, self.world, rank, B.BF16 if dtype is None else dtype, self.epoch, flags, stream)
+        return st

@@ -1,0 +1,174 @@
+"""AllGather-GEMM on the GPU against the CPU oracle, through the C ABI."""
+import itertools
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import ag_gemm as oag, schedule as osch, formats, compare
+
+pytestmark = pytest.mark.gpu
+
+TOL_BF16 = 2e-2   # max |err| <= 2e-2 * max |row| (stated for bf16 outputs with fp32 accumulation)
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2605_02953_amd import binding
+    assert torch.cuda.is_available()
+    return binding
+
+
+from gpu_util import to_dev, bits, nk, AgGemmRun  # noqa: E402
+
+
+def _run(B, cfg, shards, b_kn, rank=None, order=None, want_schedule=False):
+    rank = cfg.rank if rank is None else rank
+    run = AgGemmRun(B, cfg.world, cfg.m_per_rank, cfg.n, cfg.k)
+    sh = [to_dev(s) for s in shards]
+    bd = to_dev(nk(b_kn))
+    sched = None
+    if want_schedule:
+        st, tc = B.tile_config(0, cfg.m, cfg.n, cfg.k)
+        sched = torch.full((4 * tc["ntiles"],), -1, dtype=torch.int32, device="cuda")
+    st = run(sh, bd, rank, order=order, schedule=sched)
+    assert st == B.OK, B.status_string(st)
+    torch.cuda.synchronize()
+    assert run.status.cpu().tolist()[0] == 0
+    return bits(run.c), bits(run.workspace), (None if sched is None else sched.cpu().numpy().reshape(-1, 4)), run
+
+
+def _check(c_bits, ref64, tol=TOL_BF16):
+    err = compare.max_row_rel_error(formats.decode_bf16(c_bits), ref64)
+    assert err <= tol, err
+    return err
+
+
+def test_cfg1_world2_smoke(B):
+    cfg = synth.CONFIGS[1]
+    shards, b = synth.ag_gemm_inputs(cfg)
+    c, ws, sched, _ = _run(B, cfg, shards, b, want_schedule=True)
+    assert np.array_equal(ws, oag.gather(shards))          # the all-gather reproduces the input
+    _check(c, oag.ag_gemm(shards, b))
+    _check_schedule(B, cfg, cfg.rank, sched)
+
+
+def _check_schedule(B, cfg, rank, sched):
+    st, tc = B.tile_config(0, cfg.m, cfg.n, cfg.k)
+    assert st == B.OK
+    nt = tc["ntiles"]
+    assert nt == osch.cdiv(cfg.m, tc["block_m"]) * osch.cdiv(cfg.n, tc["block_n"])
+    want = []
+    for wg in range(nt):
+        pid = osch.xcd_remap(wg, nt, tc["num_xcd"], tc["per_xcd"]) if tc["num_xcd"] else wg
+        want.append(osch.ag_tile(pid, cfg.m, cfg.n, tc["block_m"], tc["block_n"], tc["group_m"], rank, cfg.world))
+    assert np.array_equal(sched, np.asarray(want, dtype=np.int32))
+
+
+@pytest.mark.parametrize("world,m_r,n,k", [
+    (2, 128, 256, 256),      # one small tile row per shard
+    (4, 200, 264, 328),      # ragged rows, columns and contraction tail (328 = 5*64 + 8)
+    (8, 505, 3080, 200),     # 256x256 tiles with ragged edges on every side, 208 tiles
+    (3, 64, 8, 8),           # minimum contraction and width
+])
+def test_integer_inputs_are_bit_exact(B, world, m_r, n, k):
+    # products and sums of small integers are exact in fp32, so the only rounding is the final
+    # bf16 one: the GPU must match the oracle bit for bit, whatever the tile or lane layout
+    cfg = synth.CONFIGS[2].scaled(world=world, m_per_rank=m_r, n=n, k=k, rank=world - 1)
+    shards, b = synth.ag_gemm_inputs(cfg, integer=True)
+    c, ws, sched, _ = _run(B, cfg, shards, b, want_schedule=True)
+    want = formats.encode_bf16_rne(oag.ag_gemm(shards, b).astype(np.float32))
+    assert np.array_equal(ws, oag.gather(shards))
+    assert np.array_equal(c, want)
+    _check_schedule(B, cfg, cfg.rank, sched)
+
+
+@pytest.mark.parametrize("world,m_r,n,k", [(4, 200, 264, 328), (8, 505, 3080, 456)])
+def test_normal_inputs_within_tolerance(B, world, m_r, n, k):
+    cfg = synth.CONFIGS[2].scaled(world=world, m_per_rank=m_r, n=n, k=k, rank=1)
+    shards, b = synth.ag_gemm_inputs(cfg)
+    c, ws, _, _ = _run(B, cfg, shards, b)
+    _check(c, oag.ag_gemm(shards, b))
+
+
+def test_result_independent_of_rank_and_arrival_order(B):
+    cfg = synth.CONFIGS[2].scaled(world=4, m_per_rank=192, n=384, k=512)
+    shards, b = synth.ag_gemm_inputs(cfg)
+    ref = None
+    orders = [None, [3, 2, 1, 0], [1, 3, 0, 2]]
+    for rank, order in itertools.product(range(cfg.world), orders):
+        c, ws, _, _ = _run(B, cfg, shards, b, rank=rank, order=order)
+        if ref is None:
+            ref = c
+            _check(c, oag.ag_gemm(shards, b))
+        assert np.array_equal(c, ref), (rank, order)
+
+
+def test_epoch_reuse_sees_fresh_data(B):
+    # same buffers, new shard contents and a new epoch every call: a consumer that read a stale
+    # copy of the workspace (left in a cache by the previous call) would fail here
+    cfg = synth.CONFIGS[2].scaled(world=8, m_per_rank=256, n=2048, k=1024)
+    run = AgGemmRun(B, cfg.world, cfg.m_per_rank, cfg.n, cfg.k)
+    _, b = synth.ag_gemm_inputs(cfg, integer=True)
+    bd = to_dev(nk(b))
+    for it in range(4):
+        shards, _ = synth.ag_gemm_inputs(cfg.scaled(seed=it + 1), integer=True)
+        sh = [to_dev(s) for s in shards]
+        assert run(sh, bd, rank=it % cfg.world) == B.OK
+        torch.cuda.synchronize()
+        assert run.status.cpu().tolist()[0] == 0
+        want = formats.encode_bf16_rne(oag.ag_gemm(shards, b).astype(np.float32))
+        assert np.array_equal(bits(run.c), want), it
+        assert run.signals.cpu().numpy()[:cfg.world].tolist() == [run.epoch] * cfg.world
+        assert run.signals.cpu().numpy()[cfg.world:].tolist() == [0] * (run.signals.numel() - cfg.world)
+
+
+def test_external_producer_and_timeout(B):
+    cfg = synth.CONFIGS[2].scaled(world=4, m_per_rank=128, n=256, k=256)
+    shards, b = synth.ag_gemm_inputs(cfg, integer=True)
+    want = formats.encode_bf16_rne(oag.ag_gemm(shards, b).astype(np.float32))
+    run = AgGemmRun(B, cfg.world, cfg.m_per_rank, cfg.n, cfg.k)
+    sh = [to_dev(s) for s in shards]
+    bd = to_dev(nk(b))
+    # (a) a separate publisher delivers the shards in a scrambled order with idle gaps; it is
+    # enqueued first, on its own stream, and the consumer only waits
+    side = torch.cuda.Stream()
+    order = [2, 0, 3, 1]
+    dst = [run.workspace[s * cfg.m_per_rank:(s + 1) * cfg.m_per_rank] for s in order]
+    src = [sh[s] for s in order]
+    nbytes = [cfg.m_per_rank * cfg.k * 2] * cfg.world
+    st = B.publish_chunks(dst, src, nbytes, order, run.signals, run.epoch + 1, delay_cycles=20000, stream=side)
+    assert st == B.OK
+    assert run(None, bd, rank=1, flags=B.EXTERNAL_PRODUCER) == B.OK
+    torch.cuda.synchronize()
+    assert run.status.cpu().tolist()[0] == 0
+    assert np.array_equal(bits(run.c), want)
+    # (b) nobody raises the flags: with a tiny spin limit every wait gives up, the kernel ends
+    # and reports the time-out instead of hanging
+    B.set_spin_limit(64)
+    try:
+        assert run(None, bd, rank=0, flags=B.EXTERNAL_PRODUCER) == B.OK
+        torch.cuda.synchronize()
+        s = run.status.cpu().tolist()
+        assert s[0] == B.ERR_TIMEOUT and 0 <= s[1] < cfg.world
+    finally:
+        B.set_spin_limit(1 << 20)
+    # (c) the buffers stay usable afterwards
+    run.status.zero_()
+    assert run(sh, bd, rank=2) == B.OK
+    torch.cuda.synchronize()
+    assert run.status.cpu().tolist()[0] == 0 and np.array_equal(bits(run.c), want)
+
+
+def test_cfg2_full_size_every_element(B):
+    cfg = synth.CONFIGS[2]
+    shards, b = synth.ag_gemm_inputs(cfg)
+    c, ws, sched, _ = _run(B, cfg, shards, b, want_schedule=True)
+    assert np.array_equal(ws, oag.gather(shards))
+    _check_schedule(B, cfg, cfg.rank, sched)
+    cd = formats.decode_bf16(c)
+    worst = 0.0
+    for r0 in range(0, cfg.m, 1024):       # one shard of rows at a time keeps the fp64 copies small
+        rows = np.arange(r0, r0 + 1024)
+        worst = max(worst, compare.max_row_rel_error(cd[rows], oag.ag_gemm(shards, b, rows=rows)))
+    assert worst <= TOL_BF16, worst
