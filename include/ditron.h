@@ -136,8 +136,8 @@ ditron_status_t ditron_ag_gemm(const void* const* a_shards, const void* b, int b
  *  scatter_buf   device [world, m/world, n] bf16: the destination slots (slot `rank` unused)
  *  out           device out [m/world, n] bf16
  *  signals       device int32[ditron_signal_words(world, chunks_per_slot)]:
- *                words [0, world) are the GEMM's segment flags, words
- *                [world, world + world*chunks_per_slot) the arrival flags (slot-major)
+ *                words [0, world) are the GEMM's segment flags; the arrival flag of
+ *                (peer s, row chunk c) is word 2*world + s*chunks_per_slot + c
  *  schedule_out  with DITRON_DUMP_SCHEDULE: (pid_m, pid_n, segment_start, segment_end) per
  *                GEMM work-group
  *  arrival_order host int[world-1] (peers in delivery order) or NULL

@@ -97,15 +97,6 @@ extern "C" ditron_status_t ditron_ag_gemm_fp8(const void* const*, const void*, i
                                               int32_t, unsigned, void*) {
   return DITRON_ERR_UNSUPPORTED;
 }
-extern "C" ditron_status_t ditron_gemm_rs(const void*, const void*, int, void*, const void* const*, void*, void*,
-                                          int32_t*, int32_t*, int32_t*, const int*, int, int, int, int, int, int,
-                                          int32_t, unsigned, void*) {
-  return DITRON_ERR_UNSUPPORTED;
-}
-extern "C" ditron_status_t ditron_reduce_slots(const void* const*, void*, const int32_t*, int32_t*, int, int, int,
-                                               int, int32_t, void*) {
-  return DITRON_ERR_UNSUPPORTED;
-}
 extern "C" ditron_status_t ditron_moe_ag_grouped_gemm(const void* const*, const int32_t*, const void*, int, void*,
                                                       int32_t*, int32_t*, int32_t*, int32_t*, void*, int32_t*,
                                                       int32_t*, const int*, int, int, int, int, int, int, int, int,

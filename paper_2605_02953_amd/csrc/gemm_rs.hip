@@ -1,0 +1,318 @@
+// GEMM-ReduceScatter, one rank's share (paper, Appendix "GEMM Reduce-Scatter").
+//
+// Launch 1 holds the emulated peers and the GEMM.  The first `num_producers` work-groups
+// copy, peer by peer in delivery order and row chunk by row chunk, the block each peer would
+// push into this rank's scatter buffer, raising one flag per (peer, chunk).  The other
+// work-groups are the tiles of the local GEMM P = A . B, visited from the segment of rank+1
+// to the rank's own segment; a tile bumps the counter of every segment it touches and the
+// tile that completes a segment raises the segment flag.
+// Launch 2 is the reduction: each work-group waits for the flags of the row chunk it sums
+// (the peers' arrival flags and the GEMM's flag for the own segment), adds the `world`
+// blocks in fp32 in slot order with 128-bit loads, rounds once to bf16.
+#include "gemm_core.h"
+#include "launch.h"
+
+namespace ditron {
+
+struct GemmRsParams {
+  const void* peer[DITRON_MAX_WORLD];
+  int order[DITRON_MAX_WORLD];
+  const char* a;
+  const char* b;
+  __bf16* gemm_out;
+  char* scatter_buf;
+  int32_t* seg_flags;      // [world]
+  int32_t* seg_counters;   // [world]
+  int32_t* arr_flags;      // [world * chunks]
+  int32_t* arr_counters;   // [world * chunks]
+  int32_t* status;
+  int32_t* schedule;
+  int m, n, k, world, rank, m_per_rank, chunks, n_peers;
+  int32_t epoch;
+  int num_producers;
+  int group_m, num_xcd, per_xcd, npm, npn;
+};
+
+template <class T>
+__global__ __launch_bounds__(T::THREADS) void gemm_rs_kernel(const GemmRsParams p) {
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  if ((int)blockIdx.x < p.num_producers) {
+    const size_t slot_bytes = (size_t)p.m_per_rank * p.n * 2;
+    const size_t chunk_bytes = slot_bytes / p.chunks;
+    for (int i = 0; i < p.n_peers; ++i) {
+      const int s = p.order[i];
+      for (int c = 0; c < p.chunks; ++c) {
+        copy_slice(p.scatter_buf + s * slot_bytes + c * chunk_bytes, (const char*)p.peer[s] + c * chunk_bytes,
+                   chunk_bytes, blockIdx.x, p.num_producers);
+        publish_after_all(p.arr_counters + s * p.chunks + c, p.num_producers, p.arr_flags + s * p.chunks + c,
+                          p.epoch);
+      }
+    }
+    return;
+  }
+  const int wg = blockIdx.x - p.num_producers;
+  const int pid = xcd_remap(wg, p.npm * p.npn, p.num_xcd, p.per_xcd);
+  int pid_m, pid_n;
+  grouped_order(pid, p.npm, p.npn, p.group_m, pid_m, pid_n);
+  // scatter mode: the next rank's segment first, the own segment last
+  pid_m = (pid_m + ((p.rank + 1) * p.m_per_rank) / T::BM) % p.npm;
+  const int m0 = pid_m * T::BM, n0 = pid_n * T::BN;
+  const int seg_start = m0 / p.m_per_rank;
+  const int seg_end = (min(m0 + T::BM, p.m) - 1) / p.m_per_rank;
+  if (p.schedule && threadIdx.x == 0) {
+    int32_t* rec = p.schedule + 4 * (size_t)wg;
+    rec[0] = pid_m; rec[1] = pid_n; rec[2] = seg_start; rec[3] = seg_end;
+  }
+  const size_t row_bytes = (size_t)p.k * 2;
+  const char* a_tile = p.a;
+  const char* b_tile = p.b;
+  const int M = p.m, N = p.n;
+  auto a_row = [=](int r) { return a_tile + (size_t)min(m0 + r, M - 1) * row_bytes; };
+  auto b_row = [=](int r) { return b_tile + (size_t)min(n0 + r, N - 1) * row_bytes; };
+  f32x16_t acc[T::NI][T::MI];
+  gemm_mainloop<T>(acc, a_row, b_row, p.k, lds);
+  store_tile_bf16<T>(acc, p.gemm_out, (size_t)p.n, m0, n0, M, N, nullptr, 1, nullptr);
+
+  // segment completion: one lane per touched segment
+  __syncthreads();
+  const int seg = seg_start + (int)threadIdx.x;
+  if (seg <= seg_end) {
+    const int first = (p.m_per_rank * seg) / T::BM;
+    const int last = (p.m_per_rank * (seg + 1) - 1) / T::BM;
+    const int target = p.npn * (last - first + 1);
+    const int old = __hip_atomic_fetch_add(p.seg_counters + seg, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    if (old == target - 1) {
+      __hip_atomic_store(p.seg_counters + seg, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      flag_raise(p.seg_flags + seg, p.epoch);
+    }
+  }
+}
+
+// ------------------------------------------------------------------ reduction
+struct ReduceParams {
+  const void* slot[DITRON_MAX_WORLD];
+  const int32_t* gate[DITRON_MAX_WORLD];  // first flag of slot s (chunk c at gate[s] + c*gate_stride[s]) or null
+  int gate_stride[DITRON_MAX_WORLD];
+  __bf16* out;
+  int32_t* status;
+  size_t vec_per_chunk;  // 16-byte vectors per row chunk
+  int chunks, world;
+  int32_t epoch;
+  unsigned spin_limit;
+  int wgs_per_chunk;
+};
+
+constexpr int kReduceThreads = 256;
+constexpr int kReduceUnroll = 4;   // 16-byte vectors per lane per step
+
+__device__ __forceinline__ void set_bf16x8(float (&acc)[8], const u32x4_t v) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    acc[2 * j] = __builtin_bit_cast(float, v[j] << 16);
+    acc[2 * j + 1] = __builtin_bit_cast(float, v[j] & 0xFFFF0000u);
+  }
+}
+
+__device__ __forceinline__ void add_bf16x8(float (&acc)[8], const u32x4_t v) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    acc[2 * j] += __builtin_bit_cast(float, v[j] << 16);
+    acc[2 * j + 1] += __builtin_bit_cast(float, v[j] & 0xFFFF0000u);
+  }
+}
+
+__device__ __forceinline__ u32x4_t pack_bf16x8(const float (&acc)[8]) {
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  u32x4_t r;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    bf16x2_t v = {(__bf16)acc[2 * j], (__bf16)acc[2 * j + 1]};
+    r[j] = __builtin_bit_cast(uint32_t, v);
+  }
+  return r;
+}
+
+// WORLD > 0 fixes the number of slots at compile time (fully unrolled slot loop).
+template <int WORLD>
+__global__ __launch_bounds__(kReduceThreads) void reduce_slots_kernel(const ReduceParams p) {
+  const int chunk = blockIdx.x / p.wgs_per_chunk;
+  const int part = blockIdx.x % p.wgs_per_chunk;
+  const int world = WORLD > 0 ? WORLD : p.world;
+  if (threadIdx.x == 0) {
+    for (int s = 0; s < world; ++s)
+      if (p.gate[s]) flag_wait_lane(p.gate[s], chunk * p.gate_stride[s], 1, p.epoch, p.spin_limit, p.status);
+  }
+  __syncthreads();
+  const size_t base = (size_t)chunk * p.vec_per_chunk;
+  const size_t step = (size_t)p.wgs_per_chunk * kReduceThreads;
+  u32x4_t* out = (u32x4_t*)p.out + base;
+  size_t i = (size_t)part * kReduceThreads + threadIdx.x;
+  for (; i + (kReduceUnroll - 1) * step < p.vec_per_chunk; i += kReduceUnroll * step) {
+    float acc[kReduceUnroll][8];
+    {
+      u32x4_t v[kReduceUnroll];
+#pragma unroll
+      for (int u = 0; u < kReduceUnroll; ++u)
+        v[u] = __builtin_nontemporal_load((const u32x4_t*)p.slot[0] + base + i + u * step);
+#pragma unroll
+      for (int u = 0; u < kReduceUnroll; ++u) set_bf16x8(acc[u], v[u]);
+    }
+#pragma unroll
+    for (int s = 1; s < world; ++s) {
+      u32x4_t v[kReduceUnroll];
+#pragma unroll
+      for (int u = 0; u < kReduceUnroll; ++u)
+        v[u] = __builtin_nontemporal_load((const u32x4_t*)p.slot[s] + base + i + u * step);
+#pragma unroll
+      for (int u = 0; u < kReduceUnroll; ++u) add_bf16x8(acc[u], v[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < kReduceUnroll; ++u) __builtin_nontemporal_store(pack_bf16x8(acc[u]), out + i + u * step);
+  }
+  for (; i < p.vec_per_chunk; i += step) {
+    float acc[8];
+    set_bf16x8(acc, ((const u32x4_t*)p.slot[0])[base + i]);
+    for (int s = 1; s < world; ++s) add_bf16x8(acc, ((const u32x4_t*)p.slot[s])[base + i]);
+    out[i] = pack_bf16x8(acc);
+  }
+}
+
+static ditron_status_t launch_reduce(ReduceParams& p, hipStream_t stream) {
+  // enough work-groups to cover the chip several times over, at least one per row chunk
+  const size_t per_wg = (size_t)kReduceThreads * kReduceUnroll;
+  size_t want = (p.vec_per_chunk + per_wg - 1) / per_wg;
+  const size_t cap = (size_t)(2048 / p.chunks > 0 ? 2048 / p.chunks : 1);
+  if (want > cap) want = cap;
+  if (want < 1) want = 1;
+  p.wgs_per_chunk = (int)want;
+  const dim3 grid((unsigned)(p.wgs_per_chunk * p.chunks));
+  if (p.world == 8) hipLaunchKernelGGL(reduce_slots_kernel<8>, grid, dim3(kReduceThreads), 0, stream, p);
+  else if (p.world == 4) hipLaunchKernelGGL(reduce_slots_kernel<4>, grid, dim3(kReduceThreads), 0, stream, p);
+  else if (p.world == 2) hipLaunchKernelGGL(reduce_slots_kernel<2>, grid, dim3(kReduceThreads), 0, stream, p);
+  else hipLaunchKernelGGL(reduce_slots_kernel<0>, grid, dim3(kReduceThreads), 0, stream, p);
+  return hipGetLastError() == hipSuccess ? DITRON_OK : DITRON_ERR_HIP;
+}
+
+template <class T>
+static ditron_status_t launch_rs(GemmRsParams& p, hipStream_t stream) {
+  p.npm = cdiv(p.m, T::BM);
+  p.npn = cdiv(p.n, T::BN);
+  auto kern = gemm_rs_kernel<T>;
+  if (!set_dynamic_lds((const void*)kern, T::LDS_BYTES)) return DITRON_ERR_HIP;
+  const unsigned grid = (unsigned)(p.num_producers + p.npm * p.npn);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(T::THREADS), T::LDS_BYTES, stream, p);
+  return hipGetLastError() == hipSuccess ? DITRON_OK : DITRON_ERR_HIP;
+}
+
+}  // namespace ditron
+
+using namespace ditron;
+
+extern "C" ditron_status_t ditron_reduce_slots(const void* const* slots, void* out, const int32_t* signals,
+                                               int32_t* status, int rows, int n, int world, int chunks,
+                                               int32_t epoch, void* stream) {
+  if (world < 1 || world > DITRON_MAX_WORLD || rows <= 0 || n <= 0 || chunks < 1) return DITRON_ERR_INVALID_ARG;
+  if (!slots || !out || !aligned16(out) || (signals && !status)) return DITRON_ERR_INVALID_ARG;
+  if (n % 8 != 0) return DITRON_ERR_UNSUPPORTED;
+  if (rows % chunks != 0) return DITRON_ERR_INVALID_ARG;
+  ReduceParams p{};
+  for (int s = 0; s < world; ++s) {
+    if (!slots[s] || !aligned16(slots[s])) return DITRON_ERR_INVALID_ARG;
+    p.slot[s] = slots[s];
+    p.gate[s] = signals ? signals + (size_t)s * chunks : nullptr;
+    p.gate_stride[s] = 1;
+  }
+  p.out = (__bf16*)out;
+  p.status = status;
+  p.vec_per_chunk = (size_t)(rows / chunks) * n / 8;
+  p.chunks = chunks;
+  p.world = world;
+  p.epoch = epoch;
+  p.spin_limit = g_spin_limit;
+  return launch_reduce(p, (hipStream_t)stream);
+}
+
+extern "C" ditron_status_t ditron_gemm_rs(const void* a, const void* b, int b_layout, void* gemm_out,
+                                          const void* const* peer_partials, void* scatter_buf, void* out,
+                                          int32_t* signals, int32_t* status, int32_t* schedule_out,
+                                          const int* arrival_order, int m, int n, int k_local, int world, int rank,
+                                          int chunks_per_slot, int32_t epoch, unsigned flags, void* stream) {
+  if (world < 1 || world > DITRON_MAX_WORLD || rank < 0 || rank >= world) return DITRON_ERR_INVALID_ARG;
+  if (m <= 0 || n <= 0 || k_local <= 0 || m % world != 0 || chunks_per_slot < 1) return DITRON_ERR_INVALID_ARG;
+  const int m_r = m / world;
+  if (m_r % chunks_per_slot != 0) return DITRON_ERR_INVALID_ARG;
+  if (!a || !b || !gemm_out || !out || !signals || !status) return DITRON_ERR_INVALID_ARG;
+  if (world > 1 && !scatter_buf) return DITRON_ERR_INVALID_ARG;
+  if (!aligned16(a) || !aligned16(b) || !aligned16(gemm_out) || !aligned16(out) || !aligned16(scatter_buf) ||
+      !aligned16(signals))
+    return DITRON_ERR_INVALID_ARG;
+  const bool emulate = (flags & DITRON_EMULATE_PRODUCER) != 0;
+  const bool external = (flags & DITRON_EXTERNAL_PRODUCER) != 0;
+  if (emulate == external) return DITRON_ERR_INVALID_ARG;
+  if ((flags & DITRON_DUMP_SCHEDULE) && !schedule_out) return DITRON_ERR_INVALID_ARG;
+  if (b_layout != DITRON_B_KN && b_layout != DITRON_B_NK) return DITRON_ERR_INVALID_ARG;
+  if (b_layout != DITRON_B_NK) return DITRON_ERR_UNSUPPORTED;
+  if (k_local % 8 != 0 || n % 8 != 0) return DITRON_ERR_UNSUPPORTED;
+
+  GemmRsParams p{};
+  p.n_peers = world - 1;
+  if (emulate) {
+    if (world > 1 && !peer_partials) return DITRON_ERR_INVALID_ARG;
+    bool seen[DITRON_MAX_WORLD] = {false};
+    for (int i = 0; i < world - 1; ++i) {
+      const int s = arrival_order ? arrival_order[i] : ((rank - 1 - i) % world + world) % world;
+      if (s < 0 || s >= world || s == rank || seen[s]) return DITRON_ERR_INVALID_ARG;
+      seen[s] = true;
+      p.order[i] = s;
+      if (!peer_partials[s] || !aligned16(peer_partials[s])) return DITRON_ERR_INVALID_ARG;
+      p.peer[s] = peer_partials[s];
+    }
+  }
+  p.a = (const char*)a;
+  p.b = (const char*)b;
+  p.gemm_out = (__bf16*)gemm_out;
+  p.scatter_buf = (char*)scatter_buf;
+  p.seg_flags = signals;
+  p.seg_counters = signals + world;
+  p.arr_flags = signals + 2 * world;
+  p.arr_counters = signals + 2 * world + world * chunks_per_slot;
+  p.status = status;
+  p.schedule = (flags & DITRON_DUMP_SCHEDULE) ? schedule_out : nullptr;
+  p.m = m;
+  p.n = n;
+  p.k = k_local;
+  p.world = world;
+  p.rank = rank;
+  p.m_per_rank = m_r;
+  p.chunks = chunks_per_slot;
+  p.epoch = epoch;
+  TileChoice tc = choose_tile(m, n, k_local);
+  p.group_m = tc.group_m;
+  p.num_xcd = tc.num_xcd;
+  p.per_xcd = tc.per_xcd;
+  p.num_producers = (emulate && world > 1) ? tc.producers : 0;
+  ditron_status_t st = tc.big ? launch_rs<TileBig>(p, (hipStream_t)stream) : launch_rs<TileSmall>(p, (hipStream_t)stream);
+  if (st != DITRON_OK) return st;
+
+  ReduceParams r{};
+  const size_t slot_bytes = (size_t)m_r * n * 2;
+  for (int s = 0; s < world; ++s) {
+    if (s == rank) {
+      r.slot[s] = (const char*)gemm_out + (size_t)rank * slot_bytes;
+      r.gate[s] = p.seg_flags + rank;   // the GEMM's flag for the own segment gates every chunk
+      r.gate_stride[s] = 0;
+    } else {
+      r.slot[s] = (const char*)scatter_buf + (size_t)s * slot_bytes;
+      r.gate[s] = p.arr_flags + (size_t)s * chunks_per_slot;
+      r.gate_stride[s] = 1;
+    }
+  }
+  r.out = (__bf16*)out;
+  r.status = status;
+  r.vec_per_chunk = (size_t)(m_r / chunks_per_slot) * n / 8;
+  r.chunks = chunks_per_slot;
+  r.world = world;
+  r.epoch = epoch;
+  r.spin_limit = g_spin_limit;
+  return launch_reduce(r, (hipStream_t)stream);
+}

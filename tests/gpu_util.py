@@ -46,3 +46,27 @@ class AgGemmRun:
                        self.workspace, self.signals, self.status, schedule, order, self.m_per_rank, self.n,
                        self.k, self.world, rank, B.BF16 if dtype is None else dtype, self.epoch, flags, stream)
         return st
+
+
+class GemmRsRun:
+    """Buffers for repeated ditron_gemm_rs calls on one problem shape."""
+
+    def __init__(self, B, world, m, n, k, chunks=1):
+        self.B, self.world, self.m, self.n, self.k, self.chunks = B, world, m, n, k, chunks
+        m_r = m // world
+        self.gemm_out = torch.zeros((m, n), dtype=torch.int16, device="cuda")
+        self.scatter = torch.zeros((world, m_r, n), dtype=torch.int16, device="cuda")
+        self.out = torch.zeros((m_r, n), dtype=torch.int16, device="cuda")
+        self.signals = torch.zeros(B.signal_words(world, chunks), dtype=torch.int32, device="cuda")
+        self.status = torch.zeros(B.STATUS_WORDS, dtype=torch.int32, device="cuda")
+        self.epoch = 0
+
+    def __call__(self, a_dev, b_dev, peers, rank, order=None, flags=None, schedule=None, stream=None):
+        B = self.B
+        self.epoch += 1
+        flags = B.EMULATE_PRODUCER if flags is None else flags
+        if schedule is not None:
+            flags |= B.DUMP_SCHEDULE
+        return B.gemm_rs(a_dev, b_dev, B.B_NK, self.gemm_out, peers, self.scatter, self.out, self.signals,
+                         self.status, schedule, order, self.m, self.n, self.k, self.world, rank, self.chunks,
+                         self.epoch, flags, stream)

@@ -1,0 +1,135 @@
+"""GEMM-ReduceScatter on the GPU against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import gemm_rs as ors, schedule as osch, formats, compare
+
+pytestmark = pytest.mark.gpu
+
+TOL_BF16 = 2e-2
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2605_02953_amd import binding
+    assert torch.cuda.is_available()
+    return binding
+
+
+from gpu_util import to_dev, bits, nk, GemmRsRun  # noqa: E402
+
+
+def _ok(B, st, run):
+    assert st == B.OK, B.status_string(st)
+    torch.cuda.synchronize()
+    assert run.status.cpu().tolist()[0] == 0
+
+
+@pytest.mark.parametrize("world,rows,n,chunks,gated", [
+    (8, 64, 256, 1, False), (8, 96, 1000 * 8, 4, True), (4, 33, 40, 1, True), (3, 10, 8, 2, False),
+    (1, 5, 16, 1, True), (2, 128, 4096, 8, True)])
+def test_reduce_slots_exact(B, world, rows, n, chunks, gated):
+    rng = synth.rng_for(7, world, rows)
+    slots = [synth.normal_bf16(rng, (rows, n), std=3.0) for _ in range(world)]
+    sd = [to_dev(s) for s in slots]
+    out = torch.zeros((rows, n), dtype=torch.int16, device="cuda")
+    status = torch.zeros(B.STATUS_WORDS, dtype=torch.int32, device="cuda")
+    sig = torch.full((world * chunks,), 5, dtype=torch.int32, device="cuda") if gated else None
+    st = B.reduce_slots(sd, out, sig, status, rows, n, world, chunks, 5)
+    assert st == B.OK, B.status_string(st)
+    torch.cuda.synchronize()
+    assert status.cpu().tolist()[0] == 0
+    got = bits(out)
+    # specified arithmetic: fp32 adds in slot order, one rounding -> identical bits
+    assert np.array_equal(got, ors.reduce_slots_f32_ordered(slots))
+    # and within one bf16 ulp of the exact sum
+    exact = ors.reduce_slots_f64(slots)
+    ulp = np.maximum(np.abs(exact), 2.0 ** -126) * 2.0 ** -7
+    assert np.all(np.abs(formats.decode_bf16(got) - exact) <= ulp)
+
+
+def _all_partials(B, cfg, a_list, b_list):
+    """Every emulated rank's full partial product, computed by the library's own GEMM (this
+    is what each peer would hold); returns device tensors [m, n]."""
+    run = GemmRsRun(B, cfg.world, cfg.m, cfg.n, cfg.k)
+    zero = torch.zeros((cfg.m_per_rank, cfg.n), dtype=torch.int16, device="cuda")
+    parts = []
+    for s in range(cfg.world):
+        st = run(to_dev(a_list[s]), to_dev(nk(b_list[s])), [zero] * cfg.world, s)
+        _ok(B, st, run)
+        parts.append(run.gemm_out.clone())
+    return parts
+
+
+def _check_schedule(B, cfg, rank, sched):
+    st, tc = B.tile_config(1, cfg.m, cfg.n, cfg.k)
+    nt = tc["ntiles"]
+    want = []
+    for wg in range(nt):
+        pid = osch.xcd_remap(wg, nt, tc["num_xcd"], tc["per_xcd"]) if tc["num_xcd"] else wg
+        want.append(osch.rs_tile(pid, cfg.m, cfg.n, tc["block_m"], tc["block_n"], tc["group_m"], rank, cfg.world))
+    assert np.array_equal(sched, np.asarray(want, dtype=np.int32))
+
+
+@pytest.mark.parametrize("world,m_r,n,k,chunks,integer", [
+    (4, 128, 256, 64, 1, True),
+    (4, 100, 264, 72, 2, True),       # segments that straddle tiles, ragged everything
+    (8, 505, 3080, 200, 5, True),     # 256x256 tiles, ragged edges
+    (2, 192, 384, 512, 3, False),
+    (1, 256, 256, 128, 1, True),      # world 1: plain GEMM
+])
+def test_gemm_rs_end_to_end(B, world, m_r, n, k, chunks, integer):
+    cfg = synth.CONFIGS[3].scaled(world=world, m_per_rank=m_r, n=n, k=k)
+    a_list, b_list = synth.gemm_rs_inputs(cfg, integer=integer)
+    parts = _all_partials(B, cfg, a_list, b_list)
+    for s in (0, world - 1):     # stage oracle: the partial product itself
+        err = compare.max_row_rel_error(formats.decode_bf16(bits(parts[s])), ors.partial(a_list[s], b_list[s]))
+        assert err <= TOL_BF16
+    run = GemmRsRun(B, world, cfg.m, n, k, chunks)
+    st, tc = B.tile_config(1, cfg.m, n, k)
+    for d in range(world):
+        peers = [parts[s][d * m_r:(d + 1) * m_r] for s in range(world)]
+        sched = torch.full((4 * tc["ntiles"],), -1, dtype=torch.int32, device="cuda")
+        order = None if d % 2 == 0 else [s for s in range(world) if s != d]     # also a non-ring delivery
+        st = run(to_dev(a_list[d]), to_dev(nk(b_list[d])), peers, d, order=order, schedule=sched)
+        _ok(B, st, run)
+        ref = ors.gemm_rs(a_list, b_list, d)
+        got = bits(run.out)
+        if integer:
+            assert np.array_equal(got, formats.encode_bf16_rne(ref.astype(np.float32))), d
+        else:
+            assert compare.max_row_rel_error(formats.decode_bf16(got), ref) <= TOL_BF16
+        _check_schedule(B, cfg, d, sched.cpu().numpy().reshape(-1, 4))
+        sig = run.signals.cpu().numpy()
+        assert sig[:world].tolist() == [run.epoch] * world            # every segment flag raised
+        assert sig[world:2 * world].tolist() == [0] * world            # counters left at zero
+        arr = sig[2 * world:2 * world + world * chunks].reshape(world, chunks)
+        for s in range(world):
+            if s != d:                                                  # every peer chunk was flagged
+                assert arr[s].tolist() == [run.epoch] * chunks
+        # the scatter buffer holds exactly what the peers sent
+        for s in range(world):
+            if s != d:
+                assert torch.equal(run.scatter[s], peers[s])
+
+
+def test_cfg3_full_size(B):
+    cfg = synth.CONFIGS[3]
+    a_list, b_list = synth.gemm_rs_inputs(cfg)
+    parts = _all_partials(B, cfg, a_list, b_list)
+    d, m_r = cfg.rank, cfg.m_per_rank
+    run = GemmRsRun(B, cfg.world, cfg.m, cfg.n, cfg.k, chunks=4)
+    peers = [parts[s][d * m_r:(d + 1) * m_r] for s in range(cfg.world)]
+    st = run(to_dev(a_list[d]), to_dev(nk(b_list[d])), peers, d)
+    _ok(B, st, run)
+    ref = ors.gemm_rs(a_list, b_list, d)
+    assert compare.max_row_rel_error(formats.decode_bf16(bits(run.out)), ref) <= TOL_BF16
+    # the reduction in isolation on the actual slot contents: bit-exact to the specified arithmetic
+    slots = [bits(parts[s][d * m_r:(d + 1) * m_r]) for s in range(cfg.world)]
+    assert np.array_equal(bits(run.out), ors.reduce_slots_f32_ordered(slots))
+    # sampled rows of the partial product
+    rows = np.arange(0, cfg.m, 61)
+    pref = formats.decode_bf16(a_list[d][rows]) @ formats.decode_bf16(b_list[d])
+    assert compare.max_row_rel_error(formats.decode_bf16(bits(run.gemm_out)[rows]), pref) <= TOL_BF16
