@@ -181,12 +181,16 @@ ditron_status_t ditron_reduce_slots(const void* const* slots, void* out, const i
  *  counts        device out int32 [world * num_experts]
  *  expert_offsets device out int32 [num_local_experts + 1]
  *  gather_idx    device out int32 [max_rows]
- *  tile_records  device out int32 [1 + 4*max_tiles]: ntiles, then (expert_id, tiled_m,
- *                segment_start, segment_end) per tile, max_tiles =
- *                ditron_moe_max_tiles(max_rows, num_local_experts)
+ *  tile_records  device out int32 [1 + 5*max_tiles], max_tiles =
+ *                ditron_moe_max_tiles(max_rows, num_local_experts): word 0 = ntiles, then
+ *                (expert_id, tiled_m, segment_start, segment_end) per tile in execution
+ *                order (expert_id counted from expert_begin, tiled_m = index of the tile in
+ *                the unsorted per-expert order); the last max_tiles words are internal
+ *                (first output row of each tile)
  *  workspace     device [world*tokens_per_rank, hidden] bf16 gathered tokens
  *  signals       device int32[ditron_signal_words(world, 1)]
- *  If R exceeds max_rows, status[0] = DITRON_ERR_WORKSPACE and no GEMM tile runs.
+ *  If R exceeds max_rows, status[0] = DITRON_ERR_WORKSPACE, status[2] = R and no GEMM tile
+ *  runs.  Limits: num_experts <= 256, num_local_experts <= 64, max_tiles <= 4096.
  */
 ditron_status_t ditron_moe_ag_grouped_gemm(const void* const* x_shards, const int32_t* topk_ids,
                                            const void* w, int w_layout, void* y, int32_t* counts,

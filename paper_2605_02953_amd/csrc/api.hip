@@ -43,6 +43,11 @@ extern "C" ditron_status_t ditron_tile_config(int op, int m, int n, int k, int d
   if (!out || m <= 0 || n <= 0 || k <= 0 || op < 0 || op > 2) return DITRON_ERR_INVALID_ARG;
   if (dtype != DITRON_BF16) return DITRON_ERR_UNSUPPORTED;
   TileChoice t = choose_tile(m, n, k);
+  if (op == 2) {  // the grouped GEMM always uses the small tile; m is max_rows
+    t.big = false;
+    t.block_m = t.block_n = TileSmall::BM;
+    t.threads = TileSmall::THREADS;
+  }
   out[0] = t.block_m;
   out[1] = t.block_n;
   out[2] = t.group_m;
@@ -97,10 +102,3 @@ extern "C" ditron_status_t ditron_ag_gemm_fp8(const void* const*, const void*, i
                                               int32_t, unsigned, void*) {
   return DITRON_ERR_UNSUPPORTED;
 }
-extern "C" ditron_status_t ditron_moe_ag_grouped_gemm(const void* const*, const int32_t*, const void*, int, void*,
-                                                      int32_t*, int32_t*, int32_t*, int32_t*, void*, int32_t*,
-                                                      int32_t*, const int*, int, int, int, int, int, int, int, int,
-                                                      int, int, int32_t, unsigned, void*) {
-  return DITRON_ERR_UNSUPPORTED;
-}
-extern "C" int ditron_moe_max_tiles(int, int) { return 0; }

@@ -1,0 +1,323 @@
+// MoE AllGather + grouped GEMM, one rank's share (paper: "ag_group_gemm" of the kernel
+// list; tile ordering after `threadblock_swizzle_ag_moe_kernel`, Appendix "Swizzle").
+//
+// Launch 1 (one work-group, integer only): per-(rank, expert) histogram, exclusive scan of
+// the local experts' totals, stable gather index, then the tile list: every local expert's
+// rows are cut into BLOCK_M row tiles, each tile learns the span of source ranks its rows
+// come from and the ring stage at which the last of them arrives, and tiles are emitted
+// grouped by expert, ascending stage, ties in original order.
+// Launch 2: producer work-groups copy the token shards into the workspace in delivery order
+// and raise one flag per shard; every other work-group takes one (tile, column block), waits
+// for the shard flags of its tile, gathers its rows through gather_idx while staging them in
+// LDS and multiplies by its expert's weights.
+#include "gemm_core.h"
+#include "launch.h"
+
+namespace ditron {
+
+constexpr int kRouteThreads = 1024;
+constexpr int kRouteWaves = kRouteThreads / 64;
+constexpr int kMaxExperts = 256;       // experts (global) the routing kernel can histogram
+constexpr int kMaxLocalExperts = 64;
+constexpr int kMaxTilesLds = 4096;     // tile stages kept in LDS by the schedule step
+
+struct MoeRouteParams {
+  const int32_t* topk_ids;   // [tokens * top_k]
+  int32_t* counts;           // [world * num_experts]
+  int32_t* expert_offsets;   // [num_local + 1]
+  int32_t* gather_idx;       // [max_rows]
+  int32_t* tile_records;     // [0] = ntiles ; 4 words per tile ; then max_tiles words: first row of the tile
+  int32_t* status;
+  int tokens_per_rank, top_k, num_experts, expert_begin, num_local, max_rows, max_tiles;
+  int world, rank, block_m;
+};
+
+__global__ __launch_bounds__(kRouteThreads) void moe_route_kernel(const MoeRouteParams p) {
+  __shared__ int s_counts[DITRON_MAX_WORLD * kMaxExperts];       // [world][num_experts]
+  __shared__ int s_offsets[kMaxLocalExperts + 1];
+  __shared__ int s_wave_base[kRouteWaves][kMaxLocalExperts];     // running output position per (wave, expert)
+  __shared__ int s_tile_acc[kMaxLocalExperts + 1];               // exclusive prefix of tiles per expert
+  __shared__ int s_cum[kMaxLocalExperts][DITRON_MAX_WORLD];      // inclusive per-rank cumulative rows per expert
+  __shared__ int s_stage[kMaxTilesLds];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int F = p.world * p.tokens_per_rank * p.top_k;
+  const int per_shard = p.tokens_per_rank * p.top_k;
+  const int E = p.num_experts, EL = p.num_local;
+
+  for (int i = tid; i < p.world * E; i += kRouteThreads) s_counts[i] = 0;
+  for (int i = tid; i < kRouteWaves * kMaxLocalExperts; i += kRouteThreads) (&s_wave_base[0][0])[i] = 0;
+  __syncthreads();
+
+  // histogram over (source rank, expert), and per-wave totals for the local experts.  A wave
+  // owns one contiguous range of assignments so that ranks inside an expert follow f.
+  const int per_wave = cdiv(cdiv(F, kRouteWaves), 64) * 64;
+  const int w_begin = min(wave * per_wave, F), w_end = min(w_begin + per_wave, F);
+  for (int f = w_begin + lane; f < w_end; f += 64) {
+    const int e = p.topk_ids[f];
+    if (e >= 0 && e < E) {
+      atomicAdd(&s_counts[(f / per_shard) * E + e], 1);
+      const int j = e - p.expert_begin;
+      if (j >= 0 && j < EL) atomicAdd(&s_wave_base[wave][j], 1);
+    }
+  }
+  __syncthreads();
+  for (int i = tid; i < p.world * E; i += kRouteThreads) p.counts[i] = s_counts[i];
+
+  // totals of the local experts -> exclusive scan; per-rank cumulative rows
+  if (tid < EL) {
+    int run = 0;
+    for (int s = 0; s < p.world; ++s) {
+      run += s_counts[s * E + p.expert_begin + tid];
+      s_cum[tid][s] = run;
+    }
+  }
+  __syncthreads();
+  if (tid == 0) {
+    int run = 0, tiles = 0;
+    for (int j = 0; j < EL; ++j) {
+      s_offsets[j] = run;
+      s_tile_acc[j] = tiles;
+      const int n_j = s_cum[j][p.world - 1];
+      run += n_j;
+      tiles += cdiv(n_j, p.block_m);
+    }
+    s_offsets[EL] = run;
+    s_tile_acc[EL] = tiles;
+  }
+  __syncthreads();
+  for (int j = tid; j <= EL; j += kRouteThreads) p.expert_offsets[j] = s_offsets[j];
+  const int R = s_offsets[EL];
+  const int ntiles = s_tile_acc[EL];
+  const bool fits = R <= p.max_rows && ntiles <= p.max_tiles && ntiles <= kMaxTilesLds;
+  if (!fits) {
+    if (tid == 0) {
+      p.status[0] = DITRON_ERR_WORKSPACE;
+      p.status[2] = R;
+      p.tile_records[0] = 0;
+    }
+    return;
+  }
+
+  // wave totals -> first output position of every (wave, expert)
+  if (tid < EL) {
+    int run = s_offsets[tid];
+    for (int w = 0; w < kRouteWaves; ++w) {
+      const int c = s_wave_base[w][tid];
+      s_wave_base[w][tid] = run;
+      run += c;
+    }
+  }
+  __syncthreads();
+
+  // stable placement: 64 assignments at a time, lanes with the same expert rank themselves
+  for (int f0 = w_begin; f0 < w_end; f0 += 64) {
+    const int f = f0 + lane;
+    int j = -1;
+    if (f < w_end) {
+      const int e = p.topk_ids[f];
+      j = e - p.expert_begin;
+      if (j < 0 || j >= EL) j = -1;
+    }
+    unsigned long long todo = __ballot(j >= 0);
+    while (todo) {
+      const int leader = __ffsll((long long)todo) - 1;
+      const int jl = __shfl(j, leader);
+      const unsigned long long same = __ballot(j == jl);
+      const int base = s_wave_base[wave][jl];
+      if (j == jl) {
+        const int before = __popcll(same & ((1ull << lane) - 1ull));
+        p.gather_idx[base + before] = f;
+      }
+      __builtin_amdgcn_wave_barrier();
+      if (lane == leader) s_wave_base[wave][jl] = base + __popcll(same);
+      __builtin_amdgcn_wave_barrier();
+      todo &= ~same;
+    }
+  }
+
+  // tile list.  stage of a tile: position in the ring order rank, rank+1, ... of the last
+  // source rank among its rows
+  for (int t = tid; t < ntiles; t += kRouteThreads) {
+    int j = 0;
+    while (s_tile_acc[j + 1] <= t) ++j;
+    const int q0 = (t - s_tile_acc[j]) * p.block_m;
+    const int q1 = min(q0 + p.block_m, s_cum[j][p.world - 1]);
+    int seg_start = 0, seg_end = 0;
+    for (int s = 0; s < p.world; ++s) {
+      seg_start += (s_cum[j][s] <= q0);
+      seg_end += (s_cum[j][s] <= q1 - 1);
+    }
+    int stage = 0;
+    for (int s = seg_start; s <= seg_end; ++s) stage = max(stage, (s - p.rank + p.world) % p.world);
+    s_stage[t] = stage | (seg_start << 8) | (seg_end << 16);
+  }
+  __syncthreads();
+  int32_t* rec = p.tile_records + 1;
+  int32_t* row0 = p.tile_records + 1 + 4 * p.max_tiles;
+  for (int t = tid; t < ntiles; t += kRouteThreads) {
+    int j = 0;
+    while (s_tile_acc[j + 1] <= t) ++j;
+    const int mine = s_stage[t] & 0xFF;
+    int before = 0;
+    for (int u = s_tile_acc[j]; u < s_tile_acc[j + 1]; ++u) {
+      const int other = s_stage[u] & 0xFF;
+      before += (other < mine) || (other == mine && u < t);
+    }
+    const int pos = s_tile_acc[j] + before;
+    rec[4 * pos + 0] = j;
+    rec[4 * pos + 1] = t;
+    rec[4 * pos + 2] = (s_stage[t] >> 8) & 0xFF;
+    rec[4 * pos + 3] = (s_stage[t] >> 16) & 0xFF;
+    row0[pos] = s_offsets[j] + (t - s_tile_acc[j]) * p.block_m;
+  }
+  if (tid == 0) p.tile_records[0] = ntiles;
+}
+
+struct MoeGemmParams {
+  const void* shard[DITRON_MAX_WORLD];
+  int order[DITRON_MAX_WORLD];
+  char* workspace;
+  const char* w;
+  __bf16* y;
+  const int32_t* expert_offsets;
+  const int32_t* gather_idx;
+  const int32_t* tile_records;
+  int32_t* flags;
+  int32_t* arrivals;
+  int32_t* status;
+  int tokens_per_rank, hidden, inter, top_k, world, max_tiles, npn;
+  int32_t epoch;
+  int num_producers;
+  unsigned spin_limit;
+};
+
+template <class T>
+__global__ __launch_bounds__(T::THREADS) void moe_grouped_gemm_kernel(const MoeGemmParams p) {
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  if ((int)blockIdx.x < p.num_producers) {
+    const size_t shard_bytes = (size_t)p.tokens_per_rank * p.hidden * 2;
+    for (int i = 0; i < p.world; ++i) {
+      const int s = p.order[i];
+      copy_slice(p.workspace + (size_t)s * shard_bytes, p.shard[s], shard_bytes, blockIdx.x, p.num_producers);
+      publish_after_all(p.arrivals + s, p.num_producers, p.flags + s, p.epoch);
+    }
+    return;
+  }
+  const int wg = blockIdx.x - p.num_producers;
+  const int pos = wg / p.npn, pid_n = wg % p.npn;
+  const int ntiles = p.tile_records[0];
+  if (pos >= ntiles) return;
+  const int32_t* rec = p.tile_records + 1 + 4 * pos;
+  const int j = rec[0], seg_start = rec[2], seg_end = rec[3];
+  const int p0 = p.tile_records[1 + 4 * p.max_tiles + pos];
+  const int p_end = min(p0 + T::BM, p.expert_offsets[j + 1]);
+  flag_wait_block(p.flags, seg_start, seg_end - seg_start + 1, p.epoch, p.spin_limit, p.status);
+
+  const int n0 = pid_n * T::BN;
+  const size_t row_bytes = (size_t)p.hidden * 2;
+  const char* x = p.workspace;
+  const char* wj = p.w + (size_t)j * p.inter * row_bytes;
+  const int32_t* gidx = p.gather_idx;
+  const int top_k = p.top_k, N = p.inter;
+  auto a_row = [=](int r) { return x + (size_t)(gidx[min(p0 + r, p_end - 1)] / top_k) * row_bytes; };
+  auto b_row = [=](int r) { return wj + (size_t)min(n0 + r, N - 1) * row_bytes; };
+  f32x16_t acc[T::NI][T::MI];
+  gemm_mainloop<T>(acc, a_row, b_row, p.hidden, lds);
+  store_tile_bf16<T>(acc, p.y, (size_t)p.inter, p0, n0, p_end, N, nullptr, 1, nullptr);
+}
+
+}  // namespace ditron
+
+using namespace ditron;
+
+typedef TileSmall MoeTile;
+
+extern "C" int ditron_moe_max_tiles(int max_rows, int num_local_experts) {
+  if (max_rows < 0 || num_local_experts < 0) return 0;
+  return cdiv(max_rows, MoeTile::BM) + num_local_experts;
+}
+
+extern "C" ditron_status_t ditron_moe_ag_grouped_gemm(
+    const void* const* x_shards, const int32_t* topk_ids, const void* w, int w_layout, void* y, int32_t* counts,
+    int32_t* expert_offsets, int32_t* gather_idx, int32_t* tile_records, void* workspace, int32_t* signals,
+    int32_t* status, const int* arrival_order, int tokens_per_rank, int hidden, int inter, int num_experts,
+    int top_k, int expert_begin, int num_local_experts, int max_rows, int world, int rank, int32_t epoch,
+    unsigned flags, void* stream) {
+  if (world < 1 || world > DITRON_MAX_WORLD || rank < 0 || rank >= world) return DITRON_ERR_INVALID_ARG;
+  if (tokens_per_rank <= 0 || hidden <= 0 || inter <= 0 || num_experts <= 0 || top_k <= 0 || max_rows <= 0)
+    return DITRON_ERR_INVALID_ARG;
+  if (expert_begin < 0 || num_local_experts <= 0 || expert_begin + num_local_experts > num_experts)
+    return DITRON_ERR_INVALID_ARG;
+  if (!topk_ids || !w || !y || !counts || !expert_offsets || !gather_idx || !tile_records || !workspace ||
+      !signals || !status)
+    return DITRON_ERR_INVALID_ARG;
+  if (!aligned16(w) || !aligned16(y) || !aligned16(workspace) || !aligned16(signals)) return DITRON_ERR_INVALID_ARG;
+  const bool emulate = (flags & DITRON_EMULATE_PRODUCER) != 0;
+  const bool external = (flags & DITRON_EXTERNAL_PRODUCER) != 0;
+  if (emulate == external) return DITRON_ERR_INVALID_ARG;
+  if (w_layout != DITRON_B_KN && w_layout != DITRON_B_NK) return DITRON_ERR_INVALID_ARG;
+  if (emulate) {
+    if (!x_shards) return DITRON_ERR_INVALID_ARG;
+    for (int s = 0; s < world; ++s)
+      if (!x_shards[s] || !aligned16(x_shards[s])) return DITRON_ERR_INVALID_ARG;
+    if (arrival_order && !is_permutation(arrival_order, world)) return DITRON_ERR_INVALID_ARG;
+  }
+  if (w_layout != DITRON_B_NK) return DITRON_ERR_UNSUPPORTED;
+  if (hidden % 8 != 0 || inter % 8 != 0) return DITRON_ERR_UNSUPPORTED;
+  if (num_experts > kMaxExperts || num_local_experts > kMaxLocalExperts) return DITRON_ERR_UNSUPPORTED;
+  if ((long)world * num_experts > (long)DITRON_MAX_WORLD * kMaxExperts) return DITRON_ERR_UNSUPPORTED;
+  const int max_tiles = ditron_moe_max_tiles(max_rows, num_local_experts);
+  if (max_tiles > kMaxTilesLds) return DITRON_ERR_UNSUPPORTED;
+  if ((long)world * tokens_per_rank * top_k > 0x7fffffffL) return DITRON_ERR_UNSUPPORTED;
+
+  hipStream_t s = (hipStream_t)stream;
+  MoeRouteParams r{};
+  r.topk_ids = topk_ids;
+  r.counts = counts;
+  r.expert_offsets = expert_offsets;
+  r.gather_idx = gather_idx;
+  r.tile_records = tile_records;
+  r.status = status;
+  r.tokens_per_rank = tokens_per_rank;
+  r.top_k = top_k;
+  r.num_experts = num_experts;
+  r.expert_begin = expert_begin;
+  r.num_local = num_local_experts;
+  r.max_rows = max_rows;
+  r.max_tiles = max_tiles;
+  r.world = world;
+  r.rank = rank;
+  r.block_m = MoeTile::BM;
+  hipLaunchKernelGGL(moe_route_kernel, dim3(1), dim3(kRouteThreads), 0, s, r);
+  if (hipGetLastError() != hipSuccess) return DITRON_ERR_HIP;
+
+  MoeGemmParams g{};
+  for (int i = 0; i < world; ++i) {
+    g.shard[i] = emulate ? x_shards[i] : nullptr;
+    g.order[i] = arrival_order ? arrival_order[i] : (rank + i) % world;
+  }
+  g.workspace = (char*)workspace;
+  g.w = (const char*)w;
+  g.y = (__bf16*)y;
+  g.expert_offsets = expert_offsets;
+  g.gather_idx = gather_idx;
+  g.tile_records = tile_records;
+  g.flags = signals;
+  g.arrivals = signals + world;
+  g.status = status;
+  g.tokens_per_rank = tokens_per_rank;
+  g.hidden = hidden;
+  g.inter = inter;
+  g.top_k = top_k;
+  g.world = world;
+  g.max_tiles = max_tiles;
+  g.npn = cdiv(inter, MoeTile::BN);
+  g.epoch = epoch;
+  g.num_producers = emulate ? 16 : 0;
+  g.spin_limit = g_spin_limit;
+  auto kern = moe_grouped_gemm_kernel<MoeTile>;
+  if (!set_dynamic_lds((const void*)kern, MoeTile::LDS_BYTES)) return DITRON_ERR_HIP;
+  const unsigned grid = (unsigned)(g.num_producers + max_tiles * g.npn);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(MoeTile::THREADS), MoeTile::LDS_BYTES, s, g);
+  return hipGetLastError() == hipSuccess ? DITRON_OK : DITRON_ERR_HIP;
+}

@@ -70,3 +70,32 @@ class GemmRsRun:
         return B.gemm_rs(a_dev, b_dev, B.B_NK, self.gemm_out, peers, self.scatter, self.out, self.signals,
                          self.status, schedule, order, self.m, self.n, self.k, self.world, rank, self.chunks,
                          self.epoch, flags, stream)
+
+
+class MoeRun:
+    """Buffers for repeated ditron_moe_ag_grouped_gemm calls on one problem shape."""
+
+    def __init__(self, B, world, tokens_per_rank, hidden, inter, num_experts, top_k, num_local, max_rows):
+        self.B = B
+        self.dims = (tokens_per_rank, hidden, inter, num_experts, top_k, num_local, max_rows, world)
+        self.max_tiles = B.moe_max_tiles(max_rows, num_local)
+        i32 = dict(dtype=torch.int32, device="cuda")
+        self.workspace = torch.zeros((world * tokens_per_rank, hidden), dtype=torch.int16, device="cuda")
+        self.y = torch.full((max_rows, inter), 0x7FC0, dtype=torch.int16, device="cuda")   # NaN pattern: untouched rows stay visible
+        self.counts = torch.full((world * num_experts,), -1, **i32)
+        self.offsets = torch.full((num_local + 1,), -1, **i32)
+        self.gather = torch.full((max_rows,), -1, **i32)
+        self.records = torch.full((1 + 5 * self.max_tiles,), -1, **i32)
+        self.signals = torch.zeros(B.signal_words(world, 1), **i32)
+        self.status = torch.zeros(B.STATUS_WORDS, **i32)
+        self.epoch = 0
+
+    def __call__(self, x_dev, ids_dev, w_dev, expert_begin, rank, order=None, flags=None, stream=None):
+        B = self.B
+        t_r, hidden, inter, ne, top_k, nl, max_rows, world = self.dims
+        self.epoch += 1
+        flags = B.EMULATE_PRODUCER if flags is None else flags
+        return B.moe_ag_grouped_gemm(x_dev, ids_dev, w_dev, B.B_NK, self.y, self.counts, self.offsets, self.gather,
+                                     self.records, self.workspace, self.signals, self.status, order, t_r, hidden,
+                                     inter, ne, top_k, expert_begin, nl, max_rows, world, rank, self.epoch, flags,
+                                     stream)

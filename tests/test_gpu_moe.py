@@ -1,0 +1,109 @@
+"""MoE AllGather + grouped GEMM on the GPU against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import moe as omoe, formats, compare
+
+pytestmark = pytest.mark.gpu
+
+TOL_BF16 = 2e-2
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2605_02953_amd import binding
+    assert torch.cuda.is_available()
+    return binding
+
+
+from gpu_util import to_dev, bits, MoeRun  # noqa: E402
+
+
+def w_nk(w_ekn):
+    """logical [E_l, hidden, inter] -> physical [E_l, inter, hidden]."""
+    return np.ascontiguousarray(np.transpose(w_ekn, (0, 2, 1)))
+
+
+def _run_and_check(B, cfg, xs, ids, w, max_rows, integer, order=None, block_m=128):
+    e0 = cfg.rank * cfg.num_local_experts if (cfg.rank + 1) * cfg.num_local_experts <= cfg.num_experts else 0
+    run = MoeRun(B, cfg.world, cfg.tokens_per_rank, cfg.k, cfg.n, cfg.num_experts, cfg.top_k,
+                 cfg.num_local_experts, max_rows)
+    st = run([to_dev(x) for x in xs], to_dev(ids), to_dev(w_nk(w)), e0, cfg.rank, order=order)
+    assert st == B.OK, B.status_string(st)
+    torch.cuda.synchronize()
+    assert run.status.cpu().tolist()[0] == 0
+    st2, tc = B.tile_config(2, max_rows, cfg.n, cfg.k)
+    assert st2 == B.OK and tc["block_m"] == block_m
+    # integer results: bit-exact
+    count, offsets, gather = omoe.route(ids, cfg.world, cfg.num_experts, e0, cfg.num_local_experts)
+    R = int(offsets[-1])
+    assert np.array_equal(run.counts.cpu().numpy().reshape(cfg.world, cfg.num_experts), count)
+    assert np.array_equal(run.offsets.cpu().numpy(), offsets)
+    assert np.array_equal(run.gather.cpu().numpy()[:R], gather)
+    assert (run.gather.cpu().numpy()[R:] == -1).all()
+    sch = omoe.tile_schedule(count, e0, cfg.num_local_experts, block_m, cfg.rank, cfg.world)
+    rec = run.records.cpu().numpy()
+    assert rec[0] == sch["ntiles"]
+    got = rec[1:1 + 4 * sch["ntiles"]].reshape(-1, 4)
+    want = np.stack([sch["expert_id"], sch["tiled_m"], sch["segment_start"], sch["segment_end"]], axis=1) \
+        if sch["ntiles"] else np.zeros((0, 4), dtype=np.int64)
+    assert np.array_equal(got, want)
+    # gathered tokens landed in the workspace unchanged
+    assert np.array_equal(bits(run.workspace), np.concatenate(xs, axis=0))
+    # floating point
+    y = bits(run.y)
+    ref = omoe.grouped_gemm(xs, ids, w, cfg.world, cfg.num_experts, e0)
+    if integer:
+        assert np.array_equal(y[:R], formats.encode_bf16_rne(ref.astype(np.float32)))
+    else:
+        assert compare.max_row_rel_error(formats.decode_bf16(y[:R]), ref) <= TOL_BF16
+    assert (y[R:] == 0x7FC0).all()          # rows beyond R are not written
+    return run, R
+
+
+@pytest.mark.parametrize("world,t_r,hidden,inter,experts,top_k,local,rank,integer", [
+    (2, 64, 64, 128, 4, 2, 2, 1, True),
+    (4, 100, 72, 136, 12, 3, 3, 2, True),       # ragged hidden tail and width, odd expert counts
+    (8, 128, 256, 264, 64, 2, 8, 5, True),
+    (8, 128, 512, 384, 16, 2, 16, 3, False),    # every expert local (the paper's placement)
+    (1, 300, 64, 64, 3, 1, 3, 0, True),
+])
+def test_moe_end_to_end(B, world, t_r, hidden, inter, experts, top_k, local, rank, integer):
+    cfg = synth.CONFIGS[4].scaled(world=world, tokens_per_rank=t_r, k=hidden, n=inter, num_experts=experts,
+                                  top_k=top_k, num_local_experts=local, rank=rank)
+    xs, ids, w = synth.moe_inputs(cfg, integer=integer)
+    max_rows = world * t_r * top_k
+    order = None if rank % 2 else list(reversed(range(world)))
+    _run_and_check(B, cfg, xs, ids, w, max_rows, integer, order=order)
+
+
+def test_moe_degenerate_routings(B):
+    cfg = synth.CONFIGS[4].scaled(world=4, tokens_per_rank=96, k=64, n=128, num_experts=8, top_k=1,
+                                  num_local_experts=4, rank=1)
+    xs, _, w = synth.moe_inputs(cfg, integer=True)
+    # everything to one local expert; then nothing to any local expert
+    for target in (5, 0):
+        ids = np.full((4 * 96, 1), target, dtype=np.int32)
+        _run_and_check(B, cfg, xs, ids, w, 4 * 96, True)
+
+
+def test_moe_row_overflow_is_reported(B):
+    cfg = synth.CONFIGS[4].scaled(world=2, tokens_per_rank=64, k=64, n=128, num_experts=2, top_k=1,
+                                  num_local_experts=2, rank=0)
+    xs, ids, w = synth.moe_inputs(cfg, integer=True)
+    run = MoeRun(B, 2, 64, 64, 128, 2, 1, 2, max_rows=100)          # 128 rows are routed here
+    st = run([to_dev(x) for x in xs], to_dev(ids), to_dev(w_nk(w)), 0, 0)
+    assert st == B.OK
+    torch.cuda.synchronize()
+    s = run.status.cpu().tolist()
+    assert s[0] == B.ERR_WORKSPACE and s[2] == 128
+    assert (bits(run.y) == 0x7FC0).all()
+
+
+def test_cfg4_full_size(B):
+    cfg = synth.CONFIGS[4]
+    xs, ids, w = synth.moe_inputs(cfg)
+    run, R = _run_and_check(B, cfg, xs, ids, w, max_rows=4096, integer=False)
+    assert 1500 < R < 2600
