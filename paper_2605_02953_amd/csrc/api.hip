@@ -41,8 +41,9 @@ extern "C" size_t ditron_signal_words(int world, int chunks) {
 
 extern "C" ditron_status_t ditron_tile_config(int op, int m, int n, int k, int dtype, int out[8]) {
   if (!out || m <= 0 || n <= 0 || k <= 0 || op < 0 || op > 2) return DITRON_ERR_INVALID_ARG;
-  if (dtype != DITRON_BF16) return DITRON_ERR_UNSUPPORTED;
-  TileChoice t = choose_tile(m, n, k);
+  if (dtype != DITRON_BF16 && dtype != DITRON_FP8_E4M3) return DITRON_ERR_INVALID_ARG;
+  if (dtype == DITRON_FP8_E4M3 && op != 0) return DITRON_ERR_UNSUPPORTED;
+  TileChoice t = dtype == DITRON_FP8_E4M3 ? choose_tile_fp8(m, n, k) : choose_tile(m, n, k);
   if (op == 2) {  // the grouped GEMM always uses the small tile; m is max_rows
     t.big = false;
     t.block_m = t.block_n = TileSmall::BM;
@@ -94,11 +95,4 @@ extern "C" ditron_status_t ditron_publish_chunks(void* const* dst, const void* c
   p.delay_cycles = delay_cycles;
   hipLaunchKernelGGL(publish_chunks_kernel, dim3(1), dim3(1024), 0, (hipStream_t)stream, p);
   return hipGetLastError() == hipSuccess ? DITRON_OK : DITRON_ERR_HIP;
-}
-
-// Placeholders until the operators land.
-extern "C" ditron_status_t ditron_ag_gemm_fp8(const void* const*, const void*, int, void*, const float*, const float*,
-                                              void*, int32_t*, int32_t*, int32_t*, const int*, int, int, int, int, int,
-                                              int32_t, unsigned, void*) {
-  return DITRON_ERR_UNSUPPORTED;
 }

@@ -35,6 +35,20 @@ inline TileChoice choose_tile(int m, int n, int /*k*/) {
   return t;
 }
 
+// fp8 path: one tile shape, 128 rows x 32 columns, 4 waves.
+inline TileChoice choose_tile_fp8(int /*m*/, int /*n*/, int /*k*/) {
+  TileChoice t{};
+  t.big = false;
+  t.block_m = 128;
+  t.block_n = 32;
+  t.threads = 256;
+  t.group_m = 4;
+  t.num_xcd = 8;
+  t.per_xcd = 32;
+  t.producers = 8;
+  return t;
+}
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 inline bool is_permutation(const int* v, int n) {
