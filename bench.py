@@ -115,6 +115,208 @@ def bench_ag_gemm(args, cfg_id):
     return out
 
 
+def _events(torch, n):
+    return [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+
+
+def _timed(torch, args, step):
+    """W warm-up steps, then K timed steps with events around each; returns (ms per step by the
+    host clock around the whole region, mean ms between the per-step events)."""
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = _events(torch, args.steps)
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        ev[i][0].record()
+        step()
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return wall * 1e3 / args.steps, sum(a.elapsed_time(b) for a, b in ev) / args.steps
+
+
+def bench_gemm_rs(args):
+    import torch
+    import synth
+    from paper_2605_02953_amd import binding as B
+    from gpu_util import to_dev, nk, GemmRsRun
+
+    cfg = synth.CONFIGS[3]
+    d, m_r = cfg.rank, cfg.m_per_rank
+    a_list, b_list = synth.gemm_rs_inputs(cfg)
+    run = GemmRsRun(B, cfg.world, cfg.m, cfg.n, cfg.k, chunks=4)
+    zero = torch.zeros((m_r, cfg.n), dtype=torch.int16, device="cuda")
+    # the blocks the peers would send: their own partial products' rows for this rank
+    peers = []
+    for s in range(cfg.world):
+        if s == d:
+            peers.append(zero)
+            continue
+        st = run(to_dev(a_list[s]), to_dev(nk(b_list[s])), [zero] * cfg.world, s)
+        assert st == B.OK
+        torch.cuda.synchronize()
+        peers.append(run.gemm_out[d * m_r:(d + 1) * m_r].clone())
+    ad, bd = to_dev(a_list[d]), to_dev(nk(b_list[d]))
+
+    def step():
+        st = run(ad, bd, peers, d)
+        if st != B.OK:
+            raise RuntimeError(B.status_string(st))
+
+    ms_per_step, ev_ms = _timed(torch, args, step)
+    if run.status.cpu().tolist()[0] != 0:
+        raise RuntimeError("kernel reported a signal time-out")
+    flops = 2.0 * cfg.m * cfg.n * cfg.k
+
+    # the reduction alone on buffer sets that rotate through more than the 256 MB last-level cache
+    nsets = 4
+    sets = [[torch.randint(-30000, 30000, (m_r, cfg.n), dtype=torch.int16, device="cuda") for _ in range(cfg.world)]
+            for _ in range(nsets)]
+    outs = [torch.empty((m_r, cfg.n), dtype=torch.int16, device="cuda") for _ in range(nsets)]
+    status = torch.zeros(B.STATUS_WORDS, dtype=torch.int32, device="cuda")
+    for i in range(2 * nsets):
+        B.reduce_slots(sets[i % nsets], outs[i % nsets], None, status, m_r, cfg.n, cfg.world, 1, 1)
+    torch.cuda.synchronize()
+    nrep = 40
+    ev = _events(torch, nrep)
+    for i in range(nrep):
+        ev[i][0].record()
+        B.reduce_slots(sets[i % nsets], outs[i % nsets], None, status, m_r, cfg.n, cfg.world, 1, 1)
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    red_ms = sum(a.elapsed_time(b) for a, b in ev) / nrep
+    red_bytes = (cfg.world + 1) * m_r * cfg.n * 2
+    red_gbs = red_bytes / (red_ms * 1e-3) / 1e9
+
+    achieved = flops / (ev_ms * 1e-3) / 1e12
+    out = {
+        "metric": "TFLOP/s of one rank's GEMM-ReduceScatter share (GEMM + emulated peer arrival + reduction)",
+        "value": flops / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"cfg3: GEMM-RS world={cfg.world} rank={d} A [{cfg.m},{cfg.k}] B [{cfg.k},{cfg.n}] stored [n,k], "
+                               f"7 peer blocks [{m_r},{cfg.n}] bf16, 4 row chunks per block", "latency_us": ev_ms * 1e3},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": MEASURED_TRAFFIC.get("cfg3"),
+                     "kernel": "gemm_rs_kernel + reduce_slots_kernel (whole step between events)", "kernel_ms": ev_ms},
+        "reduction": {"bound": "hbm", "achieved": red_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                      "frac": red_gbs / PEAK_HBM_GBS, "us": red_ms * 1e3, "bytes": red_bytes,
+                      "note": "reduce_slots_kernel alone, 4 rotating buffer sets (604 MB) so the 256 MB cache cannot hold them"},
+    }
+    if not args.no_cpu:
+        from oracle import gemm_rs as ors
+        t0 = time.perf_counter()
+        ors.gemm_rs(a_list, b_list, d)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": flops / dt / 1e12, "unit": "TFLOP/s",
+                               "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count())), "kind": "oracle",
+                               "seconds": dt, "sample": "the rank's whole output block (sum over 8 ranks of [1024,3584].[3584,8192] in fp64)"}
+    return out
+
+
+def bench_moe(args):
+    import torch
+    import synth
+    from paper_2605_02953_amd import binding as B
+    from gpu_util import to_dev, MoeRun
+
+    cfg = synth.CONFIGS[4]
+    xs, ids, w = synth.moe_inputs(cfg)
+    e0 = cfg.rank * cfg.num_local_experts
+    max_rows = 4096
+    run = MoeRun(B, cfg.world, cfg.tokens_per_rank, cfg.k, cfg.n, cfg.num_experts, cfg.top_k, cfg.num_local_experts, max_rows)
+    xd = [to_dev(x) for x in xs]
+    idd = to_dev(ids)
+    wd = to_dev(np.ascontiguousarray(np.transpose(w, (0, 2, 1))))
+
+    def step():
+        st = run(xd, idd, wd, e0, cfg.rank)
+        if st != B.OK:
+            raise RuntimeError(B.status_string(st))
+
+    ms_per_step, ev_ms = _timed(torch, args, step)
+    if run.status.cpu().tolist()[0] != 0:
+        raise RuntimeError("kernel reported an error")
+    R = int(run.offsets.cpu()[-1])
+    flops = 2.0 * R * cfg.k * cfg.n
+    w_bytes = w.size * 2
+    alg_bytes = w_bytes + R * cfg.k * 2 + R * cfg.n * 2
+    gbs = alg_bytes / (ev_ms * 1e-3) / 1e9
+    out = {
+        "metric": "TFLOP/s of one rank's MoE AllGather + grouped GEMM share (route + schedule + gather + GEMM)",
+        "value": flops / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"cfg4: MoE world={cfg.world} rank={cfg.rank} tokens 8x{cfg.tokens_per_rank} hidden {cfg.k} inter {cfg.n} "
+                               f"{cfg.num_experts} experts top-{cfg.top_k}, {cfg.num_local_experts} local, R={R}", "latency_us": ev_ms * 1e3},
+        "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
+                     "traffic": MEASURED_TRAFFIC.get("cfg4"),
+                     "kernel": "moe_route_kernel + moe_grouped_gemm_kernel (whole step between events)", "kernel_ms": ev_ms,
+                     "bytes": alg_bytes},
+    }
+    if not args.no_cpu:
+        from oracle import moe as omoe
+        t0 = time.perf_counter()
+        omoe.grouped_gemm(xs, ids, w, cfg.world, cfg.num_experts, e0)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": flops / dt / 1e12, "unit": "TFLOP/s",
+                               "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count())), "kind": "oracle",
+                               "seconds": dt, "sample": "the whole workload (route in Python loops + fp64 grouped GEMM)"}
+    return out
+
+
+def bench_fp8(args):
+    import torch
+    import synth
+    from paper_2605_02953_amd import binding as B
+    from gpu_util import to_dev, nk, AgGemmRun
+
+    cfg = synth.CONFIGS[5]
+    a, sa, b, sb = synth.fp8_ag_gemm_inputs(cfg)
+    ad = [to_dev(x) for x in a]
+    # rotate the weight matrix through several copies so it is streamed from HBM, not from cache
+    nsets = 5
+    bds = [to_dev(nk(b)) for _ in range(nsets)]
+    sad, sbd = to_dev(sa), to_dev(sb)
+    run = AgGemmRun(B, cfg.world, cfg.m_per_rank, cfg.n, cfg.k, esize=1)
+    it = [0]
+
+    def step():
+        it[0] += 1
+        st = run(ad, bds[it[0] % nsets], cfg.rank, dtype=B.FP8_E4M3, a_scales=sad, b_scales=sbd)
+        if st != B.OK:
+            raise RuntimeError(B.status_string(st))
+
+    ms_per_step, ev_ms = _timed(torch, args, step)
+    if run.status.cpu().tolist()[0] != 0:
+        raise RuntimeError("kernel reported a signal time-out")
+    flops = 2.0 * cfg.m * cfg.n * cfg.k
+    alg_bytes = cfg.k * cfg.n + cfg.m * cfg.k + cfg.m * cfg.n * 2
+    gbs = alg_bytes / (ev_ms * 1e-3) / 1e9
+    out = {
+        "metric": "latency (us) of one rank's decode-shaped fp8 AllGather-GEMM share",
+        "value": ms_per_step * 1e3, "unit": "us",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "fp8_e4m3", "data": "synthetic",
+        "config": {"workload": f"cfg5: fp8 AG-GEMM world={cfg.world} A 8x[{cfg.m_per_rank},{cfg.k}] B [{cfg.k},{cfg.n}] stored [n,k] "
+                               f"-> C [{cfg.m},{cfg.n}] bf16; weights rotated over {nsets} copies", "latency_us": ev_ms * 1e3,
+                   "tflops": flops / (ev_ms * 1e-3) / 1e12},
+        "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
+                     "traffic": MEASURED_TRAFFIC.get("cfg5"), "kernel": "ag_gemm_fp8_kernel", "kernel_ms": ev_ms,
+                     "bytes": alg_bytes},
+    }
+    if not args.no_cpu:
+        from oracle import ag_gemm as oag
+        t0 = time.perf_counter()
+        oag.ag_gemm(a, b, dtype="e4m3", a_scales=sa, b_scales=sb)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": dt * 1e6, "unit": "us",
+                               "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count())), "kind": "oracle",
+                               "seconds": dt, "sample": "the whole workload (table decode + fp64 GEMM)"}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -128,6 +330,12 @@ def main():
         sys.exit(2)
     if args.workload in ("cfg1", "cfg2"):
         out = bench_ag_gemm(args, int(args.workload[3:]))
+    elif args.workload == "cfg3":
+        out = bench_gemm_rs(args)
+    elif args.workload == "cfg4":
+        out = bench_moe(args)
+    elif args.workload == "cfg5":
+        out = bench_fp8(args)
     else:
         print(f"bench.py: unknown workload {args.workload}", file=sys.stderr)
         sys.exit(2)

@@ -1,0 +1,106 @@
+"""CPU-side checks of the C ABI: the library loads, exports every function the header
+declares, and rejects bad arguments before touching a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "ditron.h")
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2605_02953_amd import binding
+    return binding
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ditron_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(B):
+    names = _declared_functions()
+    assert {"ditron_ag_gemm", "ditron_gemm_rs", "ditron_moe_ag_grouped_gemm", "ditron_reduce_slots",
+            "ditron_publish_chunks", "ditron_tile_config", "ditron_signal_words"} <= set(names)
+    for n in names:
+        assert hasattr(B.lib, n), n
+
+
+def test_sizes_and_strings(B):
+    assert B.signal_words(8, 1) == 32 and B.signal_words(8, 4) == 80 and B.signal_words(0, 1) == 0
+    assert B.status_string(B.OK) == "ok" and "time" in B.status_string(B.ERR_TIMEOUT)
+    assert B.moe_max_tiles(4096, 8) == 4096 // 128 + 8
+
+
+def test_tile_config(B):
+    st, tc = B.tile_config(0, 8192, 3584, 8192)
+    assert st == B.OK and (tc["block_m"], tc["block_n"], tc["ntiles"], tc["threads"]) == (256, 256, 448, 512)
+    st, tc = B.tile_config(0, 256, 256, 256)
+    assert st == B.OK and (tc["block_m"], tc["ntiles"]) == (128, 4)
+    st, tc = B.tile_config(0, 128, 8192, 8192, B.FP8_E4M3)
+    assert st == B.OK and (tc["block_m"], tc["block_n"], tc["ntiles"]) == (128, 32, 256)
+    assert B.tile_config(7, 1, 1, 1)[0] == B.ERR_INVALID_ARG
+
+
+def test_ag_gemm_argument_checks(B):
+    null = None
+    fake = 0x1000          # never dereferenced: the checks fail first
+    args = dict(a_shards=[fake, fake], b=fake, b_layout=B.B_NK, c=fake, a_scales=null, b_scales=null,
+                workspace=fake, signals=fake, status=fake, schedule_out=null, arrival_order=null,
+                m_per_rank=128, n=256, k=256, world=2, rank=0, dtype=B.BF16, epoch=1,
+                flags=B.EMULATE_PRODUCER, stream=ctypes.c_void_p(0))
+
+    def call(**kw):
+        a = dict(args)
+        a.update(kw)
+        s = a.pop("stream")
+        return B.lib.ditron_ag_gemm(B._ptr_array(a["a_shards"]), B._ptr(a["b"]), a["b_layout"], B._ptr(a["c"]),
+                                    None, None, B._ptr(a["workspace"]), B._ptr(a["signals"]), B._ptr(a["status"]),
+                                    B._ptr(a["schedule_out"]), B._int_array(a["arrival_order"]), a["m_per_rank"],
+                                    a["n"], a["k"], a["world"], a["rank"], a["dtype"], a["epoch"], a["flags"], s)
+
+    assert call(world=0) == B.ERR_INVALID_ARG
+    assert call(world=B.MAX_WORLD + 1, a_shards=[fake] * 40) == B.ERR_INVALID_ARG
+    assert call(rank=2) == B.ERR_INVALID_ARG
+    assert call(k=0) == B.ERR_INVALID_ARG
+    assert call(b=null) == B.ERR_INVALID_ARG
+    assert call(c=0x1008) == B.ERR_INVALID_ARG                       # misaligned
+    assert call(flags=0) == B.ERR_INVALID_ARG                        # no producer mode
+    assert call(flags=B.EMULATE_PRODUCER | B.EXTERNAL_PRODUCER) == B.ERR_INVALID_ARG
+    assert call(flags=B.EMULATE_PRODUCER | B.DUMP_SCHEDULE) == B.ERR_INVALID_ARG   # no schedule buffer
+    assert call(arrival_order=[0, 0]) == B.ERR_INVALID_ARG           # not a permutation
+    assert call(a_shards=[fake, None]) == B.ERR_INVALID_ARG
+    assert call(dtype=9) == B.ERR_INVALID_ARG
+    assert call(b_layout=B.B_KN) == B.ERR_UNSUPPORTED
+    assert call(k=260) == B.ERR_UNSUPPORTED                          # contraction not a multiple of 8
+
+
+def test_gemm_rs_and_moe_argument_checks(B):
+    fake = 0x1000
+    z = ctypes.c_void_p(0)
+    st = B.lib.ditron_gemm_rs(B._ptr(fake), B._ptr(fake), B.B_NK, B._ptr(fake), None, B._ptr(fake), B._ptr(fake),
+                              B._ptr(fake), B._ptr(fake), None, None, 1000, 256, 64, 8, 0, 1, 1,
+                              B.EMULATE_PRODUCER, z)
+    assert st == B.ERR_INVALID_ARG          # m not divisible by world
+    st = B.lib.ditron_gemm_rs(B._ptr(fake), B._ptr(fake), B.B_NK, B._ptr(fake), None, B._ptr(fake), B._ptr(fake),
+                              B._ptr(fake), B._ptr(fake), None, None, 1024, 256, 64, 8, 0, 3, 1,
+                              B.EMULATE_PRODUCER, z)
+    assert st == B.ERR_INVALID_ARG          # chunks do not divide the rows per rank
+    st = B.lib.ditron_reduce_slots(None, B._ptr(fake), None, None, 8, 8, 2, 1, 1, z)
+    assert st == B.ERR_INVALID_ARG
+    st = B.moe_ag_grouped_gemm([fake] * 8, fake, fake, B.B_NK, fake, fake, fake, fake, fake, fake, fake, fake, None,
+                               1024, 4096, 1536, 64, 2, 60, 8, 4096, 8, 0, 1, B.EMULATE_PRODUCER, stream=_S())
+    assert st == B.ERR_INVALID_ARG          # local experts run past the expert count
+    st = B.moe_ag_grouped_gemm([fake] * 8, fake, fake, B.B_NK, fake, fake, fake, fake, fake, fake, fake, fake, None,
+                               1024, 4096, 1536, 512, 2, 0, 8, 4096, 8, 0, 1, B.EMULATE_PRODUCER, stream=_S())
+    assert st == B.ERR_UNSUPPORTED          # more experts than the routing kernel holds
+    st = B.publish_chunks([fake], [fake], [24], [0], fake, 1, stream=_S())
+    assert st == B.ERR_INVALID_ARG          # size not a multiple of 16
+
+
+class _S:
+    cuda_stream = 0
