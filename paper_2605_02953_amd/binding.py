@@ -8,7 +8,8 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libditron.so")
+# DITRON_LIB lets a developer point at another build of the same library (e.g. a tuning variant)
+LIB_PATH = os.environ.get("DITRON_LIB") or os.path.join(_HERE, "libditron.so")
 
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_TIMEOUT = range(6)
 BF16, FP8_E4M3 = 0, 1

@@ -59,14 +59,12 @@ __global__ __launch_bounds__(T::THREADS) void ag_gemm_kernel(const AgGemmParams 
   }
   flag_wait_block(p.flags, rank_beg, rank_end - rank_beg + 1, p.epoch, p.spin_limit, p.status);
 
-  const size_t row_bytes = (size_t)p.k * 2;
-  const char* a_tile = p.workspace;
-  const char* b_tile = p.b;
+  const uint32_t row_bytes = (uint32_t)p.k * 2u;
   const int M = p.m, N = p.n;
-  auto a_row = [=](int r) { return a_tile + (size_t)min(m0 + r, M - 1) * row_bytes; };
-  auto b_row = [=](int r) { return b_tile + (size_t)min(n0 + r, N - 1) * row_bytes; };
+  auto a_row = [=](int r) { return (uint32_t)min(m0 + r, M - 1) * row_bytes; };
+  auto b_row = [=](int r) { return (uint32_t)min(n0 + r, N - 1) * row_bytes; };
   f32x16_t acc[T::NI][T::MI];
-  gemm_mainloop<T>(acc, a_row, b_row, p.k, lds);
+  gemm_mainloop<T>(acc, p.workspace, a_row, p.b, b_row, p.k, lds);
   store_tile_bf16<T>(acc, p.c, (size_t)p.n, m0, n0, M, N, p.a_scales, p.m_per_rank, p.b_scales);
 }
 
@@ -110,6 +108,7 @@ extern "C" ditron_status_t ditron_ag_gemm(const void* const* a_shards, const voi
                                                           schedule_out, arrival_order, m_per_rank, n, k, world, rank, epoch, flags, stream);
   if (b_layout != DITRON_B_NK) return DITRON_ERR_UNSUPPORTED;
   if (k % 8 != 0 || n % 8 != 0) return DITRON_ERR_UNSUPPORTED;
+  if (!fits_32bit((size_t)m_per_rank * world, k, 2) || !fits_32bit(n, k, 2)) return DITRON_ERR_UNSUPPORTED;
 
   AgGemmParams p{};
   for (int i = 0; i < world; ++i) {

@@ -43,13 +43,6 @@ struct AgGemmFp8Params {
   int group_m, num_xcd, per_xcd, npm, npn;
 };
 
-__device__ __forceinline__ void barrier_no_drain() {
-  // all waves arrive; outstanding direct-to-LDS loads are deliberately left in flight
-  asm volatile("" ::: "memory");
-  __builtin_amdgcn_s_barrier();
-  asm volatile("" ::: "memory");
-}
-
 __global__ __launch_bounds__(Fp8Tile::THREADS) void ag_gemm_fp8_kernel(const AgGemmFp8Params p) {
   typedef Fp8Tile T;
   extern __shared__ __attribute__((aligned(1024))) char lds[];
@@ -87,12 +80,12 @@ __global__ __launch_bounds__(Fp8Tile::THREADS) void ag_gemm_fp8_kernel(const AgG
 #pragma unroll
   for (int i = 0; i < T::A_LOADS; ++i) {
     const int r = (wave * T::A_LOADS + i) * 8 + (lane >> 3);
-    const int c = (lane & 7) ^ swz(r);
+    const int c = (lane & 7) ^ swz128(r);
     a_kc[i] = c * 16;
     a_ptr[i] = p.workspace + (size_t)min(m0 + r, p.m - 1) * K + c * 16;
   }
   const int rb = wave * 8 + (lane >> 3);
-  const int cb = (lane & 7) ^ swz(rb);
+  const int cb = (lane & 7) ^ swz128(rb);
   const int b_kc = cb * 16;
   const char* b_ptr = p.b + (size_t)min(n0 + rb, p.n - 1) * K + cb * 16;
 
@@ -137,7 +130,7 @@ __global__ __launch_bounds__(Fp8Tile::THREADS) void ag_gemm_fp8_kernel(const AgG
     for (int mb = 0; mb < 2; ++mb) acc[nb][mb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
   const int l16 = lane & 15, g = lane >> 4;
-  const int sw = swz(l16);
+  const int sw = swz128(l16);
   const int off0 = ((2 * g) ^ sw) * 16, off1 = ((2 * g + 1) ^ sw) * 16;
 
 #pragma unroll 1

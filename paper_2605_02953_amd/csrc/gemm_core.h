@@ -1,10 +1,9 @@
 // bf16 MFMA tile engine for gfx950: C_tile[BM,BN] (fp32) += A_tile[BM,K] . B_tile[BN,K]^T.
 //
 // Both operands are read as rows that are contiguous along the contraction dimension.
-// A K-slice of BK=64 elements of BM + BN rows is staged in LDS as 128-byte rows whose eight
-// 16-byte chunks are XOR-swizzled by the row index; the staging uses the direct
-// global->LDS load (each wave writes 1 KiB = 8 consecutive rows per instruction, the
-// swizzle is applied on the global-address side).  Each wave owns a WTM x WTN sub-tile and
+// A K-slice of BK=64 elements of BM + BN rows is staged in LDS as 128-byte rows (one cache
+// line per row) whose eight 16-byte chunks are XOR-swizzled by the row index; the staging
+// uses the direct global->LDS load, which needs no registers.  Each wave owns a WTM x WTN sub-tile and
 // feeds v_mfma_f32_32x32x16_bf16 from 128-bit LDS reads.  The instruction's row operand is
 // taken from the B rows and its column operand from the A rows, so that a lane ends up with
 // four consecutive output columns of one output row (an 8-byte bf16 store).
@@ -17,107 +16,179 @@ namespace ditron {
 // stage these instead (the direct-to-LDS load has no per-lane zero fill).
 __device__ const u32x4_t kZeroChunk = {0u, 0u, 0u, 0u};
 
-template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, int NSTAGE_ = 2>
+template <int BM_, int BN_, int WAVES_M_, int WAVES_N_>
 struct GemmTile {
-  static constexpr int BM = BM_, BN = BN_, BK = 64, NSTAGE = NSTAGE_;
+  static constexpr int BM = BM_, BN = BN_, BK = 64, NSTAGE = 2;
   static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
   static constexpr int NWAVES = WAVES_M * WAVES_N, THREADS = 64 * NWAVES;
   static constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
   static constexpr int MI = WTM / 32, NI = WTN / 32;
-  static constexpr int ROW_BYTES = 128;                 // BK bf16
-  static constexpr int ROWS_PER_LOAD = 8;               // rows written by one wave-wide load
-  static constexpr int A_LOADS = BM / ROWS_PER_LOAD / NWAVES;
-  static constexpr int B_LOADS = BN / ROWS_PER_LOAD / NWAVES;
-  static constexpr int LOADS = A_LOADS + B_LOADS;
+  static constexpr int KS = BK / 16;                    // MFMA steps per K tile
+  static constexpr int ROW_BYTES = 128;                 // BK bf16 = one cache line per row per K tile
+  static constexpr int ROWS_PER_LOAD = 8;               // rows written by one wave-wide 1 KiB load
+  // the four waves of the first group stage the A rows, the four of the second group the B rows
+  static constexpr int A_LOADS = BM / ROWS_PER_LOAD / 4;
+  static constexpr int B_LOADS = BN / ROWS_PER_LOAD / 4;
   static constexpr int A_BYTES = BM * ROW_BYTES, B_BYTES = BN * ROW_BYTES;
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
   static constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
+  static_assert(NWAVES == 8, "two groups of four waves (one wave of each group per SIMD)");
+  static_assert(BM == BN, "both groups issue the same number of loads");
   static_assert(BM % (32 * WAVES_M) == 0 && BN % (32 * WAVES_N) == 0, "wave tile must be 32-aligned");
-  static_assert(BM % (ROWS_PER_LOAD * NWAVES) == 0 && BN % (ROWS_PER_LOAD * NWAVES) == 0, "load split");
+  static_assert(A_LOADS <= 15, "wait counts are 4-bit immediates");
 };
 
-// Chunk swizzle: the 16-byte chunk c of LDS row r is stored at chunk position c ^ swz(r).
-// Conflict-free for 128-bit reads of 8 or 16 consecutive rows at one logical chunk.
-__device__ __forceinline__ int swz(int r) { return (r & 7) ^ ((r >> 3) & 1); }
+// Chunk swizzle for 128-byte LDS rows (eight 16-byte chunks): chunk c of row r is stored at
+// chunk position c ^ swz128(r).  Makes 128-bit reads of 8 or of 16 consecutive rows at one
+// logical chunk hit distinct banks; invariant under adding a multiple of 16 rows.
+__device__ __forceinline__ int swz128(int r) { return (r & 7) ^ ((r >> 3) & 1); }
 
-__device__ __forceinline__ void wait_vmcnt0() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+// The explicit waits are pinned in place: the scheduler must not move matrix instructions
+// behind them (a wave blocked in a wait issues nothing).
+__device__ __forceinline__ void wait_vmcnt0() {
+  __builtin_amdgcn_sched_barrier(0);
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+  __builtin_amdgcn_sched_barrier(0);
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N <= 15, "vmcnt immediate");
+  __builtin_amdgcn_sched_barrier(0);
+  __builtin_amdgcn_s_waitcnt(0x0F70 | N);
+  __builtin_amdgcn_sched_barrier(0);
+}
+__device__ __forceinline__ void wait_lgkmcnt0() {
+  __builtin_amdgcn_sched_barrier(0);
+  __builtin_amdgcn_s_waitcnt(0xC07F);
+  __builtin_amdgcn_sched_barrier(0);
+}
 
-template <class T>
-struct TileLoader {
-  const char* ptr[T::LOADS];  // this lane's source address for K tile 0, per load instruction
-  int kc[T::LOADS];           // element offset of the lane's chunk inside a K tile
+// Work-group barrier that leaves outstanding global loads in flight (the plain
+// __syncthreads() drains them).  The empty asm statements stop the compiler from moving
+// memory accesses across it; sched_barrier keeps the instruction scheduler from moving
+// anything else (the phases of the two wave groups must not be blended).
+__device__ __forceinline__ void barrier_no_drain() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_sched_barrier(0);
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_sched_barrier(0);
+  asm volatile("" ::: "memory");
+}
 
-  // a_row(r) / b_row(r): start of tile-local row r (already clamped to a valid row).
-  template <class ARow, class BRow>
-  __device__ __forceinline__ void init(ARow a_row, BRow b_row) {
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+// Direct global -> LDS staging of one operand's rows of a K tile by a group of four waves.
+// A wave-wide load writes 1 KiB = 8 rows x 128 B; the LDS side of that write is fixed
+// (lane i writes bytes [16 i, 16 i + 16)), so the row swizzle is applied on the global side:
+// the lane that fills chunk position p of row r fetches chunk p ^ swz128(r).
+template <int NLOADS>
+struct HalfLoader {
+  const char* base;           // operand base address (uniform)
+  uint32_t off[NLOADS];       // this lane's byte offset from `base` for K tile 0, per load instruction
+  int wave4;                  // wave index inside the group
+
+  // row(r): byte offset (from `base_`) of the start of tile-local row r, already clamped to a valid row
+  template <class Row>
+  __device__ __forceinline__ void init(const char* base_, Row row, int wave_in_group) {
+    const int lane = threadIdx.x & 63;
+    base = base_;
+    wave4 = wave_in_group;
 #pragma unroll
-    for (int i = 0; i < T::A_LOADS; ++i) {
-      const int r = (wave * T::A_LOADS + i) * T::ROWS_PER_LOAD + (lane >> 3);
-      const int c = (lane & 7) ^ swz(r);
-      kc[i] = c * 8;
-      ptr[i] = a_row(r) + c * 16;
-    }
-#pragma unroll
-    for (int i = 0; i < T::B_LOADS; ++i) {
-      const int r = (wave * T::B_LOADS + i) * T::ROWS_PER_LOAD + (lane >> 3);
-      const int c = (lane & 7) ^ swz(r);
-      kc[T::A_LOADS + i] = c * 8;
-      ptr[T::A_LOADS + i] = b_row(r) + c * 16;
+    for (int i = 0; i < NLOADS; ++i) {
+      const int r = (wave_in_group * NLOADS + i) * 8 + (lane >> 3);
+      const int c = (lane & 7) ^ swz128(r);
+      off[i] = row(r) + (uint32_t)(c * 16);
     }
   }
 
-  // Start the loads of K tile `kt` into the LDS stage at `stage`.
+  // Start this group's loads of K tile `kt` into the operand area at `dst` of an LDS stage.
   template <bool PARTIAL>
-  __device__ __forceinline__ void issue(char* stage, int kt, int K) const {
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  __device__ __forceinline__ void issue(char* dst, int kt, int K) const {
+    const int lane = threadIdx.x & 63;
+    const char* tile_base = base + (size_t)kt * 128;
+    // keep the uniform part of the address in scalar registers: the loads then take the form
+    // "scalar base + 32-bit lane offset" and no 64-bit per-lane addresses have to be kept alive
+    asm volatile("" : "+s"(tile_base));
 #pragma unroll
-    for (int i = 0; i < T::LOADS; ++i) {
-      const char* src = ptr[i] + (size_t)kt * T::ROW_BYTES;
+    for (int i = 0; i < NLOADS; ++i) {
+      const char* src = tile_base + off[i];
       if (PARTIAL) {
-        if (kt * T::BK + kc[i] >= K) src = (const char*)&kZeroChunk;
+        const int r = (wave4 * NLOADS + i) * 8 + (lane >> 3);
+        const int c = (lane & 7) ^ swz128(r);
+        if (kt * 64 + c * 8 >= K) src = (const char*)&kZeroChunk;
       }
-      char* dst = (i < T::A_LOADS)
-                      ? stage + (wave * T::A_LOADS + i) * 1024
-                      : stage + T::A_BYTES + (wave * T::B_LOADS + (i - T::A_LOADS)) * 1024;
-      __builtin_amdgcn_global_load_lds(src, DITRON_LDS(dst), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(src, DITRON_LDS(dst + (wave4 * NLOADS + i) * 1024), 16, 0, 0);
     }
   }
 };
 
-// One K tile of MFMA work for the calling wave.  acc[ni][mi] is the 32x32 block whose
-// instruction rows are B rows wn*WTN + ni*32.. and instruction columns A rows wm*WTM + mi*32...
+// All operand fragments of one K tile for the calling wave (KS steps of 16).
 template <class T>
-__device__ __forceinline__ void mma_stage(f32x16_t (&acc)[T::NI][T::MI], const char* stage, int wm, int wn) {
-  const int lane = threadIdx.x & 63;
-  const int lr = lane & 31, lh = lane >> 5;
-  const char* a_base = stage + (wm * T::WTM + lr) * T::ROW_BYTES;
-  const char* b_base = stage + T::A_BYTES + (wn * T::WTN + lr) * T::ROW_BYTES;
-  const int sw = swz(lr);  // tile bases are multiples of 32, so the swizzle depends on lr only
+struct Frags {
+  bf16x8_t a[T::KS][T::MI];
+  bf16x8_t b[T::KS][T::NI];
+};
+
+template <class T>
+__device__ __forceinline__ void load_frags(Frags<T>& f, const char* stage, int a_off, int b_off, int sw, int lh) {
 #pragma unroll
-  for (int ks = 0; ks < T::BK / 16; ++ks) {
+  for (int ks = 0; ks < T::KS; ++ks) {
     const int off = ((ks * 2 + lh) ^ sw) * 16;
-    bf16x8_t af[T::MI], bfr[T::NI];
 #pragma unroll
-    for (int ni = 0; ni < T::NI; ++ni) bfr[ni] = *(const bf16x8_t*)(b_base + ni * 32 * T::ROW_BYTES + off);
+    for (int ni = 0; ni < T::NI; ++ni) f.b[ks][ni] = *(const bf16x8_t*)(stage + b_off + ni * 32 * T::ROW_BYTES + off);
 #pragma unroll
-    for (int mi = 0; mi < T::MI; ++mi) af[mi] = *(const bf16x8_t*)(a_base + mi * 32 * T::ROW_BYTES + off);
+    for (int mi = 0; mi < T::MI; ++mi) f.a[ks][mi] = *(const bf16x8_t*)(stage + a_off + mi * 32 * T::ROW_BYTES + off);
+  }
+}
+
+// acc[ni][mi] is the 32x32 block whose instruction rows are B rows wn*WTN + ni*32.. and whose
+// instruction columns are A rows wm*WTM + mi*32...
+template <class T>
+__device__ __forceinline__ void mma_tile(f32x16_t (&acc)[T::NI][T::MI], const Frags<T>& f) {
+#pragma unroll
+  for (int ks = 0; ks < T::KS; ++ks)
 #pragma unroll
     for (int ni = 0; ni < T::NI; ++ni)
 #pragma unroll
       for (int mi = 0; mi < T::MI; ++mi)
-        acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ni], af[mi], acc[ni][mi], 0, 0, 0);
-  }
+        acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[ks][ni], f.a[ks][mi], acc[ni][mi], 0, 0, 0);
+}
+
+// Which WTM x WTN sub-tile of the output tile a wave owns.  Waves w and w+4 (same SIMD, one
+// of each group) get neighbouring sub-tiles.
+template <class T>
+__device__ __forceinline__ void wave_subtile(int& wm, int& wn) {
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wt = (wave & 3) * 2 + (wave >> 2);
+  wm = wt / T::WAVES_N;
+  wn = wt % T::WAVES_N;
 }
 
 // Full contraction for one output tile.  K must be a multiple of 8; the last K tile may be
 // partial.  `lds` is T::LDS_BYTES of dynamic shared memory.
+//
+// Ping-pong schedule.  The eight waves form two groups of four; waves w and w+4 share a SIMD.
+// Time is cut into phases separated by work-group barriers.  In every phase one group
+// multiplies a whole K tile out of registers (its MFMAs issue back to back, nothing to wait
+// for) while the other group fetches the fragments of its next K tile from LDS; at the
+// barrier they swap.  So each SIMD always has exactly one wave feeding the matrix pipe and the
+// barrier itself costs no matrix time.  K tiles live in two LDS stages filled by direct
+// global -> LDS loads: group 0 loads the A rows, group 1 the B rows, each issuing the loads of
+// tile kt+2 right after the barrier that retires tile kt, two phases before they are needed.
+//
+// a_base / b_base are the operands' base addresses; a_row(r) / b_row(r) give the byte offset of
+// tile-local row r from its base (32 bits: an operand must be smaller than 4 GiB).
 template <class T, class ARow, class BRow>
-__device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[T::NI][T::MI], ARow a_row, BRow b_row, int K,
-                                              char* lds) {
-  static_assert(T::NSTAGE == 2, "two LDS stages");
-  const int wave = threadIdx.x >> 6;
-  const int wm = wave / T::WAVES_N, wn = wave % T::WAVES_N;
+__device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[T::NI][T::MI], const char* a_base, ARow a_row,
+                                              const char* b_base, BRow b_row, int K, char* lds) {
+  static_assert(T::NSTAGE == 2 && T::BK == 64, "pipeline below is written for 2 stages of 64");
+  constexpr int NL = T::A_LOADS;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int group = wave >> 2;                 // 0: waves 0-3, 1: waves 4-7
+  int wm, wn;
+  wave_subtile<T>(wm, wn);
+  const int lr = lane & 31, lh = lane >> 5;
+  const int a_off = (wm * T::WTM + lr) * T::ROW_BYTES;
+  const int b_off = T::A_BYTES + (wn * T::WTN + lr) * T::ROW_BYTES;
+  const int sw = swz128(lr);
 #pragma unroll
   for (int ni = 0; ni < T::NI; ++ni)
 #pragma unroll
@@ -125,21 +196,49 @@ __device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[T::NI][T::MI], ARo
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[ni][mi][v] = 0.f;
 
-  TileLoader<T> loader;
-  loader.init(a_row, b_row);
   const int kt_full = K / T::BK;
   const int kt_all = (K + T::BK - 1) / T::BK;
+  HalfLoader<NL> ld;
+  if (group == 0) ld.init(a_base, a_row, wave & 3);
+  else ld.init(b_base, b_row, wave & 3);
+  const int half_off = group == 0 ? 0 : T::A_BYTES;
+  auto issue = [&](int kt) {
+    char* dst = lds + (kt & 1) * T::STAGE_BYTES + half_off;
+    if (kt < kt_full) ld.template issue<false>(dst, kt, K);
+    else ld.template issue<true>(dst, kt, K);
+  };
 
-  if (kt_full > 0) loader.template issue<false>(lds, 0, K);
-  else loader.template issue<true>(lds, 0, K);
-
-  for (int kt = 0; kt < kt_all; ++kt) {
+  issue(0);
+  if (kt_all > 1) {
+    issue(1);
+    wait_vmcnt<NL>();
+  } else {
     wait_vmcnt0();
-    __syncthreads();  // tile kt has landed for every wave; every wave has finished tile kt-1
-    const int nxt = kt + 1;
-    if (nxt < kt_full) loader.template issue<false>(lds + (nxt & 1) * T::STAGE_BYTES, nxt, K);
-    else if (nxt < kt_all) loader.template issue<true>(lds + (nxt & 1) * T::STAGE_BYTES, nxt, K);
-    mma_stage<T>(acc, lds + (kt & 1) * T::STAGE_BYTES, wm, wn);
+  }
+  barrier_no_drain();   // tile 0 is in LDS
+
+  Frags<T> f;
+  if (group == 0) {
+    load_frags<T>(f, lds, a_off, b_off, sw, lh);
+    for (int kt = 0; kt < kt_all; ++kt) {
+      wait_lgkmcnt0();
+      barrier_no_drain();                        // even phase starts: this group multiplies tile kt
+      mma_tile<T>(acc, f);
+      wait_vmcnt0();                             // own share of tile kt+1 has landed
+      barrier_no_drain();                        // odd phase starts: the other group multiplies tile kt
+      if (kt + 2 < kt_all) issue(kt + 2);        // stage kt&1 has been read by both groups
+      if (kt + 1 < kt_all) load_frags<T>(f, lds + ((kt + 1) & 1) * T::STAGE_BYTES, a_off, b_off, sw, lh);
+    }
+  } else {
+    for (int kt = 0; kt < kt_all; ++kt) {
+      barrier_no_drain();                        // even phase: fetch the fragments of tile kt
+      load_frags<T>(f, lds + (kt & 1) * T::STAGE_BYTES, a_off, b_off, sw, lh);
+      wait_vmcnt0();                             // own share of tile kt+1 has landed
+      wait_lgkmcnt0();                           // and the fragment reads are done: the stage may be refilled
+      barrier_no_drain();                        // odd phase: multiply tile kt
+      if (kt + 2 < kt_all) issue(kt + 2);
+      mma_tile<T>(acc, f);
+    }
   }
 }
 
@@ -149,8 +248,9 @@ template <class T>
 __device__ __forceinline__ void store_tile_bf16(const f32x16_t (&acc)[T::NI][T::MI], __bf16* c, size_t ldc,
                                                 int m0, int n0, int M, int N, const float* row_scale,
                                                 int rows_per_scale, const float* col_scale) {
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int wm = wave / T::WAVES_N, wn = wave % T::WAVES_N;
+  const int lane = threadIdx.x & 63;
+  int wm, wn;
+  wave_subtile<T>(wm, wn);
   const int lr = lane & 31, lh = lane >> 5;
 #pragma unroll
   for (int mi = 0; mi < T::MI; ++mi) {

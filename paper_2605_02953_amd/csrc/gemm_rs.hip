@@ -63,14 +63,12 @@ __global__ __launch_bounds__(T::THREADS) void gemm_rs_kernel(const GemmRsParams 
     int32_t* rec = p.schedule + 4 * (size_t)wg;
     rec[0] = pid_m; rec[1] = pid_n; rec[2] = seg_start; rec[3] = seg_end;
   }
-  const size_t row_bytes = (size_t)p.k * 2;
-  const char* a_tile = p.a;
-  const char* b_tile = p.b;
+  const uint32_t row_bytes = (uint32_t)p.k * 2u;
   const int M = p.m, N = p.n;
-  auto a_row = [=](int r) { return a_tile + (size_t)min(m0 + r, M - 1) * row_bytes; };
-  auto b_row = [=](int r) { return b_tile + (size_t)min(n0 + r, N - 1) * row_bytes; };
+  auto a_row = [=](int r) { return (uint32_t)min(m0 + r, M - 1) * row_bytes; };
+  auto b_row = [=](int r) { return (uint32_t)min(n0 + r, N - 1) * row_bytes; };
   f32x16_t acc[T::NI][T::MI];
-  gemm_mainloop<T>(acc, a_row, b_row, p.k, lds);
+  gemm_mainloop<T>(acc, p.a, a_row, p.b, b_row, p.k, lds);
   store_tile_bf16<T>(acc, p.gemm_out, (size_t)p.n, m0, n0, M, N, nullptr, 1, nullptr);
 
   // segment completion: one lane per touched segment
@@ -253,6 +251,7 @@ extern "C" ditron_status_t ditron_gemm_rs(const void* a, const void* b, int b_la
   if (b_layout != DITRON_B_KN && b_layout != DITRON_B_NK) return DITRON_ERR_INVALID_ARG;
   if (b_layout != DITRON_B_NK) return DITRON_ERR_UNSUPPORTED;
   if (k_local % 8 != 0 || n % 8 != 0) return DITRON_ERR_UNSUPPORTED;
+  if (!fits_32bit(m, k_local, 2) || !fits_32bit(n, k_local, 2)) return DITRON_ERR_UNSUPPORTED;
 
   GemmRsParams p{};
   p.n_peers = world - 1;

@@ -214,15 +214,15 @@ __global__ __launch_bounds__(T::THREADS) void moe_grouped_gemm_kernel(const MoeG
   flag_wait_block(p.flags, seg_start, seg_end - seg_start + 1, p.epoch, p.spin_limit, p.status);
 
   const int n0 = pid_n * T::BN;
-  const size_t row_bytes = (size_t)p.hidden * 2;
-  const char* x = p.workspace;
+  const uint32_t row_bytes = (uint32_t)p.hidden * 2u;
   const char* wj = p.w + (size_t)j * p.inter * row_bytes;
   const int32_t* gidx = p.gather_idx;
   const int top_k = p.top_k, N = p.inter;
-  auto a_row = [=](int r) { return x + (size_t)(gidx[min(p0 + r, p_end - 1)] / top_k) * row_bytes; };
-  auto b_row = [=](int r) { return wj + (size_t)min(n0 + r, N - 1) * row_bytes; };
+  // the gather happens here: a tile row is fetched from the token its assignment belongs to
+  auto a_row = [=](int r) { return (uint32_t)(gidx[min(p0 + r, p_end - 1)] / top_k) * row_bytes; };
+  auto b_row = [=](int r) { return (uint32_t)min(n0 + r, N - 1) * row_bytes; };
   f32x16_t acc[T::NI][T::MI];
-  gemm_mainloop<T>(acc, a_row, b_row, p.hidden, lds);
+  gemm_mainloop<T>(acc, p.workspace, a_row, wj, b_row, p.hidden, lds);
   store_tile_bf16<T>(acc, p.y, (size_t)p.inter, p0, n0, p_end, N, nullptr, 1, nullptr);
 }
 
@@ -264,6 +264,8 @@ extern "C" ditron_status_t ditron_moe_ag_grouped_gemm(
   }
   if (w_layout != DITRON_B_NK) return DITRON_ERR_UNSUPPORTED;
   if (hidden % 8 != 0 || inter % 8 != 0) return DITRON_ERR_UNSUPPORTED;
+  if (!fits_32bit((size_t)world * tokens_per_rank, hidden, 2) || !fits_32bit(inter, hidden, 2))
+    return DITRON_ERR_UNSUPPORTED;
   if (num_experts > kMaxExperts || num_local_experts > kMaxLocalExperts) return DITRON_ERR_UNSUPPORTED;
   if ((long)world * num_experts > (long)DITRON_MAX_WORLD * kMaxExperts) return DITRON_ERR_UNSUPPORTED;
   const int max_tiles = ditron_moe_max_tiles(max_rows, num_local_experts);
