@@ -81,7 +81,7 @@ size_t ditron_signal_words(int world, int chunks);
  * evaluate the schedule independently.  op: 0 = ag_gemm, 1 = gemm_rs, 2 = moe grouped gemm.
  * out[0]=BLOCK_M out[1]=BLOCK_N out[2]=GROUP_SIZE_M out[3]=chiplets used by the work-group
  * remap (0 = no remap) out[4]=tiles per chiplet per block out[5]=number of tiles
- * (ag_gemm / gemm_rs) out[6]=threads per work-group out[7]=producer work-groups. */
+ * (ag_gemm / gemm_rs) out[6]=threads per work-group out[7]=reserved (0). */
 ditron_status_t ditron_tile_config(int op, int m, int n, int k, int dtype, int out[8]);
 
 /*

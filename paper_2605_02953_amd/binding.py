@@ -96,7 +96,7 @@ def set_spin_limit(polls):
 def tile_config(op, m, n, k, dtype=BF16):
     out = (ctypes.c_int * 8)()
     st = lib.ditron_tile_config(op, m, n, k, dtype, out)
-    keys = ("block_m", "block_n", "group_m", "num_xcd", "per_xcd", "ntiles", "threads", "producers")
+    keys = ("block_m", "block_n", "group_m", "num_xcd", "per_xcd", "ntiles", "threads", "reserved")
     return st, dict(zip(keys, list(out)))
 
 

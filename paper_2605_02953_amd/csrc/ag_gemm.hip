@@ -27,7 +27,7 @@ struct AgGemmParams {
   int32_t* schedule;   // or null
   int m_per_rank, m, n, k, world, rank;
   int32_t epoch;
-  int num_producers;
+  int num_producers, teams;
   unsigned spin_limit;
   int group_m, num_xcd, per_xcd, npm, npn;
 };
@@ -37,11 +37,11 @@ __global__ __launch_bounds__(T::THREADS) void ag_gemm_kernel(const AgGemmParams 
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   if ((int)blockIdx.x < p.num_producers) {
     const size_t shard_bytes = (size_t)p.m_per_rank * p.k * 2;
-    for (int i = 0; i < p.world; ++i) {
-      const int s = p.order[i];
-      copy_slice(p.workspace + (size_t)s * shard_bytes, p.shard[s], shard_bytes, blockIdx.x, p.num_producers);
-      publish_after_all(p.arrivals + s, p.num_producers, p.flags + s, p.epoch);
-    }
+    produce_chunks(
+        p.world, shard_bytes, blockIdx.x, p.num_producers, p.teams, p.epoch,
+        [&](int i) { return (void*)(p.workspace + (size_t)p.order[i] * shard_bytes); },
+        [&](int i) { return p.shard[p.order[i]]; }, [&](int i) { return p.flags + p.order[i]; },
+        [&](int i) { return p.arrivals + p.order[i]; });
     return;
   }
   const int wg = blockIdx.x - p.num_producers;
@@ -136,7 +136,9 @@ extern "C" ditron_status_t ditron_ag_gemm(const void* const* a_shards, const voi
   p.group_m = tc.group_m;
   p.num_xcd = tc.num_xcd;
   p.per_xcd = tc.per_xcd;
-  p.num_producers = emulate ? tc.producers : 0;
+  const ProducerPlan pl = plan_producers((size_t)p.m * k * 2, world);
+  p.num_producers = emulate ? pl.producers : 0;
+  p.teams = pl.teams;
   if (tc.big) return launch_ag<TileBig>(p, (hipStream_t)stream);
   return launch_ag<TileSmall>(p, (hipStream_t)stream);
 }

@@ -38,7 +38,7 @@ struct AgGemmFp8Params {
   int32_t* schedule;
   int m_per_rank, m, n, k, world, rank;
   int32_t epoch;
-  int num_producers;
+  int num_producers, teams;
   unsigned spin_limit;
   int group_m, num_xcd, per_xcd, npm, npn;
 };
@@ -48,11 +48,11 @@ __global__ __launch_bounds__(Fp8Tile::THREADS) void ag_gemm_fp8_kernel(const AgG
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   if ((int)blockIdx.x < p.num_producers) {
     const size_t shard_bytes = (size_t)p.m_per_rank * p.k;
-    for (int i = 0; i < p.world; ++i) {
-      const int s = p.order[i];
-      copy_slice(p.workspace + (size_t)s * shard_bytes, p.shard[s], shard_bytes, blockIdx.x, p.num_producers);
-      publish_after_all(p.arrivals + s, p.num_producers, p.flags + s, p.epoch);
-    }
+    produce_chunks(
+        p.world, shard_bytes, blockIdx.x, p.num_producers, p.teams, p.epoch,
+        [&](int i) { return (void*)(p.workspace + (size_t)p.order[i] * shard_bytes); },
+        [&](int i) { return p.shard[p.order[i]]; }, [&](int i) { return p.flags + p.order[i]; },
+        [&](int i) { return p.arrivals + p.order[i]; });
     return;
   }
   const int wg = blockIdx.x - p.num_producers;
@@ -221,7 +221,9 @@ extern "C" ditron_status_t ditron_ag_gemm_fp8(const void* const* a_shards, const
   p.group_m = tc.group_m;
   p.num_xcd = tc.num_xcd;
   p.per_xcd = tc.per_xcd;
-  p.num_producers = emulate ? tc.producers : 0;
+  const ProducerPlan pl = plan_producers((size_t)p.m * k, world);
+  p.num_producers = emulate ? pl.producers : 0;
+  p.teams = pl.teams;
   p.npm = cdiv(p.m, Fp8Tile::BM);
   p.npn = cdiv(p.n, Fp8Tile::BN);
   auto kern = ag_gemm_fp8_kernel;

@@ -56,7 +56,7 @@ extern "C" ditron_status_t ditron_tile_config(int op, int m, int n, int k, int d
   out[4] = t.per_xcd;
   out[5] = cdiv(m, t.block_m) * cdiv(n, t.block_n);
   out[6] = t.threads;
-  out[7] = t.producers;
+  out[7] = 0;
   return DITRON_OK;
 }
 

@@ -57,35 +57,56 @@ __device__ inline void flag_wait_block(const int32_t* flags, int first, int coun
 // work-group being part `part` of `nparts` cooperating work-groups.
 __device__ inline void copy_slice(void* __restrict__ dst, const void* __restrict__ src, size_t bytes,
                                   int part, int nparts) {
+  constexpr int U = 16;  // independent 16-byte loads in flight per lane
   const size_t n16 = bytes >> 4;
   const u32x4_t* s = (const u32x4_t*)src;
   u32x4_t* d = (u32x4_t*)dst;
   const size_t stride = (size_t)nparts * blockDim.x;
-  size_t i = (size_t)part * blockDim.x + threadIdx.x;
-  // four independent 16-byte loads in flight per lane
-  for (; i + 3 * stride < n16; i += 4 * stride) {
-    u32x4_t v0 = __builtin_nontemporal_load(s + i);
-    u32x4_t v1 = __builtin_nontemporal_load(s + i + stride);
-    u32x4_t v2 = __builtin_nontemporal_load(s + i + 2 * stride);
-    u32x4_t v3 = __builtin_nontemporal_load(s + i + 3 * stride);
-    d[i] = v0;
-    d[i + stride] = v1;
-    d[i + 2 * stride] = v2;
-    d[i + 3 * stride] = v3;
+  for (size_t i = (size_t)part * blockDim.x + threadIdx.x; i < n16; i += U * stride) {
+    // all loads of a round are issued before the first store, whatever the length of the slice
+    u32x4_t v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (i + u * stride < n16) v[u] = __builtin_nontemporal_load(s + i + u * stride);
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (i + u * stride < n16) d[i + u * stride] = v[u];
   }
-  for (; i < n16; i += stride) d[i] = s[i];
 }
 
 // After every cooperating work-group has finished its slice of a chunk, the last one to
 // arrive raises the chunk's flag and leaves the arrival counter at zero for the next call.
+// Arrivals are release-only; just the last arrival pays for an acquire (on this chip an
+// agent-scope acquire invalidates the chiplet's L2, which the GEMM tiles next door live on).
 __device__ inline void publish_after_all(int32_t* counter, int nparts, int32_t* flag, int32_t value) {
   __syncthreads();
   if (threadIdx.x == 0) {
-    int old = __hip_atomic_fetch_add(counter, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    int old = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
     if (old == nparts - 1) {
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
       __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       flag_raise(flag, value);
     }
+  }
+}
+
+// The emulated peers.  `nchunks` chunks of `chunk_bytes` are delivered by the `nparts` producer
+// work-groups (this one is `part`); dst(i) / src(i) / flag(i) / counter(i) give the addresses of
+// the chunk at delivery position i.  The producers split into `teams` teams; team t delivers
+// chunks t, t + teams, ... one after the other, all its members sharing each copy, and the
+// member that finishes a chunk last raises its flag.  One team means strictly sequential
+// arrival in delivery order (a ring); as many teams as chunks means everything is in flight
+// at once (a full mesh where every peer pushes at the same time).
+template <class Dst, class Src, class Flag, class Counter>
+__device__ inline void produce_chunks(int nchunks, size_t chunk_bytes, int part, int nparts, int teams,
+                                      int32_t epoch, Dst dst, Src src, Flag flag, Counter counter) {
+  teams = max(1, min(teams, min(nparts, nchunks)));
+  const int team_size = nparts / teams;
+  const int team = part / team_size, member = part % team_size;
+  if (team >= teams) return;   // left-over work-groups when nparts is not a multiple of teams
+  for (int i = team; i < nchunks; i += teams) {
+    copy_slice(dst(i), src(i), chunk_bytes, member, team_size);
+    publish_after_all(counter(i), team_size, flag(i), epoch);
   }
 }
 

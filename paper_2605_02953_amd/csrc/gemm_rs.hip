@@ -1,8 +1,8 @@
 // GEMM-ReduceScatter, one rank's share (paper, Appendix "GEMM Reduce-Scatter").
 //
-// Launch 1 holds the emulated peers and the GEMM.  The first `num_producers` work-groups
+// Launch 1 holds the GEMM and the emulated peers.  The last `num_producers` work-groups
 // copy, peer by peer in delivery order and row chunk by row chunk, the block each peer would
-// push into this rank's scatter buffer, raising one flag per (peer, chunk).  The other
+// push into this rank's scatter buffer, raising one flag per (peer, chunk).  The first
 // work-groups are the tiles of the local GEMM P = A . B, visited from the segment of rank+1
 // to the rank's own segment; a tile bumps the counter of every segment it touches and the
 // tile that completes a segment raises the segment flag.
@@ -29,29 +29,32 @@ struct GemmRsParams {
   int32_t* schedule;
   int m, n, k, world, rank, m_per_rank, chunks, n_peers;
   int32_t epoch;
-  int num_producers;
+  int num_producers, teams;
   int group_m, num_xcd, per_xcd, npm, npn;
 };
 
 template <class T>
 __global__ __launch_bounds__(T::THREADS) void gemm_rs_kernel(const GemmRsParams p) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
-  if ((int)blockIdx.x < p.num_producers) {
+  const int ntiles = p.npm * p.npn;
+  if ((int)blockIdx.x >= ntiles) {
+    // The emulated peers sit behind the GEMM tiles in the grid: nothing in this launch waits for
+    // them (only the reduction does), so they fill compute units as the last tiles drain instead
+    // of taking units away from the GEMM's first wave.
+    const int part = blockIdx.x - ntiles;
     const size_t slot_bytes = (size_t)p.m_per_rank * p.n * 2;
     const size_t chunk_bytes = slot_bytes / p.chunks;
-    for (int i = 0; i < p.n_peers; ++i) {
-      const int s = p.order[i];
-      for (int c = 0; c < p.chunks; ++c) {
-        copy_slice(p.scatter_buf + s * slot_bytes + c * chunk_bytes, (const char*)p.peer[s] + c * chunk_bytes,
-                   chunk_bytes, blockIdx.x, p.num_producers);
-        publish_after_all(p.arr_counters + s * p.chunks + c, p.num_producers, p.arr_flags + s * p.chunks + c,
-                          p.epoch);
-      }
-    }
+    // chunk index i = (delivery position of the peer) * chunks + row chunk
+    produce_chunks(
+        p.n_peers * p.chunks, chunk_bytes, part, p.num_producers, p.teams, p.epoch,
+        [&](int i) { return (void*)(p.scatter_buf + p.order[i / p.chunks] * slot_bytes + (i % p.chunks) * chunk_bytes); },
+        [&](int i) { return (const void*)((const char*)p.peer[p.order[i / p.chunks]] + (i % p.chunks) * chunk_bytes); },
+        [&](int i) { return p.arr_flags + p.order[i / p.chunks] * p.chunks + i % p.chunks; },
+        [&](int i) { return p.arr_counters + p.order[i / p.chunks] * p.chunks + i % p.chunks; });
     return;
   }
-  const int wg = blockIdx.x - p.num_producers;
-  const int pid = xcd_remap(wg, p.npm * p.npn, p.num_xcd, p.per_xcd);
+  const int wg = blockIdx.x;
+  const int pid = xcd_remap(wg, ntiles, p.num_xcd, p.per_xcd);
   int pid_m, pid_n;
   grouped_order(pid, p.npm, p.npn, p.group_m, pid_m, pid_n);
   // scatter mode: the next rank's segment first, the own segment last
@@ -78,8 +81,10 @@ __global__ __launch_bounds__(T::THREADS) void gemm_rs_kernel(const GemmRsParams 
     const int first = (p.m_per_rank * seg) / T::BM;
     const int last = (p.m_per_rank * (seg + 1) - 1) / T::BM;
     const int target = p.npn * (last - first + 1);
-    const int old = __hip_atomic_fetch_add(p.seg_counters + seg, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    // release-only arrivals; the tile that completes the segment adds the acquire (see publish_after_all)
+    const int old = __hip_atomic_fetch_add(p.seg_counters + seg, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
     if (old == target - 1) {
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
       __hip_atomic_store(p.seg_counters + seg, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       flag_raise(p.seg_flags + seg, p.epoch);
     }
@@ -100,8 +105,18 @@ struct ReduceParams {
   int wgs_per_chunk;
 };
 
-constexpr int kReduceThreads = 256;
-constexpr int kReduceUnroll = 4;   // 16-byte vectors per lane per step
+// Tunable build constants of the reduction kernel.
+#ifndef DITRON_REDUCE_THREADS
+#define DITRON_REDUCE_THREADS 1024
+#endif
+#ifndef DITRON_REDUCE_UNROLL
+#define DITRON_REDUCE_UNROLL 1
+#endif
+#ifndef DITRON_REDUCE_MAX_WGS
+#define DITRON_REDUCE_MAX_WGS 1024
+#endif
+constexpr int kReduceThreads = DITRON_REDUCE_THREADS;
+constexpr int kReduceUnroll = DITRON_REDUCE_UNROLL;   // 16-byte vectors per lane per slot in flight
 
 __device__ __forceinline__ void set_bf16x8(float (&acc)[8], const u32x4_t v) {
 #pragma unroll
@@ -179,7 +194,11 @@ static ditron_status_t launch_reduce(ReduceParams& p, hipStream_t stream) {
   // enough work-groups to cover the chip several times over, at least one per row chunk
   const size_t per_wg = (size_t)kReduceThreads * kReduceUnroll;
   size_t want = (p.vec_per_chunk + per_wg - 1) / per_wg;
-  const size_t cap = (size_t)(2048 / p.chunks > 0 ? 2048 / p.chunks : 1);
+  // a gated work-group pays for an acquire (cache invalidation) before it may read: keep those few
+  bool gated = false;
+  for (int s = 0; s < p.world; ++s) gated = gated || p.gate[s] != nullptr;
+  const int max_wgs = gated ? 256 : DITRON_REDUCE_MAX_WGS;
+  const size_t cap = (size_t)(max_wgs / p.chunks > 0 ? max_wgs / p.chunks : 1);
   if (want > cap) want = cap;
   if (want < 1) want = 1;
   p.wgs_per_chunk = (int)want;
@@ -289,7 +308,9 @@ extern "C" ditron_status_t ditron_gemm_rs(const void* a, const void* b, int b_la
   p.group_m = tc.group_m;
   p.num_xcd = tc.num_xcd;
   p.per_xcd = tc.per_xcd;
-  p.num_producers = (emulate && world > 1) ? tc.producers : 0;
+  const ProducerPlan pl = plan_producers((size_t)(world - 1) * m_r * n * 2, (world - 1) * chunks_per_slot);
+  p.num_producers = (emulate && world > 1) ? pl.producers : 0;
+  p.teams = pl.teams;
   ditron_status_t st = tc.big ? launch_rs<TileBig>(p, (hipStream_t)stream) : launch_rs<TileSmall>(p, (hipStream_t)stream);
   if (st != DITRON_OK) return st;
 

@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 #include "../../include/ditron.h"
 #include "gemm_core.h"
 
@@ -19,7 +20,6 @@ struct TileChoice {
   int group_m;    // GROUP_SIZE_M of the grouped tile order
   int num_xcd;    // chiplets assumed by the work-group remap (0: no remap)
   int per_xcd;    // consecutive tiles handed to one chiplet inside a remap block
-  int producers;  // work-groups that play the peers when the producer is emulated
 };
 
 inline TileChoice choose_tile(int m, int n, int /*k*/) {
@@ -31,7 +31,6 @@ inline TileChoice choose_tile(int m, int n, int /*k*/) {
   t.group_m = 4;
   t.num_xcd = 8;
   t.per_xcd = 32;
-  t.producers = 16;
   return t;
 }
 
@@ -45,8 +44,27 @@ inline TileChoice choose_tile_fp8(int /*m*/, int /*n*/, int /*k*/) {
   t.group_m = 4;
   t.num_xcd = 8;
   t.per_xcd = 32;
-  t.producers = 8;
   return t;
+}
+
+// How many work-groups play the peers, and into how many teams they split (= chunks in flight
+// at once).  On one GPU the copies are compute-unit work, so the cheapest emulation delivers
+// everything as early and as fast as possible: enough work-groups to saturate HBM for a large
+// transfer (about half a MiB each, at most one per compute unit), and as many teams as chunks,
+// which is also how a full mesh of links behaves (every peer pushes at the same time).
+struct ProducerPlan {
+  int producers, teams;
+};
+inline ProducerPlan plan_producers(size_t total_bytes, int nchunks) {
+  ProducerPlan pl{};
+  size_t want = (total_bytes + (512u << 10) - 1) / (512u << 10);
+  want = (want + 7) / 8 * 8;
+  pl.producers = (int)(want < 8 ? 8 : (want > 256 ? 256 : want));
+  pl.teams = nchunks < pl.producers ? nchunks : pl.producers;
+  if (const char* e = getenv("DITRON_PRODUCERS")) pl.producers = atoi(e);   // tuning knobs
+  if (const char* e = getenv("DITRON_TEAMS")) pl.teams = atoi(e);
+  if (pl.teams < 1) pl.teams = 1;
+  return pl;
 }
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }

@@ -187,7 +187,7 @@ struct MoeGemmParams {
   int32_t* status;
   int tokens_per_rank, hidden, inter, top_k, world, max_tiles, npn;
   int32_t epoch;
-  int num_producers;
+  int num_producers, teams;
   unsigned spin_limit;
 };
 
@@ -196,11 +196,11 @@ __global__ __launch_bounds__(T::THREADS) void moe_grouped_gemm_kernel(const MoeG
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   if ((int)blockIdx.x < p.num_producers) {
     const size_t shard_bytes = (size_t)p.tokens_per_rank * p.hidden * 2;
-    for (int i = 0; i < p.world; ++i) {
-      const int s = p.order[i];
-      copy_slice(p.workspace + (size_t)s * shard_bytes, p.shard[s], shard_bytes, blockIdx.x, p.num_producers);
-      publish_after_all(p.arrivals + s, p.num_producers, p.flags + s, p.epoch);
-    }
+    produce_chunks(
+        p.world, shard_bytes, blockIdx.x, p.num_producers, p.teams, p.epoch,
+        [&](int i) { return (void*)(p.workspace + (size_t)p.order[i] * shard_bytes); },
+        [&](int i) { return p.shard[p.order[i]]; }, [&](int i) { return p.flags + p.order[i]; },
+        [&](int i) { return p.arrivals + p.order[i]; });
     return;
   }
   const int wg = blockIdx.x - p.num_producers;
@@ -315,7 +315,9 @@ extern "C" ditron_status_t ditron_moe_ag_grouped_gemm(
   g.max_tiles = max_tiles;
   g.npn = cdiv(inter, MoeTile::BN);
   g.epoch = epoch;
-  g.num_producers = emulate ? 16 : 0;
+  const ProducerPlan pl = plan_producers((size_t)world * tokens_per_rank * hidden * 2, world);
+  g.num_producers = emulate ? pl.producers : 0;
+  g.teams = pl.teams;
   g.spin_limit = g_spin_limit;
   auto kern = moe_grouped_gemm_kernel<MoeTile>;
   if (!set_dynamic_lds((const void*)kern, MoeTile::LDS_BYTES)) return DITRON_ERR_HIP;
