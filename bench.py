@@ -115,6 +115,17 @@ def bench_ag_gemm(args, cfg_id):
     return out
 
 
+def _calibration_copy(torch):
+    """A plain device-to-device copy of known size, outside every timed region: rocprofv3 --pmc runs of this
+    script read FETCH_SIZE / WRITE_SIZE for it, which gives the factor the same counters are scaled by."""
+    nbytes = 256 << 20
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    return nbytes
+
+
 def _events(torch, n):
     return [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
 
@@ -328,6 +339,8 @@ def main():
     if args.gpus != 1:
         print("bench.py: this build measures one GPU's share on one GPU; --gpus must be 1", file=sys.stderr)
         sys.exit(2)
+    import torch
+    calib = _calibration_copy(torch)
     if args.workload in ("cfg1", "cfg2"):
         out = bench_ag_gemm(args, int(args.workload[3:]))
     elif args.workload == "cfg3":
@@ -339,6 +352,7 @@ def main():
     else:
         print(f"bench.py: unknown workload {args.workload}", file=sys.stderr)
         sys.exit(2)
+    out["calibration_copy_bytes"] = calib
     print(json.dumps(out))
 
 

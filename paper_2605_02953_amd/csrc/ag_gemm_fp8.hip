@@ -5,7 +5,7 @@
 // output tile and keeps many small B stages in flight: B (32 rows x 128 bytes per K tile)
 // runs through a 16-deep LDS ring that is started before the shard flags are even looked at
 // (B does not depend on the gather), while A (128 rows x 128 bytes per K tile, served from
-// L2) uses a 3-deep ring that starts once the flags are up.  v_mfma_f32_16x16x128_f8f6f4
+// L2) uses a 5-deep ring that starts once the flags are up.  v_mfma_f32_16x16x128_f8f6f4
 // consumes 32 contiguous bytes per lane of each operand.
 #include "gemm_core.h"
 #include "launch.h"
@@ -14,12 +14,13 @@ namespace ditron {
 
 struct Fp8Tile {
   static constexpr int BM = 128, BN = 32, BK = 128, THREADS = 256, NWAVES = 4;
-  static constexpr int NA = 3, NB = 16;                 // ring depths
+  static constexpr int NA = 5, NB = 16;                 // ring depths
   static constexpr int A_STAGE = BM * 128, B_STAGE = BN * 128;
   static constexpr int A_LOADS = BM / 8 / NWAVES;       // 4 wave-wide loads per wave per K tile
   static constexpr int LDS_BYTES = NA * A_STAGE + NB * B_STAGE;
-  // loads that may still be in flight when tile kt is needed: B(kt+NB-3), A(kt+1), B(kt+NB-2)
-  static constexpr int PENDING = 1 + A_LOADS + 1;
+  // loads issued after A(kt) that may still be in flight when tile kt is needed: the B load of
+  // the iteration that issued A(kt), then NA-2 whole iterations (A_LOADS + 1 loads each)
+  static constexpr int PENDING = 1 + (NA - 2) * (A_LOADS + 1);
 };
 
 typedef int i32x8_t __attribute__((ext_vector_type(8)));
@@ -115,13 +116,14 @@ __global__ __launch_bounds__(Fp8Tile::THREADS) void ag_gemm_fp8_kernel(const AgG
     if (lane == 0) flag_wait_lane(p.flags, rank_beg, rank_end - rank_beg + 1, p.epoch, p.spin_limit, p.status);
   }
 #pragma unroll 1
-  for (int kt = 0; kt < T::NB - 3; ++kt) issue_b(kt);
+  for (int kt = 0; kt < T::NB - T::NA; ++kt) issue_b(kt);
   barrier_no_drain();                           // flags seen by wave 0 -> A may be read by everyone
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-  issue_a(0);
-  issue_b(T::NB - 3);
-  issue_a(1);
-  issue_b(T::NB - 2);
+#pragma unroll
+  for (int j = 0; j < T::NA - 1; ++j) {
+    issue_a(j);
+    issue_b(T::NB - T::NA + j);
+  }
 
   f32x4_t acc[2][2];
 #pragma unroll
@@ -136,9 +138,9 @@ __global__ __launch_bounds__(Fp8Tile::THREADS) void ag_gemm_fp8_kernel(const AgG
 #pragma unroll 1
   for (int kt = 0; kt < kt_all; ++kt) {
     // everything up to A(kt) has landed once at most PENDING younger loads are outstanding
-    __builtin_amdgcn_s_waitcnt(0x0F70 | T::PENDING);
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (T::PENDING & 0xF) | ((T::PENDING >> 4) << 14));
     barrier_no_drain();
-    issue_a(kt + 2);
+    issue_a(kt + T::NA - 1);
     issue_b(kt + T::NB - 1);
     const char* sa = lds_a + (kt % T::NA) * T::A_STAGE + (wave * 32 + l16) * 128;
     const char* sb = lds_b + (kt % T::NB) * T::B_STAGE + l16 * 128;

@@ -55,9 +55,10 @@ __device__ inline void flag_wait_block(const int32_t* flags, int first, int coun
 // ------------------------------------------------------------------ chunk copy
 // Copy `bytes` (multiple of 16) from src to dst with 128-bit accesses, the calling
 // work-group being part `part` of `nparts` cooperating work-groups.
-__device__ inline void copy_slice(void* __restrict__ dst, const void* __restrict__ src, size_t bytes,
-                                  int part, int nparts) {
-  constexpr int U = 16;  // independent 16-byte loads in flight per lane
+// U = independent 16-byte loads in flight per lane.
+template <int U>
+__device__ inline void copy_slice_u(void* __restrict__ dst, const void* __restrict__ src, size_t bytes,
+                                    int part, int nparts) {
   const size_t n16 = bytes >> 4;
   const u32x4_t* s = (const u32x4_t*)src;
   u32x4_t* d = (u32x4_t*)dst;
@@ -72,6 +73,13 @@ __device__ inline void copy_slice(void* __restrict__ dst, const void* __restrict
     for (int u = 0; u < U; ++u)
       if (i + u * stride < n16) d[i + u * stride] = v[u];
   }
+}
+
+// A work-group keeps about 128 KiB of loads in flight whatever its size.
+__device__ inline void copy_slice(void* __restrict__ dst, const void* __restrict__ src, size_t bytes,
+                                  int part, int nparts) {
+  if (blockDim.x <= 256) copy_slice_u<32>(dst, src, bytes, part, nparts);
+  else copy_slice_u<16>(dst, src, bytes, part, nparts);
 }
 
 // After every cooperating work-group has finished its slice of a chunk, the last one to

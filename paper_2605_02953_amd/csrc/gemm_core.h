@@ -8,6 +8,7 @@
 // taken from the B rows and its column operand from the A rows, so that a lane ends up with
 // four consecutive output columns of one output row (an 8-byte bf16 store).
 #pragma once
+#include <type_traits>
 #include "common.h"
 
 namespace ditron {
@@ -32,6 +33,7 @@ struct GemmTile {
   static constexpr int A_BYTES = BM * ROW_BYTES, B_BYTES = BN * ROW_BYTES;
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
   static constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
+  static constexpr int kSchedule = 0;   // ping-pong
   static_assert(NWAVES == 8, "two groups of four waves (one wave of each group per SIMD)");
   static_assert(BM == BN, "both groups issue the same number of loads");
   static_assert(BM % (32 * WAVES_M) == 0 && BN % (32 * WAVES_N) == 0, "wave tile must be 32-aligned");
@@ -157,28 +159,189 @@ __device__ __forceinline__ void mma_tile(f32x16_t (&acc)[T::NI][T::MI], const Fr
 template <class T>
 __device__ __forceinline__ void wave_subtile(int& wm, int& wn) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int wt = (wave & 3) * 2 + (wave >> 2);
+  const int wt = T::NWAVES == 8 ? (wave & 3) * 2 + (wave >> 2) : wave;
   wm = wt / T::WAVES_N;
   wn = wt % T::WAVES_N;
 }
 
-// Full contraction for one output tile.  K must be a multiple of 8; the last K tile may be
-// partial.  `lds` is T::LDS_BYTES of dynamic shared memory.
-//
-// Ping-pong schedule.  The eight waves form two groups of four; waves w and w+4 share a SIMD.
-// Time is cut into phases separated by work-group barriers.  In every phase one group
-// multiplies a whole K tile out of registers (its MFMAs issue back to back, nothing to wait
-// for) while the other group fetches the fragments of its next K tile from LDS; at the
-// barrier they swap.  So each SIMD always has exactly one wave feeding the matrix pipe and the
-// barrier itself costs no matrix time.  K tiles live in two LDS stages filled by direct
-// global -> LDS loads: group 0 loads the A rows, group 1 the B rows, each issuing the loads of
-// tile kt+2 right after the barrier that retires tile kt, two phases before they are needed.
-//
-// a_base / b_base are the operands' base addresses; a_row(r) / b_row(r) give the byte offset of
-// tile-local row r from its base (32 bits: an operand must be smaller than 4 GiB).
+// ------------------------------------------------------------------ 4-wave tile
+// 256 x 256 output tile computed by four waves, one per SIMD, each owning 128 x 128 (256
+// accumulator registers).  Compared with the 8-wave tile every fragment read from LDS feeds
+// twice as many MFMAs, and operands are staged global -> registers -> LDS (plain loads of
+// full 128-byte lines stream from L2 faster than the direct-to-LDS form).  LDS holds two
+// stages of one 64-deep K tile each, rows of 128 bytes with the same chunk swizzle as the
+// 8-wave tile (measured free of bank conflicts for both the fragment reads and the stores).
+struct GemmTile4W {
+  static constexpr int BM = 256, BN = 256, BK = 64, NSTAGE = 2;
+  static constexpr int WAVES_M = 2, WAVES_N = 2, NWAVES = 4, THREADS = 256;
+  static constexpr int WTM = 128, WTN = 128, MI = 4, NI = 4;
+  static constexpr int kSchedule = 1;
+  static constexpr int ROW_BYTES = 128;
+  static constexpr int A_BYTES = BM * ROW_BYTES, B_BYTES = BN * ROW_BYTES;
+  static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+  static constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
+  static constexpr int ROWS_PER_PASS = THREADS / 8;           // 32 rows per pass of 16-byte loads
+  static constexpr int A_LOADS = BM / ROWS_PER_PASS, B_LOADS = BN / ROWS_PER_PASS, LOADS = A_LOADS + B_LOADS;
+};
+
+struct Frags4W {
+  bf16x8_t a[4];
+  bf16x8_t b[4];
+};
+
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, N>(f);
+  }
+}
+
+// Fragment J of step KS (0..3) of the K tile staged at `st`.  koff[KS] is the lane's swizzled
+// chunk offset for that step.  The order (b0, a0..a3, b1..b3) is the order in which mma_pair
+// consumes them.
+template <int KS, int J>
+__device__ __forceinline__ void read_one(Frags4W& f, const char* st, int a_off, int b_off, const int (&koff)[4]) {
+  const int off = koff[KS];
+  if constexpr (J == 0) f.b[0] = *(const bf16x8_t*)(st + b_off + off);
+  else if constexpr (J <= 4) f.a[J - 1] = *(const bf16x8_t*)(st + a_off + (J - 1) * 32 * 128 + off);
+  else f.b[J - 4] = *(const bf16x8_t*)(st + b_off + (J - 4) * 32 * 128 + off);
+}
+
+template <int P>
+__device__ __forceinline__ void mma_pair(f32x16_t (&acc)[4][4], const Frags4W& f) {
+  constexpr int ni = P / 2, mi = (P % 2) * 2;
+  acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[ni], f.a[mi], acc[ni][mi], 0, 0, 0);
+  acc[ni][mi + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[ni], f.a[mi + 1], acc[ni][mi + 1], 0, 0, 0);
+}
+
+struct Stager4W {
+  typedef GemmTile4W T;
+  static constexpr int kOutOfRange = 0x7ffffff0;
+  __amdgpu_buffer_rsrc_t a_rsrc, b_rsrc;
+  int off[T::LOADS];
+  u32x4_t reg[1][T::LOADS];
+  int lds_off;    // byte offset inside an operand area of a stage, pass 0
+  int kc;
+
+  template <class ARow, class BRow>
+  __device__ __forceinline__ void init(const char* a_base, ARow a_row, const char* b_base, BRow b_row) {
+    const int r = threadIdx.x >> 3, c = threadIdx.x & 7;
+    a_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)a_base, 0, kOutOfRange, 0x00020000);
+    b_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)b_base, 0, kOutOfRange, 0x00020000);
+    kc = c * 8;
+    lds_off = r * T::ROW_BYTES + ((c ^ swz128(r)) * 16);
+#pragma unroll
+    for (int i = 0; i < T::A_LOADS; ++i) off[i] = (int)(a_row(r + i * T::ROWS_PER_PASS) + (uint32_t)(c * 16));
+#pragma unroll
+    for (int i = 0; i < T::B_LOADS; ++i)
+      off[T::A_LOADS + i] = (int)(b_row(r + i * T::ROWS_PER_PASS) + (uint32_t)(c * 16));
+  }
+
+  // `kt` must be a valid K tile; a chunk past K reads as zero (lane offset pushed out of range)
+  template <int SET, int I>
+  __device__ __forceinline__ void fetch_one(int kt, int K) {
+    const bool dead = kt * 64 + kc >= K;
+    const int v = dead ? kOutOfRange : off[I];
+    reg[SET][I] = __builtin_amdgcn_raw_buffer_load_b128(I < T::A_LOADS ? a_rsrc : b_rsrc, v, kt * 128, 0);
+  }
+  template <int SET>
+  __device__ __forceinline__ void fetch(int kt, int K) {
+    static_for<0, T::LOADS>([&](auto i) { fetch_one<SET, decltype(i)::value>(kt, K); });
+  }
+
+  // `pair`: the stage that receives the K tile
+  template <int SET, int I>
+  __device__ __forceinline__ void commit_one(char* pair) const {
+    constexpr int area = I < T::A_LOADS ? 0 : T::A_BYTES;
+    constexpr int pass = I < T::A_LOADS ? I : I - T::A_LOADS;
+    *(u32x4_t*)(pair + area + lds_off + pass * T::ROWS_PER_PASS * T::ROW_BYTES) = reg[SET][I];
+  }
+  template <int SET>
+  __device__ __forceinline__ void commit(char* pair) const {
+    static_for<0, T::LOADS>([&](auto i) { commit_one<SET, decltype(i)::value>(pair); });
+  }
+};
+
+// One barrier per 64-deep K tile.  A single wave per SIMD has to keep the matrix pipe fed
+// while it also issues every memory instruction, so the loop body is written as 32 slots of
+// two MFMAs plus at most three memory instructions, each slot fenced so that the compiler
+// keeps the interleaving:
+//   steps ks0, ks1 of tile kt : fragments of the next step; LDS stores of tile kt+1
+//   step  ks2                : fragments of ks3
+//   barrier
+//   step  ks3                : first fragments of tile kt+1
+//   every other slot         : one global load of tile kt+2
+// The body is branch-free (past the end the last tile is staged again into a free stage).
+template <class ARow, class BRow>
+__device__ __forceinline__ void gemm_mainloop_4w(f32x16_t (&acc)[4][4], const char* a_base, ARow a_row,
+                                                 const char* b_base, BRow b_row, int K, char* lds) {
+  typedef GemmTile4W T;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int wm = wave / 2, wn = wave % 2;
+  const int lr = lane & 31, lh = lane >> 5;
+  const int a_off = (wm * T::WTM + lr) * T::ROW_BYTES;
+  const int b_off = T::A_BYTES + (wn * T::WTN + lr) * T::ROW_BYTES;
+  int koff[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) koff[ks] = ((ks * 2 + lh) ^ swz128(lr)) * 16;
+#pragma unroll
+  for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[ni][mi][v] = 0.f;
+
+  const int kt_all = (K + 63) / 64;
+  const int kt_last = kt_all - 1;
+  Stager4W st;
+  st.init(a_base, a_row, b_base, b_row);
+  st.template fetch<0>(0, K);
+  st.template commit<0>(lds);
+  st.template fetch<0>(min(1, kt_last), K);
+  __syncthreads();
+
+  Frags4W f0, f1;
+  static_for<0, 8>([&](auto j) { read_one<0, decltype(j)::value>(f0, lds, a_off, b_off, koff); });
+  for (int kt = 0; kt < kt_all; ++kt) {
+    constexpr int SET = 0;
+    const char* cur = lds + (kt & 1) * T::STAGE_BYTES;
+    char* nxt = lds + ((kt + 1) & 1) * T::STAGE_BYTES;
+    const int kf = min(kt + 2, kt_last);
+    static_for<0, 32>([&](auto sl) {
+      constexpr int S = decltype(sl)::value, PART = S / 8, J = S % 8;
+      if constexpr (S == 24) {
+        wait_lgkmcnt0();   // own LDS stores of tile kt+1 are done and every read of tile kt has returned
+        barrier_no_drain();
+      }
+      mma_pair<J>(acc, (PART & 1) ? f1 : f0);
+      if constexpr (PART == 0) read_one<1, J>(f1, cur, a_off, b_off, koff);
+      if constexpr (PART == 1) read_one<2, J>(f0, cur, a_off, b_off, koff);
+      if constexpr (PART == 2 && J < 4) {   // early, so that the wait before the barrier finds them done
+        read_one<3, 2 * J>(f1, cur, a_off, b_off, koff);
+        read_one<3, 2 * J + 1>(f1, cur, a_off, b_off, koff);
+      }
+      if constexpr (PART == 3 && J < 4) {
+        read_one<0, 2 * J>(f0, nxt, a_off, b_off, koff);
+        read_one<0, 2 * J + 1>(f0, nxt, a_off, b_off, koff);
+      }
+      // register i goes to LDS in slot i and is refilled (tile kt+2) in slot 2i+1:
+      // the loads are spread over the whole iteration, since a burst would saturate the
+      // address unit and stall the wave
+      if constexpr (S < 16) st.template commit_one<SET, S>(nxt);
+      if constexpr (S % 2 == 1) st.template fetch_one<SET, S / 2>(kf, K);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+  }
+}
+
 template <class T, class ARow, class BRow>
 __device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[T::NI][T::MI], const char* a_base, ARow a_row,
                                               const char* b_base, BRow b_row, int K, char* lds) {
+  if constexpr (T::kSchedule == 1) {
+    gemm_mainloop_4w(acc, a_base, a_row, b_base, b_row, K, lds);
+    return;
+  } else {
   static_assert(T::NSTAGE == 2 && T::BK == 64, "pipeline below is written for 2 stages of 64");
   constexpr int NL = T::A_LOADS;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -239,6 +402,7 @@ __device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[T::NI][T::MI], con
       if (kt + 2 < kt_all) issue(kt + 2);
       mma_tile<T>(acc, f);
     }
+  }
   }
 }
 

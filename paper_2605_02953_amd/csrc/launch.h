@@ -9,7 +9,9 @@
 namespace ditron {
 
 // 256x256 output tile, 8 waves as 2 (rows) x 4 (columns): 128x64 per wave, 128 KiB of LDS.
-typedef GemmTile<256, 256, 2, 4> TileBig;
+typedef GemmTile<256, 256, 2, 4> TileBig8W;
+// 256x256 output tile, 4 waves as 2 x 2: 128x128 per wave, register-staged operands.
+typedef GemmTile4W TileBig;
 // 128x128 output tile, 8 waves as 2 x 4: 64x32 per wave, 64 KiB of LDS; for problems with
 // too few 256x256 tiles to fill the chip.
 typedef GemmTile<128, 128, 2, 4> TileSmall;
@@ -69,8 +71,9 @@ inline ProducerPlan plan_producers(size_t total_bytes, int nchunks) {
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// The tile loaders address an operand with 32-bit byte offsets.
-inline bool fits_32bit(size_t rows, size_t cols, size_t esize) { return rows * cols * esize < (1ull << 32); }
+// The tile loaders address an operand with 32-bit byte offsets, and the buffer-addressed
+// loaders reserve offsets from 0x7ffffff0 up as "out of range, reads zero".
+inline bool fits_32bit(size_t rows, size_t cols, size_t esize) { return rows * cols * esize < 0x7ffffff0ull; }
 
 inline bool is_permutation(const int* v, int n) {
   bool seen[DITRON_MAX_WORLD] = {false};

@@ -49,15 +49,26 @@ __global__ __launch_bounds__(kRouteThreads) void moe_route_kernel(const MoeRoute
   __syncthreads();
 
   // histogram over (source rank, expert), and per-wave totals for the local experts.  A wave
-  // owns one contiguous range of assignments so that ranks inside an expert follow f.
+  // owns one contiguous range of assignments so that ranks inside an expert follow f.  The ids
+  // are fetched kBatch steps at a time so that the loads overlap instead of queueing one by one.
+  constexpr int kBatch = 16;
   const int per_wave = cdiv(cdiv(F, kRouteWaves), 64) * 64;
   const int w_begin = min(wave * per_wave, F), w_end = min(w_begin + per_wave, F);
-  for (int f = w_begin + lane; f < w_end; f += 64) {
-    const int e = p.topk_ids[f];
-    if (e >= 0 && e < E) {
-      atomicAdd(&s_counts[(f / per_shard) * E + e], 1);
-      const int j = e - p.expert_begin;
-      if (j >= 0 && j < EL) atomicAdd(&s_wave_base[wave][j], 1);
+  for (int f0 = w_begin; f0 < w_end; f0 += 64 * kBatch) {
+    int e[kBatch];
+#pragma unroll
+    for (int b = 0; b < kBatch; ++b) {
+      const int f = f0 + b * 64 + lane;
+      e[b] = f < w_end ? p.topk_ids[f] : -1;
+    }
+#pragma unroll
+    for (int b = 0; b < kBatch; ++b) {
+      const int f = f0 + b * 64 + lane;
+      if (e[b] >= 0 && e[b] < E) {
+        atomicAdd(&s_counts[(f / per_shard) * E + e[b]], 1);
+        const int j = e[b] - p.expert_begin;
+        if (j >= 0 && j < EL) atomicAdd(&s_wave_base[wave][j], 1);
+      }
     }
   }
   __syncthreads();
@@ -110,28 +121,37 @@ __global__ __launch_bounds__(kRouteThreads) void moe_route_kernel(const MoeRoute
   __syncthreads();
 
   // stable placement: 64 assignments at a time, lanes with the same expert rank themselves
-  for (int f0 = w_begin; f0 < w_end; f0 += 64) {
-    const int f = f0 + lane;
-    int j = -1;
-    if (f < w_end) {
-      const int e = p.topk_ids[f];
-      j = e - p.expert_begin;
-      if (j < 0 || j >= EL) j = -1;
-    }
-    unsigned long long todo = __ballot(j >= 0);
-    while (todo) {
-      const int leader = __ffsll((long long)todo) - 1;
-      const int jl = __shfl(j, leader);
-      const unsigned long long same = __ballot(j == jl);
-      const int base = s_wave_base[wave][jl];
-      if (j == jl) {
-        const int before = __popcll(same & ((1ull << lane) - 1ull));
-        p.gather_idx[base + before] = f;
+  for (int fb = w_begin; fb < w_end; fb += 64 * kBatch) {
+    int jj[kBatch];
+#pragma unroll
+    for (int b = 0; b < kBatch; ++b) {
+      const int f = fb + b * 64 + lane;
+      int j = -1;
+      if (f < w_end) {
+        j = p.topk_ids[f] - p.expert_begin;
+        if (j < 0 || j >= EL) j = -1;
       }
-      __builtin_amdgcn_wave_barrier();
-      if (lane == leader) s_wave_base[wave][jl] = base + __popcll(same);
-      __builtin_amdgcn_wave_barrier();
-      todo &= ~same;
+      jj[b] = j;
+    }
+#pragma unroll
+    for (int b = 0; b < kBatch; ++b) {
+      const int f = fb + b * 64 + lane;
+      const int j = jj[b];
+      unsigned long long todo = __ballot(j >= 0);
+      while (todo) {
+        const int leader = __ffsll((long long)todo) - 1;
+        const int jl = __shfl(j, leader);
+        const unsigned long long same = __ballot(j == jl);
+        const int base = s_wave_base[wave][jl];
+        if (j == jl) {
+          const int before = __popcll(same & ((1ull << lane) - 1ull));
+          p.gather_idx[base + before] = f;
+        }
+        __builtin_amdgcn_wave_barrier();
+        if (lane == leader) s_wave_base[wave][jl] = base + __popcll(same);
+        __builtin_amdgcn_wave_barrier();
+        todo &= ~same;
+      }
     }
   }
 
