@@ -449,4 +449,45 @@ __device__ __forceinline__ void store_tile_bf16(const f32x16_t (&acc)[T::NI][T::
   }
 }
 
+// Epilogue of the 4-wave tile: each wave turns its 128 x 128 accumulators into bf16, parks
+// them in its own 32 KiB of the (now idle) operand stages, and reads them back row by row so
+// that every global store covers whole 128-byte lines (16 lanes x 16 bytes per row; written
+// straight from the MFMA layout, a store instruction would scatter 8-byte pieces over 32
+// rows).  Rows are 256 bytes; the 16-byte slot g of row m lives at slot g ^ (m & 15), which
+// keeps both the 8-byte writes and the 16-byte reads free of bank conflicts.
+__device__ __forceinline__ void store_tile_bf16_lds(const f32x16_t (&acc)[4][4], __bf16* c, size_t ldc, int m0,
+                                                    int n0, int M, int N, char* lds) {
+  typedef GemmTile4W T;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int wm = wave / 2, wn = wave % 2;
+  const int lr = lane & 31, lh = lane >> 5;
+  __syncthreads();   // every wave is done reading the operand stages
+  char* park = lds + wave * (T::WTM * T::WTN * 2);
+#pragma unroll
+  for (int mi = 0; mi < 4; ++mi) {
+    const int m = mi * 32 + lr;
+#pragma unroll
+    for (int ni = 0; ni < 4; ++ni) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int g = ni * 4 + q;
+        bf16x4_t v = {(__bf16)acc[ni][mi][q * 4 + 0], (__bf16)acc[ni][mi][q * 4 + 1],
+                      (__bf16)acc[ni][mi][q * 4 + 2], (__bf16)acc[ni][mi][q * 4 + 3]};
+        *(bf16x4_t*)(park + m * 256 + ((g ^ (m & 15)) * 16) + lh * 8) = v;
+      }
+    }
+  }
+  // the reads below are the same wave's: LDS operations of one wave complete in order
+  wait_lgkmcnt0();
+  const int g = lane & 15;
+  const int gn = n0 + wn * T::WTN + g * 8;
+#pragma unroll 8
+  for (int it = 0; it < T::WTM / 4; ++it) {
+    const int row = it * 4 + (lane >> 4);
+    const u32x4_t v = *(const u32x4_t*)(park + row * 256 + ((g ^ (row & 15)) * 16));
+    const int gm = m0 + wm * T::WTM + row;
+    if (gm < M && gn < N) *(u32x4_t*)(c + (size_t)gm * ldc + gn) = v;
+  }
+}
+
 }  // namespace ditron
