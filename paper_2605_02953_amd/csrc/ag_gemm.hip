@@ -37,7 +37,7 @@ __global__ __launch_bounds__(T::THREADS) void ag_gemm_kernel(const AgGemmParams 
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   if ((int)blockIdx.x < p.num_producers) {
     const size_t shard_bytes = (size_t)p.m_per_rank * p.k * 2;
-    produce_chunks(
+    produce_chunks<T::THREADS>(
         p.world, shard_bytes, blockIdx.x, p.num_producers, p.teams, p.epoch,
         [&](int i) { return (void*)(p.workspace + (size_t)p.order[i] * shard_bytes); },
         [&](int i) { return p.shard[p.order[i]]; }, [&](int i) { return p.flags + p.order[i]; },

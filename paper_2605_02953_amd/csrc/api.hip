@@ -24,7 +24,7 @@ __global__ __launch_bounds__(1024) void publish_chunks_kernel(const PublishParam
       const unsigned long long t0 = wall_clock64();
       while (wall_clock64() - t0 < p.delay_cycles) __builtin_amdgcn_s_sleep(32);
     }
-    copy_slice(p.dst[i], p.src[i], p.bytes[i], 0, 1);
+    copy_slice<1024>(p.dst[i], p.src[i], p.bytes[i], 0, 1);
     __syncthreads();
     if (threadIdx.x == 0) flag_raise(p.signals + p.flag_index[i], p.epoch);
   }

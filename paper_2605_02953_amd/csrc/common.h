@@ -75,11 +75,11 @@ __device__ inline void copy_slice_u(void* __restrict__ dst, const void* __restri
   }
 }
 
-// A work-group keeps about 128 KiB of loads in flight whatever its size.
+// A work-group of THREADS threads keeps about 128 KiB of loads in flight whatever its size.
+template <int THREADS>
 __device__ inline void copy_slice(void* __restrict__ dst, const void* __restrict__ src, size_t bytes,
                                   int part, int nparts) {
-  if (blockDim.x <= 256) copy_slice_u<32>(dst, src, bytes, part, nparts);
-  else copy_slice_u<16>(dst, src, bytes, part, nparts);
+  copy_slice_u<(THREADS <= 256 ? 32 : 16)>(dst, src, bytes, part, nparts);
 }
 
 // After every cooperating work-group has finished its slice of a chunk, the last one to
@@ -105,7 +105,7 @@ __device__ inline void publish_after_all(int32_t* counter, int nparts, int32_t* 
 // member that finishes a chunk last raises its flag.  One team means strictly sequential
 // arrival in delivery order (a ring); as many teams as chunks means everything is in flight
 // at once (a full mesh where every peer pushes at the same time).
-template <class Dst, class Src, class Flag, class Counter>
+template <int THREADS, class Dst, class Src, class Flag, class Counter>
 __device__ inline void produce_chunks(int nchunks, size_t chunk_bytes, int part, int nparts, int teams,
                                       int32_t epoch, Dst dst, Src src, Flag flag, Counter counter) {
   teams = max(1, min(teams, min(nparts, nchunks)));
@@ -113,7 +113,7 @@ __device__ inline void produce_chunks(int nchunks, size_t chunk_bytes, int part,
   const int team = part / team_size, member = part % team_size;
   if (team >= teams) return;   // left-over work-groups when nparts is not a multiple of teams
   for (int i = team; i < nchunks; i += teams) {
-    copy_slice(dst(i), src(i), chunk_bytes, member, team_size);
+    copy_slice<THREADS>(dst(i), src(i), chunk_bytes, member, team_size);
     publish_after_all(counter(i), team_size, flag(i), epoch);
   }
 }

@@ -45,7 +45,7 @@ __global__ __launch_bounds__(T::THREADS) void gemm_rs_kernel(const GemmRsParams 
     const size_t slot_bytes = (size_t)p.m_per_rank * p.n * 2;
     const size_t chunk_bytes = slot_bytes / p.chunks;
     // chunk index i = (delivery position of the peer) * chunks + row chunk
-    produce_chunks(
+    produce_chunks<T::THREADS>(
         p.n_peers * p.chunks, chunk_bytes, part, p.num_producers, p.teams, p.epoch,
         [&](int i) { return (void*)(p.scatter_buf + p.order[i / p.chunks] * slot_bytes + (i % p.chunks) * chunk_bytes); },
         [&](int i) { return (const void*)((const char*)p.peer[p.order[i / p.chunks]] + (i % p.chunks) * chunk_bytes); },

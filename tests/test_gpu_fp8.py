@@ -57,6 +57,9 @@ def _integer_fp8(cfg, seed):
     (4, 50, 264, 400),       # ragged rows / columns, contraction tail of 16
     (4, 100, 40, 16),        # several row tiles, minimum contraction, fewer K tiles than ring slots
     (2, 8, 8, 4096),
+    (4, 40, 1000, 2192),     # odd number of K tiles plus a contraction tail of 16
+    (8, 256, 2048, 384),     # many tiles
+    (2, 640, 2560, 512),     # several row tiles per shard
 ])
 def test_fp8_integer_inputs_bit_exact(B, world, m_r, n, k):
     cfg = synth.CONFIGS[5].scaled(world=world, m_per_rank=m_r, n=n, k=k, rank=world - 1)
