@@ -25,8 +25,17 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_FP8_TFLOPS = 5000.0
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per launch measured with rocprofv3 --pmc (see profiles/), or None if not measured
-MEASURED_TRAFFIC = {}
+# Bytes per launch of the dominant kernel between the L2s and memory, from two rocprofv3 --pmc runs
+# (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch) of the commands given in profiles/, each scaled by
+# what the same counter reads for this script's 256 MiB calibration copy (FETCH_SIZE reports 0.500 of
+# the bytes read, WRITE_SIZE 1.000 of the bytes written).  Reads include those served by the
+# memory-side cache.
+MEASURED_TRAFFIC = {
+    "cfg2": 956.6e6 + 192.9e6,   # ag_gemm_kernel, fused launch (GEMM-only launch: 822.3e6 + 58.7e6); algorithmic 251.7e6 (+ 268.4e6 emulated gather)
+    "cfg3": 822.4e6 + 251.7e6,   # gemm_rs_kernel (reduce_slots_kernel: 134.3e6 + 16.8e6 = its algorithmic 151.0e6)
+    "cfg4": 416.6e6 + 73.3e6,    # moe_grouped_gemm_kernel
+    "cfg5": 76.9e6 + 3.1e6,      # ag_gemm_fp8_kernel; algorithmic 70.3e6
+}
 
 
 def _cpu_baseline_ag(cfg, shards, b):

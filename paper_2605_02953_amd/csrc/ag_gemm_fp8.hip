@@ -112,9 +112,7 @@ __global__ __launch_bounds__(Fp8Tile::THREADS) void ag_gemm_fp8_kernel(const AgG
 
   // wave 0 looks at the flags before it has any load in flight (loads return in order, so a
   // poll issued behind the B prefetch would wait for it); the other waves start B at once
-  if (wave == 0) {
-    if (lane == 0) flag_wait_lane(p.flags, rank_beg, rank_end - rank_beg + 1, p.epoch, p.spin_limit, p.status);
-  }
+  if (wave == 0) flag_wait_wave(p.flags, rank_beg, rank_end - rank_beg + 1, p.epoch, p.spin_limit, p.status);
 #pragma unroll 1
   for (int kt = 0; kt < T::NB - T::NA; ++kt) issue_b(kt);
   barrier_no_drain();                           // flags seen by wave 0 -> A may be read by everyone

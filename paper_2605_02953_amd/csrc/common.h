@@ -45,10 +45,29 @@ __device__ inline void flag_wait_lane(const int32_t* flags, int first, int count
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
 }
 
-// Whole work-group waits: lane 0 polls, the barrier hands the acquired view to the rest.
+// One wave waits for `count` flags, one lane per flag: a wait for several flags costs one round
+// trip to memory, not one per flag.  Called by all lanes of the wave.
+__device__ inline void flag_wait_wave(const int32_t* flags, int first, int count, int32_t value,
+                                      unsigned spin_limit, int32_t* status) {
+  for (int i = threadIdx.x & 63; i < count; i += 64) {
+    const int32_t* f = flags + first + i;
+    unsigned polls = 0;
+    while (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != value) {
+      if (++polls >= spin_limit) {
+        status[1] = first + i;
+        status[0] = DITRON_ERR_TIMEOUT;
+        break;
+      }
+      __builtin_amdgcn_s_sleep(8);
+    }
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+}
+
+// Whole work-group waits: the first wave polls, the barrier hands the acquired view to the rest.
 __device__ inline void flag_wait_block(const int32_t* flags, int first, int count, int32_t value,
                                        unsigned spin_limit, int32_t* status) {
-  if (threadIdx.x == 0) flag_wait_lane(flags, first, count, value, spin_limit, status);
+  if (threadIdx.x < 64) flag_wait_wave(flags, first, count, value, spin_limit, status);
   __syncthreads();
 }
 

@@ -152,10 +152,9 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_slots_kernel(const Redu
   const int chunk = blockIdx.x / p.wgs_per_chunk;
   const int part = blockIdx.x % p.wgs_per_chunk;
   const int world = WORLD > 0 ? WORLD : p.world;
-  if (threadIdx.x == 0) {
-    for (int s = 0; s < world; ++s)
-      if (p.gate[s]) flag_wait_lane(p.gate[s], chunk * p.gate_stride[s], 1, p.epoch, p.spin_limit, p.status);
-  }
+  // one lane per slot: the flags are looked at side by side, not one round trip after another
+  if ((int)threadIdx.x < world && p.gate[threadIdx.x])
+    flag_wait_lane(p.gate[threadIdx.x], chunk * p.gate_stride[threadIdx.x], 1, p.epoch, p.spin_limit, p.status);
   __syncthreads();
   const size_t base = (size_t)chunk * p.vec_per_chunk;
   const size_t step = (size_t)p.wgs_per_chunk * kReduceThreads;
@@ -191,14 +190,15 @@ __global__ __launch_bounds__(kReduceThreads) void reduce_slots_kernel(const Redu
   }
 }
 
-static ditron_status_t launch_reduce(ReduceParams& p, hipStream_t stream) {
+// `flags_pending`: some gate may still be down when the kernel starts (an external producer
+// that needs room on the chip to run); the waiting work-groups are then kept to half the chip.
+static ditron_status_t launch_reduce(ReduceParams& p, bool flags_pending, hipStream_t stream) {
   // enough work-groups to cover the chip several times over, at least one per row chunk
   const size_t per_wg = (size_t)kReduceThreads * kReduceUnroll;
   size_t want = (p.vec_per_chunk + per_wg - 1) / per_wg;
-  // a gated work-group pays for an acquire (cache invalidation) before it may read: keep those few
   bool gated = false;
   for (int s = 0; s < p.world; ++s) gated = gated || p.gate[s] != nullptr;
-  const int max_wgs = gated ? 256 : DITRON_REDUCE_MAX_WGS;
+  const int max_wgs = (gated && flags_pending) ? 256 : DITRON_REDUCE_MAX_WGS;
   const size_t cap = (size_t)(max_wgs / p.chunks > 0 ? max_wgs / p.chunks : 1);
   if (want > cap) want = cap;
   if (want < 1) want = 1;
@@ -247,7 +247,7 @@ extern "C" ditron_status_t ditron_reduce_slots(const void* const* slots, void* o
   p.world = world;
   p.epoch = epoch;
   p.spin_limit = g_spin_limit;
-  return launch_reduce(p, (hipStream_t)stream);
+  return launch_reduce(p, /*flags_pending=*/signals != nullptr, (hipStream_t)stream);
 }
 
 extern "C" ditron_status_t ditron_gemm_rs(const void* a, const void* b, int b_layout, void* gemm_out,
@@ -335,5 +335,6 @@ extern "C" ditron_status_t ditron_gemm_rs(const void* a, const void* b, int b_la
   r.world = world;
   r.epoch = epoch;
   r.spin_limit = g_spin_limit;
-  return launch_reduce(r, (hipStream_t)stream);
+  // with emulated peers every flag was raised by the launch before this one
+  return launch_reduce(r, /*flags_pending=*/!emulate, (hipStream_t)stream);
 }
