@@ -69,6 +69,7 @@ def bench_ag_gemm(args, cfg_id):
         if st != B.OK:
             raise RuntimeError(B.status_string(st))
 
+    _ramp(torch, step)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -110,12 +111,12 @@ def bench_ag_gemm(args, cfg_id):
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"cfg{cfg_id}: AG-GEMM world={cfg.world} rank={cfg.rank} A {cfg.world}x[{cfg.m_per_rank},{cfg.k}] "
                                f"B [{cfg.k},{cfg.n}] stored [n,k] -> C [{cfg.m},{cfg.n}] bf16, fp32 accumulate",
-                   "latency_us": kernel_ms * 1e3},
+                   "latency_us": kernel_ms * 1e3, "latency_us_quantiles": _quantiles_us(ev)},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": MEASURED_TRAFFIC.get(f"cfg{cfg_id}"),
                      "kernel": "ag_gemm_kernel (producer work-groups + GEMM tiles in one launch)",
                      "kernel_ms": kernel_ms},
-        "gemm_only": {"ms": preset_ms, "achieved": flops / (preset_ms * 1e-3) / 1e12,
+        "gemm_only": {"ms": preset_ms, "us_quantiles": _quantiles_us(pe), "achieved": flops / (preset_ms * 1e-3) / 1e12,
                       "frac": flops / (preset_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
                       "note": "same kernel, all shards resident and flags preset"},
     }
@@ -132,7 +133,15 @@ def _calibration_copy(torch):
     dst = torch.empty_like(src)
     dst.copy_(src)
     torch.cuda.synchronize()
-    return nbytes
+    # the same copy a few more times gives the bandwidth a plain copy reaches on this machine (read + write)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(10)]
+    for a, b in ev:
+        a.record()
+        dst.copy_(src)
+        b.record()
+    torch.cuda.synchronize()
+    best_ms = min(a.elapsed_time(b) for a, b in ev)
+    return nbytes, 2.0 * nbytes / (best_ms * 1e-3) / 1e9
 
 
 def _events(torch, n):
@@ -140,19 +149,30 @@ def _events(torch, n):
 
 
 RAMP_SECONDS = 0.3
+LAST_QUANTILES = None   # per-step event times of the last _timed() region
 
 
-def _timed(torch, args, step):
-    """W warm-up steps, then K timed steps with events around each; returns (ms per step by the
-    host clock around the whole region, mean ms between the per-step events)."""
-    # The chip needs about 0.1 s of sustained load before its clocks settle (measured: the fused
-    # step goes from 0.49 ms to 0.45 ms over the first ~200 launches), so a fixed, untimed ramp
-    # precedes the W warm-up steps whatever W is.
+def _ramp(torch, step):
+    """The chip needs about 0.1 s of sustained load before its clocks settle (measured: the fused cfg 2
+    step goes from 0.49 ms to 0.45 ms over the first ~200 launches), so a fixed, untimed ramp precedes
+    the W warm-up steps whatever W is."""
     t_ramp = time.perf_counter()
     while time.perf_counter() - t_ramp < RAMP_SECONDS:
         for _ in range(20):
             step()
         torch.cuda.synchronize()
+
+
+def _quantiles_us(ev):
+    t = sorted(a.elapsed_time(b) * 1e3 for a, b in ev)
+    pick = lambda q: t[min(len(t) - 1, int(q * len(t)))]
+    return {"median": pick(0.5), "p10": pick(0.1), "p90": pick(0.9)}
+
+
+def _timed(torch, args, step):
+    """W warm-up steps, then K timed steps with events around each; returns (ms per step by the
+    host clock around the whole region, mean ms between the per-step events)."""
+    _ramp(torch, step)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -164,6 +184,8 @@ def _timed(torch, args, step):
         ev[i][1].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    global LAST_QUANTILES
+    LAST_QUANTILES = _quantiles_us(ev)
     return wall * 1e3 / args.steps, sum(a.elapsed_time(b) for a, b in ev) / args.steps
 
 
@@ -360,7 +382,7 @@ def main():
         print("bench.py: this build measures one GPU's share on one GPU; --gpus must be 1", file=sys.stderr)
         sys.exit(2)
     import torch
-    calib = _calibration_copy(torch)
+    calib, copy_gbs = _calibration_copy(torch)
     if args.workload in ("cfg1", "cfg2"):
         out = bench_ag_gemm(args, int(args.workload[3:]))
     elif args.workload == "cfg3":
@@ -372,7 +394,10 @@ def main():
     else:
         print(f"bench.py: unknown workload {args.workload}", file=sys.stderr)
         sys.exit(2)
+    if LAST_QUANTILES is not None:
+        out["config"].setdefault("latency_us_quantiles", LAST_QUANTILES)
     out["calibration_copy_bytes"] = calib
+    out["plain_copy_gbs"] = copy_gbs   # read + write bytes of a 256 MiB torch copy / its best time: the HBM rate a simple kernel reaches
     out["clock_ramp_s"] = RAMP_SECONDS   # untimed load before the W warm-up steps
     print(json.dumps(out))
 
