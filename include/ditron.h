@@ -77,6 +77,24 @@ enum {
  * ranks and `chunks` flags per rank (chunks = 1 except for ditron_gemm_rs). */
 size_t ditron_signal_words(int world, int chunks);
 
+/*
+ * Tile rows across nodes.  Paper: Appendix "Swizzle", first listing (AllGather-GEMM) and second
+ * listing (GEMM-ReduceScatter): with `nnodes` nodes of world/nnodes ranks, the gather order
+ * visits the own node's tile rows first and inside a node starts at the own local rank; the
+ * scatter order starts with the next node and the next local rank; a tile row shared by two
+ * nodes is visited once.  With one node (the default) these are the plain rotations.
+ *
+ * ditron_set_num_nodes: process-wide setting read by ditron_ag_gemm and ditron_gemm_rs at call
+ * time; `world` must then be a multiple of it, and a shape for which the listing's order does
+ * not visit every tile row exactly once is refused with DITRON_ERR_UNSUPPORTED.
+ *
+ * ditron_tile_row_order: evaluates the order on the host with the very function the kernels
+ * use: out[t] (host int[ceil(m / block_m)]) = tile row visited at position t.  op 0 = gather
+ * order, 1 = scatter order.  m = rows of the full matrix (a multiple of world).
+ */
+ditron_status_t ditron_set_num_nodes(int nnodes);
+ditron_status_t ditron_tile_row_order(int op, int m, int block_m, int world, int nnodes, int rank, int* out);
+
 /* Tile shape and ordering parameters the library will use for a problem, so that a test can
  * evaluate the schedule independently.  op: 0 = ag_gemm, 1 = gemm_rs, 2 = moe grouped gemm.
  * out[0]=BLOCK_M out[1]=BLOCK_N out[2]=GROUP_SIZE_M out[3]=chiplets used by the work-group

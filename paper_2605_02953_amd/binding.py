@@ -29,6 +29,10 @@ _ip = ctypes.POINTER(ctypes.c_int)
 
 lib.ditron_signal_words.restype = ctypes.c_size_t
 lib.ditron_signal_words.argtypes = [_i, _i]
+lib.ditron_set_num_nodes.restype = _i
+lib.ditron_set_num_nodes.argtypes = [_i]
+lib.ditron_tile_row_order.restype = _i
+lib.ditron_tile_row_order.argtypes = [_i, _i, _i, _i, _i, _i, _ip]
 lib.ditron_tile_config.restype = _i
 lib.ditron_tile_config.argtypes = [_i, _i, _i, _i, _i, _ip]
 lib.ditron_set_spin_limit.restype = None
@@ -91,6 +95,17 @@ def signal_words(world, chunks=1):
 
 def set_spin_limit(polls):
     lib.ditron_set_spin_limit(int(polls))
+
+
+def set_num_nodes(nnodes):
+    return lib.ditron_set_num_nodes(nnodes)
+
+
+def tile_row_order(op, m, block_m, world, nnodes, rank):
+    npm = -(-m // block_m)
+    out = (ctypes.c_int * npm)()
+    st = lib.ditron_tile_row_order(op, m, block_m, world, nnodes, rank, out)
+    return st, list(out)
 
 
 def tile_config(op, m, n, k, dtype=BF16):

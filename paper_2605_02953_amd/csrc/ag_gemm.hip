@@ -25,7 +25,7 @@ struct AgGemmParams {
   int32_t* arrivals;   // [world] producer arrival counters
   int32_t* status;
   int32_t* schedule;   // or null
-  int m_per_rank, m, n, k, world, rank;
+  int m_per_rank, m, n, k, world, rank, nnodes;
   int32_t epoch;
   int num_producers, teams;
   unsigned spin_limit;
@@ -48,8 +48,9 @@ __global__ __launch_bounds__(T::THREADS) void ag_gemm_kernel(const AgGemmParams 
   const int pid = xcd_remap(wg, p.npm * p.npn, p.num_xcd, p.per_xcd);
   int pid_m, pid_n;
   grouped_order(pid, p.npm, p.npn, p.group_m, pid_m, pid_n);
-  // start on the rows of the rank's own shard, then follow the ring
-  pid_m = (pid_m + cdiv(p.m_per_rank * p.rank, T::BM)) % p.npm;
+  // start on the rows of the rank's own shard, then follow the ring (across nodes: own node first)
+  pid_m = p.nnodes > 1 ? tile_row_across_nodes(pid_m, p.m, p.rank, p.world, p.nnodes, T::BM, kOrderGather)
+                       : (pid_m + cdiv(p.m_per_rank * p.rank, T::BM)) % p.npm;
   const int m0 = pid_m * T::BM, n0 = pid_n * T::BN;
   const int rank_beg = m0 / p.m_per_rank;
   const int rank_end = (min(m0 + T::BM, p.m) - 1) / p.m_per_rank;
@@ -91,6 +92,7 @@ extern "C" ditron_status_t ditron_ag_gemm(const void* const* a_shards, const voi
                                           int rank, int dtype, int32_t epoch, unsigned flags, void* stream) {
   if (world < 1 || world > DITRON_MAX_WORLD || rank < 0 || rank >= world) return DITRON_ERR_INVALID_ARG;
   if (m_per_rank <= 0 || n <= 0 || k <= 0) return DITRON_ERR_INVALID_ARG;
+  if (world % g_num_nodes != 0) return DITRON_ERR_INVALID_ARG;
   if (!b || !c || !workspace || !signals || !status) return DITRON_ERR_INVALID_ARG;
   if (!aligned16(b) || !aligned16(c) || !aligned16(workspace) || !aligned16(signals)) return DITRON_ERR_INVALID_ARG;
   const bool emulate = (flags & DITRON_EMULATE_PRODUCER) != 0;
@@ -131,9 +133,12 @@ extern "C" ditron_status_t ditron_ag_gemm(const void* const* a_shards, const voi
   p.k = k;
   p.world = world;
   p.rank = rank;
+  p.nnodes = g_num_nodes;
   p.epoch = epoch;
   p.spin_limit = g_spin_limit;
   TileChoice tc = choose_tile(p.m, n, k);
+  if (p.nnodes > 1 && !node_order_is_bijection(p.m, tc.block_m, world, p.nnodes, rank, kOrderGather))
+    return DITRON_ERR_UNSUPPORTED;
   p.group_m = tc.group_m;
   p.num_xcd = tc.num_xcd;
   p.per_xcd = tc.per_xcd;

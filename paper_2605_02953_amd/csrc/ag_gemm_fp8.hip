@@ -37,7 +37,7 @@ struct AgGemmFp8Params {
   int32_t* arrivals;
   int32_t* status;
   int32_t* schedule;
-  int m_per_rank, m, n, k, world, rank;
+  int m_per_rank, m, n, k, world, rank, nnodes;
   int32_t epoch;
   int num_producers, teams;
   unsigned spin_limit;
@@ -60,7 +60,8 @@ __global__ __launch_bounds__(Fp8Tile::THREADS) void ag_gemm_fp8_kernel(const AgG
   const int pid = xcd_remap(wg, p.npm * p.npn, p.num_xcd, p.per_xcd);
   int pid_m, pid_n;
   grouped_order(pid, p.npm, p.npn, p.group_m, pid_m, pid_n);
-  pid_m = (pid_m + cdiv(p.m_per_rank * p.rank, T::BM)) % p.npm;
+  pid_m = p.nnodes > 1 ? tile_row_across_nodes(pid_m, p.m, p.rank, p.world, p.nnodes, T::BM, kOrderGather)
+                       : (pid_m + cdiv(p.m_per_rank * p.rank, T::BM)) % p.npm;
   const int m0 = pid_m * T::BM, n0 = pid_n * T::BN;
   const int rank_beg = m0 / p.m_per_rank;
   const int rank_end = (min(m0 + T::BM, p.m) - 1) / p.m_per_rank;
@@ -215,9 +216,12 @@ extern "C" ditron_status_t ditron_ag_gemm_fp8(const void* const* a_shards, const
   p.k = k;
   p.world = world;
   p.rank = rank;
+  p.nnodes = g_num_nodes;
   p.epoch = epoch;
   p.spin_limit = g_spin_limit;
   TileChoice tc = choose_tile_fp8(p.m, n, k);
+  if (p.nnodes > 1 && !node_order_is_bijection(p.m, tc.block_m, world, p.nnodes, rank, kOrderGather))
+    return DITRON_ERR_UNSUPPORTED;
   p.group_m = tc.group_m;
   p.num_xcd = tc.num_xcd;
   p.per_xcd = tc.per_xcd;

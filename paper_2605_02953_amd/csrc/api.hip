@@ -5,6 +5,7 @@
 
 namespace ditron {
 unsigned g_spin_limit = 1u << 20;
+int g_num_nodes = 1;
 
 struct PublishParams {
   void* dst[64];
@@ -57,6 +58,22 @@ extern "C" ditron_status_t ditron_tile_config(int op, int m, int n, int k, int d
   out[5] = cdiv(m, t.block_m) * cdiv(n, t.block_n);
   out[6] = t.threads;
   out[7] = 0;
+  return DITRON_OK;
+}
+
+extern "C" ditron_status_t ditron_set_num_nodes(int nnodes) {
+  if (nnodes < 1 || nnodes > DITRON_MAX_WORLD) return DITRON_ERR_INVALID_ARG;
+  g_num_nodes = nnodes;
+  return DITRON_OK;
+}
+
+extern "C" ditron_status_t ditron_tile_row_order(int op, int m, int block_m, int world, int nnodes, int rank, int* out) {
+  if (!out || (op != 0 && op != 1) || m <= 0 || block_m <= 0) return DITRON_ERR_INVALID_ARG;
+  if (world < 1 || world > DITRON_MAX_WORLD || rank < 0 || rank >= world) return DITRON_ERR_INVALID_ARG;
+  if (nnodes < 1 || world % nnodes != 0 || m % world != 0) return DITRON_ERR_INVALID_ARG;
+  const int npm = cdiv(m, block_m);
+  for (int t = 0; t < npm; ++t)
+    out[t] = tile_row_across_nodes(t, m, rank, world, nnodes, block_m, op == 0 ? kOrderGather : kOrderScatter);
   return DITRON_OK;
 }
 

@@ -149,6 +149,68 @@ __device__ inline void grouped_order(int pid, int npm, int npn, int group_m, int
   pid_n = r / size_m;
 }
 
+// ------------------------------------------------------------------ tile rows across nodes
+// Position in the visiting order -> tile row, for `nnodes` nodes of world/nnodes ranks each
+// (paper, Appendix "Swizzle", first listing for the gather order and second for the scatter
+// order).  Nodes are visited starting with the own node (gather) or the next one (scatter);
+// inside a node the rows are rotated to start at the own local rank's rows (gather) or the
+// next local rank's (scatter).  A tile row that straddles two nodes belongs to exactly one
+// of them; which one depends on the visit position and differs between the two orders.
+// With one node both reduce to the plain rotations used by the kernels.
+enum { kOrderGather = 0, kOrderScatter = 1 };
+
+// Tile rows [t_lo, t_lo + size) of the node visited at position `pos`.
+__host__ __device__ inline void node_tile_rows(int pos, int m, int nnodes, int block_m, int node_start, int mode,
+                                               int& t_lo, int& size) {
+  const int m_node = m / nnodes;
+  const int node = (pos + node_start) % nnodes;
+  const int lo = m_node * node, hi = m_node * (node + 1);
+  t_lo = lo / block_m;
+  int t_hi = (hi - 1) / block_m;
+  const bool shares_first = lo != 0 && (lo - 1) / block_m == t_lo;   // first tile row also holds rows of the node before
+  const int next_start = hi / block_m;
+  if (mode == kOrderGather) {
+    if (pos == 0 && shares_first) ++t_lo;
+    if (pos == 0 && hi != m && next_start == t_hi) --t_hi;
+    if (pos != nnodes - 1 && hi != m && next_start == t_hi) --t_hi;
+  } else {
+    if (pos != 0 && shares_first) ++t_lo;
+    if (pos == nnodes - 1 && hi != m && next_start == t_hi) --t_hi;
+  }
+  size = t_hi - t_lo + 1;
+}
+
+__host__ __device__ inline int tile_row_across_nodes(int position, int m, int rank, int world, int nnodes, int block_m,
+                                                     int mode) {
+  const int local_world = world / nnodes;
+  const int node_id = rank / local_world, local_rank = rank % local_world;
+  const int m_r = m / world, m_node = m / nnodes;
+  const int node_start = (node_id + (mode == kOrderScatter ? 1 : 0)) % nnodes;
+  // the visit position the tile falls in
+  int before = 0, pos = -1, size = 0;
+  for (int p = 0; p < nnodes; ++p) {
+    int lo, sz;
+    node_tile_rows(p, m, nnodes, block_m, node_start, mode, lo, sz);
+    if (position < before + sz) { pos = p; size = sz; break; }
+    before += sz;
+  }
+  if (pos < 0) return position;   // past the swizzled range: cannot happen while the blocks cover every tile row
+  const int nid = (pos + node_start) % nnodes;
+  // first tile row of that node = sizes of the nodes with a smaller id
+  int node_offset = 0;
+  for (int p = 0; p < nnodes; ++p) {
+    if ((p + node_start) % nnodes < nid) {
+      int lo, sz;
+      node_tile_rows(p, m, nnodes, block_m, node_start, mode, lo, sz);
+      node_offset += sz;
+    }
+  }
+  const int first_row = mode == kOrderGather ? cdiv(m_node * nid + m_r * local_rank, block_m)
+                                             : (m_node * nid + m_r * (local_rank + 1)) / block_m;
+  const int rank_offset = first_row > node_offset ? first_row - node_offset : 0;
+  return node_offset + (position - before + rank_offset) % size;
+}
+
 // Work-group index -> linear tile id.  The dispatcher deals work-groups round-robin to the
 // chiplets; inside every block of num_xcd*per_xcd tiles, chiplet x receives a run of
 // consecutive tile ids, so tiles that share operand panels share an L2, while blocks stay in

@@ -27,7 +27,7 @@ struct GemmRsParams {
   int32_t* arr_counters;   // [world * chunks]
   int32_t* status;
   int32_t* schedule;
-  int m, n, k, world, rank, m_per_rank, chunks, n_peers;
+  int m, n, k, world, rank, nnodes, m_per_rank, chunks, n_peers;
   int32_t epoch;
   int num_producers, teams;
   int group_m, num_xcd, per_xcd, npm, npn;
@@ -58,7 +58,8 @@ __global__ __launch_bounds__(T::THREADS) void gemm_rs_kernel(const GemmRsParams 
   int pid_m, pid_n;
   grouped_order(pid, p.npm, p.npn, p.group_m, pid_m, pid_n);
   // scatter mode: the next rank's segment first, the own segment last
-  pid_m = (pid_m + ((p.rank + 1) * p.m_per_rank) / T::BM) % p.npm;
+  pid_m = p.nnodes > 1 ? tile_row_across_nodes(pid_m, p.m, p.rank, p.world, p.nnodes, T::BM, kOrderScatter)
+                       : (pid_m + ((p.rank + 1) * p.m_per_rank) / T::BM) % p.npm;
   const int m0 = pid_m * T::BM, n0 = pid_n * T::BN;
   const int seg_start = m0 / p.m_per_rank;
   const int seg_end = (min(m0 + T::BM, p.m) - 1) / p.m_per_rank;
@@ -257,6 +258,7 @@ extern "C" ditron_status_t ditron_gemm_rs(const void* a, const void* b, int b_la
                                           int chunks_per_slot, int32_t epoch, unsigned flags, void* stream) {
   if (world < 1 || world > DITRON_MAX_WORLD || rank < 0 || rank >= world) return DITRON_ERR_INVALID_ARG;
   if (m <= 0 || n <= 0 || k_local <= 0 || m % world != 0 || chunks_per_slot < 1) return DITRON_ERR_INVALID_ARG;
+  if (world % g_num_nodes != 0) return DITRON_ERR_INVALID_ARG;
   const int m_r = m / world;
   if (m_r % chunks_per_slot != 0) return DITRON_ERR_INVALID_ARG;
   if (!a || !b || !gemm_out || !out || !signals || !status) return DITRON_ERR_INVALID_ARG;
@@ -302,10 +304,13 @@ extern "C" ditron_status_t ditron_gemm_rs(const void* a, const void* b, int b_la
   p.k = k_local;
   p.world = world;
   p.rank = rank;
+  p.nnodes = g_num_nodes;
   p.m_per_rank = m_r;
   p.chunks = chunks_per_slot;
   p.epoch = epoch;
   TileChoice tc = choose_tile(m, n, k_local);
+  if (p.nnodes > 1 && !node_order_is_bijection(m, tc.block_m, world, p.nnodes, rank, kOrderScatter))
+    return DITRON_ERR_UNSUPPORTED;
   p.group_m = tc.group_m;
   p.num_xcd = tc.num_xcd;
   p.per_xcd = tc.per_xcd;

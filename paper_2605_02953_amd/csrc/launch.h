@@ -75,6 +75,19 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 // loaders reserve offsets from 0x7ffffff0 up as "out of range, reads zero".
 inline bool fits_32bit(size_t rows, size_t cols, size_t esize) { return rows * cols * esize < 0x7ffffff0ull; }
 
+// With more than one node the tile-row order comes from the paper's multi-node listings; a shape
+// for which they do not visit every tile row exactly once is refused.
+inline bool node_order_is_bijection(int m, int block_m, int world, int nnodes, int rank, int mode) {
+  const int npm = cdiv(m, block_m);
+  std::vector<char> seen((size_t)npm, 0);
+  for (int t = 0; t < npm; ++t) {
+    const int r = tile_row_across_nodes(t, m, rank, world, nnodes, block_m, mode);
+    if (r < 0 || r >= npm || seen[(size_t)r]) return false;
+    seen[(size_t)r] = 1;
+  }
+  return true;
+}
+
 inline bool is_permutation(const int* v, int n) {
   bool seen[DITRON_MAX_WORLD] = {false};
   for (int i = 0; i < n; ++i) {
@@ -90,6 +103,7 @@ inline bool set_dynamic_lds(const void* func, int bytes) {
 }
 
 extern unsigned g_spin_limit;
+extern int g_num_nodes;
 
 }  // namespace ditron
 

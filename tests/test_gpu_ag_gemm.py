@@ -172,3 +172,50 @@ def test_cfg2_full_size_every_element(B):
         rows = np.arange(r0, r0 + 1024)
         worst = max(worst, compare.max_row_rel_error(cd[rows], oag.ag_gemm(shards, b, rows=rows)))
     assert worst <= TOL_BF16, worst
+
+
+@pytest.mark.parametrize("world,nnodes,m_r,n,k", [
+    (4, 2, 128, 256, 64),        # two nodes of two ranks, one small tile row per rank
+    (8, 2, 200, 264, 72),        # tile rows shared between ranks and between the two nodes
+    (8, 4, 505, 3080, 64),       # 256x256 tiles, four nodes
+])
+def test_tile_rows_follow_the_multi_node_order(B, world, nnodes, m_r, n, k):
+    """With more than one node the kernel visits tile rows in the order of the paper's first swizzle
+    listing (checked against the oracle through the schedule dump); the product does not change."""
+    cfg = synth.CONFIGS[2].scaled(world=world, m_per_rank=m_r, n=n, k=k)
+    shards, b = synth.ag_gemm_inputs(cfg, integer=True)
+    want_c = formats.encode_bf16_rne(oag.ag_gemm(shards, b).astype(np.float32))
+    st, tc = B.tile_config(0, cfg.m, n, k)
+    npm, npn = osch.cdiv(cfg.m, tc["block_m"]), osch.cdiv(n, tc["block_n"])
+    assert B.set_num_nodes(nnodes) == B.OK
+    try:
+        for rank in (0, world // nnodes, world - 1):
+            c, ws, sched, _ = _run(B, cfg, shards, b, rank=rank, want_schedule=True)
+            assert np.array_equal(c, want_c)
+            want = []
+            for wg in range(tc["ntiles"]):
+                pid = osch.xcd_remap(wg, tc["ntiles"], tc["num_xcd"], tc["per_xcd"]) if tc["num_xcd"] else wg
+                pm, pn = osch.grouped_order(pid, npm, npn, tc["group_m"])
+                pm = osch.ag_swizzle_multinode(pm, cfg.m, rank, world, nnodes, tc["block_m"])
+                row0 = pm * tc["block_m"]
+                want.append((pm, pn, row0 // m_r, (min(row0 + tc["block_m"], cfg.m) - 1) // m_r))
+            assert np.array_equal(sched, np.asarray(want, dtype=np.int32))
+    finally:
+        B.set_num_nodes(1)
+
+
+def test_multi_node_order_that_skips_rows_is_refused(B):
+    # 37 rows per rank, four nodes, 128-row tiles: the listing's order is not a permutation of the
+    # tile rows for rank 4; the library refuses instead of computing a partial product
+    cfg = synth.CONFIGS[2].scaled(world=8, m_per_rank=37, n=128, k=64)
+    st, order = B.tile_row_order(0, cfg.m, 128, 8, 4, 4)
+    assert st == B.OK and sorted(order) != list(range(len(order)))
+    shards, b = synth.ag_gemm_inputs(cfg, integer=True)
+    run = AgGemmRun(B, cfg.world, cfg.m_per_rank, cfg.n, cfg.k)
+    assert B.set_num_nodes(4) == B.OK
+    try:
+        assert run([to_dev(s) for s in shards], to_dev(nk(b)), 4) == B.ERR_UNSUPPORTED
+        assert run([to_dev(s) for s in shards], to_dev(nk(b)), 0) == B.OK      # rank 0's order is fine
+        torch.cuda.synchronize()
+    finally:
+        B.set_num_nodes(1)

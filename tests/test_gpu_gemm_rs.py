@@ -133,3 +133,37 @@ def test_cfg3_full_size(B):
     rows = np.arange(0, cfg.m, 61)
     pref = formats.decode_bf16(a_list[d][rows]) @ formats.decode_bf16(b_list[d])
     assert compare.max_row_rel_error(formats.decode_bf16(bits(run.gemm_out)[rows]), pref) <= TOL_BF16
+
+
+@pytest.mark.parametrize("world,nnodes,m_r,n,k,chunks", [
+    (4, 2, 128, 256, 64, 1),
+    (8, 2, 200, 264, 72, 2),       # tile rows shared between segments and between the two nodes
+])
+def test_gemm_rs_multi_node_order(B, world, nnodes, m_r, n, k, chunks):
+    """Scatter order across nodes (the paper's second swizzle listing): next node first, own segment
+    last; the reduced output and the segment flags are what they are with one node."""
+    cfg = synth.CONFIGS[3].scaled(world=world, m_per_rank=m_r, n=n, k=k)
+    a_list, b_list = synth.gemm_rs_inputs(cfg, integer=True)
+    parts = _all_partials(B, cfg, a_list, b_list)
+    run = GemmRsRun(B, world, cfg.m, n, k, chunks)
+    st, tc = B.tile_config(1, cfg.m, n, k)
+    npm, npn = osch.cdiv(cfg.m, tc["block_m"]), osch.cdiv(n, tc["block_n"])
+    assert B.set_num_nodes(nnodes) == B.OK
+    try:
+        for d in (0, world // nnodes, world - 1):
+            peers = [parts[s][d * m_r:(d + 1) * m_r] for s in range(world)]
+            sched = torch.full((4 * tc["ntiles"],), -1, dtype=torch.int32, device="cuda")
+            st = run(to_dev(a_list[d]), to_dev(nk(b_list[d])), peers, d, schedule=sched)
+            _ok(B, st, run)
+            assert np.array_equal(bits(run.out), formats.encode_bf16_rne(ors.gemm_rs(a_list, b_list, d).astype(np.float32)))
+            want = []
+            for wg in range(tc["ntiles"]):
+                pid = osch.xcd_remap(wg, tc["ntiles"], tc["num_xcd"], tc["per_xcd"]) if tc["num_xcd"] else wg
+                pm, pn = osch.grouped_order(pid, npm, npn, tc["group_m"])
+                pm = osch.rs_swizzle_multinode(pm, cfg.m, d, world, nnodes, tc["block_m"])
+                want.append((pm, pn, (pm * tc["block_m"]) // m_r, (min((pm + 1) * tc["block_m"], cfg.m) - 1) // m_r))
+            assert np.array_equal(sched.cpu().numpy().reshape(-1, 4), np.asarray(want, dtype=np.int32))
+            sig = run.signals.cpu().numpy()
+            assert sig[:world].tolist() == [run.epoch] * world
+    finally:
+        B.set_num_nodes(1)
