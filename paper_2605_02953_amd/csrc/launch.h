@@ -8,8 +8,6 @@
 
 namespace ditron {
 
-// 256x256 output tile, 8 waves as 2 (rows) x 4 (columns): 128x64 per wave, 128 KiB of LDS.
-typedef GemmTile<256, 256, 2, 4> TileBig8W;
 // 256x256 output tile, 4 waves as 2 x 2: 128x128 per wave, register-staged operands.
 typedef GemmTile4W TileBig;
 // 128x128 output tile, 8 waves as 2 x 4: 64x32 per wave, 64 KiB of LDS; for problems with
@@ -63,8 +61,6 @@ inline ProducerPlan plan_producers(size_t total_bytes, int nchunks) {
   want = (want + 7) / 8 * 8;
   pl.producers = (int)(want < 8 ? 8 : (want > 256 ? 256 : want));
   pl.teams = nchunks < pl.producers ? nchunks : pl.producers;
-  if (const char* e = getenv("DITRON_PRODUCERS")) pl.producers = atoi(e);   // tuning knobs
-  if (const char* e = getenv("DITRON_TEAMS")) pl.teams = atoi(e);
   if (pl.teams < 1) pl.teams = 1;
   return pl;
 }
