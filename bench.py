@@ -339,6 +339,112 @@ def bench_moe(args):
     return out
 
 
+# Per-rank shares (world 8) of the paper's evaluation shapes: Appendix "Evaluation Setup", tables
+# "Shapes for AllGather+GEMM" (N divided by the ranks) and "Shapes for GEMM+ReduceScatter" (K divided).
+SWEEP_AG = [("LLaMA3-7B", 1376, 4096), ("LLaMA3.1-8B", 1792, 4096), ("LLaMA3.1-70B", 3584, 8192),
+            ("LLaMA3.1-405B", 6656, 16384), ("Mistral-7B", 1792, 4096), ("Qwen2-72B", 3696, 8192)]
+SWEEP_RS = [("LLaMA3-7B", 4096, 1376), ("LLaMA3.1-8B", 4096, 1792), ("LLaMA3.1-70B", 8192, 3584),
+            ("LLaMA3.1-405B", 16384, 6656), ("Mistral-7B", 4096, 1792), ("Qwen2-72B", 8192, 3696)]
+
+
+def bench_sweep(args):
+    """Both bf16 operators over the shapes of the paper's two dense tables (M = 8192, world 8, rank 0),
+    random N(0,1) / N(0,1/K) bf16 generated on the device.  One step = all twelve problems once."""
+    import math
+    import torch
+    from paper_2605_02953_amd import binding as B
+    from gpu_util import AgGemmRun, GemmRsRun
+
+    world, m_r = 8, 1024
+    m = world * m_r
+
+    def rnd(shape, std):
+        return (torch.randn(shape, device="cuda") * std).to(torch.bfloat16).view(torch.int16)
+
+    rows, problems = [], []
+    for name, n, k in SWEEP_AG:
+        run = AgGemmRun(B, world, m_r, n, k)
+        sh = [rnd((m_r, k), 1.0) for _ in range(world)]
+        bd = rnd((n, k), k ** -0.5)
+
+        def fused(run=run, sh=sh, bd=bd):
+            assert run(sh, bd, 0) == B.OK
+
+        def preset(run=run, bd=bd):
+            run.signals[:world] = run.epoch + 1
+            return lambda: run(None, bd, 0, flags=B.EXTERNAL_PRODUCER)
+
+        problems.append(("ag_gemm", name, n, k, fused, preset, run))
+    for name, n, k in SWEEP_RS:
+        run = GemmRsRun(B, world, m, n, k, chunks=4)
+        a, bd = rnd((m, k), 1.0), rnd((n, k), k ** -0.5)
+        peers = [rnd((m_r, n), 1.0) for _ in range(world)]
+
+        def fused(run=run, a=a, bd=bd, peers=peers):
+            assert run(a, bd, peers, 0) == B.OK
+
+        def preset(run=run, a=a, bd=bd):
+            run.signals[2 * world:2 * world + world * run.chunks] = run.epoch + 1
+            return lambda: run(a, bd, None, 0, flags=B.EXTERNAL_PRODUCER)
+
+        problems.append(("gemm_rs", name, n, k, fused, preset, run))
+
+    def step():
+        for pr in problems:
+            pr[4]()
+
+    _ramp(torch, step)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    reps = max(1, args.steps)
+    t0 = time.perf_counter()
+    per = [[] for _ in problems]
+    for _ in range(reps):
+        for i, pr in enumerate(problems):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            pr[4]()
+            e1.record()
+            per[i].append((e0, e1))
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    pre = [[] for _ in problems]
+    for _ in range(reps):
+        for i, pr in enumerate(problems):
+            call = pr[5]()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            st = call()
+            e1.record()
+            assert st == B.OK
+            pre[i].append((e0, e1))
+    torch.cuda.synchronize()
+    total_flops, logs = 0.0, []
+    for i, (op, name, n, k, _, _, run) in enumerate(problems):
+        if run.status.cpu().tolist()[0] != 0:
+            raise RuntimeError("kernel reported a signal time-out")
+        flops = 2.0 * m * n * k
+        total_flops += flops
+        us = _quantiles_us(per[i])["median"]
+        us_p = _quantiles_us(pre[i])["median"]
+        rows.append({"op": op, "model": name, "m": m, "n": n, "k": k, "us": us, "tflops": flops / us / 1e6,
+                     "us_flags_preset": us_p, "tflops_flags_preset": flops / us_p / 1e6})
+        logs.append(math.log(flops / us / 1e6))
+    ms_per_step = wall * 1e3 / reps
+    geo = math.exp(sum(logs) / len(logs))
+    return {
+        "metric": "TFLOP/s over one pass of the paper's 6 AG-GEMM and 6 GEMM-RS shapes (per-rank share, world 8)",
+        "value": total_flops / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": reps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "sweep: AG-GEMM [8192, N/8, K] and GEMM-RS [8192, N, K/8] for the six models of the paper's shape tables"},
+        "roofline": {"bound": "mfma", "achieved": geo, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": geo / PEAK_BF16_TFLOPS,
+                     "traffic": None, "kernel": "geometric mean over the twelve problems (events around each call)"},
+        "sweep": rows,
+    }
+
+
 def bench_fp8(args):
     import torch
     import synth
@@ -411,6 +517,8 @@ def main():
         out = bench_moe(args)
     elif args.workload == "cfg5":
         out = bench_fp8(args)
+    elif args.workload == "sweep":
+        out = bench_sweep(args)
     else:
         print(f"bench.py: unknown workload {args.workload}", file=sys.stderr)
         sys.exit(2)
