@@ -120,7 +120,12 @@ __global__ __launch_bounds__(kRouteThreads) void moe_route_kernel(const MoeRoute
   }
   __syncthreads();
 
-  // stable placement: 64 assignments at a time, lanes with the same expert rank themselves
+  // stable placement: 64 assignments at a time.  For every local expert the lanes that hold it
+  // are found with one ballot and rank themselves by counting the lanes below them; lane l keeps
+  // the wave's running output position of local expert l in a register (there are at most 64
+  // local experts), so a round is a handful of scalar instructions and no trip through LDS.
+  int next_pos = lane < EL ? s_wave_base[wave][lane] : 0;
+  const unsigned long long below = (1ull << lane) - 1ull;
   for (int fb = w_begin; fb < w_end; fb += 64 * kBatch) {
     int jj[kBatch];
 #pragma unroll
@@ -137,20 +142,13 @@ __global__ __launch_bounds__(kRouteThreads) void moe_route_kernel(const MoeRoute
     for (int b = 0; b < kBatch; ++b) {
       const int f = fb + b * 64 + lane;
       const int j = jj[b];
-      unsigned long long todo = __ballot(j >= 0);
-      while (todo) {
-        const int leader = __ffsll((long long)todo) - 1;
-        const int jl = __shfl(j, leader);
+      if (__ballot(j >= 0) == 0) continue;
+      for (int jl = 0; jl < EL; ++jl) {
         const unsigned long long same = __ballot(j == jl);
-        const int base = s_wave_base[wave][jl];
-        if (j == jl) {
-          const int before = __popcll(same & ((1ull << lane) - 1ull));
-          p.gather_idx[base + before] = f;
-        }
-        __builtin_amdgcn_wave_barrier();
-        if (lane == leader) s_wave_base[wave][jl] = base + __popcll(same);
-        __builtin_amdgcn_wave_barrier();
-        todo &= ~same;
+        if (same == 0) continue;
+        const int base = __builtin_amdgcn_readlane(next_pos, jl);
+        if (j == jl) p.gather_idx[base + __popcll(same & below)] = f;
+        if (lane == jl) next_pos += __popcll(same);
       }
     }
   }
