@@ -96,7 +96,8 @@ ditron_status_t ditron_set_num_nodes(int nnodes);
 ditron_status_t ditron_tile_row_order(int op, int m, int block_m, int world, int nnodes, int rank, int* out);
 
 /* Tile shape and ordering parameters the library will use for a problem, so that a test can
- * evaluate the schedule independently.  op: 0 = ag_gemm, 1 = gemm_rs, 2 = moe grouped gemm.
+ * evaluate the schedule independently.  op: 0 = ag_gemm, 1 = gemm_rs, 2 = moe grouped gemm
+ * (m = max_rows; only BLOCK_M is fixed, the column block is chosen per call and reported as 0).
  * out[0]=BLOCK_M out[1]=BLOCK_N out[2]=GROUP_SIZE_M out[3]=chiplets used by the work-group
  * remap (0 = no remap) out[4]=tiles per chiplet per block out[5]=number of tiles
  * (ag_gemm / gemm_rs) out[6]=threads per work-group out[7]=reserved (0). */

@@ -66,8 +66,7 @@ __global__ __launch_bounds__(T::THREADS) void ag_gemm_kernel(const AgGemmParams 
   auto b_row = [=](int r) { return (uint32_t)min(n0 + r, N - 1) * row_bytes; };
   f32x16_t acc[T::NI][T::MI];
   gemm_mainloop<T>(acc, p.workspace, a_row, p.b, b_row, p.k, lds);
-  if constexpr (T::kSchedule == 1) store_tile_bf16_lds(acc, p.c, (size_t)p.n, m0, n0, M, N, lds);
-  else store_tile_bf16<T>(acc, p.c, (size_t)p.n, m0, n0, M, N, p.a_scales, p.m_per_rank, p.b_scales);
+  store_tile_bf16<T>(acc, p.c, (size_t)p.n, m0, n0, M, N, lds);
 }
 
 template <class T>

@@ -45,17 +45,18 @@ extern "C" ditron_status_t ditron_tile_config(int op, int m, int n, int k, int d
   if (dtype != DITRON_BF16 && dtype != DITRON_FP8_E4M3) return DITRON_ERR_INVALID_ARG;
   if (dtype == DITRON_FP8_E4M3 && op != 0) return DITRON_ERR_UNSUPPORTED;
   TileChoice t = dtype == DITRON_FP8_E4M3 ? choose_tile_fp8(m, n, k) : choose_tile(m, n, k);
-  if (op == 2) {  // the grouped GEMM always uses the small tile; m is max_rows
+  if (op == 2) {  // the grouped GEMM has its own row tile; its column block is chosen per call; m is max_rows
     t.big = false;
-    t.block_m = t.block_n = TileSmall::BM;
-    t.threads = TileSmall::THREADS;
+    t.block_m = kMoeBlockM;
+    t.block_n = 0;
+    t.threads = 256;
   }
   out[0] = t.block_m;
   out[1] = t.block_n;
   out[2] = t.group_m;
   out[3] = t.num_xcd;
   out[4] = t.per_xcd;
-  out[5] = cdiv(m, t.block_m) * cdiv(n, t.block_n);
+  out[5] = t.block_n ? cdiv(m, t.block_m) * cdiv(n, t.block_n) : 0;
   out[6] = t.threads;
   out[7] = 0;
   return DITRON_OK;

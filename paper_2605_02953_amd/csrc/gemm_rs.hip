@@ -73,8 +73,7 @@ __global__ __launch_bounds__(T::THREADS) void gemm_rs_kernel(const GemmRsParams 
   auto b_row = [=](int r) { return (uint32_t)min(n0 + r, N - 1) * row_bytes; };
   f32x16_t acc[T::NI][T::MI];
   gemm_mainloop<T>(acc, p.a, a_row, p.b, b_row, p.k, lds);
-  if constexpr (T::kSchedule == 1) store_tile_bf16_lds(acc, p.gemm_out, (size_t)p.n, m0, n0, M, N, lds);
-  else store_tile_bf16<T>(acc, p.gemm_out, (size_t)p.n, m0, n0, M, N, nullptr, 1, nullptr);
+  store_tile_bf16<T>(acc, p.gemm_out, (size_t)p.n, m0, n0, M, N, lds);
 
   // segment completion: one lane per touched segment
   __syncthreads();

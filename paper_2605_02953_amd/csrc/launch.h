@@ -8,11 +8,26 @@
 
 namespace ditron {
 
-// 256x256 output tile, 4 waves as 2 x 2: 128x128 per wave, register-staged operands.
-typedef GemmTile4W TileBig;
-// 128x128 output tile, 8 waves as 2 x 4: 64x32 per wave, 64 KiB of LDS; for problems with
-// too few 256x256 tiles to fill the chip.
-typedef GemmTile<128, 128, 2, 4> TileSmall;
+// 256x256 output tile: 128x128 per wave, 128 KiB of LDS.
+typedef GemmTile4W<256, 256> TileBig;
+// 128x128 output tile: 64x64 per wave, 64 KiB of LDS; for problems with too few 256x256 tiles
+// to fill the chip.
+typedef GemmTile4W<128, 128> TileSmall;
+// The MoE grouped GEMM: 4 waves as 2 x 2 on a 128-row tile (keeps the padding of an expert's
+// last row tile small); the column block is chosen per call.
+constexpr int kMoeBlockM = 128;
+// Column block of the grouped GEMM.  The number of row tiles is only known on the device, so
+// the host works from the expectation under even routing (rows / 128 plus half a tile of
+// padding per expert): the narrowest block whose tile count still fits one chip-wide round
+// with a fifth to spare, so that a few tiles more than expected do not start a second round;
+// if not even the widest fits, the widest (fewest loads per flop).
+inline int choose_moe_block_n(long expected_rows, int num_local_experts, int inter) {
+  const long row_tiles = cdiv((int)std::min<long>(expected_rows, 1 << 30), kMoeBlockM) + (num_local_experts + 1) / 2;
+  const int widths[3] = {128, 192, 256};
+  for (int w : widths)
+    if (row_tiles * cdiv(inter, w) * 5 <= 256 * 4) return w;
+  return 256;
+}
 
 struct TileChoice {
   bool big;

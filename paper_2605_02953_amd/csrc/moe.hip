@@ -241,18 +241,27 @@ __global__ __launch_bounds__(T::THREADS) void moe_grouped_gemm_kernel(const MoeG
   auto b_row = [=](int r) { return (uint32_t)min(n0 + r, N - 1) * row_bytes; };
   f32x16_t acc[T::NI][T::MI];
   gemm_mainloop<T>(acc, p.workspace, a_row, wj, b_row, p.hidden, lds);
-  store_tile_bf16<T>(acc, p.y, (size_t)p.inter, p0, n0, p_end, N, nullptr, 1, nullptr);
+  store_tile_bf16<T>(acc, p.y, (size_t)p.inter, p0, n0, p_end, N, lds);
 }
 
 }  // namespace ditron
 
 using namespace ditron;
 
-typedef TileSmall MoeTile;
 
 extern "C" int ditron_moe_max_tiles(int max_rows, int num_local_experts) {
   if (max_rows < 0 || num_local_experts < 0) return 0;
-  return cdiv(max_rows, MoeTile::BM) + num_local_experts;
+  return cdiv(max_rows, kMoeBlockM) + num_local_experts;
+}
+
+template <class T>
+static ditron_status_t launch_moe_gemm(MoeGemmParams& g, int max_tiles, hipStream_t s) {
+  g.npn = cdiv(g.inter, T::BN);
+  auto kern = moe_grouped_gemm_kernel<T>;
+  if (!set_dynamic_lds((const void*)kern, T::LDS_BYTES)) return DITRON_ERR_HIP;
+  const unsigned grid = (unsigned)(g.num_producers + max_tiles * g.npn);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(T::THREADS), T::LDS_BYTES, s, g);
+  return hipGetLastError() == hipSuccess ? DITRON_OK : DITRON_ERR_HIP;
 }
 
 extern "C" ditron_status_t ditron_moe_ag_grouped_gemm(
@@ -307,7 +316,7 @@ extern "C" ditron_status_t ditron_moe_ag_grouped_gemm(
   r.max_tiles = max_tiles;
   r.world = world;
   r.rank = rank;
-  r.block_m = MoeTile::BM;
+  r.block_m = kMoeBlockM;
   hipLaunchKernelGGL(moe_route_kernel, dim3(1), dim3(kRouteThreads), 0, s, r);
   if (hipGetLastError() != hipSuccess) return DITRON_ERR_HIP;
 
@@ -331,15 +340,15 @@ extern "C" ditron_status_t ditron_moe_ag_grouped_gemm(
   g.top_k = top_k;
   g.world = world;
   g.max_tiles = max_tiles;
-  g.npn = cdiv(inter, MoeTile::BN);
   g.epoch = epoch;
   const ProducerPlan pl = plan_producers((size_t)world * tokens_per_rank * hidden * 2, world);
   g.num_producers = emulate ? pl.producers : 0;
   g.teams = pl.teams;
   g.spin_limit = g_spin_limit;
-  auto kern = moe_grouped_gemm_kernel<MoeTile>;
-  if (!set_dynamic_lds((const void*)kern, MoeTile::LDS_BYTES)) return DITRON_ERR_HIP;
-  const unsigned grid = (unsigned)(g.num_producers + max_tiles * g.npn);
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(MoeTile::THREADS), MoeTile::LDS_BYTES, s, g);
-  return hipGetLastError() == hipSuccess ? DITRON_OK : DITRON_ERR_HIP;
+  const long expected_rows = (long)world * tokens_per_rank * top_k * num_local_experts / num_experts;
+  switch (choose_moe_block_n(expected_rows, num_local_experts, inter)) {
+    case 128: return launch_moe_gemm<GemmTile4W<kMoeBlockM, 128>>(g, max_tiles, s);
+    case 192: return launch_moe_gemm<GemmTile4W<kMoeBlockM, 192>>(g, max_tiles, s);
+    default: return launch_moe_gemm<GemmTile4W<kMoeBlockM, 256>>(g, max_tiles, s);
+  }
 }

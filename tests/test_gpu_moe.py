@@ -69,6 +69,8 @@ def _run_and_check(B, cfg, xs, ids, w, max_rows, integer, order=None, block_m=12
     (8, 128, 256, 264, 64, 2, 8, 5, True),
     (8, 128, 512, 384, 16, 2, 16, 3, False),    # every expert local (the paper's placement)
     (1, 300, 64, 64, 3, 1, 3, 0, True),
+    (8, 256, 64, 1544, 8, 2, 8, 2, True),       # 4096 rows x 1544 columns: the 256-column block, ragged last block
+    (8, 128, 64, 1400, 16, 2, 16, 6, True),     # 2048 rows x 1400 columns: the 192-column block, ragged last block
 ])
 def test_moe_end_to_end(B, world, t_r, hidden, inter, experts, top_k, local, rank, integer):
     cfg = synth.CONFIGS[4].scaled(world=world, tokens_per_rank=t_r, k=hidden, n=inter, num_experts=experts,
