@@ -57,7 +57,9 @@ typedef enum {
 
 typedef enum { DITRON_BF16 = 0, DITRON_FP8_E4M3 = 1 } ditron_dtype_t;
 
-/* Physical layout of the logical [k, n] right-hand matrix. */
+/* Physical layout of the logical [k, n] right-hand matrix.  The bf16 AllGather-GEMM and
+ * GEMM-ReduceScatter take both; the fp8 and MoE operators take DITRON_B_NK only (UNSUPPORTED
+ * otherwise). */
 typedef enum {
   DITRON_B_KN = 0, /* stored [k, n], n contiguous */
   DITRON_B_NK = 1  /* stored [n, k], k contiguous: the weight layout of the paper's launchers */

@@ -63,9 +63,13 @@ __global__ __launch_bounds__(T::THREADS) void ag_gemm_kernel(const AgGemmParams 
   const uint32_t row_bytes = (uint32_t)p.k * 2u;
   const int M = p.m, N = p.n;
   auto a_row = [=](int r) { return (uint32_t)min(m0 + r, M - 1) * row_bytes; };
-  auto b_row = [=](int r) { return (uint32_t)min(n0 + r, N - 1) * row_bytes; };
   f32x16_t acc[T::NI][T::MI];
-  gemm_mainloop<T>(acc, p.workspace, a_row, p.b, b_row, p.k, lds);
+  if constexpr (T::B_KN) {
+    gemm_mainloop<T>(acc, p.workspace, a_row, p.b, BColumns{(uint32_t)N * 2u, n0, N}, p.k, lds);
+  } else {
+    auto b_row = [=](int r) { return (uint32_t)min(n0 + r, N - 1) * row_bytes; };
+    gemm_mainloop<T>(acc, p.workspace, a_row, p.b, b_row, p.k, lds);
+  }
   store_tile_bf16<T>(acc, p.c, (size_t)p.n, m0, n0, M, N, lds);
 }
 
@@ -108,7 +112,6 @@ extern "C" ditron_status_t ditron_ag_gemm(const void* const* a_shards, const voi
   }
   if (dtype == DITRON_FP8_E4M3) return ditron_ag_gemm_fp8(a_shards, b, b_layout, c, a_scales, b_scales, workspace, signals, status,
                                                           schedule_out, arrival_order, m_per_rank, n, k, world, rank, epoch, flags, stream);
-  if (b_layout != DITRON_B_NK) return DITRON_ERR_UNSUPPORTED;
   if (k % 8 != 0 || n % 8 != 0) return DITRON_ERR_UNSUPPORTED;
   if (!fits_32bit((size_t)m_per_rank * world, k, 2) || !fits_32bit(n, k, 2)) return DITRON_ERR_UNSUPPORTED;
 
@@ -144,6 +147,10 @@ extern "C" ditron_status_t ditron_ag_gemm(const void* const* a_shards, const voi
   const ProducerPlan pl = plan_producers((size_t)p.m * k * 2, world);
   p.num_producers = emulate ? pl.producers : 0;
   p.teams = pl.teams;
+  if (b_layout == DITRON_B_KN) {
+    if (tc.big) return launch_ag<TileBigKN>(p, (hipStream_t)stream);
+    return launch_ag<TileSmallKN>(p, (hipStream_t)stream);
+  }
   if (tc.big) return launch_ag<TileBig>(p, (hipStream_t)stream);
   return launch_ag<TileSmall>(p, (hipStream_t)stream);
 }

@@ -61,14 +61,24 @@ __device__ __forceinline__ void barrier_no_drain() {
 // (plain loads of full 128-byte lines stream from L2 faster than the direct-to-LDS form).  LDS
 // holds two stages of one 64-deep K tile each, rows of 128 bytes (measured free of bank
 // conflicts for both the fragment reads and the staging stores).
-template <int BM_, int BN_>
+//
+// B_KN: B is stored [K, N] (N contiguous) instead of [N, K].  Its K tile is then staged as it
+// lies in memory, 64 rows of BN elements with a pitch of 2 BN + 64 bytes, and the MFMA
+// operand (eight consecutive k of one column per lane) is assembled by two transposing LDS
+// reads (ds_read_b64_tr_b16: inside each group of 16 lanes, lane i receives element i % 4 of
+// the 8-byte chunks addressed by lanes i/4, 4 + i/4, 8 + i/4, 12 + i/4; measured).  The pitch
+// makes the four rows a group touches, and the two groups that share a cycle, hit distinct banks.
+template <int BM_, int BN_, bool B_KN_ = false>
 struct GemmTile4W {
   static_assert((BM_ == 256 || BM_ == 128) && (BN_ == 256 || BN_ == 192 || BN_ == 128), "supported tile sides");
+  static_assert(!B_KN_ || BN_ != 192, "a [K, N] row of 192 elements does not split evenly over the loading lanes");
+  static constexpr bool B_KN = B_KN_;
   static constexpr int BM = BM_, BN = BN_, BK = 64, NSTAGE = 2;
   static constexpr int WAVES_M = 2, WAVES_N = 2, NWAVES = 4, THREADS = 256;
   static constexpr int WTM = BM / 2, WTN = BN / 2, MI = WTM / 32, NI = WTN / 32;
   static constexpr int ROW_BYTES = 128;
-  static constexpr int A_BYTES = BM * ROW_BYTES, B_BYTES = BN * ROW_BYTES;
+  static constexpr int PB = BN * 2 + 64;                      // B_KN: bytes between two k rows of the staged B tile
+  static constexpr int A_BYTES = BM * ROW_BYTES, B_BYTES = B_KN ? BK * PB : BN * ROW_BYTES;
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
   static constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
   static constexpr int ROWS_PER_PASS = THREADS / 8;           // 32 rows per pass of 16-byte loads
@@ -76,14 +86,15 @@ struct GemmTile4W {
   // The K loop is written as slots of two MFMAs (one B fragment, two A fragments).
   static constexpr int PAIRS = MI * NI / 2;                   // slots per 16-deep step
   static constexpr int SLOTS = 4 * PAIRS;                     // slots per 64-deep K tile
-  static constexpr int READS = MI + NI;                       // fragment reads per step
+  static constexpr int B_READS = B_KN ? 2 : 1;                // LDS reads per B fragment
+  static constexpr int READS = MI + B_READS * NI;             // fragment reads per step
   static constexpr int HALF = (PAIRS + 1) / 2;                // slots of a step that take its reads when they must be early
 };
 
 template <class T>
 struct Frags4W {
   bf16x8_t a[T::MI];
-  bf16x8_t b[T::NI];
+  bf16x4_t b[T::NI][2];   // low and high four k of the fragment ([N, K] storage fills both with one read)
 };
 
 template <int I, int N, class F>
@@ -94,15 +105,33 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
-// Fragment J of step KS (0..3) of the K tile staged at `st`.  koff[KS] is the lane's swizzled
-// chunk offset for that step.  The order (b0, a0..a[MI-1], b1..b[NI-1]) is the order in which
-// mma_pair consumes them.
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+
+// B fragment NI_ of step KS: READ 0 (and, for [K, N] storage, READ 1 for the upper four k).
+// b_off is the lane's base inside the stage: for [N, K] storage the row of its column, for
+// [K, N] storage the chunk it addresses in the transposing read.
+template <class T, int KS, int NI_, int READ>
+__device__ __forceinline__ void read_b(Frags4W<T>& f, const char* st, int b_off, const int (&koff)[4]) {
+  if constexpr (T::B_KN) {
+    const char* src = st + b_off + NI_ * 64 + (KS * 16 + READ * 4) * T::PB;
+    const s16x4_t v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)DITRON_LDS(src));
+    f.b[NI_][READ] = __builtin_bit_cast(bf16x4_t, v);
+  } else {
+    const bf16x8_t v = *(const bf16x8_t*)(st + b_off + NI_ * 32 * 128 + koff[KS]);
+    f.b[NI_][0] = __builtin_shufflevector(v, v, 0, 1, 2, 3);
+    f.b[NI_][1] = __builtin_shufflevector(v, v, 4, 5, 6, 7);
+  }
+}
+
+// Fragment read J of step KS (0..3) of the K tile staged at `st`.  koff[KS] is the lane's
+// swizzled chunk offset for that step.  The order (b0, a0..a[MI-1], b1..b[NI-1]) is the order
+// in which mma_pair consumes them.
 template <class T, int KS, int J>
 __device__ __forceinline__ void read_one(Frags4W<T>& f, const char* st, int a_off, int b_off, const int (&koff)[4]) {
-  const int off = koff[KS];
-  if constexpr (J == 0) f.b[0] = *(const bf16x8_t*)(st + b_off + off);
-  else if constexpr (J <= T::MI) f.a[J - 1] = *(const bf16x8_t*)(st + a_off + (J - 1) * 32 * 128 + off);
-  else f.b[J - T::MI] = *(const bf16x8_t*)(st + b_off + (J - T::MI) * 32 * 128 + off);
+  constexpr int BR = T::B_READS;
+  if constexpr (J < BR) read_b<T, KS, 0, J>(f, st, b_off, koff);
+  else if constexpr (J < BR + T::MI) f.a[J - BR] = *(const bf16x8_t*)(st + a_off + (J - BR) * 32 * 128 + koff[KS]);
+  else read_b<T, KS, 1 + (J - BR - T::MI) / BR, (J - BR - T::MI) % BR>(f, st, b_off, koff);
 }
 // reads [LO, HI) of a step
 template <class T, int KS, int LO, int HI>
@@ -113,18 +142,28 @@ __device__ __forceinline__ void read_range(Frags4W<T>& f, const char* st, int a_
 template <class T, int P>
 __device__ __forceinline__ void mma_pair(f32x16_t (&acc)[T::NI][T::MI], const Frags4W<T>& f) {
   constexpr int ni = P / (T::MI / 2), mi = (P % (T::MI / 2)) * 2;
-  acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[ni], f.a[mi], acc[ni][mi], 0, 0, 0);
-  acc[ni][mi + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[ni], f.a[mi + 1], acc[ni][mi + 1], 0, 0, 0);
+  const bf16x8_t b = __builtin_shufflevector(f.b[ni][0], f.b[ni][1], 0, 1, 2, 3, 4, 5, 6, 7);
+  acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, f.a[mi], acc[ni][mi], 0, 0, 0);
+  acc[ni][mi + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, f.a[mi + 1], acc[ni][mi + 1], 0, 0, 0);
 }
+
+// Where the columns of a B stored [K, N] are: the mainloop's `b_row` argument for B_KN tiles.
+struct BColumns {
+  uint32_t ld_bytes;   // bytes between two k rows (2 N)
+  int n0, n;           // first column of the tile, number of columns of B
+};
 
 template <class T>
 struct Stager4W {
   static constexpr int kOutOfRange = 0x7ffffff0;
+  static constexpr int KN_LANES = T::BN / 8;              // B_KN: lanes that cover one k row of the tile
+  static constexpr int KN_ROWS = T::THREADS / KN_LANES;   // B_KN: k rows per pass
   __amdgpu_buffer_rsrc_t a_rsrc, b_rsrc;
   int off[T::LOADS];
   u32x4_t reg[T::LOADS];
   int lds_off;    // byte offset inside an operand area of a stage, pass 0
   int kc;
+  int kn_row, kn_lds_off, kn_tile_bytes;   // B_KN: the lane's k row in pass 0, its LDS offset, bytes per K tile of B
 
   template <class ARow, class BRow>
   __device__ __forceinline__ void init(const char* a_base, ARow a_row, const char* b_base, BRow b_row) {
@@ -135,17 +174,35 @@ struct Stager4W {
     lds_off = r * T::ROW_BYTES + ((c ^ swz128(r)) * 16);
 #pragma unroll
     for (int i = 0; i < T::A_LOADS; ++i) off[i] = (int)(a_row(r + i * T::ROWS_PER_PASS) + (uint32_t)(c * 16));
+    if constexpr (T::B_KN) {
+      // lane (k row, group of 8 columns): 16 bytes = 8 columns of one k; a wave covers whole rows of the tile
+      kn_row = threadIdx.x / KN_LANES;
+      const int n8 = threadIdx.x % KN_LANES;
+      const int col = b_row.n0 + n8 * 8;
+      kn_lds_off = kn_row * T::PB + n8 * 16;
+      kn_tile_bytes = (int)(b_row.ld_bytes * 64u);
 #pragma unroll
-    for (int i = 0; i < T::B_LOADS; ++i)
-      off[T::A_LOADS + i] = (int)(b_row(r + i * T::ROWS_PER_PASS) + (uint32_t)(c * 16));
+      for (int i = 0; i < T::B_LOADS; ++i)
+        off[T::A_LOADS + i] = col < b_row.n ? (int)((uint32_t)(kn_row + i * KN_ROWS) * b_row.ld_bytes + (uint32_t)col * 2u)
+                                            : kOutOfRange;   // columns past N read as zero
+    } else {
+#pragma unroll
+      for (int i = 0; i < T::B_LOADS; ++i)
+        off[T::A_LOADS + i] = (int)(b_row(r + i * T::ROWS_PER_PASS) + (uint32_t)(c * 16));
+    }
   }
 
   // `kt` must be a valid K tile; a chunk past K reads as zero (lane offset pushed out of range)
   template <int I>
   __device__ __forceinline__ void fetch_one(int kt, int K) {
-    const bool dead = kt * 64 + kc >= K;
-    const int v = dead ? kOutOfRange : off[I];
-    reg[I] = __builtin_amdgcn_raw_buffer_load_b128(I < T::A_LOADS ? a_rsrc : b_rsrc, v, kt * 128, 0);
+    if constexpr (T::B_KN && I >= T::A_LOADS) {
+      const bool dead = kt * 64 + kn_row + (I - T::A_LOADS) * KN_ROWS >= K;
+      reg[I] = __builtin_amdgcn_raw_buffer_load_b128(b_rsrc, dead ? kOutOfRange : off[I], kt * kn_tile_bytes, 0);
+    } else {
+      const bool dead = kt * 64 + kc >= K;
+      const int v = dead ? kOutOfRange : off[I];
+      reg[I] = __builtin_amdgcn_raw_buffer_load_b128(I < T::A_LOADS ? a_rsrc : b_rsrc, v, kt * 128, 0);
+    }
   }
   template <int LO, int HI>
   __device__ __forceinline__ void fetch_range(int kt, int K) {
@@ -157,7 +214,8 @@ struct Stager4W {
   __device__ __forceinline__ void commit_one(char* stage) const {
     constexpr int area = I < T::A_LOADS ? 0 : T::A_BYTES;
     constexpr int pass = I < T::A_LOADS ? I : I - T::A_LOADS;
-    *(u32x4_t*)(stage + area + lds_off + pass * T::ROWS_PER_PASS * T::ROW_BYTES) = reg[I];
+    if constexpr (T::B_KN && I >= T::A_LOADS) *(u32x4_t*)(stage + area + kn_lds_off + pass * KN_ROWS * T::PB) = reg[I];
+    else *(u32x4_t*)(stage + area + lds_off + pass * T::ROWS_PER_PASS * T::ROW_BYTES) = reg[I];
   }
   template <int LO, int HI>
   __device__ __forceinline__ void commit_range(char* stage) const {
@@ -184,7 +242,12 @@ __device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[T::NI][T::MI], con
   const int wm = wave / 2, wn = wave % 2;
   const int lr = lane & 31, lh = lane >> 5;
   const int a_off = (wm * T::WTM + lr) * T::ROW_BYTES;
-  const int b_off = T::A_BYTES + (wn * T::WTN + lr) * T::ROW_BYTES;
+  // [N, K] storage: the row of the lane's column.  [K, N] storage: the 8-byte chunk the lane
+  // addresses in the transposing read: inside its group of 16 lanes, lane r points at k row r/4,
+  // columns 4 (r % 4) .. +3; the group serves 16 columns, the two halves of the wave 8 k each.
+  const int b_off = T::B_KN ? T::A_BYTES + (((lane & 15) >> 2) + lh * 8) * T::PB +
+                                  (wn * T::WTN + ((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2
+                            : T::A_BYTES + (wn * T::WTN + lr) * T::ROW_BYTES;
   int koff[4];
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) koff[ks] = ((ks * 2 + lh) ^ swz128(lr)) * 16;

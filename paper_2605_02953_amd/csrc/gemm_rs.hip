@@ -70,9 +70,13 @@ __global__ __launch_bounds__(T::THREADS) void gemm_rs_kernel(const GemmRsParams 
   const uint32_t row_bytes = (uint32_t)p.k * 2u;
   const int M = p.m, N = p.n;
   auto a_row = [=](int r) { return (uint32_t)min(m0 + r, M - 1) * row_bytes; };
-  auto b_row = [=](int r) { return (uint32_t)min(n0 + r, N - 1) * row_bytes; };
   f32x16_t acc[T::NI][T::MI];
-  gemm_mainloop<T>(acc, p.a, a_row, p.b, b_row, p.k, lds);
+  if constexpr (T::B_KN) {
+    gemm_mainloop<T>(acc, p.a, a_row, p.b, BColumns{(uint32_t)N * 2u, n0, N}, p.k, lds);
+  } else {
+    auto b_row = [=](int r) { return (uint32_t)min(n0 + r, N - 1) * row_bytes; };
+    gemm_mainloop<T>(acc, p.a, a_row, p.b, b_row, p.k, lds);
+  }
   store_tile_bf16<T>(acc, p.gemm_out, (size_t)p.n, m0, n0, M, N, lds);
 
   // segment completion: one lane per touched segment
@@ -270,7 +274,6 @@ extern "C" ditron_status_t ditron_gemm_rs(const void* a, const void* b, int b_la
   if (emulate == external) return DITRON_ERR_INVALID_ARG;
   if ((flags & DITRON_DUMP_SCHEDULE) && !schedule_out) return DITRON_ERR_INVALID_ARG;
   if (b_layout != DITRON_B_KN && b_layout != DITRON_B_NK) return DITRON_ERR_INVALID_ARG;
-  if (b_layout != DITRON_B_NK) return DITRON_ERR_UNSUPPORTED;
   if (k_local % 8 != 0 || n % 8 != 0) return DITRON_ERR_UNSUPPORTED;
   if (!fits_32bit(m, k_local, 2) || !fits_32bit(n, k_local, 2)) return DITRON_ERR_UNSUPPORTED;
 
@@ -316,7 +319,12 @@ extern "C" ditron_status_t ditron_gemm_rs(const void* a, const void* b, int b_la
   const ProducerPlan pl = plan_producers((size_t)(world - 1) * m_r * n * 2, (world - 1) * chunks_per_slot);
   p.num_producers = (emulate && world > 1) ? pl.producers : 0;
   p.teams = pl.teams;
-  ditron_status_t st = tc.big ? launch_rs<TileBig>(p, (hipStream_t)stream) : launch_rs<TileSmall>(p, (hipStream_t)stream);
+  ditron_status_t st;
+  if (b_layout == DITRON_B_KN) {
+    st = tc.big ? launch_rs<TileBigKN>(p, (hipStream_t)stream) : launch_rs<TileSmallKN>(p, (hipStream_t)stream);
+  } else {
+    st = tc.big ? launch_rs<TileBig>(p, (hipStream_t)stream) : launch_rs<TileSmall>(p, (hipStream_t)stream);
+  }
   if (st != DITRON_OK) return st;
 
   ReduceParams r{};

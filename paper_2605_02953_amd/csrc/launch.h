@@ -13,6 +13,9 @@ typedef GemmTile4W<256, 256> TileBig;
 // 128x128 output tile: 64x64 per wave, 64 KiB of LDS; for problems with too few 256x256 tiles
 // to fill the chip.
 typedef GemmTile4W<128, 128> TileSmall;
+// The same two for B stored [K, N].
+typedef GemmTile4W<256, 256, true> TileBigKN;
+typedef GemmTile4W<128, 128, true> TileSmallKN;
 // The MoE grouped GEMM: 4 waves as 2 x 2 on a 128-row tile (keeps the padding of an expert's
 // last row tile small); the column block is chosen per call.
 constexpr int kMoeBlockM = 128;

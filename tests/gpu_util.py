@@ -61,13 +61,13 @@ class GemmRsRun:
         self.status = torch.zeros(B.STATUS_WORDS, dtype=torch.int32, device="cuda")
         self.epoch = 0
 
-    def __call__(self, a_dev, b_dev, peers, rank, order=None, flags=None, schedule=None, stream=None):
+    def __call__(self, a_dev, b_dev, peers, rank, order=None, flags=None, schedule=None, stream=None, b_layout=None):
         B = self.B
         self.epoch += 1
         flags = B.EMULATE_PRODUCER if flags is None else flags
         if schedule is not None:
             flags |= B.DUMP_SCHEDULE
-        return B.gemm_rs(a_dev, b_dev, B.B_NK, self.gemm_out, peers, self.scatter, self.out, self.signals,
+        return B.gemm_rs(a_dev, b_dev, B.B_NK if b_layout is None else b_layout, self.gemm_out, peers, self.scatter, self.out, self.signals,
                          self.status, schedule, order, self.m, self.n, self.k, self.world, rank, self.chunks,
                          self.epoch, flags, stream)
 

@@ -22,16 +22,16 @@ def B():
 from gpu_util import to_dev, bits, nk, AgGemmRun  # noqa: E402
 
 
-def _run(B, cfg, shards, b_kn, rank=None, order=None, want_schedule=False):
+def _run(B, cfg, shards, b_kn, rank=None, order=None, want_schedule=False, kn=False):
     rank = cfg.rank if rank is None else rank
     run = AgGemmRun(B, cfg.world, cfg.m_per_rank, cfg.n, cfg.k)
     sh = [to_dev(s) for s in shards]
-    bd = to_dev(nk(b_kn))
+    bd = to_dev(b_kn if kn else nk(b_kn))     # kn: B handed over as it is stored, [k, n]
     sched = None
     if want_schedule:
         st, tc = B.tile_config(0, cfg.m, cfg.n, cfg.k)
         sched = torch.full((4 * tc["ntiles"],), -1, dtype=torch.int32, device="cuda")
-    st = run(sh, bd, rank, order=order, schedule=sched)
+    st = run(sh, bd, rank, order=order, schedule=sched, b_layout=B.B_KN if kn else B.B_NK)
     assert st == B.OK, B.status_string(st)
     torch.cuda.synchronize()
     assert run.status.cpu().tolist()[0] == 0
@@ -71,12 +71,13 @@ def _check_schedule(B, cfg, rank, sched):
     (8, 505, 3080, 200),     # 256x256 tiles with ragged edges on every side, 208 tiles
     (3, 64, 8, 8),           # minimum contraction and width
 ])
-def test_integer_inputs_are_bit_exact(B, world, m_r, n, k):
+@pytest.mark.parametrize("kn", [False, True], ids=["b_nk", "b_kn"])
+def test_integer_inputs_are_bit_exact(B, world, m_r, n, k, kn):
     # products and sums of small integers are exact in fp32, so the only rounding is the final
     # bf16 one: the GPU must match the oracle bit for bit, whatever the tile or lane layout
     cfg = synth.CONFIGS[2].scaled(world=world, m_per_rank=m_r, n=n, k=k, rank=world - 1)
     shards, b = synth.ag_gemm_inputs(cfg, integer=True)
-    c, ws, sched, _ = _run(B, cfg, shards, b, want_schedule=True)
+    c, ws, sched, _ = _run(B, cfg, shards, b, want_schedule=True, kn=kn)
     want = formats.encode_bf16_rne(oag.ag_gemm(shards, b).astype(np.float32))
     assert np.array_equal(ws, oag.gather(shards))
     assert np.array_equal(c, want)
@@ -84,10 +85,11 @@ def test_integer_inputs_are_bit_exact(B, world, m_r, n, k):
 
 
 @pytest.mark.parametrize("world,m_r,n,k", [(4, 200, 264, 328), (8, 505, 3080, 456)])
-def test_normal_inputs_within_tolerance(B, world, m_r, n, k):
+@pytest.mark.parametrize("kn", [False, True], ids=["b_nk", "b_kn"])
+def test_normal_inputs_within_tolerance(B, world, m_r, n, k, kn):
     cfg = synth.CONFIGS[2].scaled(world=world, m_per_rank=m_r, n=n, k=k, rank=1)
     shards, b = synth.ag_gemm_inputs(cfg)
-    c, ws, _, _ = _run(B, cfg, shards, b)
+    c, ws, _, _ = _run(B, cfg, shards, b, kn=kn)
     _check(c, oag.ag_gemm(shards, b))
 
 

@@ -80,7 +80,8 @@ def _check_schedule(B, cfg, rank, sched):
     (2, 192, 384, 512, 3, False),
     (1, 256, 256, 128, 1, True),      # world 1: plain GEMM
 ])
-def test_gemm_rs_end_to_end(B, world, m_r, n, k, chunks, integer):
+@pytest.mark.parametrize("kn", [False, True], ids=["b_nk", "b_kn"])
+def test_gemm_rs_end_to_end(B, world, m_r, n, k, chunks, integer, kn):
     cfg = synth.CONFIGS[3].scaled(world=world, m_per_rank=m_r, n=n, k=k)
     a_list, b_list = synth.gemm_rs_inputs(cfg, integer=integer)
     parts = _all_partials(B, cfg, a_list, b_list)
@@ -93,7 +94,8 @@ def test_gemm_rs_end_to_end(B, world, m_r, n, k, chunks, integer):
         peers = [parts[s][d * m_r:(d + 1) * m_r] for s in range(world)]
         sched = torch.full((4 * tc["ntiles"],), -1, dtype=torch.int32, device="cuda")
         order = None if d % 2 == 0 else [s for s in range(world) if s != d]     # also a non-ring delivery
-        st = run(to_dev(a_list[d]), to_dev(nk(b_list[d])), peers, d, order=order, schedule=sched)
+        b_dev = to_dev(b_list[d] if kn else nk(b_list[d]))      # kn: B handed over as it is stored, [k, n]
+        st = run(to_dev(a_list[d]), b_dev, peers, d, order=order, schedule=sched, b_layout=B.B_KN if kn else B.B_NK)
         _ok(B, st, run)
         ref = ors.gemm_rs(a_list, b_list, d)
         got = bits(run.out)

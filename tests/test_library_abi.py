@@ -75,7 +75,8 @@ def test_ag_gemm_argument_checks(B):
     assert call(arrival_order=[0, 0]) == B.ERR_INVALID_ARG           # not a permutation
     assert call(a_shards=[fake, None]) == B.ERR_INVALID_ARG
     assert call(dtype=9) == B.ERR_INVALID_ARG
-    assert call(b_layout=B.B_KN) == B.ERR_UNSUPPORTED
+    assert call(b_layout=7) == B.ERR_INVALID_ARG
+    assert call(b_layout=B.B_KN, dtype=B.FP8_E4M3) == B.ERR_UNSUPPORTED   # the fp8 operator takes B as [n, k] only
     assert call(k=260) == B.ERR_UNSUPPORTED                          # contraction not a multiple of 8
 
 
