@@ -9,6 +9,7 @@
  *   ditron_gemm_rs              GEMM-ReduceScatter      (paper, Appendix "GEMM Reduce-Scatter")
  *   ditron_moe_ag_grouped_gemm  AllGather + grouped GEMM over local experts
  *                               (paper, kernel list "ag_group_gemm"; Appendix "Swizzle", third listing)
+ *   ditron_gemm_ar              GEMM + AllReduce        (paper, Appendix "GEMM All-Reduce")
  *
  * Conventions common to every entry point
  *   - "device" pointers are GPU global memory (or pinned host memory mapped into the GPU),
@@ -99,7 +100,8 @@ ditron_status_t ditron_tile_row_order(int op, int m, int block_m, int world, int
 
 /* Tile shape and ordering parameters the library will use for a problem, so that a test can
  * evaluate the schedule independently.  op: 0 = ag_gemm, 1 = gemm_rs, 2 = moe grouped gemm
- * (m = max_rows; only BLOCK_M is fixed, the column block is chosen per call and reported as 0).
+ * (m = max_rows; only BLOCK_M is fixed, the column block is chosen per call and reported as 0),
+ * 3 = gemm_ar (out[4] is not used by it: a chiplet receives consecutive tiles of each round).
  * out[0]=BLOCK_M out[1]=BLOCK_N out[2]=GROUP_SIZE_M out[3]=chiplets used by the work-group
  * remap (0 = no remap) out[4]=tiles per chiplet per block out[5]=number of tiles
  * (ag_gemm / gemm_rs) out[6]=threads per work-group out[7]=reserved (0). */
@@ -170,6 +172,42 @@ ditron_status_t ditron_gemm_rs(const void* a, const void* b, int b_layout, void*
                                const int* arrival_order, int m, int n, int k_local, int world,
                                int rank, int chunks_per_slot, int32_t epoch, unsigned flags,
                                void* stream);
+
+/*
+ * GEMM + AllReduce, one-shot:  out[m, n] = sum_s P_s,  P_rank = A . B computed here.
+ *
+ * Paper: `gemm_allreduce_op`, `kernel_persistent_gemm_notify` and `consumer_all_reduce_kernel`
+ * of Appendix "GEMM All-Reduce", the branch that reduces every tile on every rank.  A fixed set
+ * of work-groups loops over the tiles of P_rank in the grouped order (work-group g takes
+ * positions g, g + G, ...), stores each tile into `gemm_out` (the buffer the peers read) and
+ * raises that tile's flag.  The consumer takes the tiles in the same order, waits for the
+ * tile's flag of every rank, adds the `world` published tiles in fp32 in rank order (the paper
+ * reduces through the switch; here in software) and rounds once to bf16.  Consumer and GEMM
+ * share one launch; ditron_set_comm_wgs sets how many compute units are kept for the consumer
+ * (multiple of 8, at most 192; -1 = chosen per call by a cost model, the default).
+ *
+ *  a             device [m, k_local] bf16
+ *  b, b_layout   device, logical [k_local, n] bf16
+ *  gemm_out      device out [m, n] bf16: this rank's partial product
+ *  peer_partials host array of `world` device pointers; entry s != rank is rank s's published
+ *                partial [m, n] bf16, read in place (entry `rank` is ignored); NULL if world = 1.
+ *                With DITRON_EXTERNAL_PRODUCER a tile of it must be complete before its flag
+ *                is raised.
+ *  out           device out [m, n] bf16, distinct from every partial
+ *  signals       device int32[ditron_signal_words(world, tiles)], tiles as reported by
+ *                ditron_tile_config(3, ...): the flag of (rank s, tile (pid_m, pid_n)) is word
+ *                2*world + s*tiles + pid_m*ceil(n / BLOCK_N) + pid_n; words 0 and 1 are the
+ *                consumer's queue counters, left at zero by every call
+ *  schedule_out  device int32[4 * tiles] or NULL; with DITRON_DUMP_SCHEDULE the record of
+ *                schedule position t is (pid_m, pid_n, GEMM work-group, round)
+ *  DITRON_EMULATE_PRODUCER: the call raises the peers' tile flags itself, in schedule order.
+ *  m need not be a multiple of world.
+ */
+ditron_status_t ditron_gemm_ar(const void* a, const void* b, int b_layout, void* gemm_out,
+                               const void* const* peer_partials, void* out, int32_t* signals,
+                               int32_t* status, int32_t* schedule_out, int m, int n, int k_local,
+                               int world, int rank, int32_t epoch, unsigned flags, void* stream);
+ditron_status_t ditron_set_comm_wgs(int wgs);
 
 /*
  * The reduction step of GEMM-ReduceScatter on its own: out = bf16( sum_s fp32(slots[s]) ),

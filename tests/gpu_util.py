@@ -99,3 +99,32 @@ class MoeRun:
                                      self.records, self.workspace, self.signals, self.status, order, t_r, hidden,
                                      inter, ne, top_k, expert_begin, nl, max_rows, world, rank, self.epoch, flags,
                                      stream)
+
+
+class GemmArRun:
+    """Buffers for repeated ditron_gemm_ar calls on one problem shape."""
+
+    def __init__(self, B, world, m, n, k):
+        self.B, self.world, self.m, self.n, self.k = B, world, m, n, k
+        st, self.tc = B.tile_config(3, m, n, k)
+        assert st == B.OK
+        self.ntiles = self.tc["ntiles"]
+        self.npn = -(-n // self.tc["block_n"])
+        self.gemm_out = torch.zeros((m, n), dtype=torch.int16, device="cuda")
+        self.out = torch.full((m, n), 0x7FC0, dtype=torch.int16, device="cuda")   # NaN pattern: unwritten output stays visible
+        self.signals = torch.zeros(B.signal_words(world, self.ntiles), dtype=torch.int32, device="cuda")
+        self.status = torch.zeros(B.STATUS_WORDS, dtype=torch.int32, device="cuda")
+        self.epoch = 0
+
+    def flag_index(self, s, pid_m, pid_n):
+        return 2 * self.world + s * self.ntiles + pid_m * self.npn + pid_n
+
+    def __call__(self, a_dev, b_dev, peers, rank, flags=None, schedule=None, stream=None, b_layout=None):
+        B = self.B
+        self.epoch += 1
+        flags = B.EMULATE_PRODUCER if flags is None else flags
+        if schedule is not None:
+            flags |= B.DUMP_SCHEDULE
+        return B.gemm_ar(a_dev, b_dev, B.B_NK if b_layout is None else b_layout, self.gemm_out, peers, self.out,
+                         self.signals, self.status, schedule, self.m, self.n, self.k, self.world, rank, self.epoch,
+                         flags, stream)

@@ -1,0 +1,162 @@
+"""GEMM + AllReduce on the GPU against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import gemm_ar as oar, schedule as osch, formats, compare
+
+pytestmark = pytest.mark.gpu
+
+TOL_BF16 = 2e-2   # max |err| <= 2e-2 * max |row| (bf16 outputs, fp32 accumulation)
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2605_02953_amd import binding
+    assert torch.cuda.is_available()
+    return binding
+
+
+from gpu_util import to_dev, bits, nk, GemmArRun  # noqa: E402
+
+
+def _ok(B, st, run):
+    assert st == B.OK, B.status_string(st)
+    torch.cuda.synchronize()
+    assert run.status.cpu().tolist()[0] == 0
+
+
+def _check_schedule(run, cfg, sched):
+    tc = run.tc
+    nt = run.ntiles
+    g = int(sched[:, 2].max()) + 1                       # GEMM work-groups of this call
+    assert g <= 256 and (g % 8 == 0 or g == nt)
+    want = [oar.persistent_tile(pos, cfg.m, cfg.n, tc["block_m"], tc["block_n"], tc["group_m"], g, tc["num_xcd"])
+            for pos in range(nt)]
+    assert np.array_equal(sched, np.asarray(want, dtype=np.int32))
+
+
+@pytest.mark.parametrize("kn", [False, True], ids=["b_nk", "b_kn"])
+@pytest.mark.parametrize("world,m_r,n,k,integer,comm", [
+    (4, 32, 256, 64, True, -1),        # one tile row
+    (4, 100, 264, 72, True, -1),       # ragged rows, columns and contraction tail
+    (8, 505, 3080, 200, True, -1),     # 256x256 tiles with ragged edges, a single round
+    (8, 505, 3080, 200, True, 128),    # half the chip kept for the consumer: two rounds of GEMM tiles
+    (2, 192, 384, 512, False, 8),
+    (1, 256, 256, 128, True, -1),      # world 1: the all-reduce is a copy of the partial
+    (3, 40, 8, 8, True, -1),           # minimum contraction and width, rows not a multiple of anything
+])
+def test_gemm_ar_end_to_end(B, world, m_r, n, k, integer, comm, kn):
+    cfg = synth.CONFIGS[3].scaled(world=world, m_per_rank=m_r, n=n, k=k)
+    a_list, b_list = synth.gemm_rs_inputs(cfg, integer=integer)
+    parts = [oar.partial_bits(a, b) for a, b in zip(a_list, b_list)]     # what each peer publishes
+    parts_dev = [to_dev(p) for p in parts]
+    ref = oar.gemm_ar(a_list, b_list)
+    run = GemmArRun(B, world, cfg.m, n, k)
+    assert B.set_comm_wgs(comm) == B.OK
+    try:
+        for d in sorted({0, world - 1}):
+            sched = torch.full((4 * run.ntiles,), -1, dtype=torch.int32, device="cuda")
+            b_dev = to_dev(b_list[d] if kn else nk(b_list[d]))
+            peers = [None if s == d else parts_dev[s] for s in range(world)]
+            run.out.fill_(0x7FC0)
+            st = run(to_dev(a_list[d]), b_dev, peers if world > 1 else None, d, schedule=sched,
+                     b_layout=B.B_KN if kn else B.B_NK)
+            _ok(B, st, run)
+            own = bits(run.gemm_out)
+            got = bits(run.out)
+            if integer:
+                assert np.array_equal(own, parts[d]), d
+                assert np.array_equal(got, formats.encode_bf16_rne(ref.astype(np.float32))), d
+            else:
+                pref = formats.decode_bf16(a_list[d]) @ formats.decode_bf16(b_list[d])
+                assert compare.max_row_rel_error(formats.decode_bf16(own), pref) <= TOL_BF16
+                assert compare.max_row_rel_error(formats.decode_bf16(got), ref) <= TOL_BF16
+            # the consumer on what was actually published: bit-exact to the specified arithmetic
+            published = [own if s == d else parts[s] for s in range(world)]
+            assert np.array_equal(got, oar.allreduce_partials_f32_ordered(published)), d
+            _check_schedule(run, cfg, sched.cpu().numpy().reshape(-1, 4))
+            sig = run.signals.cpu().numpy()
+            assert sig[0] == 0 and sig[1] == 0                              # queue counters back at zero
+            flags = sig[2 * world:2 * world + world * run.ntiles]
+            assert flags.tolist() == [run.epoch] * (world * run.ntiles)     # every tile of every rank was announced
+    finally:
+        B.set_comm_wgs(-1)
+
+
+def test_external_producer_and_timeout(B):
+    world, m, n, k, d = 4, 256, 256, 64, 1
+    cfg = synth.CONFIGS[3].scaled(world=world, m_per_rank=m // world, n=n, k=k)
+    a_list, b_list = synth.gemm_rs_inputs(cfg, integer=True)
+    parts = [oar.partial_bits(a, b) for a, b in zip(a_list, b_list)]
+    want = formats.encode_bf16_rne(oar.gemm_ar(a_list, b_list).astype(np.float32))
+    run = GemmArRun(B, world, m, n, k)
+    bm, bn = run.tc["block_m"], run.tc["block_n"]
+    npm, npn = m // bm, n // bn
+    assert (npm, npn) == (2, 2)
+    src = [to_dev(p) for p in parts]
+    landing = [torch.zeros((m, n), dtype=torch.int16, device="cuda") for _ in range(world)]   # the peers' buffers
+    a_dev, b_dev = to_dev(a_list[d]), to_dev(nk(b_list[d]))
+    # (a) a separate publisher fills the peers' buffers tile row by tile row, in a scrambled order and
+    # with idle gaps, raising each tile's flag after its data; the consumer only waits
+    dst, srcs, nbytes, fidx = [], [], [], []
+    for s in (3, 0, 2):
+        for pm in (1, 0):
+            for pn in range(npn):
+                rows = slice(pm * bm, (pm + 1) * bm)
+                dst.append(landing[s][rows] if pn == 0 else None)
+                srcs.append(src[s][rows] if pn == 0 else None)
+                nbytes.append(bm * n * 2 if pn == 0 else 0)       # the second tile of the row rides on the same copy
+                fidx.append(run.flag_index(s, pm, pn))
+    side = torch.cuda.Stream()
+    assert B.publish_chunks(dst, srcs, nbytes, fidx, run.signals, run.epoch + 1, delay_cycles=20000, stream=side) == B.OK
+    peers = [None if s == d else landing[s] for s in range(world)]
+    st = run(a_dev, b_dev, peers, d, flags=B.EXTERNAL_PRODUCER)
+    _ok(B, st, run)
+    assert np.array_equal(bits(run.out), want)
+    # (b) nobody raises the peers' flags: with a tiny spin limit every wait gives up, the kernel ends and
+    # reports the time-out instead of hanging, and leaves the queue counters at zero
+    B.set_spin_limit(64)
+    try:
+        assert run(a_dev, b_dev, peers, d, flags=B.EXTERNAL_PRODUCER) == B.OK
+        torch.cuda.synchronize()
+        s = run.status.cpu().tolist()
+        assert s[0] == B.ERR_TIMEOUT and 0 <= s[1] < run.ntiles
+        assert run.signals.cpu().numpy()[:2].tolist() == [0, 0]
+    finally:
+        B.set_spin_limit(1 << 20)
+    # (c) the buffers stay usable afterwards
+    run.status.zero_()
+    st = run(a_dev, b_dev, [None if s == d else src[s] for s in range(world)], d)
+    _ok(B, st, run)
+    assert np.array_equal(bits(run.out), want)
+
+
+def test_table_shape_full_size(B):
+    """Shape 3 of the paper's GEMM + AllReduce table at tensor parallel 8: M 8192, N 8192, K 28672 / 8.
+    The peers' partials are made by the same GEMM (world 1 calls), as on a real node."""
+    cfg = synth.CONFIGS[3]
+    assert (cfg.m, cfg.n, cfg.k, cfg.world) == (8192, 8192, 3584, 8)
+    a_list, b_list = synth.gemm_rs_inputs(cfg)
+    d = cfg.rank
+    solo = GemmArRun(B, 1, cfg.m, cfg.n, cfg.k)
+    parts_dev = []
+    for s in range(cfg.world):
+        if s == d:
+            parts_dev.append(None)
+            continue
+        st = solo(to_dev(a_list[s]), to_dev(nk(b_list[s])), None, 0)
+        _ok(B, st, solo)
+        parts_dev.append(solo.gemm_out.clone())
+    run = GemmArRun(B, cfg.world, cfg.m, cfg.n, cfg.k)
+    st = run(to_dev(a_list[d]), to_dev(nk(b_list[d])), parts_dev, d)
+    _ok(B, st, run)
+    got = bits(run.out)
+    published = [bits(run.gemm_out) if s == d else bits(parts_dev[s]) for s in range(cfg.world)]
+    assert np.array_equal(got, oar.allreduce_partials_f32_ordered(published))
+    rows = np.arange(0, cfg.m, 67)       # sampled rows, every tile row and column, against the definition
+    ref = oar.gemm_ar(a_list, b_list, rows=rows)
+    assert compare.max_row_rel_error(formats.decode_bf16(got[rows]), ref) <= TOL_BF16
+    sig = run.signals.cpu().numpy()
+    assert sig[0] == 0 and sig[1] == 0

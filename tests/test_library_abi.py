@@ -25,7 +25,8 @@ def _declared_functions():
 def test_every_declared_symbol_is_exported(B):
     names = _declared_functions()
     assert {"ditron_ag_gemm", "ditron_gemm_rs", "ditron_moe_ag_grouped_gemm", "ditron_reduce_slots",
-            "ditron_publish_chunks", "ditron_tile_config", "ditron_signal_words"} <= set(names)
+            "ditron_publish_chunks", "ditron_tile_config", "ditron_signal_words", "ditron_gemm_ar",
+            "ditron_set_comm_wgs"} <= set(names)
     for n in names:
         assert hasattr(B.lib, n), n
 
@@ -101,6 +102,32 @@ def test_gemm_rs_and_moe_argument_checks(B):
     assert st == B.ERR_UNSUPPORTED          # more experts than the routing kernel holds
     st = B.publish_chunks([fake], [fake], [24], [0], fake, 1, stream=_S())
     assert st == B.ERR_INVALID_ARG          # size not a multiple of 16
+
+
+def test_gemm_ar_argument_checks(B):
+    fake, other = 0x1000, 0x2000
+    args = dict(a=fake, b=fake, b_layout=B.B_NK, gemm_out=fake, peer_partials=[other] * 4, out=other + 0x1000,
+                signals=fake, status=fake, schedule_out=None, m=256, n=256, k_local=64, world=4, rank=0, epoch=1,
+                flags=B.EMULATE_PRODUCER)
+
+    def call(**kw):
+        a = dict(args)
+        a.update(kw)
+        return B.gemm_ar(stream=_S(), **a)
+
+    assert call(world=0) == B.ERR_INVALID_ARG
+    assert call(rank=4) == B.ERR_INVALID_ARG
+    assert call(out=fake) == B.ERR_INVALID_ARG                        # output on top of the published partial
+    assert call(peer_partials=None) == B.ERR_INVALID_ARG
+    assert call(peer_partials=[other, None, other, other]) == B.ERR_INVALID_ARG
+    assert call(flags=0) == B.ERR_INVALID_ARG
+    assert call(flags=B.EMULATE_PRODUCER | B.DUMP_SCHEDULE) == B.ERR_INVALID_ARG   # no schedule buffer
+    assert call(b_layout=5) == B.ERR_INVALID_ARG
+    assert call(k_local=60) == B.ERR_UNSUPPORTED
+    assert call(n=100) == B.ERR_UNSUPPORTED
+    assert B.set_comm_wgs(1000) == B.ERR_INVALID_ARG and B.set_comm_wgs(-1) == B.OK
+    st, tc = B.tile_config(3, 8192, 8192, 3584)
+    assert st == B.OK and (tc["block_m"], tc["block_n"], tc["ntiles"]) == (256, 256, 1024)
 
 
 class _S:
