@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the fused communication + GEMM hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg4|cfg5|cfg1]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg4|cfg5|cfg1|gemm_ar|sweep]
 
 A step is one pass of the whole path for the workload: for cfg2 (the default, the
 configuration the headline metric is quoted on) one ditron_ag_gemm call with the emulated
@@ -288,6 +288,97 @@ def bench_gemm_rs(args):
     return out
 
 
+def bench_gemm_ar(args):
+    """GEMM + AllReduce (one-shot) at shape 3 of the paper's GEMM + AllReduce table under tensor parallel 8:
+    M 8192, N 8192, K 28672 / 8 (the operands of cfg3), the seven peers' partials resident in HBM."""
+    import torch
+    import synth
+    from paper_2605_02953_amd import binding as B
+    from gpu_util import to_dev, nk, GemmArRun
+
+    cfg = synth.CONFIGS[3]
+    d = cfg.rank
+    a_list, b_list = synth.gemm_rs_inputs(cfg)
+    solo = GemmArRun(B, 1, cfg.m, cfg.n, cfg.k)
+    peers = []
+    for s in range(cfg.world):          # the peers' published partials, made by the same GEMM
+        if s == d:
+            peers.append(None)
+            continue
+        st = solo(to_dev(a_list[s]), to_dev(nk(b_list[s])), None, 0)
+        assert st == B.OK
+        torch.cuda.synchronize()
+        peers.append(solo.gemm_out.clone())
+    ad, bd = to_dev(a_list[d]), to_dev(nk(b_list[d]))
+    run = GemmArRun(B, cfg.world, cfg.m, cfg.n, cfg.k)
+
+    def step():
+        st = run(ad, bd, peers, d)
+        if st != B.OK:
+            raise RuntimeError(B.status_string(st))
+
+    ms_per_step, ev_ms = _timed(torch, args, step)
+    if run.status.cpu().tolist()[0] != 0:
+        raise RuntimeError("kernel reported a signal time-out")
+    flops = 2.0 * cfg.m * cfg.n * cfg.k
+    red_bytes = (cfg.world + 1) * cfg.m * cfg.n * 2
+
+    # the GEMM with its per-tile flags alone (world 1: the consumer only copies the partial)
+    for _ in range(5):
+        solo(ad, bd, None, 0)
+    torch.cuda.synchronize()
+    ev = _events(torch, args.steps)
+    for i in range(args.steps):
+        ev[i][0].record()
+        solo(ad, bd, None, 0)
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    solo_ms = sum(a.elapsed_time(b) for a, b in ev) / args.steps
+
+    # the all-reduce of the eight partials alone, as a plain streaming kernel over the whole chip
+    slots = [run.gemm_out if s == d else peers[s] for s in range(cfg.world)]
+    status = torch.zeros(B.STATUS_WORDS, dtype=torch.int32, device="cuda")
+    for _ in range(3):
+        B.reduce_slots(slots, run.out, None, status, cfg.m, cfg.n, cfg.world, 1, 1)
+    torch.cuda.synchronize()
+    ev = _events(torch, 20)
+    for i in range(20):
+        ev[i][0].record()
+        B.reduce_slots(slots, run.out, None, status, cfg.m, cfg.n, cfg.world, 1, 1)
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    red_ms = sum(a.elapsed_time(b) for a, b in ev) / 20
+
+    achieved = flops / (ev_ms * 1e-3) / 1e12
+    out = {
+        "metric": "TFLOP/s of one rank's GEMM + AllReduce share (GEMM with per-tile flags, one-shot software all-reduce)",
+        "value": flops / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"gemm_ar: GEMM-AR world={cfg.world} rank={d} A [{cfg.m},{cfg.k}] B [{cfg.k},{cfg.n}] stored [n,k], "
+                               f"7 peer partials [{cfg.m},{cfg.n}] bf16 resident -> out [{cfg.m},{cfg.n}] bf16", "latency_us": ev_ms * 1e3},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": MEASURED_TRAFFIC.get("gemm_ar"),
+                     "kernel": "gemm_ar_kernel (GEMM tiles + all-reduce consumers in one launch)", "kernel_ms": ev_ms},
+        "gemm_and_copy": {"ms": solo_ms, "note": "world 1: the GEMM with its tile flags; the consumer only copies the partial (268 MB)"},
+        "allreduce_alone": {"bound": "hbm", "bytes": red_bytes, "ms": red_ms, "achieved": red_bytes / (red_ms * 1e-3) / 1e9,
+                            "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": red_bytes / (red_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                            "note": "reduce_slots_kernel over the same eight [8192,8192] partials: what the all-reduce costs when "
+                                    "nothing overlaps it (the whole chip streaming)"},
+    }
+    if not args.no_cpu:
+        from oracle import gemm_ar as oar
+        rows = np.arange(0, cfg.m, 8)
+        t0 = time.perf_counter()
+        oar.gemm_ar(a_list, b_list, rows=rows)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": 2.0 * len(rows) * cfg.n * cfg.k * cfg.world / dt / 1e12, "unit": "TFLOP/s",
+                               "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count())), "kind": "oracle", "seconds": dt,
+                               "sample": f"every 8th row of the output ({len(rows)} rows x {cfg.n} columns, all 8 ranks' products in fp64; "
+                                         "the oracle computes every rank's share, the GPU figure counts one)"}
+    return out
+
+
 def bench_moe(args):
     import torch
     import synth
@@ -517,6 +608,8 @@ def main():
         out = bench_moe(args)
     elif args.workload == "cfg5":
         out = bench_fp8(args)
+    elif args.workload == "gemm_ar":
+        out = bench_gemm_ar(args)
     elif args.workload == "sweep":
         out = bench_sweep(args)
     else:

@@ -101,7 +101,7 @@ ditron_status_t ditron_tile_row_order(int op, int m, int block_m, int world, int
 /* Tile shape and ordering parameters the library will use for a problem, so that a test can
  * evaluate the schedule independently.  op: 0 = ag_gemm, 1 = gemm_rs, 2 = moe grouped gemm
  * (m = max_rows; only BLOCK_M is fixed, the column block is chosen per call and reported as 0),
- * 3 = gemm_ar (out[4] is not used by it: a chiplet receives consecutive tiles of each round).
+ * 3 = gemm_ar.
  * out[0]=BLOCK_M out[1]=BLOCK_N out[2]=GROUP_SIZE_M out[3]=chiplets used by the work-group
  * remap (0 = no remap) out[4]=tiles per chiplet per block out[5]=number of tiles
  * (ag_gemm / gemm_rs) out[6]=threads per work-group out[7]=reserved (0). */
@@ -177,14 +177,14 @@ ditron_status_t ditron_gemm_rs(const void* a, const void* b, int b_layout, void*
  * GEMM + AllReduce, one-shot:  out[m, n] = sum_s P_s,  P_rank = A . B computed here.
  *
  * Paper: `gemm_allreduce_op`, `kernel_persistent_gemm_notify` and `consumer_all_reduce_kernel`
- * of Appendix "GEMM All-Reduce", the branch that reduces every tile on every rank.  A fixed set
- * of work-groups loops over the tiles of P_rank in the grouped order (work-group g takes
- * positions g, g + G, ...), stores each tile into `gemm_out` (the buffer the peers read) and
- * raises that tile's flag.  The consumer takes the tiles in the same order, waits for the
- * tile's flag of every rank, adds the `world` published tiles in fp32 in rank order (the paper
- * reduces through the switch; here in software) and rounds once to bf16.  Consumer and GEMM
- * share one launch; ditron_set_comm_wgs sets how many compute units are kept for the consumer
- * (multiple of 8, at most 192; -1 = chosen per call by a cost model, the default).
+ * of Appendix "GEMM All-Reduce", the branch that reduces every tile on every rank.  The tiles
+ * of P_rank are computed in the grouped order, each stored into `gemm_out` (the buffer the
+ * peers read) and announced by that tile's flag.  The consumer takes the tiles in the same
+ * order, waits for the tile's flag of every rank, adds the `world` published tiles in fp32 in
+ * rank order (the paper reduces through the switch; here in software) and rounds once to bf16.
+ * GEMM tiles and consumer work-groups share one launch: some consumers follow the first
+ * chip-wide round of tiles and reduce finished tiles while later rounds are computed, the rest
+ * follow the last tile.
  *
  *  a             device [m, k_local] bf16
  *  b, b_layout   device, logical [k_local, n] bf16
@@ -199,15 +199,15 @@ ditron_status_t ditron_gemm_rs(const void* a, const void* b, int b_layout, void*
  *                2*world + s*tiles + pid_m*ceil(n / BLOCK_N) + pid_n; words 0 and 1 are the
  *                consumer's queue counters, left at zero by every call
  *  schedule_out  device int32[4 * tiles] or NULL; with DITRON_DUMP_SCHEDULE the record of
- *                schedule position t is (pid_m, pid_n, GEMM work-group, round)
- *  DITRON_EMULATE_PRODUCER: the call raises the peers' tile flags itself, in schedule order.
+ *                position t of the tile order is (pid_m, pid_n, index of the tile's work-group
+ *                in the launch with the emulated peers not counted, 0)
+ *  DITRON_EMULATE_PRODUCER: the call raises the peers' tile flags itself, in tile order.
  *  m need not be a multiple of world.
  */
 ditron_status_t ditron_gemm_ar(const void* a, const void* b, int b_layout, void* gemm_out,
                                const void* const* peer_partials, void* out, int32_t* signals,
                                int32_t* status, int32_t* schedule_out, int m, int n, int k_local,
                                int world, int rank, int32_t epoch, unsigned flags, void* stream);
-ditron_status_t ditron_set_comm_wgs(int wgs);
 
 /*
  * The reduction step of GEMM-ReduceScatter on its own: out = bf16( sum_s fp32(slots[s]) ),

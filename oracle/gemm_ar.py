@@ -44,17 +44,24 @@ def tile_flag_index(pid_m, pid_n, num_pid_n):
     return pid_m * num_pid_n + pid_n
 
 
-def persistent_tile(position, m, n, block_m, block_n, group_m, gemm_wgs, num_xcd=0):
-    """Tile taken at `position` of the persistent GEMM's schedule.
-
-    `gemm_wgs` work-groups loop over the tiles; work-group g takes positions g, g+G, g+2G...
-    (persistent GEMM listing: the range with step NUM_GEMM_SMS), and a position maps to a
-    tile through the grouped order.  num_xcd > 0 adds the chiplet remap of this build inside
-    every round of G positions.  Returns (pid_m, pid_n, work-group, round)."""
+def tile_at_position(position, m, n, block_m, block_n, group_m, num_xcd=0, per_xcd=0):
+    """Tile at `position` of the GEMM's tile order: the grouped order of the persistent GEMM
+    listing (its `_compute_pid`).  num_xcd > 0 adds the chiplet remap of this build (blocks of
+    num_xcd * per_xcd positions, a run of consecutive tile ids per chiplet).  -> (pid_m, pid_n)"""
     npm, npn = cdiv(m, block_m), cdiv(n, block_n)
     ntiles = npm * npn
     assert 0 <= position < ntiles
+    tile_id = xcd_remap(position, ntiles, num_xcd, per_xcd) if num_xcd else position
+    return grouped_order(tile_id, npm, npn, group_m)
+
+
+def persistent_tile(position, m, n, block_m, block_n, group_m, gemm_wgs, num_xcd=0):
+    """The paper's persistent form of the same order: `gemm_wgs` work-groups loop over the tiles,
+    work-group g taking positions g, g+G, g+2G, ... (the range with step NUM_GEMM_SMS).  With the
+    chiplet remap a round of G positions is one remap block.
+    Returns (pid_m, pid_n, work-group, round)."""
+    ntiles = cdiv(m, block_m) * cdiv(n, block_n)
     assert not num_xcd or gemm_wgs % num_xcd == 0 or ntiles <= gemm_wgs   # a round is a whole number of chiplet runs
-    tile_id = xcd_remap(position, ntiles, num_xcd, cdiv(gemm_wgs, num_xcd)) if num_xcd else position
-    pid_m, pid_n = grouped_order(tile_id, npm, npn, group_m)
+    pid_m, pid_n = tile_at_position(position, m, n, block_m, block_n, group_m, num_xcd,
+                                    cdiv(gemm_wgs, num_xcd) if num_xcd else 0)
     return pid_m, pid_n, position % gemm_wgs, position // gemm_wgs

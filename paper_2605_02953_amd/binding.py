@@ -47,8 +47,6 @@ lib.ditron_gemm_rs.argtypes = [_vp, _vp, _i, _vp, _pp, _vp, _vp, _vp, _vp, _vp, 
                                _i, _i, _i, _i, _i, _i, _i32, _u, _vp]
 lib.ditron_gemm_ar.restype = _i
 lib.ditron_gemm_ar.argtypes = [_vp, _vp, _i, _vp, _pp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i32, _u, _vp]
-lib.ditron_set_comm_wgs.restype = _i
-lib.ditron_set_comm_wgs.argtypes = [_i]
 lib.ditron_reduce_slots.restype = _i
 lib.ditron_reduce_slots.argtypes = [_pp, _vp, _vp, _vp, _i, _i, _i, _i, _i32, _vp]
 lib.ditron_moe_ag_grouped_gemm.restype = _i
@@ -140,10 +138,6 @@ def gemm_ar(a, b, b_layout, gemm_out, peer_partials, out, signals, status, sched
     return lib.ditron_gemm_ar(_ptr(a), _ptr(b), b_layout, _ptr(gemm_out), _ptr_array(peer_partials), _ptr(out),
                               _ptr(signals), _ptr(status), _ptr(schedule_out), m, n, k_local, world, rank, epoch,
                               flags, _stream(stream))
-
-
-def set_comm_wgs(wgs):
-    return lib.ditron_set_comm_wgs(wgs)
 
 
 def reduce_slots(slots, out, signals, status, rows, n, world, chunks, epoch, stream=None):

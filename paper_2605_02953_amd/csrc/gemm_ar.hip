@@ -1,24 +1,40 @@
 // GEMM + AllReduce in one-shot form, one rank's share (paper, Appendix "GEMM All-Reduce").
 //
 // One launch holds three kinds of work-groups.
-//  * The persistent GEMM: `gemm_wgs` work-groups loop over the tiles of P = A . B (work-group g
-//    takes positions g, g + G, ... of the grouped tile order), store each tile as bf16 into the
-//    buffer the peers would read, and raise the tile's flag in this rank's flag array.
+//  * GEMM tiles: one work-group per tile of P = A . B, taken in the grouped tile order; it stores
+//    the tile as bf16 into the buffer the peers would read and raises the tile's flag in this
+//    rank's flag array.
 //  * The emulated peers (lowest indices): every other rank's partial is resident in this GPU's
 //    memory, so a peer is reduced to what the consumer sees of it, its tile flags, raised in the
 //    order a peer's own GEMM finishes tiles.
-//  * The all-reduce consumer: work-groups draw tickets; ticket q is the tile at position q of
-//    the GEMM's schedule, so tiles are reduced in the order they are finished.  The holder waits
-//    for the tile's flag of every rank (one lane per rank), adds the `world` published tiles in
+//  * The all-reduce consumer: work-groups that draw tickets; ticket q is the tile at position q
+//    of the tile order, so tiles are reduced in the order they are finished.  The holder waits
+//    for the tile's flag of every rank (one lane per rank), adds the `world` published copies in
 //    fp32 in rank order with 128-bit loads, rounds once to bf16 and writes the output tile.
-//    GEMM work-groups that run out of tiles draw tickets too, so the last round of tiles is
-//    reduced by the whole chip.
-// The paper runs the consumer as a second kernel on compute units set aside for it and reduces
-// through the switch (multimem); here there is no switch, the sum is done in software, and the
-// number of compute units set aside is chosen per call from a cost model (zero when one more
-// round of GEMM tiles would cost more than the overlap wins).
+// Where the consumers sit in the grid decides when they run.  When the GEMM needs more than one
+// chip-wide round of tiles, X consumers follow the first round of tiles: they take X compute
+// units as the first tiles retire and keep them to the end, reducing finished tiles while the
+// other units compute the next ones.  Behind the last tile sit as many consumers again as the
+// chip has units; they pick up compute units as the last tiles retire and the whole chip
+// finishes the queue.  A tile never waits, and a consumer only waits (bounded) for tiles that
+// are ahead of it in the grid, so the launch cannot deadlock.
+//
+// Sizing X: one work-group streams about 50 GB/s on its compute unit whatever it keeps in
+// flight (measured; the whole chip reaches 5.4 TB/s only with all units streaming), so the
+// reduction costs least unit-time when few units do it all along: X is the number of units
+// that reduce the whole output in the time the remaining units need for the GEMM.
+//
+// The paper runs a persistent GEMM on a fixed set of compute units and the consumer as a second
+// kernel on the rest, reducing through the switch (multimem).  Here there is no switch (the sum
+// is done in software), and a persistent GEMM measured slower on this chip: work-groups looping
+// over tiles in lock step ask for the same operand panels at the same instants (K loop 13 %
+// slower than one work-group per tile, which the dispatcher staggers and load-balances).
 #include "gemm_core.h"
 #include "launch.h"
+
+#ifndef DITRON_AR_UNROLL
+#define DITRON_AR_UNROLL 4   // 16-byte vectors per lane and rank in flight in the consumer (256 x 256 tiles)
+#endif
 
 namespace ditron {
 
@@ -29,14 +45,16 @@ struct GemmArParams {
   __bf16* gemm_out;
   __bf16* out;
   int32_t* ticket;       // next position of the reduce queue
-  int32_t* done;         // work-groups that have left the queue
+  int32_t* done;         // consumers that have left the queue
   int32_t* tile_flags;   // [world][ntiles]
   int32_t* status;
   int32_t* schedule;
   int m, n, k, world, rank;
   int32_t epoch;
   unsigned spin_limit;
-  int num_producers, gemm_wgs, reduce_wgs;
+  int num_producers;
+  int head_tiles;        // tiles ahead of the early consumers
+  int early, late;       // consumers behind the first round of tiles / behind the last tile
   int group_m, num_xcd, per_xcd, npm, npn;
 };
 
@@ -136,35 +154,36 @@ __global__ __launch_bounds__(T::THREADS) void gemm_ar_kernel(const GemmArParams 
     return;
   }
   wg -= p.num_producers;
+  // grid: head_tiles tiles, `early` consumers, the remaining tiles, `late` consumers
+  int pos = -1;
+  if (wg < p.head_tiles) pos = wg;
+  else if (wg >= p.head_tiles + p.early && wg < ntiles + p.early) pos = wg - p.early;
 
-  if (wg < p.gemm_wgs) {
+  if (pos >= 0) {
+    int pid_m, pid_n;
+    ar_tile_at(p, pos, ntiles, pid_m, pid_n);
+    const int m0 = pid_m * T::BM, n0 = pid_n * T::BN;
+    if (p.schedule && threadIdx.x == 0) {
+      int32_t* rec = p.schedule + 4 * (size_t)pos;
+      rec[0] = pid_m; rec[1] = pid_n; rec[2] = wg; rec[3] = 0;
+    }
     const uint32_t row_bytes = (uint32_t)p.k * 2u;
     const int M = p.m, N = p.n;
-    for (int pos = wg; pos < ntiles; pos += p.gemm_wgs) {
-      int pid_m, pid_n;
-      ar_tile_at(p, pos, ntiles, pid_m, pid_n);
-      const int m0 = pid_m * T::BM, n0 = pid_n * T::BN;
-      if (p.schedule && threadIdx.x == 0) {
-        int32_t* rec = p.schedule + 4 * (size_t)pos;
-        rec[0] = pid_m; rec[1] = pid_n; rec[2] = wg; rec[3] = pos / p.gemm_wgs;
-      }
-      auto a_row = [=](int r) { return (uint32_t)min(m0 + r, M - 1) * row_bytes; };
-      f32x16_t acc[T::NI][T::MI];
-      if constexpr (T::B_KN) {
-        gemm_mainloop<T>(acc, p.a, a_row, p.b, BColumns{(uint32_t)N * 2u, n0, N}, p.k, lds);
-      } else {
-        auto b_row = [=](int r) { return (uint32_t)min(n0 + r, N - 1) * row_bytes; };
-        gemm_mainloop<T>(acc, p.a, a_row, p.b, b_row, p.k, lds);
-      }
-      store_tile_bf16<T>(acc, p.gemm_out, (size_t)p.n, m0, n0, M, N, lds);
-      // every wave's stores are issued and the parked tile is no longer read: notify, and the
-      // next tile may overwrite the operand stages
-      __syncthreads();
-      if (threadIdx.x == 0) flag_raise(p.tile_flags + (size_t)p.rank * ntiles + pid_m * p.npn + pid_n, p.epoch);
+    auto a_row = [=](int r) { return (uint32_t)min(m0 + r, M - 1) * row_bytes; };
+    f32x16_t acc[T::NI][T::MI];
+    if constexpr (T::B_KN) {
+      gemm_mainloop<T>(acc, p.a, a_row, p.b, BColumns{(uint32_t)N * 2u, n0, N}, p.k, lds);
+    } else {
+      auto b_row = [=](int r) { return (uint32_t)min(n0 + r, N - 1) * row_bytes; };
+      gemm_mainloop<T>(acc, p.a, a_row, p.b, b_row, p.k, lds);
     }
+    store_tile_bf16<T>(acc, p.gemm_out, (size_t)p.n, m0, n0, M, N, lds);
+    __syncthreads();   // every wave's stores are issued: notify
+    if (threadIdx.x == 0) flag_raise(p.tile_flags + (size_t)p.rank * ntiles + pid_m * p.npn + pid_n, p.epoch);
+    return;
   }
 
-  // the reduce queue
+  // a consumer: draw tickets until the queue is empty
   volatile int* drawn = (volatile int*)lds;
   for (;;) {
     __syncthreads();   // the previous ticket has been read by every wave
@@ -177,21 +196,41 @@ __global__ __launch_bounds__(T::THREADS) void gemm_ar_kernel(const GemmArParams 
     if ((int)threadIdx.x < p.world)
       flag_wait_lane(p.tile_flags + (size_t)threadIdx.x * ntiles, pid_m * p.npn + pid_n, 1, p.epoch, p.spin_limit, p.status);
     __syncthreads();
-    ar_reduce_tile<T, WORLD, (T::BM * T::BN / 8 / T::THREADS >= 32 ? 4 : 2)>(p, pid_m * T::BM, pid_n * T::BN);
+    ar_reduce_tile<T, WORLD, (T::BM * T::BN / 8 / T::THREADS >= 32 ? DITRON_AR_UNROLL : 2)>(p, pid_m * T::BM, pid_n * T::BN);
   }
-  // the last work-group to leave puts the queue back to zero for the next call
+  // the last consumer to leave puts the queue back to zero for the next call
   if (threadIdx.x == 0) {
     const int old = __hip_atomic_fetch_add(p.done, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-    if (old == p.gemm_wgs + p.reduce_wgs - 1) {
+    if (old == p.early + p.late - 1) {
       __hip_atomic_store(p.ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       __hip_atomic_store(p.done, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
 }
 
+#ifndef DITRON_AR_EARLY
+#define DITRON_AR_EARLY -1   // early consumers; -1: sized per call
+#endif
+
 template <class T>
-static ditron_status_t launch_ar(GemmArParams& p, hipStream_t stream) {
-  const unsigned grid = (unsigned)(p.num_producers + p.gemm_wgs + p.reduce_wgs);
+static ditron_status_t launch_ar(GemmArParams& p, int units, hipStream_t stream) {
+  const int ntiles = p.npm * p.npn;
+  units = units / 8 * 8;
+  p.head_tiles = std::min(ntiles, units);
+  p.early = 0;
+  if (ntiles > units) {
+    // X units reduce (world + 1) tile-sized streams per tile at ~40 GB/s each (50 while streaming,
+    // less the waits) while units - X compute the tiles at the per-unit MFMA rate of a full-chip
+    // GEMM: balance the two
+    constexpr double kUnitBytes = 40e9, kUnitFlops = 4.4e12;
+    const double t_reduce = (double)(p.world + 1) * T::BM * T::BN * 2 / kUnitBytes;   // unit-seconds per tile
+    const double t_gemm = 2.0 * T::BM * T::BN * p.k / kUnitFlops;
+    int x = (int)(units * t_reduce / (t_reduce + t_gemm) / 8 + 0.5) * 8;
+    if (DITRON_AR_EARLY >= 0) x = DITRON_AR_EARLY;
+    p.early = std::max(0, std::min(x, units / 2));
+  }
+  p.late = std::min(units, ntiles);
+  const unsigned grid = (unsigned)(p.num_producers + ntiles + p.early + p.late);
   auto launch = [&](auto kern) {
     if (!set_dynamic_lds((const void*)kern, T::LDS_BYTES)) return DITRON_ERR_HIP;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(T::THREADS), T::LDS_BYTES, stream, p);
@@ -201,59 +240,9 @@ static ditron_status_t launch_ar(GemmArParams& p, hipStream_t stream) {
   return launch(gemm_ar_kernel<T, 0>);
 }
 
-int g_comm_wgs = -1;   // work-groups (= compute units) set aside for the all-reduce consumer; -1: cost model
-
-// Compute units set aside for the consumer.  Taking X units away from the GEMM can add a round
-// of tiles; leaving none means that the whole reduction runs after the GEMM.  The model takes a
-// tile's MFMA time from the measured per-unit GEMM rate, lets X consumer units each stream at
-// the measured single-unit rate while the GEMM runs, and reduces whatever the last round of
-// tiles leaves at the chip's full streaming rate.
-struct CommPlan {
-  int gemm_wgs, reduce_wgs;
-};
-static CommPlan plan_comm(int units, int ntiles, int block_m, int block_n, int k, int world, int forced) {
-  constexpr double kUnitFlops = 5.5e12;       // one compute unit inside a full-chip GEMM
-  constexpr double kUnitBytes = 45e9;         // one compute unit streaming on its own work-group
-  constexpr double kChipBytes = 5.0e12;       // the whole chip streaming
-  const int kUnits = units / 8 * 8;
-  const double t_tile = 2.0 * block_m * block_n * k / kUnitFlops;
-  const double tile_bytes = (double)(world + 1) * block_m * block_n * 2;
-  auto shape = [&](int x) {
-    CommPlan c{};
-    c.gemm_wgs = std::min(kUnits - x, ntiles);
-    c.reduce_wgs = std::min(x, ntiles);
-    return c;
-  };
-  if (forced >= 0) return shape(std::min(forced / 8 * 8, kUnits - 8));
-  int best = 0;
-  double best_t = 0;
-  for (int x = 0; x <= kUnits / 2; x += 8) {
-    const int g = std::min(kUnits - x, ntiles);
-    const int rounds = cdiv(ntiles, g);
-    const int last = ntiles - (rounds - 1) * g;
-    const double t_gemm = rounds * t_tile;
-    double t;
-    if (x == 0 || rounds == 1) {
-      if (x) continue;   // a single round leaves nothing to overlap
-      t = t_gemm + ntiles * tile_bytes / kChipBytes;
-    } else {
-      const double early = (double)(ntiles - last) * tile_bytes / (x * kUnitBytes);
-      t = std::max(t_gemm, t_tile + early) + last * tile_bytes / kChipBytes;
-    }
-    if (x == 0 || t < best_t) { best = x; best_t = t; }
-  }
-  return shape(best);
-}
-
 }  // namespace ditron
 
 using namespace ditron;
-
-extern "C" ditron_status_t ditron_set_comm_wgs(int wgs) {
-  if (wgs < -1 || wgs > 192) return DITRON_ERR_INVALID_ARG;
-  g_comm_wgs = wgs;
-  return DITRON_OK;
-}
 
 extern "C" ditron_status_t ditron_gemm_ar(const void* a, const void* b, int b_layout, void* gemm_out,
                                           const void* const* peer_partials, void* out, int32_t* signals,
@@ -286,19 +275,16 @@ extern "C" ditron_status_t ditron_gemm_ar(const void* a, const void* b, int b_la
   p.npm = cdiv(m, tc.block_m);
   p.npn = cdiv(n, tc.block_n);
   const int ntiles = p.npm * p.npn;
-  // every GEMM work-group must be resident at once (the consumer waits for their tiles while it
-  // holds a compute unit), so the plan is made for the compute units this device has
   int dev = 0, units = 0;
   if (hipGetDevice(&dev) != hipSuccess ||
       hipDeviceGetAttribute(&units, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || units < 16)
     return DITRON_ERR_HIP;
-  const CommPlan cp = plan_comm(units, ntiles, tc.block_m, tc.block_n, k_local, world, g_comm_wgs);
   p.a = (const char*)a;
+  p.ticket = signals;
+  p.done = signals + 1;
   p.b = (const char*)b;
   p.gemm_out = (__bf16*)gemm_out;
   p.out = (__bf16*)out;
-  p.ticket = signals;
-  p.done = signals + 1;
   p.tile_flags = signals + 2 * world;
   p.status = status;
   p.schedule = (flags & DITRON_DUMP_SCHEDULE) ? schedule_out : nullptr;
@@ -310,12 +296,10 @@ extern "C" ditron_status_t ditron_gemm_ar(const void* a, const void* b, int b_la
   p.epoch = epoch;
   p.spin_limit = g_spin_limit;
   p.num_producers = (emulate && world > 1) ? 8 : 0;
-  p.gemm_wgs = cp.gemm_wgs;
-  p.reduce_wgs = cp.reduce_wgs;
   p.group_m = tc.group_m;
   p.num_xcd = tc.num_xcd;
-  p.per_xcd = cdiv(p.gemm_wgs, tc.num_xcd);
+  p.per_xcd = tc.per_xcd;
   const hipStream_t s = (hipStream_t)stream;
-  if (b_layout == DITRON_B_KN) return tc.big ? launch_ar<TileBigKN>(p, s) : launch_ar<TileSmallKN>(p, s);
-  return tc.big ? launch_ar<TileBig>(p, s) : launch_ar<TileSmall>(p, s);
+  if (b_layout == DITRON_B_KN) return tc.big ? launch_ar<TileBigKN>(p, units, s) : launch_ar<TileSmallKN>(p, units, s);
+  return tc.big ? launch_ar<TileBig>(p, units, s) : launch_ar<TileSmall>(p, units, s);
 }

@@ -30,59 +30,58 @@ def _ok(B, st, run):
 def _check_schedule(run, cfg, sched):
     tc = run.tc
     nt = run.ntiles
-    g = int(sched[:, 2].max()) + 1                       # GEMM work-groups of this call
-    assert g <= 256 and (g % 8 == 0 or g == nt)
-    want = [oar.persistent_tile(pos, cfg.m, cfg.n, tc["block_m"], tc["block_n"], tc["group_m"], g, tc["num_xcd"])
-            for pos in range(nt)]
-    assert np.array_equal(sched, np.asarray(want, dtype=np.int32))
+    want = [oar.tile_at_position(pos, cfg.m, cfg.n, tc["block_m"], tc["block_n"], tc["group_m"], tc["num_xcd"],
+                                 tc["per_xcd"]) for pos in range(nt)]
+    assert np.array_equal(sched[:, :2], np.asarray(want, dtype=np.int32))
+    # where the tiles sit in the launch (consumers in between not counted as tiles): in order, and on the
+    # chiplet the remap assumes
+    grid = sched[:, 2]
+    assert (np.diff(grid) > 0).all()
+    assert ((grid - np.arange(nt)) % 8 == 0).all()
 
 
 @pytest.mark.parametrize("kn", [False, True], ids=["b_nk", "b_kn"])
-@pytest.mark.parametrize("world,m_r,n,k,integer,comm", [
-    (4, 32, 256, 64, True, -1),        # one tile row
-    (4, 100, 264, 72, True, -1),       # ragged rows, columns and contraction tail
-    (8, 505, 3080, 200, True, -1),     # 256x256 tiles with ragged edges, a single round
-    (8, 505, 3080, 200, True, 128),    # half the chip kept for the consumer: two rounds of GEMM tiles
-    (2, 192, 384, 512, False, 8),
-    (1, 256, 256, 128, True, -1),      # world 1: the all-reduce is a copy of the partial
-    (3, 40, 8, 8, True, -1),           # minimum contraction and width, rows not a multiple of anything
+@pytest.mark.parametrize("world,m_r,n,k,integer", [
+    (4, 32, 256, 64, True),        # one tile row
+    (4, 100, 264, 72, True),       # ragged rows, columns and contraction tail
+    (8, 505, 3080, 200, True),     # 256x256 tiles with ragged edges, a single round: all tiles, then the consumers
+    (8, 315, 2600, 64, True),      # 420 tiles of 128x128: more than one round, consumers behind the first one
+    (2, 192, 384, 512, False),
+    (1, 256, 256, 128, True),      # world 1: the all-reduce is a copy of the partial
+    (3, 40, 8, 8, True),           # minimum contraction and width, rows not a multiple of anything
 ])
-def test_gemm_ar_end_to_end(B, world, m_r, n, k, integer, comm, kn):
+def test_gemm_ar_end_to_end(B, world, m_r, n, k, integer, kn):
     cfg = synth.CONFIGS[3].scaled(world=world, m_per_rank=m_r, n=n, k=k)
     a_list, b_list = synth.gemm_rs_inputs(cfg, integer=integer)
     parts = [oar.partial_bits(a, b) for a, b in zip(a_list, b_list)]     # what each peer publishes
     parts_dev = [to_dev(p) for p in parts]
     ref = oar.gemm_ar(a_list, b_list)
     run = GemmArRun(B, world, cfg.m, n, k)
-    assert B.set_comm_wgs(comm) == B.OK
-    try:
-        for d in sorted({0, world - 1}):
-            sched = torch.full((4 * run.ntiles,), -1, dtype=torch.int32, device="cuda")
-            b_dev = to_dev(b_list[d] if kn else nk(b_list[d]))
-            peers = [None if s == d else parts_dev[s] for s in range(world)]
-            run.out.fill_(0x7FC0)
-            st = run(to_dev(a_list[d]), b_dev, peers if world > 1 else None, d, schedule=sched,
-                     b_layout=B.B_KN if kn else B.B_NK)
-            _ok(B, st, run)
-            own = bits(run.gemm_out)
-            got = bits(run.out)
-            if integer:
-                assert np.array_equal(own, parts[d]), d
-                assert np.array_equal(got, formats.encode_bf16_rne(ref.astype(np.float32))), d
-            else:
-                pref = formats.decode_bf16(a_list[d]) @ formats.decode_bf16(b_list[d])
-                assert compare.max_row_rel_error(formats.decode_bf16(own), pref) <= TOL_BF16
-                assert compare.max_row_rel_error(formats.decode_bf16(got), ref) <= TOL_BF16
-            # the consumer on what was actually published: bit-exact to the specified arithmetic
-            published = [own if s == d else parts[s] for s in range(world)]
-            assert np.array_equal(got, oar.allreduce_partials_f32_ordered(published)), d
-            _check_schedule(run, cfg, sched.cpu().numpy().reshape(-1, 4))
-            sig = run.signals.cpu().numpy()
-            assert sig[0] == 0 and sig[1] == 0                              # queue counters back at zero
-            flags = sig[2 * world:2 * world + world * run.ntiles]
-            assert flags.tolist() == [run.epoch] * (world * run.ntiles)     # every tile of every rank was announced
-    finally:
-        B.set_comm_wgs(-1)
+    for d in sorted({0, world - 1}):
+        sched = torch.full((4 * run.ntiles,), -1, dtype=torch.int32, device="cuda")
+        b_dev = to_dev(b_list[d] if kn else nk(b_list[d]))
+        peers = [None if s == d else parts_dev[s] for s in range(world)]
+        run.out.fill_(0x7FC0)
+        st = run(to_dev(a_list[d]), b_dev, peers if world > 1 else None, d, schedule=sched,
+                 b_layout=B.B_KN if kn else B.B_NK)
+        _ok(B, st, run)
+        own = bits(run.gemm_out)
+        got = bits(run.out)
+        if integer:
+            assert np.array_equal(own, parts[d]), d
+            assert np.array_equal(got, formats.encode_bf16_rne(ref.astype(np.float32))), d
+        else:
+            pref = formats.decode_bf16(a_list[d]) @ formats.decode_bf16(b_list[d])
+            assert compare.max_row_rel_error(formats.decode_bf16(own), pref) <= TOL_BF16
+            assert compare.max_row_rel_error(formats.decode_bf16(got), ref) <= TOL_BF16
+        # the consumer on what was actually published: bit-exact to the specified arithmetic
+        published = [own if s == d else parts[s] for s in range(world)]
+        assert np.array_equal(got, oar.allreduce_partials_f32_ordered(published)), d
+        _check_schedule(run, cfg, sched.cpu().numpy().reshape(-1, 4))
+        sig = run.signals.cpu().numpy()
+        assert not sig[:2 * world].any()                                # the queue counters are back at zero
+        flags = sig[2 * world:2 * world + world * run.ntiles]
+        assert flags.tolist() == [run.epoch] * (world * run.ntiles)     # every tile of every rank was announced
 
 
 def test_external_producer_and_timeout(B):
@@ -158,5 +157,3 @@ def test_table_shape_full_size(B):
     rows = np.arange(0, cfg.m, 67)       # sampled rows, every tile row and column, against the definition
     ref = oar.gemm_ar(a_list, b_list, rows=rows)
     assert compare.max_row_rel_error(formats.decode_bf16(got[rows]), ref) <= TOL_BF16
-    sig = run.signals.cpu().numpy()
-    assert sig[0] == 0 and sig[1] == 0

@@ -25,8 +25,7 @@ def _declared_functions():
 def test_every_declared_symbol_is_exported(B):
     names = _declared_functions()
     assert {"ditron_ag_gemm", "ditron_gemm_rs", "ditron_moe_ag_grouped_gemm", "ditron_reduce_slots",
-            "ditron_publish_chunks", "ditron_tile_config", "ditron_signal_words", "ditron_gemm_ar",
-            "ditron_set_comm_wgs"} <= set(names)
+            "ditron_publish_chunks", "ditron_tile_config", "ditron_signal_words", "ditron_gemm_ar"} <= set(names)
     for n in names:
         assert hasattr(B.lib, n), n
 
@@ -125,7 +124,6 @@ def test_gemm_ar_argument_checks(B):
     assert call(b_layout=5) == B.ERR_INVALID_ARG
     assert call(k_local=60) == B.ERR_UNSUPPORTED
     assert call(n=100) == B.ERR_UNSUPPORTED
-    assert B.set_comm_wgs(1000) == B.ERR_INVALID_ARG and B.set_comm_wgs(-1) == B.OK
     st, tc = B.tile_config(3, 8192, 8192, 3584)
     assert st == B.OK and (tc["block_m"], tc["block_n"], tc["ntiles"]) == (256, 256, 1024)
 
