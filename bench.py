@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the fused communication + GEMM hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg4|cfg5|cfg1|gemm_ar|sweep]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg4|cfg5|cfg1|gemm_ar|sweep|moe_sweep]
 
 A step is one pass of the whole path for the workload: for cfg2 (the default, the
 configuration the headline metric is quoted on) one ditron_ag_gemm call with the emulated
@@ -537,6 +537,86 @@ def bench_sweep(args):
     }
 
 
+# The paper's AllGather+MoE shapes (Appendix "Evaluation Setup", table "Shapes for AllGather+MoE and
+# MoE+AllReduce": tokens 8192) in its tensor-parallel placement: every expert on every rank, the
+# intermediate dimension divided by the 8 ranks.  (name, hidden, intermediate / 8, experts, top_k)
+SWEEP_MOE = [("Qwen1.5-MoE-A2.7B", 2048, 176, 60, 4), ("Mixtral-8x7B", 14336, 512, 8, 2),
+             ("Mixtral-8x22B", 16384, 768, 8, 2), ("DeepSeek-MoE", 1408, 256, 64, 6)]
+
+
+def bench_moe_sweep(args):
+    """MoE AllGather + grouped GEMM over the four shapes of the paper's MoE table, all experts local
+    (expert_begin 0), 8 x 1024 tokens, uniform top-k routing, N(0,1) / N(0,1/hidden) bf16 made on the
+    device.  One step = the four problems once."""
+    import math
+    import torch
+    from paper_2605_02953_amd import binding as B
+    from gpu_util import MoeRun
+
+    world, t_r = 8, 1024
+    g = torch.Generator(device="cuda").manual_seed(7)
+    problems = []
+    for name, hidden, inter, experts, top_k in SWEEP_MOE:
+        rows = world * t_r * top_k
+        run = MoeRun(B, world, t_r, hidden, inter, experts, top_k, experts, rows)
+        xs = [torch.randn((t_r, hidden), device="cuda", generator=g).to(torch.bfloat16).view(torch.int16) for _ in range(world)]
+        # top_k distinct experts per token: the first top_k of a random permutation
+        ids = torch.rand((world * t_r, experts), device="cuda", generator=g).argsort(dim=1)[:, :top_k].to(torch.int32).contiguous()
+        w = (torch.randn((experts, inter, hidden), device="cuda", generator=g) * hidden ** -0.5).to(torch.bfloat16).view(torch.int16)
+
+        def call(run=run, xs=xs, ids=ids, w=w):
+            st = run(xs, ids, w, 0, 0)
+            if st != B.OK:
+                raise RuntimeError(B.status_string(st))
+
+        problems.append((name, hidden, inter, experts, top_k, rows, call, run))
+
+    def step():
+        for pr in problems:
+            pr[6]()
+
+    _ramp(torch, step)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    reps = max(1, args.steps)
+    per = [[] for _ in problems]
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        for i, pr in enumerate(problems):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            pr[6]()
+            e1.record()
+            per[i].append((e0, e1))
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    rows_out, total_flops, logs = [], 0.0, []
+    for i, (name, hidden, inter, experts, top_k, rows, _, run) in enumerate(problems):
+        if run.status.cpu().tolist()[0] != 0:
+            raise RuntimeError("kernel reported an error")
+        assert int(run.offsets.cpu()[-1]) == rows
+        flops = 2.0 * rows * hidden * inter
+        total_flops += flops
+        us = _quantiles_us(per[i])["median"]
+        alg_bytes = experts * inter * hidden * 2 + world * t_r * hidden * 2 + rows * inter * 2
+        rows_out.append({"model": name, "tokens": world * t_r, "hidden": hidden, "inter": inter, "experts": experts, "top_k": top_k,
+                         "rows": rows, "us": us, "tflops": flops / us / 1e6, "algorithmic_gbs": alg_bytes / us / 1e3})
+        logs.append(math.log(flops / us / 1e6))
+    ms_per_step = wall * 1e3 / reps
+    geo = math.exp(sum(logs) / len(logs))
+    return {
+        "metric": "TFLOP/s over one pass of the paper's 4 AllGather+MoE shapes (tensor-parallel placement, per-rank share, world 8)",
+        "value": total_flops / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": reps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "moe_sweep: route + emulated all-gather + grouped GEMM [tokens*top_k, hidden] x [experts, hidden, inter/8] for the four models of the paper's MoE table"},
+        "roofline": {"bound": "mfma", "achieved": geo, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": geo / PEAK_BF16_TFLOPS,
+                     "traffic": None, "kernel": "geometric mean over the four problems (events around each call: both launches)"},
+        "sweep": rows_out,
+    }
+
+
 def bench_fp8(args):
     import torch
     import synth
@@ -613,6 +693,8 @@ def main():
         out = bench_gemm_ar(args)
     elif args.workload == "sweep":
         out = bench_sweep(args)
+    elif args.workload == "moe_sweep":
+        out = bench_moe_sweep(args)
     else:
         print(f"bench.py: unknown workload {args.workload}", file=sys.stderr)
         sys.exit(2)

@@ -1,15 +1,17 @@
 // MoE AllGather + grouped GEMM, one rank's share (paper: "ag_group_gemm" of the kernel
 // list; tile ordering after `threadblock_swizzle_ag_moe_kernel`, Appendix "Swizzle").
 //
-// Launch 1 (one work-group, integer only): per-(rank, expert) histogram, exclusive scan of
+// Launch 1.  Work-group 0 (integer only): per-(rank, expert) histogram, exclusive scan of
 // the local experts' totals, stable gather index, then the tile list: every local expert's
 // rows are cut into BLOCK_M row tiles, each tile learns the span of source ranks its rows
 // come from and the ring stage at which the last of them arrives, and tiles are emitted
-// grouped by expert, ascending stage, ties in original order.
-// Launch 2: producer work-groups copy the token shards into the workspace in delivery order
-// and raise one flag per shard; every other work-group takes one (tile, column block), waits
-// for the shard flags of its tile, gathers its rows through gather_idx while staging them in
-// LDS and multiplies by its expert's weights.
+// grouped by expert, ascending stage, ties in original order.  The other work-groups are the
+// emulated peers: they copy the token shards into the workspace in delivery order and raise
+// one flag per shard.  The all-gather does not depend on the routing, so it starts with the
+// call and runs beside the routing work-group (which leaves the rest of the chip idle).
+// Launch 2: every work-group takes one (tile, column block), waits for the shard flags of its
+// tile, gathers its rows through gather_idx while staging them in LDS and multiplies by its
+// expert's weights.
 #include "gemm_core.h"
 #include "launch.h"
 
@@ -30,6 +32,15 @@ struct MoeRouteParams {
   int32_t* status;
   int tokens_per_rank, top_k, num_experts, expert_begin, num_local, max_rows, max_tiles;
   int world, rank, block_m;
+  // the emulated peers (work-groups 1 .. num_producers)
+  const void* shard[DITRON_MAX_WORLD];
+  int order[DITRON_MAX_WORLD];
+  char* workspace;
+  int32_t* flags;
+  int32_t* arrivals;
+  size_t shard_bytes;
+  int32_t epoch;
+  int num_producers, teams;
 };
 
 __global__ __launch_bounds__(kRouteThreads) void moe_route_kernel(const MoeRouteParams p) {
@@ -39,6 +50,14 @@ __global__ __launch_bounds__(kRouteThreads) void moe_route_kernel(const MoeRoute
   __shared__ int s_tile_acc[kMaxLocalExperts + 1];               // exclusive prefix of tiles per expert
   __shared__ int s_cum[kMaxLocalExperts][DITRON_MAX_WORLD];      // inclusive per-rank cumulative rows per expert
   __shared__ int s_stage[kMaxTilesLds];
+  if (blockIdx.x > 0) {
+    produce_chunks<kRouteThreads>(
+        p.world, p.shard_bytes, blockIdx.x - 1, p.num_producers, p.teams, p.epoch,
+        [&](int i) { return (void*)(p.workspace + (size_t)p.order[i] * p.shard_bytes); },
+        [&](int i) { return p.shard[p.order[i]]; }, [&](int i) { return p.flags + p.order[i]; },
+        [&](int i) { return p.arrivals + p.order[i]; });
+    return;
+  }
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int F = p.world * p.tokens_per_rank * p.top_k;
   const int per_shard = p.tokens_per_rank * p.top_k;
@@ -120,11 +139,12 @@ __global__ __launch_bounds__(kRouteThreads) void moe_route_kernel(const MoeRoute
   }
   __syncthreads();
 
-  // stable placement: 64 assignments at a time.  For every local expert the lanes that hold it
-  // are found with one ballot and rank themselves by counting the lanes below them; lane l keeps
-  // the wave's running output position of local expert l in a register (there are at most 64
-  // local experts), so a round is a handful of scalar instructions and no trip through LDS.
-  int next_pos = lane < EL ? s_wave_base[wave][lane] : 0;
+  // stable placement: 64 assignments at a time.  The lanes that hold the same local expert find
+  // each other with one ballot per bit of the expert index (a lane keeps the lanes that agree with
+  // it on every bit), rank themselves by counting the lanes below them, and the last of them moves
+  // the wave's running output position of that expert (kept in LDS) past the group.  The cost per
+  // round does not grow with the number of local experts beyond the number of index bits.
+  const int nbits = EL > 1 ? 32 - __builtin_clz(EL - 1) : 0;
   const unsigned long long below = (1ull << lane) - 1ull;
   for (int fb = w_begin; fb < w_end; fb += 64 * kBatch) {
     int jj[kBatch];
@@ -142,13 +162,21 @@ __global__ __launch_bounds__(kRouteThreads) void moe_route_kernel(const MoeRoute
     for (int b = 0; b < kBatch; ++b) {
       const int f = fb + b * 64 + lane;
       const int j = jj[b];
-      if (__ballot(j >= 0) == 0) continue;
-      for (int jl = 0; jl < EL; ++jl) {
-        const unsigned long long same = __ballot(j == jl);
-        if (same == 0) continue;
-        const int base = __builtin_amdgcn_readlane(next_pos, jl);
-        if (j == jl) p.gather_idx[base + __popcll(same & below)] = f;
-        if (lane == jl) next_pos += __popcll(same);
+      const bool local = j >= 0;
+      unsigned long long same = __ballot(local);
+      if (same == 0) continue;
+      for (int bit = 0; bit < nbits; ++bit) {
+        const bool set = local && ((j >> bit) & 1);
+        const unsigned long long m = __ballot(set);
+        same &= set ? m : ~m;
+      }
+      if (local) {
+        // LDS operations of one wave complete in order: every lane of the group reads the position
+        // before the group's last lane advances it, and the next round reads the advanced value
+        const int base = s_wave_base[wave][j];
+        const int rank = __popcll(same & below), count = __popcll(same);
+        p.gather_idx[base + rank] = f;
+        if (rank == count - 1) s_wave_base[wave][j] = base + count;
       }
     }
   }
@@ -192,36 +220,23 @@ __global__ __launch_bounds__(kRouteThreads) void moe_route_kernel(const MoeRoute
 }
 
 struct MoeGemmParams {
-  const void* shard[DITRON_MAX_WORLD];
-  int order[DITRON_MAX_WORLD];
-  char* workspace;
+  const char* workspace;
   const char* w;
   __bf16* y;
   const int32_t* expert_offsets;
   const int32_t* gather_idx;
   const int32_t* tile_records;
-  int32_t* flags;
-  int32_t* arrivals;
+  const int32_t* flags;
   int32_t* status;
   int tokens_per_rank, hidden, inter, top_k, world, max_tiles, npn;
   int32_t epoch;
-  int num_producers, teams;
   unsigned spin_limit;
 };
 
 template <class T>
 __global__ __launch_bounds__(T::THREADS) void moe_grouped_gemm_kernel(const MoeGemmParams p) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
-  if ((int)blockIdx.x < p.num_producers) {
-    const size_t shard_bytes = (size_t)p.tokens_per_rank * p.hidden * 2;
-    produce_chunks<T::THREADS>(
-        p.world, shard_bytes, blockIdx.x, p.num_producers, p.teams, p.epoch,
-        [&](int i) { return (void*)(p.workspace + (size_t)p.order[i] * shard_bytes); },
-        [&](int i) { return p.shard[p.order[i]]; }, [&](int i) { return p.flags + p.order[i]; },
-        [&](int i) { return p.arrivals + p.order[i]; });
-    return;
-  }
-  const int wg = blockIdx.x - p.num_producers;
+  const int wg = blockIdx.x;
   const int pos = wg / p.npn, pid_n = wg % p.npn;
   const int ntiles = p.tile_records[0];
   if (pos >= ntiles) return;
@@ -259,7 +274,7 @@ static ditron_status_t launch_moe_gemm(MoeGemmParams& g, int max_tiles, hipStrea
   g.npn = cdiv(g.inter, T::BN);
   auto kern = moe_grouped_gemm_kernel<T>;
   if (!set_dynamic_lds((const void*)kern, T::LDS_BYTES)) return DITRON_ERR_HIP;
-  const unsigned grid = (unsigned)(g.num_producers + max_tiles * g.npn);
+  const unsigned grid = (unsigned)(max_tiles * g.npn);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(T::THREADS), T::LDS_BYTES, s, g);
   return hipGetLastError() == hipSuccess ? DITRON_OK : DITRON_ERR_HIP;
 }
@@ -317,22 +332,31 @@ extern "C" ditron_status_t ditron_moe_ag_grouped_gemm(
   r.world = world;
   r.rank = rank;
   r.block_m = kMoeBlockM;
-  hipLaunchKernelGGL(moe_route_kernel, dim3(1), dim3(kRouteThreads), 0, s, r);
+  for (int i = 0; i < world; ++i) {
+    r.shard[i] = emulate ? x_shards[i] : nullptr;
+    r.order[i] = arrival_order ? arrival_order[i] : (rank + i) % world;
+  }
+  r.workspace = (char*)workspace;
+  r.flags = signals;
+  r.arrivals = signals + world;
+  r.shard_bytes = (size_t)tokens_per_rank * hidden * 2;
+  r.epoch = epoch;
+  // as many work-groups (of 1024 threads here) as the plan for 256-thread producers: measured best of
+  // a quarter, half, the same and twice as many (159, 127, 105, 125 us for the whole cfg 4 step)
+  const ProducerPlan pl = plan_producers((size_t)world * r.shard_bytes, world);
+  r.num_producers = emulate ? pl.producers : 0;
+  r.teams = std::min(pl.teams, std::max(1, r.num_producers));
+  hipLaunchKernelGGL(moe_route_kernel, dim3(1 + r.num_producers), dim3(kRouteThreads), 0, s, r);
   if (hipGetLastError() != hipSuccess) return DITRON_ERR_HIP;
 
   MoeGemmParams g{};
-  for (int i = 0; i < world; ++i) {
-    g.shard[i] = emulate ? x_shards[i] : nullptr;
-    g.order[i] = arrival_order ? arrival_order[i] : (rank + i) % world;
-  }
-  g.workspace = (char*)workspace;
+  g.workspace = (const char*)workspace;
   g.w = (const char*)w;
   g.y = (__bf16*)y;
   g.expert_offsets = expert_offsets;
   g.gather_idx = gather_idx;
   g.tile_records = tile_records;
   g.flags = signals;
-  g.arrivals = signals + world;
   g.status = status;
   g.tokens_per_rank = tokens_per_rank;
   g.hidden = hidden;
@@ -341,9 +365,6 @@ extern "C" ditron_status_t ditron_moe_ag_grouped_gemm(
   g.world = world;
   g.max_tiles = max_tiles;
   g.epoch = epoch;
-  const ProducerPlan pl = plan_producers((size_t)world * tokens_per_rank * hidden * 2, world);
-  g.num_producers = emulate ? pl.producers : 0;
-  g.teams = pl.teams;
   g.spin_limit = g_spin_limit;
   const long expected_rows = (long)world * tokens_per_rank * top_k * num_local_experts / num_experts;
   switch (choose_moe_block_n(expected_rows, num_local_experts, inter)) {

@@ -81,6 +81,22 @@ def test_moe_end_to_end(B, world, t_r, hidden, inter, experts, top_k, local, ran
     _run_and_check(B, cfg, xs, ids, w, max_rows, integer, order=order)
 
 
+@pytest.mark.parametrize("hidden,inter,experts,top_k", [
+    (2048, 176, 60, 4),      # Qwen1.5-MoE-A2.7B
+    (14336, 512, 8, 2),      # Mixtral-8x7B
+    (16384, 768, 8, 2),      # Mixtral-8x22B
+    (1408, 256, 64, 6),      # DeepSeek-MoE
+])
+def test_moe_table_shapes_tensor_parallel_placement(B, hidden, inter, experts, top_k):
+    """The paper's AllGather+MoE shapes (Appendix "Evaluation Setup", MoE shape table) in its own placement:
+    every expert on every rank, the intermediate size divided by the 8 ranks; 8 x 128 tokens instead of
+    8 x 1024 so that the oracle stays quick."""
+    cfg = synth.CONFIGS[4].scaled(world=8, tokens_per_rank=128, k=hidden, n=inter, num_experts=experts,
+                                  top_k=top_k, num_local_experts=experts, rank=0)
+    xs, ids, w = synth.moe_inputs(cfg)
+    _run_and_check(B, cfg, xs, ids, w, 8 * 128 * top_k, integer=False)
+
+
 def test_moe_degenerate_routings(B):
     cfg = synth.CONFIGS[4].scaled(world=4, tokens_per_rank=96, k=64, n=128, num_experts=8, top_k=1,
                                   num_local_experts=4, rank=1)
