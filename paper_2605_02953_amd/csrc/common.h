@@ -74,8 +74,10 @@ __device__ inline void flag_wait_block(const int32_t* flags, int first, int coun
 // ------------------------------------------------------------------ chunk copy
 // Copy `bytes` (multiple of 16) from src to dst with 128-bit accesses, the calling
 // work-group being part `part` of `nparts` cooperating work-groups.
-// U = independent 16-byte loads in flight per lane.
-template <int U>
+// U = independent 16-byte loads in flight per lane.  STREAM: the stores bypass the chiplet's L2
+// (right when nothing on the chip reads the copy soon: the flag's release then has no dirty
+// lines to write back; wrong when GEMM tiles next door are waiting for the data).
+template <int U, bool STREAM = false>
 __device__ inline void copy_slice_u(void* __restrict__ dst, const void* __restrict__ src, size_t bytes,
                                     int part, int nparts) {
   const size_t n16 = bytes >> 4;
@@ -90,15 +92,17 @@ __device__ inline void copy_slice_u(void* __restrict__ dst, const void* __restri
       if (i + u * stride < n16) v[u] = __builtin_nontemporal_load(s + i + u * stride);
 #pragma unroll
     for (int u = 0; u < U; ++u)
-      if (i + u * stride < n16) d[i + u * stride] = v[u];
+      if (i + u * stride < n16) {
+        if (STREAM) __builtin_nontemporal_store(v[u], d + i + u * stride); else d[i + u * stride] = v[u];
+      }
   }
 }
 
 // A work-group of THREADS threads keeps about 128 KiB of loads in flight whatever its size.
-template <int THREADS>
+template <int THREADS, bool STREAM = false>
 __device__ inline void copy_slice(void* __restrict__ dst, const void* __restrict__ src, size_t bytes,
                                   int part, int nparts) {
-  copy_slice_u<(THREADS <= 256 ? 32 : 16)>(dst, src, bytes, part, nparts);
+  copy_slice_u<(THREADS <= 256 ? 32 : 16), STREAM>(dst, src, bytes, part, nparts);
 }
 
 // After every cooperating work-group has finished its slice of a chunk, the last one to
@@ -124,7 +128,7 @@ __device__ inline void publish_after_all(int32_t* counter, int nparts, int32_t* 
 // member that finishes a chunk last raises its flag.  One team means strictly sequential
 // arrival in delivery order (a ring); as many teams as chunks means everything is in flight
 // at once (a full mesh where every peer pushes at the same time).
-template <int THREADS, class Dst, class Src, class Flag, class Counter>
+template <int THREADS, bool STREAM = false, class Dst, class Src, class Flag, class Counter>
 __device__ inline void produce_chunks(int nchunks, size_t chunk_bytes, int part, int nparts, int teams,
                                       int32_t epoch, Dst dst, Src src, Flag flag, Counter counter) {
   teams = max(1, min(teams, min(nparts, nchunks)));
@@ -132,7 +136,7 @@ __device__ inline void produce_chunks(int nchunks, size_t chunk_bytes, int part,
   const int team = part / team_size, member = part % team_size;
   if (team >= teams) return;   // left-over work-groups when nparts is not a multiple of teams
   for (int i = team; i < nchunks; i += teams) {
-    copy_slice<THREADS>(dst(i), src(i), chunk_bytes, member, team_size);
+    copy_slice<THREADS, STREAM>(dst(i), src(i), chunk_bytes, member, team_size);
     publish_after_all(counter(i), team_size, flag(i), epoch);
   }
 }

@@ -51,7 +51,8 @@ __global__ __launch_bounds__(kRouteThreads) void moe_route_kernel(const MoeRoute
   __shared__ int s_cum[kMaxLocalExperts][DITRON_MAX_WORLD];      // inclusive per-rank cumulative rows per expert
   __shared__ int s_stage[kMaxTilesLds];
   if (blockIdx.x > 0) {
-    produce_chunks<kRouteThreads>(
+    // streaming stores: the grouped GEMM that reads the workspace is a later launch
+    produce_chunks<kRouteThreads, true>(
         p.world, p.shard_bytes, blockIdx.x - 1, p.num_producers, p.teams, p.epoch,
         [&](int i) { return (void*)(p.workspace + (size_t)p.order[i] * p.shard_bytes); },
         [&](int i) { return p.shard[p.order[i]]; }, [&](int i) { return p.flags + p.order[i]; },
