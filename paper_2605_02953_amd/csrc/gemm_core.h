@@ -304,8 +304,9 @@ __device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[T::NI][T::MI], con
 // SL lanes; written straight from the MFMA layout, a store instruction would scatter 8-byte
 // pieces over 32 rows).  A parked row has SLP >= SL slots (a power of two); the 16-byte slot g
 // of row m lives at slot g ^ key(m), which keeps the 8-byte writes (2-way at worst) and the
-// 16-byte reads away from bank conflicts.
-template <class T>
+// 16-byte reads away from bank conflicts.  STREAM: global stores with the streaming hint (for a tile
+// that is followed by a release and read much later: nothing dirty is left for the release to write back).
+template <class T, bool STREAM = false>
 __device__ __forceinline__ void store_tile_bf16(const f32x16_t (&acc)[T::NI][T::MI], __bf16* c, size_t ldc, int m0,
                                                     int n0, int M, int N, char* lds) {
   constexpr int SL = T::WTN / 8;            // 16-byte slots of data per row: 16, 12 or 8
@@ -342,7 +343,9 @@ __device__ __forceinline__ void store_tile_bf16(const f32x16_t (&acc)[T::NI][T::
     const int row = it * ROWS_PER_READ + lane / SLP;
     const u32x4_t v = *(const u32x4_t*)(park + row * ROW + ((g ^ key(row)) * 16));
     const int gm = m0 + wm * T::WTM + row;
-    if (g < SL && gm < M && gn < N) *(u32x4_t*)(c + (size_t)gm * ldc + gn) = v;
+    if (g < SL && gm < M && gn < N) {
+      if (STREAM) __builtin_nontemporal_store(v, (u32x4_t*)(c + (size_t)gm * ldc + gn)); else *(u32x4_t*)(c + (size_t)gm * ldc + gn) = v;
+    }
   }
 }
 
