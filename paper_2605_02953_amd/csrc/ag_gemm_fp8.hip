@@ -5,22 +5,24 @@
 // output tile and keeps many small B stages in flight: B (32 rows x 128 bytes per K tile)
 // runs through a 16-deep LDS ring that is started before the shard flags are even looked at
 // (B does not depend on the gather), while A (128 rows x 128 bytes per K tile, served from
-// L2) uses a 5-deep ring that starts once the flags are up.  v_mfma_f32_16x16x128_f8f6f4
-// consumes 32 contiguous bytes per lane of each operand.
+// L2) uses a 5-deep ring that starts once the flags are up.  The two streams are issued by
+// different waves: a wave's loads return in order, so an A load (L2 latency) queued behind a
+// B load (HBM latency) would wait for it.  Waves 0-3 fetch A and compute, waves 4-7 only
+// fetch B; one barrier per K tile joins them.  v_mfma_f32_16x16x128_f8f6f4 consumes 32
+// contiguous bytes per lane of each operand.
 #include "gemm_core.h"
 #include "launch.h"
 
 namespace ditron {
 
 struct Fp8Tile {
-  static constexpr int BM = 128, BN = 32, BK = 128, THREADS = 256, NWAVES = 4;
+  static constexpr int BM = 128, BN = 32, BK = 128, NWAVES = 4, THREADS = 512;   // 4 compute waves + 4 B loaders
   static constexpr int NA = 5, NB = 16;                 // ring depths
   static constexpr int A_STAGE = BM * 128, B_STAGE = BN * 128;
   static constexpr int A_LOADS = BM / 8 / NWAVES;       // 4 wave-wide loads per wave per K tile
   static constexpr int LDS_BYTES = NA * A_STAGE + NB * B_STAGE;
-  // loads issued after A(kt) that may still be in flight when tile kt is needed: the B load of
-  // the iteration that issued A(kt), then NA-2 whole iterations (A_LOADS + 1 loads each)
-  static constexpr int PENDING = 1 + (NA - 2) * (A_LOADS + 1);
+  // loads of a wave that may still be in flight when tile kt is needed: the younger tiles of its ring
+  static constexpr int PENDING_A = (NA - 2) * A_LOADS, PENDING_B = NB - 2;
 };
 
 typedef int i32x8_t __attribute__((ext_vector_type(8)));
@@ -86,7 +88,9 @@ __global__ __launch_bounds__(Fp8Tile::THREADS) void ag_gemm_fp8_kernel(const AgG
     a_kc[i] = c * 16;
     a_ptr[i] = p.workspace + (size_t)min(m0 + r, p.m - 1) * K + c * 16;
   }
-  const int rb = wave * 8 + (lane >> 3);
+  const bool loader = wave >= T::NWAVES;        // waves 4-7 stream B, waves 0-3 stream A and compute
+  const int lw = wave - T::NWAVES;
+  const int rb = (loader ? lw : 0) * 8 + (lane >> 3);
   const int cb = (lane & 7) ^ swz128(rb);
   const int b_kc = cb * 16;
   const char* b_ptr = p.b + (size_t)min(n0 + rb, p.n - 1) * K + cb * 16;
@@ -108,21 +112,30 @@ __global__ __launch_bounds__(Fp8Tile::THREADS) void ag_gemm_fp8_kernel(const AgG
     char* stage = lds_b + (kt % T::NB) * T::B_STAGE;
     const char* src = b_ptr + (size_t)kte * T::BK;
     if (kte * T::BK + b_kc >= K) src = (const char*)&kZeroChunk;
-    __builtin_amdgcn_global_load_lds(src, DITRON_LDS(stage + wave * 1024), 16, 0, 0);
+    __builtin_amdgcn_global_load_lds(src, DITRON_LDS(stage + lw * 1024), 16, 0, 0);
   };
 
-  // wave 0 looks at the flags before it has any load in flight (loads return in order, so a
-  // poll issued behind the B prefetch would wait for it); the other waves start B at once
+  // wave 0 looks at the flags; the loaders start B at once (it does not depend on the gather)
   if (wave == 0) flag_wait_wave(p.flags, rank_beg, rank_end - rank_beg + 1, p.epoch, p.spin_limit, p.status);
+  if (loader) {
 #pragma unroll 1
-  for (int kt = 0; kt < T::NB - T::NA; ++kt) issue_b(kt);
+    for (int kt = 0; kt < T::NB - 1; ++kt) issue_b(kt);
+  }
   barrier_no_drain();                           // flags seen by wave 0 -> A may be read by everyone
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-#pragma unroll
-  for (int j = 0; j < T::NA - 1; ++j) {
-    issue_a(j);
-    issue_b(T::NB - T::NA + j);
+  if (loader) {
+#pragma unroll 1
+    for (int kt = 0; kt < kt_all; ++kt) {
+      // B(kt) has landed once at most PENDING_B younger loads of this wave are outstanding
+      __builtin_amdgcn_s_waitcnt(0x0F70 | (T::PENDING_B & 0xF) | ((T::PENDING_B >> 4) << 14));
+      barrier_no_drain();
+      issue_b(kt + T::NB - 1);                  // into the stage every wave finished reading before this barrier
+    }
+    wait_vmcnt0();                              // the redundant tail loads land before the LDS is handed back
+    return;
   }
+#pragma unroll
+  for (int j = 0; j < T::NA - 1; ++j) issue_a(j);
 
   f32x4_t acc[2][2];
 #pragma unroll
@@ -136,11 +149,10 @@ __global__ __launch_bounds__(Fp8Tile::THREADS) void ag_gemm_fp8_kernel(const AgG
 
 #pragma unroll 1
   for (int kt = 0; kt < kt_all; ++kt) {
-    // everything up to A(kt) has landed once at most PENDING younger loads are outstanding
-    __builtin_amdgcn_s_waitcnt(0x0F70 | (T::PENDING & 0xF) | ((T::PENDING >> 4) << 14));
+    // A(kt) has landed once at most PENDING_A younger loads of this wave are outstanding
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (T::PENDING_A & 0xF) | ((T::PENDING_A >> 4) << 14));
     barrier_no_drain();
     issue_a(kt + T::NA - 1);
-    issue_b(kt + T::NB - 1);
     const char* sa = lds_a + (kt % T::NA) * T::A_STAGE + (wave * 32 + l16) * 128;
     const char* sb = lds_b + (kt % T::NB) * T::B_STAGE + l16 * 128;
     i32x8_t af[2], bf[2];

@@ -52,13 +52,13 @@ inline TileChoice choose_tile(int m, int n, int /*k*/) {
   return t;
 }
 
-// fp8 path: one tile shape, 128 rows x 32 columns, 4 waves.
+// fp8 path: one tile shape, 128 rows x 32 columns, 4 computing waves + 4 loading waves.
 inline TileChoice choose_tile_fp8(int /*m*/, int /*n*/, int /*k*/) {
   TileChoice t{};
   t.big = false;
   t.block_m = 128;
   t.block_n = 32;
-  t.threads = 256;
+  t.threads = 512;
   t.group_m = 4;
   t.num_xcd = 8;
   t.per_xcd = 32;
