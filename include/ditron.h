@@ -174,6 +174,30 @@ ditron_status_t ditron_gemm_rs(const void* a, const void* b, int b_layout, void*
                                void* stream);
 
 /*
+ * GEMM-ReduceScatter with the scatter fused into the GEMM's stores.  Paper: the FUSE_SCATTER branch of
+ * `kernel_gemm_rs_producer` and of `gemm_rs_op` (Appendix "GEMM Reduce-Scatter"): instead of writing
+ * its partial product to a local [m, n] buffer, a tile stores the rows of segment d directly into
+ * rank d's buffer, row m landing at row rank*(m/world) + m % (m/world), i.e. in slot `rank` of
+ * that rank's [world, m/world, n] buffer; the reduction then sums the `world` slots of the local
+ * buffer.  Everything else (tile order, segment counters and flags, emulated arrival of the
+ * peers' blocks into the local slots, gated reduction) is as in ditron_gemm_rs.
+ *
+ *  scatter_dsts  host array of `world` device pointers, each a [world, m/world, n] bf16 buffer:
+ *                entry d stands for the buffer of rank d (on one GPU: any distinct device
+ *                buffers); entry `rank` is this rank's own buffer, the one the peers' blocks
+ *                arrive in and the reduction reads.  Only slot `rank` of the other entries is
+ *                written.
+ *  other arguments as for ditron_gemm_rs (there is no gemm_out).
+ */
+ditron_status_t ditron_gemm_rs_fuse_scatter(const void* a, const void* b, int b_layout,
+                                            void* const* scatter_dsts, const void* const* peer_partials,
+                                            void* out, int32_t* signals, int32_t* status,
+                                            int32_t* schedule_out, const int* arrival_order, int m,
+                                            int n, int k_local, int world, int rank,
+                                            int chunks_per_slot, int32_t epoch, unsigned flags,
+                                            void* stream);
+
+/*
  * GEMM + AllReduce, one-shot:  out[m, n] = sum_s P_s,  P_rank = A . B computed here.
  *
  * Paper: `gemm_allreduce_op`, `kernel_persistent_gemm_notify` and `consumer_all_reduce_kernel`

@@ -50,3 +50,12 @@ def reduce_slots_f32_ordered(slots):
     for s in slots[1:]:
         acc = (acc + decode_bf16(s).astype(np.float32)).astype(np.float32)
     return encode_bf16_rne(acc)
+
+
+def fused_scatter_row(m_row, rank, world, m):
+    """Where row `m_row` of rank `rank`'s partial product goes when the scatter is fused into the GEMM's
+    stores (producer kernel, FUSE_SCATTER branch): (destination rank, row in that rank's [M, N] buffer).
+    The destination is the owner of the row's segment; inside its buffer the row lands in the slot of the
+    sending rank, at the row's offset inside the segment."""
+    m_r = m // world
+    return m_row // m_r, rank * m_r + m_row % m_r

@@ -45,6 +45,9 @@ lib.ditron_ag_gemm.argtypes = [_pp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, 
 lib.ditron_gemm_rs.restype = _i
 lib.ditron_gemm_rs.argtypes = [_vp, _vp, _i, _vp, _pp, _vp, _vp, _vp, _vp, _vp, _ip,
                                _i, _i, _i, _i, _i, _i, _i32, _u, _vp]
+lib.ditron_gemm_rs_fuse_scatter.restype = _i
+lib.ditron_gemm_rs_fuse_scatter.argtypes = [_vp, _vp, _i, _pp, _pp, _vp, _vp, _vp, _vp, _ip,
+                                            _i, _i, _i, _i, _i, _i, _i32, _u, _vp]
 lib.ditron_gemm_ar.restype = _i
 lib.ditron_gemm_ar.argtypes = [_vp, _vp, _i, _vp, _pp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i32, _u, _vp]
 lib.ditron_reduce_slots.restype = _i
@@ -131,6 +134,14 @@ def gemm_rs(a, b, b_layout, gemm_out, peer_partials, scatter_buf, out, signals, 
                               _ptr(scatter_buf), _ptr(out), _ptr(signals), _ptr(status), _ptr(schedule_out),
                               _int_array(arrival_order), m, n, k_local, world, rank, chunks_per_slot, epoch,
                               flags, _stream(stream))
+
+
+def gemm_rs_fuse_scatter(a, b, b_layout, scatter_dsts, peer_partials, out, signals, status, schedule_out,
+                         arrival_order, m, n, k_local, world, rank, chunks_per_slot, epoch, flags, stream=None):
+    return lib.ditron_gemm_rs_fuse_scatter(_ptr(a), _ptr(b), b_layout, _ptr_array(scatter_dsts),
+                                           _ptr_array(peer_partials), _ptr(out), _ptr(signals), _ptr(status),
+                                           _ptr(schedule_out), _int_array(arrival_order), m, n, k_local, world, rank,
+                                           chunks_per_slot, epoch, flags, _stream(stream))
 
 
 def gemm_ar(a, b, b_layout, gemm_out, peer_partials, out, signals, status, schedule_out, m, n, k_local, world,

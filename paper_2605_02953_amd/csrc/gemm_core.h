@@ -306,19 +306,24 @@ __device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[T::NI][T::MI], con
 // of row m lives at slot g ^ key(m), which keeps the 8-byte writes (2-way at worst) and the
 // 16-byte reads away from bank conflicts.  STREAM: global stores with the streaming hint (for a tile
 // that is followed by a release and read much later: nothing dirty is left for the release to write back).
-template <class T, bool STREAM = false>
-__device__ __forceinline__ void store_tile_bf16(const f32x16_t (&acc)[T::NI][T::MI], __bf16* c, size_t ldc, int m0,
-                                                    int n0, int M, int N, char* lds) {
-  constexpr int SL = T::WTN / 8;            // 16-byte slots of data per row: 16, 12 or 8
-  constexpr int SLP = SL <= 8 ? 8 : 16;     // slots per parked row
-  constexpr int ROW = SLP * 16;             // bytes per parked row
+template <class T>
+struct ParkedTile {
+  static constexpr int SL = T::WTN / 8;            // 16-byte slots of data per row: 16, 12 or 8
+  static constexpr int SLP = SL <= 8 ? 8 : 16;     // slots per parked row
+  static constexpr int ROW = SLP * 16;             // bytes per parked row
   static_assert(4 * T::WTM * ROW <= T::LDS_BYTES, "the parked tile fits in the operand stages");
-  auto key = [](int m) { return SLP == 16 ? (m & 15) : ((m >> 1) & 7); };   // 128-byte rows pair up in a 256-byte bank window
+  // 128-byte rows pair up in a 256-byte bank window
+  __device__ static __forceinline__ int key(int m) { return SLP == 16 ? (m & 15) : ((m >> 1) & 7); }
+};
+
+// First half of the epilogue: accumulators -> bf16 -> the wave's piece of the operand stages.
+template <class T>
+__device__ __forceinline__ void park_tile_bf16(const f32x16_t (&acc)[T::NI][T::MI], char* lds) {
+  typedef ParkedTile<T> P;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-  const int wm = wave / 2, wn = wave % 2;
   const int lr = lane & 31, lh = lane >> 5;
   __syncthreads();   // every wave is done reading the operand stages
-  char* park = lds + wave * (T::WTM * ROW);
+  char* park = lds + wave * (T::WTM * P::ROW);
 #pragma unroll
   for (int mi = 0; mi < T::MI; ++mi) {
     const int m = mi * 32 + lr;
@@ -329,24 +334,43 @@ __device__ __forceinline__ void store_tile_bf16(const f32x16_t (&acc)[T::NI][T::
         const int g = ni * 4 + q;
         bf16x4_t v = {(__bf16)acc[ni][mi][q * 4 + 0], (__bf16)acc[ni][mi][q * 4 + 1],
                       (__bf16)acc[ni][mi][q * 4 + 2], (__bf16)acc[ni][mi][q * 4 + 3]};
-        *(bf16x4_t*)(park + m * ROW + ((g ^ key(m)) * 16) + lh * 8) = v;
+        *(bf16x4_t*)(park + m * P::ROW + ((g ^ P::key(m)) * 16) + lh * 8) = v;
       }
     }
   }
-  // the reads below are the same wave's: LDS operations of one wave complete in order
+  // the reads that follow are the same wave's: LDS operations of one wave complete in order
   wait_lgkmcnt0();
-  constexpr int ROWS_PER_READ = 64 / SLP;
-  const int g = lane % SLP;
+}
+
+// Second half: the rows m_lo <= m < m_hi of the parked tile (global row numbers; the tile starts at row
+// m0, column n0) go to c[m, n] with leading dimension ldc.  May be called several times with different
+// windows and destinations.
+template <class T, bool STREAM = false>
+__device__ __forceinline__ void store_parked_bf16(__bf16* c, size_t ldc, int m0, int n0, int m_lo, int m_hi, int N,
+                                                      const char* lds) {
+  typedef ParkedTile<T> P;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int wm = wave / 2, wn = wave % 2;
+  const char* park = lds + wave * (T::WTM * P::ROW);
+  constexpr int ROWS_PER_READ = 64 / P::SLP;
+  const int g = lane % P::SLP;
   const int gn = n0 + wn * T::WTN + g * 8;
 #pragma unroll 8
   for (int it = 0; it < T::WTM / ROWS_PER_READ; ++it) {
-    const int row = it * ROWS_PER_READ + lane / SLP;
-    const u32x4_t v = *(const u32x4_t*)(park + row * ROW + ((g ^ key(row)) * 16));
+    const int row = it * ROWS_PER_READ + lane / P::SLP;
+    const u32x4_t v = *(const u32x4_t*)(park + row * P::ROW + ((g ^ P::key(row)) * 16));
     const int gm = m0 + wm * T::WTM + row;
-    if (g < SL && gm < M && gn < N) {
+    if (g < P::SL && gm >= m_lo && gm < m_hi && gn < N) {
       if (STREAM) __builtin_nontemporal_store(v, (u32x4_t*)(c + (size_t)gm * ldc + gn)); else *(u32x4_t*)(c + (size_t)gm * ldc + gn) = v;
     }
   }
+}
+
+template <class T, bool STREAM = false>
+__device__ __forceinline__ void store_tile_bf16(const f32x16_t (&acc)[T::NI][T::MI], __bf16* c, size_t ldc, int m0,
+                                                    int n0, int M, int N, char* lds) {
+  park_tile_bf16<T>(acc, lds);
+  store_parked_bf16<T, STREAM>(c, ldc, m0, n0, m0, M, N, lds);
 }
 
 }  // namespace ditron

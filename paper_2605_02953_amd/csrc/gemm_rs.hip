@@ -20,6 +20,8 @@ struct GemmRsParams {
   const char* a;
   const char* b;
   __bf16* gemm_out;
+  __bf16* dst[DITRON_MAX_WORLD];   // fused scatter: rank d's [world, m_per_rank, n] buffer (dst[rank] is the local one)
+  int fuse_scatter;
   char* scatter_buf;
   int32_t* seg_flags;      // [world]
   int32_t* seg_counters;   // [world]
@@ -79,7 +81,18 @@ __global__ __launch_bounds__(T::THREADS) void gemm_rs_kernel(const GemmRsParams 
   }
   // streaming stores: the segment counter's release below would otherwise write the tile back out of the
   // chiplet's L2, and the partial is read only by the reduction, later (measured: 1.7 % of the step)
-  store_tile_bf16<T, true>(acc, p.gemm_out, (size_t)p.n, m0, n0, M, N, lds);
+  if (p.fuse_scatter) {
+    // the rows of segment d go straight to slot `rank` of rank d's buffer, row m landing at
+    // rank * m_per_rank + m % m_per_rank (the listing's remote store)
+    park_tile_bf16<T>(acc, lds);
+    for (int seg = seg_start; seg <= seg_end; ++seg) {
+      __bf16* c = p.dst[seg] + (ptrdiff_t)(p.rank - seg) * p.m_per_rank * p.n;
+      store_parked_bf16<T, true>(c, (size_t)p.n, m0, n0, max(m0, seg * p.m_per_rank),
+                                 min(min(m0 + T::BM, M), (seg + 1) * p.m_per_rank), N, lds);
+    }
+  } else {
+    store_tile_bf16<T, true>(acc, p.gemm_out, (size_t)p.n, m0, n0, M, N, lds);
+  }
 
   // segment completion: one lane per touched segment
   __syncthreads();
@@ -256,17 +269,19 @@ extern "C" ditron_status_t ditron_reduce_slots(const void* const* slots, void* o
   return launch_reduce(p, /*flags_pending=*/signals != nullptr, (hipStream_t)stream);
 }
 
-extern "C" ditron_status_t ditron_gemm_rs(const void* a, const void* b, int b_layout, void* gemm_out,
-                                          const void* const* peer_partials, void* scatter_buf, void* out,
-                                          int32_t* signals, int32_t* status, int32_t* schedule_out,
-                                          const int* arrival_order, int m, int n, int k_local, int world, int rank,
-                                          int chunks_per_slot, int32_t epoch, unsigned flags, void* stream) {
+static ditron_status_t gemm_rs_impl(const void* a, const void* b, int b_layout, void* gemm_out,
+                                    void* const* scatter_dsts, const void* const* peer_partials, void* scatter_buf,
+                                    void* out, int32_t* signals, int32_t* status, int32_t* schedule_out,
+                                    const int* arrival_order, int m, int n, int k_local, int world, int rank,
+                                    int chunks_per_slot, int32_t epoch, unsigned flags, void* stream) {
+  const bool fuse = scatter_dsts != nullptr;
+
   if (world < 1 || world > DITRON_MAX_WORLD || rank < 0 || rank >= world) return DITRON_ERR_INVALID_ARG;
   if (m <= 0 || n <= 0 || k_local <= 0 || m % world != 0 || chunks_per_slot < 1) return DITRON_ERR_INVALID_ARG;
   if (world % g_num_nodes != 0) return DITRON_ERR_INVALID_ARG;
   const int m_r = m / world;
   if (m_r % chunks_per_slot != 0) return DITRON_ERR_INVALID_ARG;
-  if (!a || !b || !gemm_out || !out || !signals || !status) return DITRON_ERR_INVALID_ARG;
+  if (!a || !b || (!fuse && !gemm_out) || !out || !signals || !status) return DITRON_ERR_INVALID_ARG;
   if (world > 1 && !scatter_buf) return DITRON_ERR_INVALID_ARG;
   if (!aligned16(a) || !aligned16(b) || !aligned16(gemm_out) || !aligned16(out) || !aligned16(scatter_buf) ||
       !aligned16(signals))
@@ -296,6 +311,13 @@ extern "C" ditron_status_t ditron_gemm_rs(const void* a, const void* b, int b_la
   p.a = (const char*)a;
   p.b = (const char*)b;
   p.gemm_out = (__bf16*)gemm_out;
+  p.fuse_scatter = fuse;
+  if (fuse) {
+    for (int d = 0; d < world; ++d) {
+      if (!scatter_dsts[d] || !aligned16(scatter_dsts[d])) return DITRON_ERR_INVALID_ARG;
+      p.dst[d] = (__bf16*)scatter_dsts[d];
+    }
+  }
   p.scatter_buf = (char*)scatter_buf;
   p.seg_flags = signals;
   p.seg_counters = signals + world;
@@ -333,7 +355,7 @@ extern "C" ditron_status_t ditron_gemm_rs(const void* a, const void* b, int b_la
   const size_t slot_bytes = (size_t)m_r * n * 2;
   for (int s = 0; s < world; ++s) {
     if (s == rank) {
-      r.slot[s] = (const char*)gemm_out + (size_t)rank * slot_bytes;
+      r.slot[s] = fuse ? (const char*)scatter_buf + (size_t)rank * slot_bytes : (const char*)gemm_out + (size_t)rank * slot_bytes;
       r.gate[s] = p.seg_flags + rank;   // the GEMM's flag for the own segment gates every chunk
       r.gate_stride[s] = 0;
     } else {
@@ -351,4 +373,24 @@ extern "C" ditron_status_t ditron_gemm_rs(const void* a, const void* b, int b_la
   r.spin_limit = g_spin_limit;
   // with emulated peers every flag was raised by the launch before this one
   return launch_reduce(r, /*flags_pending=*/!emulate, (hipStream_t)stream);
+}
+
+extern "C" ditron_status_t ditron_gemm_rs(const void* a, const void* b, int b_layout, void* gemm_out,
+                                          const void* const* peer_partials, void* scatter_buf, void* out,
+                                          int32_t* signals, int32_t* status, int32_t* schedule_out,
+                                          const int* arrival_order, int m, int n, int k_local, int world, int rank,
+                                          int chunks_per_slot, int32_t epoch, unsigned flags, void* stream) {
+  return gemm_rs_impl(a, b, b_layout, gemm_out, nullptr, peer_partials, scatter_buf, out, signals, status, schedule_out,
+                      arrival_order, m, n, k_local, world, rank, chunks_per_slot, epoch, flags, stream);
+}
+
+extern "C" ditron_status_t ditron_gemm_rs_fuse_scatter(const void* a, const void* b, int b_layout,
+                                                       void* const* scatter_dsts, const void* const* peer_partials,
+                                                       void* out, int32_t* signals, int32_t* status,
+                                                       int32_t* schedule_out, const int* arrival_order, int m, int n,
+                                                       int k_local, int world, int rank, int chunks_per_slot,
+                                                       int32_t epoch, unsigned flags, void* stream) {
+  if (!scatter_dsts || world < 1 || world > DITRON_MAX_WORLD || rank < 0 || rank >= world) return DITRON_ERR_INVALID_ARG;
+  return gemm_rs_impl(a, b, b_layout, nullptr, scatter_dsts, peer_partials, scatter_dsts[rank], out, signals, status,
+                      schedule_out, arrival_order, m, n, k_local, world, rank, chunks_per_slot, epoch, flags, stream);
 }

@@ -169,3 +169,51 @@ def test_gemm_rs_multi_node_order(B, world, nnodes, m_r, n, k, chunks):
             assert sig[:world].tolist() == [run.epoch] * world
     finally:
         B.set_num_nodes(1)
+
+
+@pytest.mark.parametrize("world,m_r,n,k,chunks,integer", [
+    (4, 128, 256, 64, 1, True),
+    (4, 100, 264, 72, 2, True),       # tiles that straddle two or three segments, ragged everything
+    (8, 505, 3080, 200, 5, True),     # 256x256 tiles
+    (2, 192, 384, 512, 3, False),
+    (1, 256, 256, 128, 1, True),
+])
+def test_gemm_rs_fused_scatter(B, world, m_r, n, k, chunks, integer):
+    """The FUSE_SCATTER branch of the producer listing: segment d of the partial goes straight to slot `rank`
+    of rank d's buffer (rows rank*M_r + m % M_r); the reduced output is what the unfused path gives."""
+    cfg = synth.CONFIGS[3].scaled(world=world, m_per_rank=m_r, n=n, k=k)
+    a_list, b_list = synth.gemm_rs_inputs(cfg, integer=integer)
+    parts = _all_partials(B, cfg, a_list, b_list)
+    signals = torch.zeros(B.signal_words(world, chunks), dtype=torch.int32, device="cuda")
+    status = torch.zeros(B.STATUS_WORDS, dtype=torch.int32, device="cuda")
+    out = torch.zeros((m_r, n), dtype=torch.int16, device="cuda")
+    for epoch, d in enumerate(sorted({0, world - 1}), start=1):
+        dsts = [torch.full((world, m_r, n), 0x7FC0, dtype=torch.int16, device="cuda") for _ in range(world)]
+        peers = [parts[s][d * m_r:(d + 1) * m_r] for s in range(world)]
+        st = B.gemm_rs_fuse_scatter(to_dev(a_list[d]), to_dev(nk(b_list[d])), B.B_NK, dsts, peers, out, signals, status,
+                                    None, None, cfg.m, n, k, world, d, chunks, epoch, B.EMULATE_PRODUCER)
+        assert st == B.OK, B.status_string(st)
+        torch.cuda.synchronize()
+        assert status.cpu().tolist()[0] == 0
+        own = bits(parts[d])                       # this rank's partial as the unfused GEMM writes it
+        for t in range(world):
+            buf = bits(dsts[t])
+            # slot d of every rank's buffer holds segment t of this rank's partial, at the rows the listing gives
+            for r in (t * m_r, t * m_r + m_r // 2, (t + 1) * m_r - 1):
+                dest, row = ors.fused_scatter_row(r, d, world, cfg.m)
+                assert dest == t and np.array_equal(buf.reshape(world * m_r, n)[row], own[r])
+            assert np.array_equal(buf[d], own[t * m_r:(t + 1) * m_r])
+            for s in range(world):
+                if s == d:
+                    continue
+                if t == d:
+                    assert torch.equal(dsts[t][s], peers[s])       # the peers' blocks arrived in the local buffer
+                else:
+                    assert (buf[s] == 0x7FC0).all()                # nothing else of a remote buffer is touched
+        ref = ors.gemm_rs(a_list, b_list, d)
+        got = bits(out)
+        if integer:
+            assert np.array_equal(got, formats.encode_bf16_rne(ref.astype(np.float32))), d
+        else:
+            assert compare.max_row_rel_error(formats.decode_bf16(got), ref) <= TOL_BF16
+        assert np.array_equal(got, ors.reduce_slots_f32_ordered([bits(dsts[d][s]) for s in range(world)]))

@@ -149,3 +149,25 @@ def test_row_metric():
     assert e[0] == pytest.approx(0.1) and e[1] == 0 and e[2] == 0
     got[1, 0] = 1e-30
     assert compare.row_rel_error(got, ref)[1] == np.inf
+
+
+def test_fused_scatter_rows_by_hand():
+    # 2 ranks, 4 rows: rank 1's rows 0, 1 belong to rank 0 and land in its slot 1 (rows 2, 3); its rows 2, 3
+    # are its own and land in its own slot 1 (rows 2, 3)
+    assert [ors.fused_scatter_row(r, 1, 2, 4) for r in range(4)] == [(0, 2), (0, 3), (1, 2), (1, 3)]
+    assert [ors.fused_scatter_row(r, 0, 2, 4) for r in range(4)] == [(0, 0), (0, 1), (1, 0), (1, 1)]
+    # every destination buffer receives every one of its rows exactly once over all senders, and summing the
+    # slots of a buffer gives the reduce-scatter result
+    world, m, n = 4, 12, 3
+    rng = np.random.default_rng(0)
+    parts = [rng.integers(-4, 5, size=(m, n)).astype(np.float64) for _ in range(world)]
+    bufs = [np.full((m, n), np.nan) for _ in range(world)]
+    for s in range(world):
+        for r in range(m):
+            d, row = ors.fused_scatter_row(r, s, world, m)
+            assert np.isnan(bufs[d][row]).all()
+            bufs[d][row] = parts[s][r]
+    m_r = m // world
+    for d in range(world):
+        assert not np.isnan(bufs[d]).any()
+        assert np.array_equal(bufs[d].reshape(world, m_r, n).sum(axis=0), sum(p[d * m_r:(d + 1) * m_r] for p in parts))
