@@ -32,10 +32,6 @@
 #include "gemm_core.h"
 #include "launch.h"
 
-#ifndef DITRON_AR_UNROLL
-#define DITRON_AR_UNROLL 4   // 16-byte vectors per lane and rank in flight in the consumer (256 x 256 tiles)
-#endif
-
 namespace ditron {
 
 struct GemmArParams {
@@ -196,7 +192,7 @@ __global__ __launch_bounds__(T::THREADS) void gemm_ar_kernel(const GemmArParams 
     if ((int)threadIdx.x < p.world)
       flag_wait_lane(p.tile_flags + (size_t)threadIdx.x * ntiles, pid_m * p.npn + pid_n, 1, p.epoch, p.spin_limit, p.status);
     __syncthreads();
-    ar_reduce_tile<T, WORLD, (T::BM * T::BN / 8 / T::THREADS >= 32 ? DITRON_AR_UNROLL : 2)>(p, pid_m * T::BM, pid_n * T::BN);
+    ar_reduce_tile<T, WORLD, (T::BM * T::BN / 8 / T::THREADS >= 32 ? 4 : 2)>(p, pid_m * T::BM, pid_n * T::BN);
   }
   // the last consumer to leave puts the queue back to zero for the next call
   if (threadIdx.x == 0) {
@@ -207,10 +203,6 @@ __global__ __launch_bounds__(T::THREADS) void gemm_ar_kernel(const GemmArParams 
     }
   }
 }
-
-#ifndef DITRON_AR_EARLY
-#define DITRON_AR_EARLY -1   // early consumers; -1: sized per call
-#endif
 
 template <class T>
 static ditron_status_t launch_ar(GemmArParams& p, int units, hipStream_t stream) {
@@ -226,7 +218,6 @@ static ditron_status_t launch_ar(GemmArParams& p, int units, hipStream_t stream)
     const double t_reduce = (double)(p.world + 1) * T::BM * T::BN * 2 / kUnitBytes;   // unit-seconds per tile
     const double t_gemm = 2.0 * T::BM * T::BN * p.k / kUnitFlops;
     int x = (int)(units * t_reduce / (t_reduce + t_gemm) / 8 + 0.5) * 8;
-    if (DITRON_AR_EARLY >= 0) x = DITRON_AR_EARLY;
     p.early = std::max(0, std::min(x, units / 2));
   }
   p.late = std::min(units, ntiles);

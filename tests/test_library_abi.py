@@ -91,6 +91,12 @@ def test_gemm_rs_and_moe_argument_checks(B):
                               B._ptr(fake), B._ptr(fake), None, None, 1024, 256, 64, 8, 0, 3, 1,
                               B.EMULATE_PRODUCER, z)
     assert st == B.ERR_INVALID_ARG          # chunks do not divide the rows per rank
+    st = B.gemm_rs_fuse_scatter(fake, fake, B.B_NK, None, None, fake, fake, fake, None, None, 1024, 256, 64, 8, 0, 1, 1,
+                                B.EMULATE_PRODUCER, stream=_S())
+    assert st == B.ERR_INVALID_ARG          # no destination buffers
+    st = B.gemm_rs_fuse_scatter(fake, fake, B.B_NK, [fake] * 7 + [None], [fake] * 8, fake, fake, fake, None, None, 1024,
+                                256, 64, 8, 0, 1, 1, B.EMULATE_PRODUCER, stream=_S())
+    assert st == B.ERR_INVALID_ARG          # a destination is missing
     st = B.lib.ditron_reduce_slots(None, B._ptr(fake), None, None, 8, 8, 2, 1, 1, z)
     assert st == B.ERR_INVALID_ARG
     st = B.moe_ag_grouped_gemm([fake] * 8, fake, fake, B.B_NK, fake, fake, fake, fake, fake, fake, fake, fake, None,
