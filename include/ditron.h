@@ -234,6 +234,34 @@ ditron_status_t ditron_gemm_ar(const void* a, const void* b, int b_layout, void*
                                int world, int rank, int32_t epoch, unsigned flags, void* stream);
 
 /*
+ * GEMM + AllReduce, two-shot: the default branch of the same listings (USE_MULTIMEM_ST).  The tiles
+ * are dealt to the ranks; a rank reduces only the tiles it owns (waiting for their flags from every
+ * rank) and stores each reduced tile into every rank's output buffer, and the other tiles of its own
+ * output arrive from their owners; the call ends once every peer has signalled that its tiles have
+ * been broadcast.  The paper deals blocks of NUM_COMM_SMS consecutive tile ids round-robin; here
+ * position q of the GEMM's tile order belongs to rank q % world.  The paper broadcasts through the
+ * switch (`multimem.st`); here with one store per destination.
+ *
+ *  out_dsts      host array of `world` device pointers [m, n] bf16: entry d stands for the output
+ *                buffer of rank d (on one GPU: any distinct device buffers); entry `rank` is this
+ *                rank's output, complete when the call returns.  Of the other entries only the
+ *                tiles this rank owns are written.
+ *  peer_reduced  DITRON_EMULATE_PRODUCER: host array of `world` device pointers [m, n] bf16, entry
+ *                s != rank holding what rank s broadcasts (only the tiles it owns are read); the
+ *                emulated peers copy those tiles into this rank's output and then raise the flags
+ *                below.  Ignored with DITRON_EXTERNAL_PRODUCER.
+ *  signals       as for ditron_gemm_ar, plus word 2*world + world*tiles + s: rank s has broadcast
+ *                all its tiles (raised by the peers; word 2 is an internal counter left at zero)
+ *  other arguments as for ditron_gemm_ar.
+ */
+ditron_status_t ditron_gemm_ar_two_shot(const void* a, const void* b, int b_layout, void* gemm_out,
+                                        const void* const* peer_partials, void* const* out_dsts,
+                                        const void* const* peer_reduced, int32_t* signals,
+                                        int32_t* status, int32_t* schedule_out, int m, int n,
+                                        int k_local, int world, int rank, int32_t epoch,
+                                        unsigned flags, void* stream);
+
+/*
  * The reduction step of GEMM-ReduceScatter on its own: out = bf16( sum_s fp32(slots[s]) ),
  * slot order 0..world-1.  slots: host array of `world` device pointers [rows, n] bf16.
  * `signals` may be NULL (no gating); otherwise word s*chunks + c gates row chunk c of slot s.

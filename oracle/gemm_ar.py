@@ -65,3 +65,10 @@ def persistent_tile(position, m, n, block_m, block_n, group_m, gemm_wgs, num_xcd
     pid_m, pid_n = tile_at_position(position, m, n, block_m, block_n, group_m, num_xcd,
                                     cdiv(gemm_wgs, num_xcd) if num_xcd else 0)
     return pid_m, pid_n, position % gemm_wgs, position // gemm_wgs
+
+
+def two_shot_owner(position, world):
+    """Two-shot form (the consumer listing's broadcast branch): the rank that reduces the tile at
+    `position` of the tile order and broadcasts it.  The listing deals blocks of NUM_COMM_SMS consecutive
+    tiles to the ranks in turn; with blocks of one tile that is position mod world."""
+    return position % world

@@ -50,6 +50,8 @@ lib.ditron_gemm_rs_fuse_scatter.argtypes = [_vp, _vp, _i, _pp, _pp, _vp, _vp, _v
                                             _i, _i, _i, _i, _i, _i, _i32, _u, _vp]
 lib.ditron_gemm_ar.restype = _i
 lib.ditron_gemm_ar.argtypes = [_vp, _vp, _i, _vp, _pp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i32, _u, _vp]
+lib.ditron_gemm_ar_two_shot.restype = _i
+lib.ditron_gemm_ar_two_shot.argtypes = [_vp, _vp, _i, _vp, _pp, _pp, _pp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i32, _u, _vp]
 lib.ditron_reduce_slots.restype = _i
 lib.ditron_reduce_slots.argtypes = [_pp, _vp, _vp, _vp, _i, _i, _i, _i, _i32, _vp]
 lib.ditron_moe_ag_grouped_gemm.restype = _i
@@ -149,6 +151,13 @@ def gemm_ar(a, b, b_layout, gemm_out, peer_partials, out, signals, status, sched
     return lib.ditron_gemm_ar(_ptr(a), _ptr(b), b_layout, _ptr(gemm_out), _ptr_array(peer_partials), _ptr(out),
                               _ptr(signals), _ptr(status), _ptr(schedule_out), m, n, k_local, world, rank, epoch,
                               flags, _stream(stream))
+
+
+def gemm_ar_two_shot(a, b, b_layout, gemm_out, peer_partials, out_dsts, peer_reduced, signals, status, schedule_out,
+                     m, n, k_local, world, rank, epoch, flags, stream=None):
+    return lib.ditron_gemm_ar_two_shot(_ptr(a), _ptr(b), b_layout, _ptr(gemm_out), _ptr_array(peer_partials),
+                                       _ptr_array(out_dsts), _ptr_array(peer_reduced), _ptr(signals), _ptr(status),
+                                       _ptr(schedule_out), m, n, k_local, world, rank, epoch, flags, _stream(stream))
 
 
 def reduce_slots(slots, out, signals, status, rows, n, world, chunks, epoch, stream=None):

@@ -43,6 +43,11 @@ struct GemmArParams {
   int32_t* ticket;       // next position of the reduce queue
   int32_t* done;         // consumers that have left the queue
   int32_t* tile_flags;   // [world][ntiles]
+  // two-shot only
+  __bf16* out_dst[DITRON_MAX_WORLD];      // every rank's output buffer; out_dst[rank] is `out`
+  const void* reduced[DITRON_MAX_WORLD];  // emulated peers: what rank s broadcasts (only the tiles it owns are read)
+  int32_t* peer_done;                     // [world]: rank s has broadcast all its tiles
+  int32_t* prod_count;                    // arrival counter of the emulated peers
   int32_t* status;
   int32_t* schedule;
   int m, n, k, world, rank;
@@ -87,7 +92,7 @@ __device__ __forceinline__ u32x4_t ar_pack(const float (&acc)[8]) {
 // Sum of the `world` published copies of one output tile.  U vectors of 16 bytes per lane and
 // rank are in flight at once (a single work-group owns its compute unit, so the loads in
 // flight per lane are what fills the memory pipe).
-template <class T, int WORLD, int U>
+template <class T, int WORLD, int U, bool TWO>
 __device__ __forceinline__ void ar_reduce_tile(const GemmArParams& p, int m0, int n0) {
   const int world = WORLD > 0 ? WORLD : p.world;
   const int tile_m = min(T::BM, p.m - m0), tile_n = min(T::BN, p.n - n0);
@@ -125,13 +130,46 @@ __device__ __forceinline__ void ar_reduce_tile(const GemmArParams& p, int m0, in
 #pragma unroll
           for (int s = 1; s < WORLD; ++s) ar_add(acc[u], x[u][s]);
         }
-        __builtin_nontemporal_store(ar_pack(acc[u]), out + off[u]);
+        const u32x4_t r = ar_pack(acc[u]);
+        if constexpr (TWO) {   // the broadcast: the reduced tile goes to every rank's output
+          for (int d = 0; d < world; ++d) __builtin_nontemporal_store(r, (u32x4_t*)p.out_dst[d] + off[u]);
+        } else {
+          __builtin_nontemporal_store(r, out + off[u]);
+        }
       }
     }
   }
 }
 
-template <class T, int WORLD>
+// Two-shot, emulated peers: one tile of what a peer broadcasts lands in the local output.
+template <class T>
+__device__ __forceinline__ void ar_copy_tile(const GemmArParams& p, const void* src, int m0, int n0) {
+  const int tile_m = min(T::BM, p.m - m0), tile_n = min(T::BN, p.n - n0);
+  const int vpr = tile_n >> 3;
+  const int nvec = tile_m * vpr;
+  const size_t ld = (size_t)p.n >> 3;
+  const size_t base = (size_t)m0 * ld + ((size_t)n0 >> 3);
+  constexpr int U = 8;
+  for (int v0 = threadIdx.x; v0 < nvec; v0 += T::THREADS * U) {
+    size_t off[U];
+    u32x4_t x[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int v = v0 + u * T::THREADS;
+      const int row = v / vpr;
+      off[u] = base + (size_t)row * ld + (v - row * vpr);
+      if (v < nvec) x[u] = __builtin_nontemporal_load((const u32x4_t*)src + off[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (v0 + u * T::THREADS < nvec) __builtin_nontemporal_store(x[u], (u32x4_t*)p.out + off[u]);
+  }
+}
+
+// TWO: the two-shot form.  Position q of the tile order belongs to rank q % world; a rank reduces only
+// its own tiles and stores each reduced tile into every rank's output; the other tiles of its output
+// arrive from their owners.
+template <class T, int WORLD, bool TWO>
 __global__ __launch_bounds__(T::THREADS) void gemm_ar_kernel(const GemmArParams p) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const int ntiles = p.npm * p.npn;
@@ -146,6 +184,31 @@ __global__ __launch_bounds__(T::THREADS) void gemm_ar_kernel(const GemmArParams 
       int pid_m, pid_n;
       ar_tile_at(p, i / peers, ntiles, pid_m, pid_n);
       flag_raise(p.tile_flags + (size_t)s * ntiles + pid_m * p.npn + pid_n, p.epoch);
+    }
+    if constexpr (TWO) {
+      // the peers' broadcasts: the i-th tile that is not ours is position (i / (W-1)) W + s, s the
+      // (i % (W-1))-th rank other than ours
+      for (int i = wg;; i += p.num_producers) {
+        const int block = (i / peers) * p.world;     // first position of the block of `world` positions
+        if (block >= ntiles) break;
+        int s = i % peers;
+        if (s >= p.rank) ++s;
+        const int q = block + s;
+        if (q >= ntiles) continue;
+        int pid_m, pid_n;
+        ar_tile_at(p, q, ntiles, pid_m, pid_n);
+        ar_copy_tile<T>(p, p.reduced[s], pid_m * T::BM, pid_n * T::BN);
+      }
+      __syncthreads();
+      if (threadIdx.x == 0) {
+        const int old = __hip_atomic_fetch_add(p.prod_count, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        if (old == p.num_producers - 1) {
+          __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+          __hip_atomic_store(p.prod_count, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          for (int r = 0; r < p.world; ++r)
+            if (r != p.rank) flag_raise(p.peer_done + r, p.epoch);
+        }
+      }
     }
     return;
   }
@@ -185,19 +248,24 @@ __global__ __launch_bounds__(T::THREADS) void gemm_ar_kernel(const GemmArParams 
     __syncthreads();   // the previous ticket has been read by every wave
     if (threadIdx.x == 0) *drawn = __hip_atomic_fetch_add(p.ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
-    const int q = *drawn;
+    const int q = TWO ? *drawn * p.world + p.rank : *drawn;   // two-shot: only the positions this rank owns
     if (q >= ntiles) break;
     int pid_m, pid_n;
     ar_tile_at(p, q, ntiles, pid_m, pid_n);
     if ((int)threadIdx.x < p.world)
       flag_wait_lane(p.tile_flags + (size_t)threadIdx.x * ntiles, pid_m * p.npn + pid_n, 1, p.epoch, p.spin_limit, p.status);
     __syncthreads();
-    ar_reduce_tile<T, WORLD, (T::BM * T::BN / 8 / T::THREADS >= 32 ? 4 : 2)>(p, pid_m * T::BM, pid_n * T::BN);
+    ar_reduce_tile<T, WORLD, (T::BM * T::BN / 8 / T::THREADS >= 32 ? 4 : 2), TWO>(p, pid_m * T::BM, pid_n * T::BN);
   }
   // the last consumer to leave puts the queue back to zero for the next call
   if (threadIdx.x == 0) {
     const int old = __hip_atomic_fetch_add(p.done, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
     if (old == p.early + p.late - 1) {
+      if constexpr (TWO) {
+        // the output is complete when the call returns: the peers' broadcasts must have landed too
+        for (int r = 0; r < p.world; ++r)
+          if (r != p.rank) flag_wait_lane(p.peer_done, r, 1, p.epoch, p.spin_limit, p.status);
+      }
       __hip_atomic_store(p.ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       __hip_atomic_store(p.done, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
@@ -205,19 +273,21 @@ __global__ __launch_bounds__(T::THREADS) void gemm_ar_kernel(const GemmArParams 
 }
 
 template <class T>
-static ditron_status_t launch_ar(GemmArParams& p, int units, hipStream_t stream) {
+static ditron_status_t launch_ar(GemmArParams& p, int units, bool two_shot, hipStream_t stream) {
   const int ntiles = p.npm * p.npn;
   units = units / 8 * 8;
   p.head_tiles = std::min(ntiles, units);
   p.early = 0;
   if (ntiles > units) {
-    // X units reduce (world + 1) tile-sized streams per tile at ~40 GB/s each (50 while streaming,
-    // less the waits) while units - X compute the tiles at the per-unit MFMA rate of a full-chip
-    // GEMM: balance the two
+    // X units reduce while units - X compute the tiles at the per-unit MFMA rate of a full-chip GEMM:
+    // balance the two.  Per GEMM tile the consumer moves (world + 1) tile-sized streams in the one-shot
+    // form and 2 in the two-shot form (world reads and world writes for one tile in `world`), at ~40 GB/s
+    // per unit (50 while streaming, less the waits).
     constexpr double kUnitBytes = 40e9, kUnitFlops = 4.4e12;
-    const double t_reduce = (double)(p.world + 1) * T::BM * T::BN * 2 / kUnitBytes;   // unit-seconds per tile
+    const double streams = two_shot ? 2.0 : p.world + 1.0;
+    const double t_reduce = streams * T::BM * T::BN * 2 / kUnitBytes;   // unit-seconds per tile
     const double t_gemm = 2.0 * T::BM * T::BN * p.k / kUnitFlops;
-    int x = (int)(units * t_reduce / (t_reduce + t_gemm) / 8 + 0.5) * 8;
+    const int x = (int)(units * t_reduce / (t_reduce + t_gemm) / 8 + 0.5) * 8;
     p.early = std::max(0, std::min(x, units / 2));
   }
   p.late = std::min(units, ntiles);
@@ -227,18 +297,21 @@ static ditron_status_t launch_ar(GemmArParams& p, int units, hipStream_t stream)
     hipLaunchKernelGGL(kern, dim3(grid), dim3(T::THREADS), T::LDS_BYTES, stream, p);
     return hipGetLastError() == hipSuccess ? DITRON_OK : DITRON_ERR_HIP;
   };
-  if (p.world == 8) return launch(gemm_ar_kernel<T, 8>);
-  return launch(gemm_ar_kernel<T, 0>);
+  if (two_shot) return p.world == 8 ? launch(gemm_ar_kernel<T, 8, true>) : launch(gemm_ar_kernel<T, 0, true>);
+  return p.world == 8 ? launch(gemm_ar_kernel<T, 8, false>) : launch(gemm_ar_kernel<T, 0, false>);
 }
 
 }  // namespace ditron
 
 using namespace ditron;
 
-extern "C" ditron_status_t ditron_gemm_ar(const void* a, const void* b, int b_layout, void* gemm_out,
-                                          const void* const* peer_partials, void* out, int32_t* signals,
-                                          int32_t* status, int32_t* schedule_out, int m, int n, int k_local,
-                                          int world, int rank, int32_t epoch, unsigned flags, void* stream) {
+static ditron_status_t gemm_ar_impl(const void* a, const void* b, int b_layout, void* gemm_out,
+                                    const void* const* peer_partials, void* out, void* const* out_dsts,
+                                    const void* const* peer_reduced, int32_t* signals, int32_t* status,
+                                    int32_t* schedule_out, int m, int n, int k_local, int world, int rank,
+                                    int32_t epoch, unsigned flags, void* stream) {
+  const bool two_shot = out_dsts != nullptr;
+
   if (world < 1 || world > DITRON_MAX_WORLD || rank < 0 || rank >= world) return DITRON_ERR_INVALID_ARG;
   if (m <= 0 || n <= 0 || k_local <= 0) return DITRON_ERR_INVALID_ARG;
   if (!a || !b || !gemm_out || !out || !signals || !status || out == gemm_out) return DITRON_ERR_INVALID_ARG;
@@ -254,6 +327,17 @@ extern "C" ditron_status_t ditron_gemm_ar(const void* a, const void* b, int b_la
   if (!fits_32bit(m, k_local, 2) || !fits_32bit(n, k_local, 2)) return DITRON_ERR_UNSUPPORTED;
 
   GemmArParams p{};
+  if (two_shot) {
+    for (int s = 0; s < world; ++s) {
+      if (!out_dsts[s] || !aligned16(out_dsts[s]) || out_dsts[s] == gemm_out) return DITRON_ERR_INVALID_ARG;
+      p.out_dst[s] = (__bf16*)out_dsts[s];
+      if (s != rank && emulate) {
+        if (!peer_reduced || !peer_reduced[s] || !aligned16(peer_reduced[s]) || peer_reduced[s] == out)
+          return DITRON_ERR_INVALID_ARG;
+        p.reduced[s] = peer_reduced[s];
+      }
+    }
+  }
   for (int s = 0; s < world; ++s) {
     if (s == rank) {
       p.part[s] = gemm_out;
@@ -277,6 +361,8 @@ extern "C" ditron_status_t ditron_gemm_ar(const void* a, const void* b, int b_la
   p.gemm_out = (__bf16*)gemm_out;
   p.out = (__bf16*)out;
   p.tile_flags = signals + 2 * world;
+  p.peer_done = signals + 2 * world + (size_t)world * ntiles;
+  p.prod_count = signals + 2;
   p.status = status;
   p.schedule = (flags & DITRON_DUMP_SCHEDULE) ? schedule_out : nullptr;
   p.m = m;
@@ -286,11 +372,31 @@ extern "C" ditron_status_t ditron_gemm_ar(const void* a, const void* b, int b_la
   p.rank = rank;
   p.epoch = epoch;
   p.spin_limit = g_spin_limit;
-  p.num_producers = (emulate && world > 1) ? 8 : 0;
+  // one-shot: the emulated peers only raise flags; two-shot: they also copy the peers' broadcasts
+  p.num_producers = (emulate && world > 1) ? (two_shot ? 64 : 8) : 0;
   p.group_m = tc.group_m;
   p.num_xcd = tc.num_xcd;
   p.per_xcd = tc.per_xcd;
   const hipStream_t s = (hipStream_t)stream;
-  if (b_layout == DITRON_B_KN) return tc.big ? launch_ar<TileBigKN>(p, units, s) : launch_ar<TileSmallKN>(p, units, s);
-  return tc.big ? launch_ar<TileBig>(p, units, s) : launch_ar<TileSmall>(p, units, s);
+  if (b_layout == DITRON_B_KN) return tc.big ? launch_ar<TileBigKN>(p, units, two_shot, s) : launch_ar<TileSmallKN>(p, units, two_shot, s);
+  return tc.big ? launch_ar<TileBig>(p, units, two_shot, s) : launch_ar<TileSmall>(p, units, two_shot, s);
+}
+
+extern "C" ditron_status_t ditron_gemm_ar(const void* a, const void* b, int b_layout, void* gemm_out,
+                                          const void* const* peer_partials, void* out, int32_t* signals,
+                                          int32_t* status, int32_t* schedule_out, int m, int n, int k_local,
+                                          int world, int rank, int32_t epoch, unsigned flags, void* stream) {
+  return gemm_ar_impl(a, b, b_layout, gemm_out, peer_partials, out, nullptr, nullptr, signals, status, schedule_out, m, n,
+                      k_local, world, rank, epoch, flags, stream);
+}
+
+extern "C" ditron_status_t ditron_gemm_ar_two_shot(const void* a, const void* b, int b_layout, void* gemm_out,
+                                                   const void* const* peer_partials, void* const* out_dsts,
+                                                   const void* const* peer_reduced, int32_t* signals,
+                                                   int32_t* status, int32_t* schedule_out, int m, int n,
+                                                   int k_local, int world, int rank, int32_t epoch, unsigned flags,
+                                                   void* stream) {
+  if (!out_dsts || world < 1 || world > DITRON_MAX_WORLD || rank < 0 || rank >= world) return DITRON_ERR_INVALID_ARG;
+  return gemm_ar_impl(a, b, b_layout, gemm_out, peer_partials, out_dsts[rank], out_dsts, peer_reduced, signals, status,
+                      schedule_out, m, n, k_local, world, rank, epoch, flags, stream);
 }

@@ -157,3 +157,60 @@ def test_table_shape_full_size(B):
     rows = np.arange(0, cfg.m, 67)       # sampled rows, every tile row and column, against the definition
     ref = oar.gemm_ar(a_list, b_list, rows=rows)
     assert compare.max_row_rel_error(formats.decode_bf16(got[rows]), ref) <= TOL_BF16
+
+
+@pytest.mark.parametrize("world,m_r,n,k,integer", [
+    (4, 32, 256, 64, True),
+    (4, 100, 264, 72, True),       # ragged edges, 12 tiles
+    (8, 505, 3080, 200, True),     # 256x256 tiles, 208 of them
+    (8, 315, 2600, 64, True),      # 420 tiles: more than one round
+    (3, 128, 384, 128, False),     # a world that does not divide the tile count
+    (1, 256, 256, 128, True),
+])
+def test_gemm_ar_two_shot(B, world, m_r, n, k, integer):
+    """The broadcast branch of the consumer listing: the rank reduces the tiles it owns and stores them
+    into every rank's output; the rest of its own output arrives from the owners."""
+    cfg = synth.CONFIGS[3].scaled(world=world, m_per_rank=m_r, n=n, k=k)
+    a_list, b_list = synth.gemm_rs_inputs(cfg, integer=integer)
+    parts = [oar.partial_bits(a, b) for a, b in zip(a_list, b_list)]
+    parts_dev = [to_dev(p) for p in parts]
+    run = GemmArRun(B, world, cfg.m, n, k)
+    bm, bn = run.tc["block_m"], run.tc["block_n"]
+    for d in sorted({0, world - 1}):
+        sched = torch.full((4 * run.ntiles,), -1, dtype=torch.int32, device="cuda")
+        outs = [torch.full((cfg.m, n), 0x7FC0, dtype=torch.int16, device="cuda") for _ in range(world)]
+        peers = [None if s == d else parts_dev[s] for s in range(world)]
+        run.epoch += 1
+        a_dev, b_dev = to_dev(a_list[d]), to_dev(nk(b_list[d]))
+        # what the peers broadcast: the all-reduce of what every rank publishes (this rank's own partial comes
+        # from a first, one-shot call, as its peers would see it)
+        st = run(a_dev, b_dev, peers if world > 1 else None, d)
+        _ok(B, st, run)
+        published = [bits(run.gemm_out) if s == d else parts[s] for s in range(world)]
+        full = oar.allreduce_partials_f32_ordered(published)
+        reduced = [None if s == d else to_dev(full) for s in range(world)]
+        run.epoch += 1
+        st = B.gemm_ar_two_shot(a_dev, b_dev, B.B_NK, run.gemm_out, peers if world > 1 else None, outs,
+                                reduced if world > 1 else None, run.signals, run.status, sched, cfg.m, n, k, world, d,
+                                run.epoch, B.EMULATE_PRODUCER | B.DUMP_SCHEDULE)
+        _ok(B, st, run)
+        assert np.array_equal(bits(outs[d]), full)                      # own output: complete
+        rec = sched.cpu().numpy().reshape(-1, 4)
+        _check_schedule(run, cfg, rec)
+        for t in range(world):
+            if t == d:
+                continue
+            buf = bits(outs[t])
+            for q in range(run.ntiles):                                  # a peer's output: exactly the tiles this rank owns
+                pm, pn = rec[q, 0], rec[q, 1]
+                blk = (slice(pm * bm, min((pm + 1) * bm, cfg.m)), slice(pn * bn, min((pn + 1) * bn, n)))
+                if oar.two_shot_owner(q, world) == d:
+                    assert np.array_equal(buf[blk], full[blk]), (t, q)
+                else:
+                    assert (buf[blk] == 0x7FC0).all(), (t, q)
+        if integer:
+            assert np.array_equal(full, formats.encode_bf16_rne(oar.gemm_ar(a_list, b_list).astype(np.float32)))
+        sig = run.signals.cpu().numpy()
+        assert not sig[:2 * world].any()
+        done = sig[2 * world + world * run.ntiles:2 * world + world * run.ntiles + world]
+        assert [done[s] for s in range(world) if s != d] == [run.epoch] * (world - 1)

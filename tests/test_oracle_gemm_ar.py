@@ -122,3 +122,12 @@ def test_persistent_schedule_invariants(m, n, bm, bn, group_m, wgs, xcd):
             plain = {osch.grouped_order(t, npm, npn, group_m) for t in range(rnd * g, min(nt, (rnd + 1) * g))}
             mine = {oar.persistent_tile(p, m, n, bm, bn, group_m, g, xcd)[:2] for p in range(rnd * g, min(nt, (rnd + 1) * g))}
             assert plain == mine
+
+
+def test_two_shot_ownership_is_a_partition():
+    for world, nt in ((8, 1024), (3, 10), (4, 4), (1, 7)):
+        owners = [oar.two_shot_owner(q, world) for q in range(nt)]
+        assert set(owners) <= set(range(world))
+        counts = np.bincount(owners, minlength=world)
+        assert counts.sum() == nt and counts.max() - counts.min() <= 1      # every tile once, dealt evenly
+        assert owners[:world] == list(range(world))[:nt]                    # in turn, starting with rank 0
