@@ -26,9 +26,8 @@
 //
 // The paper runs a persistent GEMM on a fixed set of compute units and the consumer as a second
 // kernel on the rest, reducing through the switch (multimem).  Here there is no switch (the sum
-// is done in software), and a persistent GEMM measured slower on this chip: work-groups looping
-// over tiles in lock step ask for the same operand panels at the same instants (K loop 13 %
-// slower than one work-group per tile, which the dispatcher staggers and load-balances).
+// is done in software), and a persistent GEMM measured slower on this chip (its K loop ran 13 %
+// slower than with one work-group per tile, which the dispatcher also load-balances).
 #include "gemm_core.h"
 #include "launch.h"
 
