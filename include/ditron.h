@@ -100,7 +100,8 @@ ditron_status_t ditron_tile_row_order(int op, int m, int block_m, int world, int
 
 /* Tile shape and ordering parameters the library will use for a problem, so that a test can
  * evaluate the schedule independently.  op: 0 = ag_gemm, 1 = gemm_rs, 2 = moe grouped gemm
- * (m = max_rows; only BLOCK_M is fixed, the column block is chosen per call and reported as 0),
+ * (m = max_rows; the smallest BLOCK_M is reported and 0 for the column block: both are chosen per
+ * call, see ditron_moe_tile_choice),
  * 3 = gemm_ar.
  * out[0]=BLOCK_M out[1]=BLOCK_N out[2]=GROUP_SIZE_M out[3]=chiplets used by the work-group
  * remap (0 = no remap) out[4]=tiles per chiplet per block out[5]=number of tiles
@@ -313,6 +314,12 @@ ditron_status_t ditron_moe_ag_grouped_gemm(const void* const* x_shards, const in
                                            int expert_begin, int num_local_experts, int max_rows,
                                            int world, int rank, int32_t epoch, unsigned flags,
                                            void* stream);
+
+/* Tile of the grouped GEMM for a call with these sizes (total_tokens = world * tokens_per_rank):
+ * out[0] = BLOCK_M (128, or 256 when the experts are large), out[1] = BLOCK_N.  The tile schedule
+ * in tile_records is cut with this BLOCK_M. */
+ditron_status_t ditron_moe_tile_choice(int total_tokens, int top_k, int num_experts,
+                                       int num_local_experts, int inter, int out[2]);
 
 /* Upper bound on the number of row tiles of the grouped GEMM. */
 int ditron_moe_max_tiles(int max_rows, int num_local_experts);

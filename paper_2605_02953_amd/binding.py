@@ -57,6 +57,8 @@ lib.ditron_reduce_slots.argtypes = [_pp, _vp, _vp, _vp, _i, _i, _i, _i, _i32, _v
 lib.ditron_moe_ag_grouped_gemm.restype = _i
 lib.ditron_moe_ag_grouped_gemm.argtypes = [_pp, _vp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _ip,
                                            _i, _i, _i, _i, _i, _i, _i, _i, _i, _i, _i32, _u, _vp]
+lib.ditron_moe_tile_choice.restype = _i
+lib.ditron_moe_tile_choice.argtypes = [_i, _i, _i, _i, _i, _ip]
 lib.ditron_moe_max_tiles.restype = _i
 lib.ditron_moe_max_tiles.argtypes = [_i, _i]
 lib.ditron_publish_chunks.restype = _i
@@ -163,6 +165,12 @@ def gemm_ar_two_shot(a, b, b_layout, gemm_out, peer_partials, out_dsts, peer_red
 def reduce_slots(slots, out, signals, status, rows, n, world, chunks, epoch, stream=None):
     return lib.ditron_reduce_slots(_ptr_array(slots), _ptr(out), _ptr(signals), _ptr(status), rows, n, world,
                                    chunks, epoch, _stream(stream))
+
+
+def moe_tile_choice(total_tokens, top_k, num_experts, num_local_experts, inter):
+    out = (ctypes.c_int * 2)()
+    st = lib.ditron_moe_tile_choice(total_tokens, top_k, num_experts, num_local_experts, inter, out)
+    return st, out[0], out[1]
 
 
 def moe_max_tiles(max_rows, num_local_experts):

@@ -62,6 +62,17 @@ extern "C" ditron_status_t ditron_tile_config(int op, int m, int n, int k, int d
   return DITRON_OK;
 }
 
+extern "C" ditron_status_t ditron_moe_tile_choice(int total_tokens, int top_k, int num_experts, int num_local_experts,
+                                                  int inter, int out[2]) {
+  if (!out || total_tokens <= 0 || top_k <= 0 || num_experts <= 0 || num_local_experts <= 0 ||
+      num_local_experts > num_experts || inter <= 0)
+    return DITRON_ERR_INVALID_ARG;
+  const MoeTile t = choose_moe_tile(moe_expected_rows(total_tokens, top_k, num_experts, num_local_experts), num_local_experts, inter);
+  out[0] = t.block_m;
+  out[1] = t.block_n;
+  return DITRON_OK;
+}
+
 extern "C" ditron_status_t ditron_set_num_nodes(int nnodes) {
   if (nnodes < 1 || nnodes > DITRON_MAX_WORLD) return DITRON_ERR_INVALID_ARG;
   g_num_nodes = nnodes;

@@ -16,10 +16,14 @@ typedef GemmTile4W<128, 128> TileSmall;
 // The same two for B stored [K, N].
 typedef GemmTile4W<256, 256, true> TileBigKN;
 typedef GemmTile4W<128, 128, true> TileSmallKN;
-// The MoE grouped GEMM: 4 waves as 2 x 2 on a 128-row tile (keeps the padding of an expert's
-// last row tile small); the column block is chosen per call.
-constexpr int kMoeBlockM = 128;
-// Column block of the grouped GEMM.  The number of row tiles is only known on the device, so
+// The MoE grouped GEMM: 4 waves as 2 x 2.  An expert's rows are padded to whole row tiles, so the row
+// tile is 128 unless the experts are large (1024 rows or more each under even routing), where the
+// 256-row tile's fewer loads per MFMA are worth more than the padding.
+constexpr int kMoeBlockM = 128;   // the smallest row tile: what the upper bound on the tile count assumes
+struct MoeTile {
+  int block_m, block_n;
+};
+// Column block for 128-row tiles.  The number of row tiles is only known on the device, so
 // the host works from the expectation under even routing (rows / 128 plus half a tile of
 // padding per expert): the narrowest block whose tile count still fits one chip-wide round
 // with a fifth to spare, so that a few tiles more than expected do not start a second round;
@@ -30,6 +34,21 @@ inline int choose_moe_block_n(long expected_rows, int num_local_experts, int int
   for (int w : widths)
     if (row_tiles * cdiv(inter, w) * 5 <= 256 * 4) return w;
   return 256;
+}
+inline MoeTile choose_moe_tile(long expected_rows, int num_local_experts, int inter) {
+  MoeTile t{};
+  if (expected_rows / num_local_experts >= 1024) {
+    t.block_m = 256;
+    t.block_n = inter <= 128 ? 128 : 256;
+  } else {
+    t.block_m = kMoeBlockM;
+    t.block_n = choose_moe_block_n(expected_rows, num_local_experts, inter);
+  }
+  return t;
+}
+// rows routed to the local experts if every expert received the same number of assignments
+inline long moe_expected_rows(long total_tokens, int top_k, int num_experts, int num_local_experts) {
+  return total_tokens * top_k * num_local_experts / num_experts;
 }
 
 struct TileChoice {

@@ -332,7 +332,9 @@ extern "C" ditron_status_t ditron_moe_ag_grouped_gemm(
   r.max_tiles = max_tiles;
   r.world = world;
   r.rank = rank;
-  r.block_m = kMoeBlockM;
+  const MoeTile mt = choose_moe_tile(moe_expected_rows((long)world * tokens_per_rank, top_k, num_experts, num_local_experts),
+                                     num_local_experts, inter);
+  r.block_m = mt.block_m;
   for (int i = 0; i < world; ++i) {
     r.shard[i] = emulate ? x_shards[i] : nullptr;
     r.order[i] = arrival_order ? arrival_order[i] : (rank + i) % world;
@@ -367,10 +369,13 @@ extern "C" ditron_status_t ditron_moe_ag_grouped_gemm(
   g.max_tiles = max_tiles;
   g.epoch = epoch;
   g.spin_limit = g_spin_limit;
-  const long expected_rows = (long)world * tokens_per_rank * top_k * num_local_experts / num_experts;
-  switch (choose_moe_block_n(expected_rows, num_local_experts, inter)) {
-    case 128: return launch_moe_gemm<GemmTile4W<kMoeBlockM, 128>>(g, max_tiles, s);
-    case 192: return launch_moe_gemm<GemmTile4W<kMoeBlockM, 192>>(g, max_tiles, s);
-    default: return launch_moe_gemm<GemmTile4W<kMoeBlockM, 256>>(g, max_tiles, s);
+  if (mt.block_m == 256) {
+    if (mt.block_n == 128) return launch_moe_gemm<GemmTile4W<256, 128>>(g, max_tiles, s);
+    return launch_moe_gemm<GemmTile4W<256, 256>>(g, max_tiles, s);
+  }
+  switch (mt.block_n) {
+    case 128: return launch_moe_gemm<GemmTile4W<128, 128>>(g, max_tiles, s);
+    case 192: return launch_moe_gemm<GemmTile4W<128, 192>>(g, max_tiles, s);
+    default: return launch_moe_gemm<GemmTile4W<128, 256>>(g, max_tiles, s);
   }
 }

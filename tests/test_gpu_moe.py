@@ -27,6 +27,8 @@ def w_nk(w_ekn):
 
 
 def _run_and_check(B, cfg, xs, ids, w, max_rows, integer, order=None, block_m=128):
+    st0, bm, bn = B.moe_tile_choice(cfg.world * cfg.tokens_per_rank, cfg.top_k, cfg.num_experts, cfg.num_local_experts, cfg.n)
+    assert st0 == B.OK and bm == block_m and bn in (128, 192, 256)
     e0 = cfg.rank * cfg.num_local_experts if (cfg.rank + 1) * cfg.num_local_experts <= cfg.num_experts else 0
     run = MoeRun(B, cfg.world, cfg.tokens_per_rank, cfg.k, cfg.n, cfg.num_experts, cfg.top_k,
                  cfg.num_local_experts, max_rows)
@@ -34,8 +36,6 @@ def _run_and_check(B, cfg, xs, ids, w, max_rows, integer, order=None, block_m=12
     assert st == B.OK, B.status_string(st)
     torch.cuda.synchronize()
     assert run.status.cpu().tolist()[0] == 0
-    st2, tc = B.tile_config(2, max_rows, cfg.n, cfg.k)
-    assert st2 == B.OK and tc["block_m"] == block_m
     # integer results: bit-exact
     count, offsets, gather = omoe.route(ids, cfg.world, cfg.num_experts, e0, cfg.num_local_experts)
     R = int(offsets[-1])
@@ -95,6 +95,14 @@ def test_moe_table_shapes_tensor_parallel_placement(B, hidden, inter, experts, t
                                   top_k=top_k, num_local_experts=experts, rank=0)
     xs, ids, w = synth.moe_inputs(cfg)
     _run_and_check(B, cfg, xs, ids, w, 8 * 128 * top_k, integer=False)
+
+
+def test_moe_large_experts_use_the_256_row_tile(B):
+    """2048 rows per expert (the Mixtral-8x22B shape at half its tokens): the schedule is cut in 256-row tiles."""
+    cfg = synth.CONFIGS[4].scaled(world=8, tokens_per_rank=512, k=2048, n=776, num_experts=8, top_k=2,
+                                  num_local_experts=8, rank=0)
+    xs, ids, w = synth.moe_inputs(cfg, integer=True)
+    _run_and_check(B, cfg, xs, ids, w, 8 * 512 * 2, integer=True, block_m=256)
 
 
 def test_moe_degenerate_routings(B):
