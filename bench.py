@@ -35,7 +35,7 @@ MEASURED_TRAFFIC = {
     "cfg3": 822.4e6 + 253.8e6,   # gemm_rs_kernel (reduce_slots_kernel: 134.3e6 + 16.8e6 = its algorithmic 151.0e6)
     "cfg4": 227.2e6 + 6.2e6,     # moe_grouped_gemm_kernel (the emulated gather, in the routing launch: 67.3e6 + 67.1e6)
     "gemm_ar": 1999.3e6 + 268.8e6,   # gemm_ar_kernel, fused launch: operand panels ~0.9e9 + eight partials 1.07e9 read; partial + output written
-    "cfg5": 76.8e6 + 3.1e6,      # ag_gemm_fp8_kernel; algorithmic 70.3e6
+    "cfg5": 76.8e6 + 3.1e6,      # ag_gemm_decode_kernel (fp8); algorithmic 70.3e6
 }
 
 

@@ -102,7 +102,8 @@ ditron_status_t ditron_tile_row_order(int op, int m, int block_m, int world, int
  * evaluate the schedule independently.  op: 0 = ag_gemm, 1 = gemm_rs, 2 = moe grouped gemm
  * (m = max_rows; the smallest BLOCK_M is reported and 0 for the column block: both are chosen per
  * call, see ditron_moe_tile_choice),
- * 3 = gemm_ar.
+ * 3 = gemm_ar, 4 = ag_gemm with B stored [k, n] (bf16 problems with few 128 x 128 tiles and B stored
+ * [n, k] use the 128 x 32 tile of the decode kernel, which the [k, n] layout does not).
  * out[0]=BLOCK_M out[1]=BLOCK_N out[2]=GROUP_SIZE_M out[3]=chiplets used by the work-group
  * remap (0 = no remap) out[4]=tiles per chiplet per block out[5]=number of tiles
  * (ag_gemm / gemm_rs) out[6]=threads per work-group out[7]=reserved (0). */

@@ -1,5 +1,6 @@
-// fp8 (OCP e4m3) AllGather-GEMM, tuned for decode-shaped problems (few rows, wide weight
-// matrix): C[m, n] = (gather(A) . B) * a_scale[row shard] * b_scale[col], bf16 out.
+// AllGather-GEMM for decode-shaped problems (few rows, wide weight matrix), fp8 (OCP e4m3) or
+// bf16 operands: C[m, n] = (gather(A) . B) * a_scale[row shard] * b_scale[col], bf16 out (no
+// scales for bf16).
 //
 // The work is bound by streaming B once from HBM, so a work-group owns a 128-row x 32-column
 // output tile and keeps many small B stages in flight: B (32 rows x 128 bytes per K tile)
@@ -8,8 +9,9 @@
 // L2) uses a 5-deep ring that starts once the flags are up.  The two streams are issued by
 // different waves: a wave's loads return in order, so an A load (L2 latency) queued behind a
 // B load (HBM latency) would wait for it.  Waves 0-3 fetch A and compute, waves 4-7 only
-// fetch B; one barrier per K tile joins them.  v_mfma_f32_16x16x128_f8f6f4 consumes 32
-// contiguous bytes per lane of each operand.
+// fetch B; one barrier per K tile joins them.  A K tile is 128 bytes of a row for either type:
+// v_mfma_f32_16x16x128_f8f6f4 consumes 32 contiguous bytes per lane of each operand (one MFMA
+// per K tile and 16 x 16 block), v_mfma_f32_16x16x32_bf16 16 bytes (two MFMAs).
 #include "gemm_core.h"
 #include "launch.h"
 
@@ -39,18 +41,20 @@ struct AgGemmFp8Params {
   int32_t* arrivals;
   int32_t* status;
   int32_t* schedule;
-  int m_per_rank, m, n, k, world, rank, nnodes;
+  int m_per_rank, m, n, k, world, rank, nnodes;   // k in elements
   int32_t epoch;
   int num_producers, teams;
   unsigned spin_limit;
   int group_m, num_xcd, per_xcd, npm, npn;
 };
 
-__global__ __launch_bounds__(Fp8Tile::THREADS) void ag_gemm_fp8_kernel(const AgGemmFp8Params p) {
+template <bool BF16>
+__global__ __launch_bounds__(Fp8Tile::THREADS) void ag_gemm_decode_kernel(const AgGemmFp8Params p) {
   typedef Fp8Tile T;
+  const int K = p.k * (BF16 ? 2 : 1);   // bytes per row of A and of B
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   if ((int)blockIdx.x < p.num_producers) {
-    const size_t shard_bytes = (size_t)p.m_per_rank * p.k;
+    const size_t shard_bytes = (size_t)p.m_per_rank * K;
     produce_chunks<T::THREADS>(
         p.world, shard_bytes, blockIdx.x, p.num_producers, p.teams, p.epoch,
         [&](int i) { return (void*)(p.workspace + (size_t)p.order[i] * shard_bytes); },
@@ -73,7 +77,6 @@ __global__ __launch_bounds__(Fp8Tile::THREADS) void ag_gemm_fp8_kernel(const AgG
   }
 
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-  const int K = p.k;
   const int kt_all = (K + T::BK - 1) / T::BK;
   char* lds_a = lds;
   char* lds_b = lds + T::NA * T::A_STAGE;
@@ -155,24 +158,44 @@ __global__ __launch_bounds__(Fp8Tile::THREADS) void ag_gemm_fp8_kernel(const AgG
     issue_a(kt + T::NA - 1);
     const char* sa = lds_a + (kt % T::NA) * T::A_STAGE + (wave * 32 + l16) * 128;
     const char* sb = lds_b + (kt % T::NB) * T::B_STAGE + l16 * 128;
-    i32x8_t af[2], bf[2];
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb) {
-      const u32x4_t lo = *(const u32x4_t*)(sa + mb * 16 * 128 + off0);
-      const u32x4_t hi = *(const u32x4_t*)(sa + mb * 16 * 128 + off1);
-      af[mb] = i32x8_t{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
-    }
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-      const u32x4_t lo = *(const u32x4_t*)(sb + nb * 16 * 128 + off0);
-      const u32x4_t hi = *(const u32x4_t*)(sb + nb * 16 * 128 + off1);
-      bf[nb] = i32x8_t{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
-    }
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb)
+    if constexpr (BF16) {
+      // MFMA j of the K tile takes k = 32 j + 8 g .. + 7 of the lane's row: 16-byte chunk 4 j + g
+      bf16x8_t af[2][2], bf[2][2];
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
-        acc[nb][mb] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bf[nb], af[mb], acc[nb][mb], 0, 0, 0, 0, 0, 0);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) af[mb][j] = *(const bf16x8_t*)(sa + mb * 16 * 128 + (((4 * j + g) ^ sw) * 16));
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) bf[nb][j] = *(const bf16x8_t*)(sb + nb * 16 * 128 + (((4 * j + g) ^ sw) * 16));
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+          for (int mb = 0; mb < 2; ++mb)
+            acc[nb][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bf[nb][j], af[mb][j], acc[nb][mb], 0, 0, 0);
+    } else {
+      i32x8_t af[2], bf[2];
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb) {
+        const u32x4_t lo = *(const u32x4_t*)(sa + mb * 16 * 128 + off0);
+        const u32x4_t hi = *(const u32x4_t*)(sa + mb * 16 * 128 + off1);
+        af[mb] = i32x8_t{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+      }
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb) {
+        const u32x4_t lo = *(const u32x4_t*)(sb + nb * 16 * 128 + off0);
+        const u32x4_t hi = *(const u32x4_t*)(sb + nb * 16 * 128 + off1);
+        bf[nb] = i32x8_t{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+      }
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+          acc[nb][mb] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bf[nb], af[mb], acc[nb][mb], 0, 0, 0, 0, 0, 0);
+    }
   }
   // drain the redundant tail loads before the LDS is handed back
   wait_vmcnt0();
@@ -199,14 +222,15 @@ __global__ __launch_bounds__(Fp8Tile::THREADS) void ag_gemm_fp8_kernel(const AgG
 
 using namespace ditron;
 
-extern "C" ditron_status_t ditron_ag_gemm_fp8(const void* const* a_shards, const void* b, int b_layout, void* c,
-                                              const float* a_scales, const float* b_scales, void* workspace,
-                                              int32_t* signals, int32_t* status, int32_t* schedule_out,
-                                              const int* arrival_order, int m_per_rank, int n, int k, int world,
-                                              int rank, int32_t epoch, unsigned flags, void* stream) {
+extern "C" ditron_status_t ditron_ag_gemm_decode(const void* const* a_shards, const void* b, int b_layout, void* c,
+                                                 const float* a_scales, const float* b_scales, void* workspace,
+                                                 int32_t* signals, int32_t* status, int32_t* schedule_out,
+                                                 const int* arrival_order, int m_per_rank, int n, int k, int world,
+                                                 int rank, int dtype, int32_t epoch, unsigned flags, void* stream) {
   // pointer / enum checks were done by ditron_ag_gemm
+  const bool bf16 = dtype == DITRON_BF16;
   if (b_layout != DITRON_B_NK) return DITRON_ERR_UNSUPPORTED;
-  if (k % 16 != 0 || n % 8 != 0) return DITRON_ERR_UNSUPPORTED;
+  if (k % (bf16 ? 8 : 16) != 0 || n % 8 != 0) return DITRON_ERR_UNSUPPORTED;
   const bool emulate = (flags & DITRON_EMULATE_PRODUCER) != 0;
   AgGemmFp8Params p{};
   for (int i = 0; i < world; ++i) {
@@ -216,8 +240,8 @@ extern "C" ditron_status_t ditron_ag_gemm_fp8(const void* const* a_shards, const
   p.workspace = (char*)workspace;
   p.b = (const char*)b;
   p.c = (__bf16*)c;
-  p.a_scales = a_scales;
-  p.b_scales = b_scales;
+  p.a_scales = bf16 ? nullptr : a_scales;
+  p.b_scales = bf16 ? nullptr : b_scales;
   p.flags = signals;
   p.arrivals = signals + world;
   p.status = status;
@@ -231,18 +255,18 @@ extern "C" ditron_status_t ditron_ag_gemm_fp8(const void* const* a_shards, const
   p.nnodes = g_num_nodes;
   p.epoch = epoch;
   p.spin_limit = g_spin_limit;
-  TileChoice tc = choose_tile_fp8(p.m, n, k);
+  TileChoice tc = choose_tile_decode(p.m, n, k);
   if (p.nnodes > 1 && !node_order_is_bijection(p.m, tc.block_m, world, p.nnodes, rank, kOrderGather))
     return DITRON_ERR_UNSUPPORTED;
   p.group_m = tc.group_m;
   p.num_xcd = tc.num_xcd;
   p.per_xcd = tc.per_xcd;
-  const ProducerPlan pl = plan_producers((size_t)p.m * k, world);
+  const ProducerPlan pl = plan_producers((size_t)p.m * k * (bf16 ? 2 : 1), world);
   p.num_producers = emulate ? pl.producers : 0;
   p.teams = pl.teams;
   p.npm = cdiv(p.m, Fp8Tile::BM);
   p.npn = cdiv(p.n, Fp8Tile::BN);
-  auto kern = ag_gemm_fp8_kernel;
+  auto kern = bf16 ? ag_gemm_decode_kernel<true> : ag_gemm_decode_kernel<false>;
   if (!set_dynamic_lds((const void*)kern, Fp8Tile::LDS_BYTES)) return DITRON_ERR_HIP;
   const unsigned grid = (unsigned)(p.num_producers + p.npm * p.npn);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(Fp8Tile::THREADS), Fp8Tile::LDS_BYTES, (hipStream_t)stream, p);

@@ -41,10 +41,11 @@ extern "C" size_t ditron_signal_words(int world, int chunks) {
 }
 
 extern "C" ditron_status_t ditron_tile_config(int op, int m, int n, int k, int dtype, int out[8]) {
-  if (!out || m <= 0 || n <= 0 || k <= 0 || op < 0 || op > 3) return DITRON_ERR_INVALID_ARG;
+  if (!out || m <= 0 || n <= 0 || k <= 0 || op < 0 || op > 4) return DITRON_ERR_INVALID_ARG;
   if (dtype != DITRON_BF16 && dtype != DITRON_FP8_E4M3) return DITRON_ERR_INVALID_ARG;
   if (dtype == DITRON_FP8_E4M3 && op != 0) return DITRON_ERR_UNSUPPORTED;
-  TileChoice t = dtype == DITRON_FP8_E4M3 ? choose_tile_fp8(m, n, k) : choose_tile(m, n, k);
+  const bool decode = dtype == DITRON_FP8_E4M3 || (op == 0 && bf16_ag_is_decode_shaped(m, n));
+  TileChoice t = decode ? choose_tile_decode(m, n, k) : choose_tile(m, n, k);
   if (op == 2) {  // the grouped GEMM has its own row tile; its column block is chosen per call; m is max_rows
     t.big = false;
     t.block_m = kMoeBlockM;

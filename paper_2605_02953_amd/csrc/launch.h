@@ -71,8 +71,11 @@ inline TileChoice choose_tile(int m, int n, int /*k*/) {
   return t;
 }
 
-// fp8 path: one tile shape, 128 rows x 32 columns, 4 computing waves + 4 loading waves.
-inline TileChoice choose_tile_fp8(int /*m*/, int /*n*/, int /*k*/) {
+// Decode-shaped AllGather-GEMM (fp8 always; bf16 when the 128 x 128 tiles of the tile engine would not
+// cover half the chip and B is stored [n, k]): one tile shape, 128 rows x 32 columns, 4 computing waves +
+// 4 loading waves.
+inline bool bf16_ag_is_decode_shaped(int m, int n) { return (long)cdiv(m, 128) * cdiv(n, 128) <= 128; }
+inline TileChoice choose_tile_decode(int /*m*/, int /*n*/, int /*k*/) {
   TileChoice t{};
   t.big = false;
   t.block_m = 128;
@@ -140,8 +143,8 @@ extern int g_num_nodes;
 
 }  // namespace ditron
 
-extern "C" ditron_status_t ditron_ag_gemm_fp8(const void* const* a_shards, const void* b, int b_layout, void* c,
-                                              const float* a_scales, const float* b_scales, void* workspace,
-                                              int32_t* signals, int32_t* status, int32_t* schedule_out,
-                                              const int* arrival_order, int m_per_rank, int n, int k, int world,
-                                              int rank, int32_t epoch, unsigned flags, void* stream);
+extern "C" ditron_status_t ditron_ag_gemm_decode(const void* const* a_shards, const void* b, int b_layout, void* c,
+                                                 const float* a_scales, const float* b_scales, void* workspace,
+                                                 int32_t* signals, int32_t* status, int32_t* schedule_out,
+                                                 const int* arrival_order, int m_per_rank, int n, int k, int world,
+                                                 int rank, int dtype, int32_t epoch, unsigned flags, void* stream);

@@ -29,7 +29,7 @@ def _run(B, cfg, shards, b_kn, rank=None, order=None, want_schedule=False, kn=Fa
     bd = to_dev(b_kn if kn else nk(b_kn))     # kn: B handed over as it is stored, [k, n]
     sched = None
     if want_schedule:
-        st, tc = B.tile_config(0, cfg.m, cfg.n, cfg.k)
+        st, tc = B.tile_config(4 if kn else 0, cfg.m, cfg.n, cfg.k)
         sched = torch.full((4 * tc["ntiles"],), -1, dtype=torch.int32, device="cuda")
     st = run(sh, bd, rank, order=order, schedule=sched, b_layout=B.B_KN if kn else B.B_NK)
     assert st == B.OK, B.status_string(st)
@@ -53,8 +53,8 @@ def test_cfg1_world2_smoke(B):
     _check_schedule(B, cfg, cfg.rank, sched)
 
 
-def _check_schedule(B, cfg, rank, sched):
-    st, tc = B.tile_config(0, cfg.m, cfg.n, cfg.k)
+def _check_schedule(B, cfg, rank, sched, kn=False):
+    st, tc = B.tile_config(4 if kn else 0, cfg.m, cfg.n, cfg.k)
     assert st == B.OK
     nt = tc["ntiles"]
     assert nt == osch.cdiv(cfg.m, tc["block_m"]) * osch.cdiv(cfg.n, tc["block_n"])
@@ -69,6 +69,7 @@ def _check_schedule(B, cfg, rank, sched):
     (2, 128, 256, 256),      # one small tile row per shard
     (4, 200, 264, 328),      # ragged rows, columns and contraction tail (328 = 5*64 + 8)
     (8, 505, 3080, 200),     # 256x256 tiles with ragged edges on every side, 208 tiles
+    (8, 250, 2056, 136),     # 128x128 tiles of the tile engine (too many for the decode kernel, too few 256x256 ones)
     (3, 64, 8, 8),           # minimum contraction and width
 ])
 @pytest.mark.parametrize("kn", [False, True], ids=["b_nk", "b_kn"])
@@ -81,7 +82,7 @@ def test_integer_inputs_are_bit_exact(B, world, m_r, n, k, kn):
     want = formats.encode_bf16_rne(oag.ag_gemm(shards, b).astype(np.float32))
     assert np.array_equal(ws, oag.gather(shards))
     assert np.array_equal(c, want)
-    _check_schedule(B, cfg, cfg.rank, sched)
+    _check_schedule(B, cfg, cfg.rank, sched, kn=kn)
 
 
 @pytest.mark.parametrize("world,m_r,n,k", [(4, 200, 264, 328), (8, 505, 3080, 456)])

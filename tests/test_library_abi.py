@@ -39,8 +39,12 @@ def test_sizes_and_strings(B):
 def test_tile_config(B):
     st, tc = B.tile_config(0, 8192, 3584, 8192)
     assert st == B.OK and (tc["block_m"], tc["block_n"], tc["ntiles"]) == (256, 256, 448)
-    st, tc = B.tile_config(0, 256, 256, 256)
-    assert st == B.OK and (tc["block_m"], tc["ntiles"]) == (128, 4)
+    st, tc = B.tile_config(0, 256, 256, 256)           # few tiles, B stored [n, k]: the decode kernel's 128 x 32 tile
+    assert st == B.OK and (tc["block_m"], tc["block_n"], tc["ntiles"]) == (128, 32, 16)
+    st, tc = B.tile_config(4, 256, 256, 256)           # B stored [k, n]: the tile engine
+    assert st == B.OK and (tc["block_m"], tc["block_n"], tc["ntiles"]) == (128, 128, 4)
+    st, tc = B.tile_config(0, 2048, 2048, 256)
+    assert st == B.OK and (tc["block_m"], tc["block_n"], tc["ntiles"]) == (128, 128, 256)
     st, tc = B.tile_config(0, 128, 8192, 8192, B.FP8_E4M3)
     assert st == B.OK and (tc["block_m"], tc["block_n"], tc["ntiles"]) == (128, 32, 256)
     assert B.tile_config(7, 1, 1, 1)[0] == B.ERR_INVALID_ARG
