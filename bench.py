@@ -684,7 +684,7 @@ def bench_fp8(args):
                                f"-> C [{cfg.m},{cfg.n}] bf16; weights rotated over {nsets} copies", "latency_us": ev_ms * 1e3,
                    "tflops": flops / (ev_ms * 1e-3) / 1e12},
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
-                     "traffic": MEASURED_TRAFFIC.get("cfg5"), "kernel": "ag_gemm_fp8_kernel", "kernel_ms": ev_ms,
+                     "traffic": MEASURED_TRAFFIC.get("cfg5"), "kernel": "ag_gemm_decode_kernel (fp8)", "kernel_ms": ev_ms,
                      "bytes": alg_bytes},
     }
     if not args.no_cpu:
