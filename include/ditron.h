@@ -1,15 +1,18 @@
 /*
  * ditron.h -- C ABI of the MI355X (gfx950) fused communication + GEMM kernels.
  *
- * One GPU's share of three tensor-parallel operators, with the other ranks' shards
+ * One GPU's share of the tensor-parallel operators below, with the other ranks' shards
  * resident in the same GPU's memory and published, chunk by chunk with one int32 signal
  * flag each, in the order the peer ranks would deliver them:
  *
  *   ditron_ag_gemm              AllGather-GEMM          (paper, Appendix "AllGather GEMM")
  *   ditron_gemm_rs              GEMM-ReduceScatter      (paper, Appendix "GEMM Reduce-Scatter")
+ *   ditron_gemm_rs_fuse_scatter the same with the scatter fused into the GEMM's stores
  *   ditron_moe_ag_grouped_gemm  AllGather + grouped GEMM over local experts
  *                               (paper, kernel list "ag_group_gemm"; Appendix "Swizzle", third listing)
- *   ditron_gemm_ar              GEMM + AllReduce        (paper, Appendix "GEMM All-Reduce")
+ *   ditron_gemm_ar              GEMM + AllReduce, every tile reduced on every rank
+ *   ditron_gemm_ar_two_shot     GEMM + AllReduce, tiles dealt to the ranks and broadcast
+ *                               (paper, Appendix "GEMM All-Reduce")
  *
  * Conventions common to every entry point
  *   - "device" pointers are GPU global memory (or pinned host memory mapped into the GPU),
