@@ -62,7 +62,7 @@ typedef enum {
 typedef enum { DITRON_BF16 = 0, DITRON_FP8_E4M3 = 1 } ditron_dtype_t;
 
 /* Physical layout of the logical [k, n] right-hand matrix.  The bf16 AllGather-GEMM and
- * GEMM-ReduceScatter take both; the fp8 and MoE operators take DITRON_B_NK only (UNSUPPORTED
+ * GEMM-ReduceScatter, GEMM + AllReduce and the MoE grouped GEMM take both; fp8 takes DITRON_B_NK only (UNSUPPORTED
  * otherwise). */
 typedef enum {
   DITRON_B_KN = 0, /* stored [k, n], n contiguous */
@@ -292,7 +292,8 @@ ditron_status_t ditron_reduce_slots(const void* const* slots, void* out, const i
  *  x_shards      host array of `world` device pointers [tokens_per_rank, hidden] bf16
  *  topk_ids      device int32 [world*tokens_per_rank, top_k]
  *  w, w_layout   device, per expert logical [hidden, inter] bf16, experts contiguous;
- *                layout as ditron_blayout_t (DITRON_B_NK = [E_l, inter, hidden])
+ *                layout as ditron_blayout_t (DITRON_B_NK = [E_l, inter, hidden], DITRON_B_KN =
+ *                [E_l, hidden, inter])
  *  y             device out [max_rows, inter] bf16; rows >= R are not written
  *  counts        device out int32 [world * num_experts]
  *  expert_offsets device out int32 [num_local_experts + 1]

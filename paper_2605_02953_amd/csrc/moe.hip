@@ -254,9 +254,13 @@ __global__ __launch_bounds__(T::THREADS) void moe_grouped_gemm_kernel(const MoeG
   const int top_k = p.top_k, N = p.inter;
   // the gather happens here: a tile row is fetched from the token its assignment belongs to
   auto a_row = [=](int r) { return (uint32_t)(gidx[min(p0 + r, p_end - 1)] / top_k) * row_bytes; };
-  auto b_row = [=](int r) { return (uint32_t)min(n0 + r, N - 1) * row_bytes; };
   f32x16_t acc[T::NI][T::MI];
-  gemm_mainloop<T>(acc, p.workspace, a_row, wj, b_row, p.hidden, lds);
+  if constexpr (T::B_KN) {   // expert weights stored [hidden, inter]: same bytes per expert, inter contiguous
+    gemm_mainloop<T>(acc, p.workspace, a_row, wj, BColumns{(uint32_t)N * 2u, n0, N}, p.hidden, lds);
+  } else {
+    auto b_row = [=](int r) { return (uint32_t)min(n0 + r, N - 1) * row_bytes; };
+    gemm_mainloop<T>(acc, p.workspace, a_row, wj, b_row, p.hidden, lds);
+  }
   store_tile_bf16<T>(acc, p.y, (size_t)p.inter, p0, n0, p_end, N, lds);
 }
 
@@ -305,7 +309,6 @@ extern "C" ditron_status_t ditron_moe_ag_grouped_gemm(
       if (!x_shards[s] || !aligned16(x_shards[s])) return DITRON_ERR_INVALID_ARG;
     if (arrival_order && !is_permutation(arrival_order, world)) return DITRON_ERR_INVALID_ARG;
   }
-  if (w_layout != DITRON_B_NK) return DITRON_ERR_UNSUPPORTED;
   if (hidden % 8 != 0 || inter % 8 != 0) return DITRON_ERR_UNSUPPORTED;
   if (!fits_32bit((size_t)world * tokens_per_rank, hidden, 2) || !fits_32bit(inter, hidden, 2))
     return DITRON_ERR_UNSUPPORTED;
@@ -369,6 +372,11 @@ extern "C" ditron_status_t ditron_moe_ag_grouped_gemm(
   g.max_tiles = max_tiles;
   g.epoch = epoch;
   g.spin_limit = g_spin_limit;
+  if (w_layout == DITRON_B_KN) {   // [hidden, inter] weights: the column block is 128 or 256 (a 192-column row does not split over the loading lanes)
+    const bool wide = mt.block_n > 128;
+    if (mt.block_m == 256) return wide ? launch_moe_gemm<GemmTile4W<256, 256, true>>(g, max_tiles, s) : launch_moe_gemm<GemmTile4W<256, 128, true>>(g, max_tiles, s);
+    return wide ? launch_moe_gemm<GemmTile4W<128, 256, true>>(g, max_tiles, s) : launch_moe_gemm<GemmTile4W<128, 128, true>>(g, max_tiles, s);
+  }
   if (mt.block_m == 256) {
     if (mt.block_n == 128) return launch_moe_gemm<GemmTile4W<256, 128>>(g, max_tiles, s);
     return launch_moe_gemm<GemmTile4W<256, 256>>(g, max_tiles, s);

@@ -90,12 +90,12 @@ class MoeRun:
         self.status = torch.zeros(B.STATUS_WORDS, **i32)
         self.epoch = 0
 
-    def __call__(self, x_dev, ids_dev, w_dev, expert_begin, rank, order=None, flags=None, stream=None):
+    def __call__(self, x_dev, ids_dev, w_dev, expert_begin, rank, order=None, flags=None, stream=None, w_layout=None):
         B = self.B
         t_r, hidden, inter, ne, top_k, nl, max_rows, world = self.dims
         self.epoch += 1
         flags = B.EMULATE_PRODUCER if flags is None else flags
-        return B.moe_ag_grouped_gemm(x_dev, ids_dev, w_dev, B.B_NK, self.y, self.counts, self.offsets, self.gather,
+        return B.moe_ag_grouped_gemm(x_dev, ids_dev, w_dev, B.B_NK if w_layout is None else w_layout, self.y, self.counts, self.offsets, self.gather,
                                      self.records, self.workspace, self.signals, self.status, order, t_r, hidden,
                                      inter, ne, top_k, expert_begin, nl, max_rows, world, rank, self.epoch, flags,
                                      stream)

@@ -26,13 +26,15 @@ def w_nk(w_ekn):
     return np.ascontiguousarray(np.transpose(w_ekn, (0, 2, 1)))
 
 
-def _run_and_check(B, cfg, xs, ids, w, max_rows, integer, order=None, block_m=128):
+def _run_and_check(B, cfg, xs, ids, w, max_rows, integer, order=None, block_m=128, kn=False):
     st0, bm, bn = B.moe_tile_choice(cfg.world * cfg.tokens_per_rank, cfg.top_k, cfg.num_experts, cfg.num_local_experts, cfg.n)
     assert st0 == B.OK and bm == block_m and bn in (128, 192, 256)
     e0 = cfg.rank * cfg.num_local_experts if (cfg.rank + 1) * cfg.num_local_experts <= cfg.num_experts else 0
     run = MoeRun(B, cfg.world, cfg.tokens_per_rank, cfg.k, cfg.n, cfg.num_experts, cfg.top_k,
                  cfg.num_local_experts, max_rows)
-    st = run([to_dev(x) for x in xs], to_dev(ids), to_dev(w_nk(w)), e0, cfg.rank, order=order)
+    # kn: the weights handed over as they are stored logically, [E_l, hidden, inter]
+    st = run([to_dev(x) for x in xs], to_dev(ids), to_dev(w if kn else w_nk(w)), e0, cfg.rank, order=order,
+             w_layout=B.B_KN if kn else B.B_NK)
     assert st == B.OK, B.status_string(st)
     torch.cuda.synchronize()
     assert run.status.cpu().tolist()[0] == 0
@@ -72,13 +74,14 @@ def _run_and_check(B, cfg, xs, ids, w, max_rows, integer, order=None, block_m=12
     (8, 256, 64, 1544, 8, 2, 8, 2, True),       # 4096 rows x 1544 columns: the 256-column block, ragged last block
     (8, 128, 64, 1400, 16, 2, 16, 6, True),     # 2048 rows x 1400 columns: the 192-column block, ragged last block
 ])
-def test_moe_end_to_end(B, world, t_r, hidden, inter, experts, top_k, local, rank, integer):
+@pytest.mark.parametrize("kn", [False, True], ids=["w_nk", "w_kn"])
+def test_moe_end_to_end(B, world, t_r, hidden, inter, experts, top_k, local, rank, integer, kn):
     cfg = synth.CONFIGS[4].scaled(world=world, tokens_per_rank=t_r, k=hidden, n=inter, num_experts=experts,
                                   top_k=top_k, num_local_experts=local, rank=rank)
     xs, ids, w = synth.moe_inputs(cfg, integer=integer)
     max_rows = world * t_r * top_k
     order = None if rank % 2 else list(reversed(range(world)))
-    _run_and_check(B, cfg, xs, ids, w, max_rows, integer, order=order)
+    _run_and_check(B, cfg, xs, ids, w, max_rows, integer, order=order, kn=kn)
 
 
 @pytest.mark.parametrize("hidden,inter,experts,top_k", [
@@ -103,6 +106,7 @@ def test_moe_large_experts_use_the_256_row_tile(B):
                                   num_local_experts=8, rank=0)
     xs, ids, w = synth.moe_inputs(cfg, integer=True)
     _run_and_check(B, cfg, xs, ids, w, 8 * 512 * 2, integer=True, block_m=256)
+    _run_and_check(B, cfg, xs, ids, w, 8 * 512 * 2, integer=True, block_m=256, kn=True)
 
 
 def test_moe_degenerate_routings(B):
