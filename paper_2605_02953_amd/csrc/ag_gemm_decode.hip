@@ -17,7 +17,7 @@
 
 namespace ditron {
 
-struct Fp8Tile {
+struct DecodeTile {
   static constexpr int BM = 128, BN = 32, BK = 128, NWAVES = 4, THREADS = 512;   // 4 compute waves + 4 B loaders
   static constexpr int NA = 5, NB = 16;                 // ring depths
   static constexpr int A_STAGE = BM * 128, B_STAGE = BN * 128;
@@ -29,7 +29,7 @@ struct Fp8Tile {
 
 typedef int i32x8_t __attribute__((ext_vector_type(8)));
 
-struct AgGemmFp8Params {
+struct AgGemmDecodeParams {
   const void* shard[DITRON_MAX_WORLD];
   int order[DITRON_MAX_WORLD];
   char* workspace;
@@ -49,8 +49,8 @@ struct AgGemmFp8Params {
 };
 
 template <bool BF16>
-__global__ __launch_bounds__(Fp8Tile::THREADS) void ag_gemm_decode_kernel(const AgGemmFp8Params p) {
-  typedef Fp8Tile T;
+__global__ __launch_bounds__(DecodeTile::THREADS) void ag_gemm_decode_kernel(const AgGemmDecodeParams p) {
+  typedef DecodeTile T;
   const int K = p.k * (BF16 ? 2 : 1);   // bytes per row of A and of B
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   if ((int)blockIdx.x < p.num_producers) {
@@ -232,7 +232,7 @@ extern "C" ditron_status_t ditron_ag_gemm_decode(const void* const* a_shards, co
   if (b_layout != DITRON_B_NK) return DITRON_ERR_UNSUPPORTED;
   if (k % (bf16 ? 8 : 16) != 0 || n % 8 != 0) return DITRON_ERR_UNSUPPORTED;
   const bool emulate = (flags & DITRON_EMULATE_PRODUCER) != 0;
-  AgGemmFp8Params p{};
+  AgGemmDecodeParams p{};
   for (int i = 0; i < world; ++i) {
     p.shard[i] = emulate ? a_shards[i] : nullptr;
     p.order[i] = arrival_order ? arrival_order[i] : (rank + i) % world;
@@ -264,11 +264,11 @@ extern "C" ditron_status_t ditron_ag_gemm_decode(const void* const* a_shards, co
   const ProducerPlan pl = plan_producers((size_t)p.m * k * (bf16 ? 2 : 1), world);
   p.num_producers = emulate ? pl.producers : 0;
   p.teams = pl.teams;
-  p.npm = cdiv(p.m, Fp8Tile::BM);
-  p.npn = cdiv(p.n, Fp8Tile::BN);
+  p.npm = cdiv(p.m, DecodeTile::BM);
+  p.npn = cdiv(p.n, DecodeTile::BN);
   auto kern = bf16 ? ag_gemm_decode_kernel<true> : ag_gemm_decode_kernel<false>;
-  if (!set_dynamic_lds((const void*)kern, Fp8Tile::LDS_BYTES)) return DITRON_ERR_HIP;
+  if (!set_dynamic_lds((const void*)kern, DecodeTile::LDS_BYTES)) return DITRON_ERR_HIP;
   const unsigned grid = (unsigned)(p.num_producers + p.npm * p.npn);
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(Fp8Tile::THREADS), Fp8Tile::LDS_BYTES, (hipStream_t)stream, p);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(DecodeTile::THREADS), DecodeTile::LDS_BYTES, (hipStream_t)stream, p);
   return hipGetLastError() == hipSuccess ? DITRON_OK : DITRON_ERR_HIP;
 }
