@@ -194,16 +194,18 @@ struct Stager4W {
 
   // `kt` must be a valid K tile; a chunk past K reads as zero (lane offset pushed out of range)
   template <int I>
-  __device__ __forceinline__ void fetch_one(int kt, int K) {
+  __device__ __forceinline__ u32x4_t load_one(int kt, int K) const {
     if constexpr (T::B_KN && I >= T::A_LOADS) {
       const bool dead = kt * 64 + kn_row + (I - T::A_LOADS) * KN_ROWS >= K;
-      reg[I] = __builtin_amdgcn_raw_buffer_load_b128(b_rsrc, dead ? kOutOfRange : off[I], kt * kn_tile_bytes, 0);
+      return __builtin_amdgcn_raw_buffer_load_b128(b_rsrc, dead ? kOutOfRange : off[I], kt * kn_tile_bytes, 0);
     } else {
       const bool dead = kt * 64 + kc >= K;
       const int v = dead ? kOutOfRange : off[I];
-      reg[I] = __builtin_amdgcn_raw_buffer_load_b128(I < T::A_LOADS ? a_rsrc : b_rsrc, v, kt * 128, 0);
+      return __builtin_amdgcn_raw_buffer_load_b128(I < T::A_LOADS ? a_rsrc : b_rsrc, v, kt * 128, 0);
     }
   }
+  template <int I>
+  __device__ __forceinline__ void fetch_one(int kt, int K) { reg[I] = load_one<I>(kt, K); }
   template <int LO, int HI>
   __device__ __forceinline__ void fetch_range(int kt, int K) {
     static_for<LO, HI>([&](auto i) { fetch_one<decltype(i)::value>(kt, K); });
@@ -262,9 +264,13 @@ __device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[T::NI][T::MI], con
   const int kt_last = kt_all - 1;
   Stager4W<T> st;
   st.init(a_base, a_row, b_base, b_row);
+  // the first two K tiles are requested together (the second into registers that are free until the
+  // loop starts), so the tile pays for one cold round trip to memory, not two in a row
   st.template fetch_range<0, LOADS>(0, K);
+  u32x4_t second[LOADS];
+  static_for<0, LOADS>([&](auto i) { second[decltype(i)::value] = st.template load_one<decltype(i)::value>(min(1, kt_last), K); });
   st.template commit_range<0, LOADS>(lds);
-  st.template fetch_range<0, LOADS>(min(1, kt_last), K);
+  static_for<0, LOADS>([&](auto i) { st.reg[decltype(i)::value] = second[decltype(i)::value]; });
   __syncthreads();
 
   Frags4W<T> f0, f1;
