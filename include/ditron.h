@@ -30,6 +30,8 @@
  *     pass a value different from every earlier call on the same buffer (e.g. 1, 2, 3, ...)
  *     so that no reset sits between calls.  Words beyond the flags are internal counters
  *     which every call leaves at zero.
+ *     The epoch is a launch argument: a captured HIP graph would replay the same value, for which
+ *     the flags of the previous replay already stand, so a graph must not replay these calls.
  *   - `status` is a device int32[DITRON_STATUS_WORDS], zero-filled by the caller.  Kernels
  *     never spin forever: a wait that exceeds the spin limit stores DITRON_ERR_TIMEOUT in
  *     status[0] (and the flag index in status[1]) and the work-group carries on, so the
