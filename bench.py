@@ -423,10 +423,15 @@ def bench_moe(args):
     run = MoeRun(B, cfg.world, cfg.tokens_per_rank, cfg.k, cfg.n, cfg.num_experts, cfg.top_k, cfg.num_local_experts, max_rows)
     xd = [to_dev(x) for x in xs]
     idd = to_dev(ids)
-    wd = to_dev(np.ascontiguousarray(np.transpose(w, (0, 2, 1))))
+    # the expert weights (101 MB) rotate through three copies, so that they stream from HBM and not from the
+    # 256 MB memory-side cache
+    nsets = 3
+    wds = [to_dev(np.ascontiguousarray(np.transpose(w, (0, 2, 1)))) for _ in range(nsets)]
+    it = [0]
 
     def step():
-        st = run(xd, idd, wd, e0, cfg.rank)
+        it[0] += 1
+        st = run(xd, idd, wds[it[0] % nsets], e0, cfg.rank)
         if st != B.OK:
             raise RuntimeError(B.status_string(st))
 
