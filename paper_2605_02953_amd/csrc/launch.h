@@ -25,15 +25,21 @@ struct MoeTile {
 };
 // Column block for 128-row tiles.  The number of row tiles is only known on the device, so
 // the host works from the expectation under even routing (rows / 128 plus half a tile of
-// padding per expert): the narrowest block whose tile count still fits one chip-wide round
-// with a fifth to spare, so that a few tiles more than expected do not start a second round;
-// if not even the widest fits, the widest (fewest loads per flop).
+// padding per expert).  If some width gives one tile per compute unit at most, with one row
+// tile more than expected still fitting, the narrowest such width: in a single round the time
+// is one tile's, and that is bound by the bytes a compute unit can load, (128 + width) * K
+// (measured with streamed weights at 20 row tiles x 1536 columns: 62, 72, 74 us for 128, 192,
+// 256).  With several rounds the flops decide: the width that pads `inter` least, the wider
+// one on a tie (measured: 176 columns 126, 108, 122 us; 256 columns 130, 142, 130 us).
 inline int choose_moe_block_n(long expected_rows, int num_local_experts, int inter) {
   const long row_tiles = cdiv((int)std::min<long>(expected_rows, 1 << 30), kMoeBlockM) + (num_local_experts + 1) / 2;
   const int widths[3] = {128, 192, 256};
   for (int w : widths)
-    if (row_tiles * cdiv(inter, w) * 5 <= 256 * 4) return w;
-  return 256;
+    if ((row_tiles + 1) * cdiv(inter, w) <= 256) return w;
+  int best = 256;
+  for (int w : widths)
+    if (cdiv(inter, w) * w < cdiv(inter, best) * best || (cdiv(inter, w) * w == cdiv(inter, best) * best && w > best)) best = w;
+  return best;
 }
 inline MoeTile choose_moe_tile(long expected_rows, int num_local_experts, int inter) {
   MoeTile t{};
