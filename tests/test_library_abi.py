@@ -50,6 +50,24 @@ def test_tile_config(B):
     assert B.tile_config(7, 1, 1, 1)[0] == B.ERR_INVALID_ARG
 
 
+def test_moe_tile_choice(B):
+    """Host rule for the grouped GEMM's tile: 256 rows when an expert expects 1024 rows or more; for
+    128-row tiles the narrowest column block that keeps one tile per compute unit (256 of them) with a
+    row tile to spare, else the block that pads the intermediate size least, the wider on a tie."""
+    # cfg 4: 8192 tokens, top-2 of 64 experts, 8 local -> 2048 rows, 16 + 4 row tiles; 21 x 12 blocks of 128 fit
+    assert B.moe_tile_choice(8192, 2, 64, 8, 1536) == (B.OK, 128, 128)
+    # one row tile more (22 x 12 = 264 > 256): 192 columns (22 x 8)
+    assert B.moe_tile_choice(8192 + 128 * 4, 2, 64, 8, 1536) == (B.OK, 128, 192)
+    # many tiles, 176 columns: 192 pads least; 256 columns: 128 and 256 tie, the wider wins
+    assert B.moe_tile_choice(8192, 4, 60, 60, 176) == (B.OK, 128, 192)
+    assert B.moe_tile_choice(8192, 6, 64, 64, 256) == (B.OK, 128, 256)
+    # 2048 rows per expert: the 256-row tile, 256 columns unless the intermediate size is at most 128
+    assert B.moe_tile_choice(8192, 2, 8, 8, 512) == (B.OK, 256, 256)
+    assert B.moe_tile_choice(8192, 2, 8, 8, 128) == (B.OK, 256, 128)
+    assert B.moe_tile_choice(0, 2, 8, 8, 128)[0] == B.ERR_INVALID_ARG
+    assert B.moe_tile_choice(8192, 2, 8, 9, 128)[0] == B.ERR_INVALID_ARG
+
+
 def test_ag_gemm_argument_checks(B):
     null = None
     fake = 0x1000          # never dereferenced: the checks fail first
