@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the fused communication + GEMM hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg4|cfg5|cfg1|gemm_ar|sweep|moe_sweep]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg4|cfg5|cfg1|gemm_ar|sweep|moe_sweep|yardstick]
 
 A step is one pass of the whole path for the workload: for cfg2 (the default, the
 configuration the headline metric is quoted on) one ditron_ag_gemm call with the emulated
@@ -703,6 +703,83 @@ def bench_fp8(args):
     return out
 
 
+def bench_yardstick(args):
+    """The tile engine against the vendor library's plain GEMM (hipBLASLt through torch.matmul) on the cfg 2 and
+    cfg 3 shapes, N(0,1) / N(0,1/K) bf16 made on the device, B rotating through three copies.  The engine runs as
+    ditron_ag_gemm with every shard resident and the flags preset (no communication on either side).  One
+    step = the four launches once; `value` is the engine's geometric-mean TFLOP/s."""
+    import math
+    import torch
+    from paper_2605_02953_amd import binding as B
+    from gpu_util import AgGemmRun
+
+    world, m_r = 8, 1024
+    m = world * m_r
+    problems = []
+    for name, n, k in (("cfg2 shape", 3584, 8192), ("cfg3 shape", 8192, 3584)):
+        a = torch.randn((m, k), device="cuda").to(torch.bfloat16)
+        bs = [(torch.randn((n, k), device="cuda") * k ** -0.5).to(torch.bfloat16) for _ in range(3)]
+        run = AgGemmRun(B, world, m_r, n, k)
+        run.workspace.copy_(a.view(run.workspace.dtype))
+        cnt = [0]
+
+        def ours(run=run, bs=bs, cnt=cnt):
+            cnt[0] += 1
+            run.signals[:world] = run.epoch + 1
+            assert run(None, bs[cnt[0] % 3].view(torch.int16), 0, flags=B.EXTERNAL_PRODUCER) == B.OK
+
+        def vendor(a=a, bs=bs, cnt=cnt):
+            cnt[0] += 1
+            torch.matmul(a, bs[cnt[0] % 3].t())
+
+        problems.append((name, n, k, ours, vendor))
+
+    def step():
+        for pr in problems:
+            pr[3]()
+            pr[4]()
+
+    _ramp(torch, step)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    reps = max(1, args.steps)
+    per = {}
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        for name, n, k, ours, vendor in problems:
+            for who, fn in (("engine", ours), ("vendor", vendor)):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                fn()
+                e1.record()
+                per.setdefault((name, who), []).append((e0, e1))
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    rows, logs, flops_total = [], [], 0.0
+    for name, n, k, _, _ in problems:
+        flops = 2.0 * m * n * k
+        row = {"shape": name, "m": m, "n": n, "k": k}
+        for who in ("engine", "vendor"):
+            us = _quantiles_us(per[(name, who)])["median"]
+            row[who + "_us"] = us
+            row[who + "_tflops"] = flops / us / 1e6
+        flops_total += flops
+        logs.append(math.log(row["engine_tflops"]))
+        rows.append(row)
+    value = math.exp(sum(logs) / len(logs))
+    return {
+        "metric": "TFLOP/s of the tile engine, flags preset (geometric mean over the cfg 2 and cfg 3 shapes), beside the vendor GEMM",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": reps, "warmup": args.warmup,
+        "ms_per_step": wall * 1e3 / reps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "yardstick: [8192, 3584, 8192] and [8192, 8192, 3584] bf16 GEMMs, B stored [n,k], engine vs torch.matmul"},
+        "roofline": {"bound": "mfma", "achieved": value, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": value / PEAK_BF16_TFLOPS, "traffic": None, "kernel": "ag_gemm_kernel, flags preset"},
+        "shapes": rows,
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -730,6 +807,8 @@ def main():
         out = bench_sweep(args)
     elif args.workload == "moe_sweep":
         out = bench_moe_sweep(args)
+    elif args.workload == "yardstick":
+        out = bench_yardstick(args)
     else:
         print(f"bench.py: unknown workload {args.workload}", file=sys.stderr)
         sys.exit(2)
