@@ -31,9 +31,9 @@ __device__ __forceinline__ void wait_vmcnt0() {
 }
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
-  static_assert(N >= 0 && N <= 15, "vmcnt immediate");
+  static_assert(N >= 0 && N <= 63, "vmcnt immediate (six bits: [3:0] and [15:14])");
   __builtin_amdgcn_sched_barrier(0);
-  __builtin_amdgcn_s_waitcnt(0x0F70 | N);
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
   __builtin_amdgcn_sched_barrier(0);
 }
 __device__ __forceinline__ void wait_lgkmcnt0() {
@@ -57,8 +57,10 @@ __device__ __forceinline__ void barrier_no_drain() {
 // ------------------------------------------------------------------ the tile
 // BM x BN output tile (BM 256 or 128, BN 256, 192 or 128) computed by four waves, one per SIMD,
 // each owning BM/2 x BN/2 (256 x 256: 128 x 128 per wave, 256 accumulator registers, every
-// fragment read from LDS feeds four MFMAs).  Operands are staged global -> registers -> LDS
-// (plain loads of full 128-byte lines stream from L2 faster than the direct-to-LDS form).  LDS
+// fragment read from LDS feeds four MFMAs).  Operands are staged global -> registers -> LDS, or,
+// with DIRECT, global -> LDS (`buffer_load ... lds`; measured 3 % faster on 256 x 256 tiles for
+// contraction lengths up to 8192, slower beyond 12288, for contraction lengths that are not whole K
+// tiles, and on 128-row tiles, so the launch code picks per problem).  LDS
 // holds two stages of one 64-deep K tile each, rows of 128 bytes (measured free of bank
 // conflicts for both the fragment reads and the staging stores).
 //
@@ -68,11 +70,13 @@ __device__ __forceinline__ void barrier_no_drain() {
 // reads (ds_read_b64_tr_b16: inside each group of 16 lanes, lane i receives element i % 4 of
 // the 8-byte chunks addressed by lanes i/4, 4 + i/4, 8 + i/4, 12 + i/4; measured).  The pitch
 // makes the four rows a group touches, and the two groups that share a cycle, hit distinct banks.
-template <int BM_, int BN_, bool B_KN_ = false>
+template <int BM_, int BN_, bool B_KN_ = false, bool DIRECT_ = false>
 struct GemmTile4W {
   static_assert((BM_ == 256 || BM_ == 128) && (BN_ == 256 || BN_ == 192 || BN_ == 128), "supported tile sides");
   static_assert(!B_KN_ || BN_ != 192, "a [K, N] row of 192 elements does not split evenly over the loading lanes");
+  static_assert(!DIRECT_ || !B_KN_, "the direct-to-LDS staging is written for [N, K] operands");
   static constexpr bool B_KN = B_KN_;
+  static constexpr bool DIRECT = DIRECT_;   // operands go from global memory straight into LDS (no staging registers)
   static constexpr int BM = BM_, BN = BN_, BK = 64, NSTAGE = 2;
   static constexpr int WAVES_M = 2, WAVES_N = 2, NWAVES = 4, THREADS = 256;
   static constexpr int WTM = BM / 2, WTN = BN / 2, MI = WTM / 32, NI = WTN / 32;
@@ -158,16 +162,21 @@ struct Stager4W {
   static constexpr int kOutOfRange = 0x7ffffff0;
   static constexpr int KN_LANES = T::BN / 8;              // B_KN: lanes that cover one k row of the tile
   static constexpr int KN_ROWS = T::THREADS / KN_LANES;   // B_KN: k rows per pass
+  static constexpr bool kDirect = T::DIRECT;
   __amdgpu_buffer_rsrc_t a_rsrc, b_rsrc;
   int off[T::LOADS];
   u32x4_t reg[T::LOADS];
   int lds_off;    // byte offset inside an operand area of a stage, pass 0
   int kc;
   int kn_row, kn_lds_off, kn_tile_bytes;   // B_KN: the lane's k row in pass 0, its LDS offset, bytes per K tile of B
+  int wave_lds;   // direct-to-LDS form: where the wave's 8 rows of a pass start
 
   template <class ARow, class BRow>
   __device__ __forceinline__ void init(const char* a_base, ARow a_row, const char* b_base, BRow b_row) {
-    const int r = threadIdx.x >> 3, c = threadIdx.x & 7;
+    const int r = threadIdx.x >> 3;
+    // direct-to-LDS form: the lane's LDS position is chunk (lane & 7) of its row, which holds global chunk c
+    const int c = kDirect ? ((threadIdx.x & 7) ^ swz128(r)) : (threadIdx.x & 7);
+    wave_lds = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6) * 1024;
     a_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)a_base, 0, kOutOfRange, 0x00020000);
     b_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)b_base, 0, kOutOfRange, 0x00020000);
     kc = c * 8;
@@ -203,6 +212,27 @@ struct Stager4W {
       const int v = dead ? kOutOfRange : off[I];
       return __builtin_amdgcn_raw_buffer_load_b128(I < T::A_LOADS ? a_rsrc : b_rsrc, v, kt * 128, 0);
     }
+  }
+  // Direct-to-LDS form of load I ([N, K] operands): the wave's 64 lanes fill 8 rows x 128 bytes that are
+  // contiguous in the stage (lane l lands at byte 16 l), so the swizzle is applied on the global side: `off`
+  // was built for the chunk that belongs at the lane's LDS position.  A chunk past K is pushed out of the
+  // buffer's range, for which zeros are written.
+  template <int I>
+  __device__ __forceinline__ void issue_one(int kt, int K, char* stage) const {
+    constexpr int area = I < T::A_LOADS ? 0 : T::A_BYTES;
+    constexpr int pass = I < T::A_LOADS ? I : I - T::A_LOADS;
+    const bool dead = kt * 64 + kc >= K;
+#if defined(__HIP_DEVICE_COMPILE__)   // the host pass does not know this builtin
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(I < T::A_LOADS ? a_rsrc : b_rsrc,
+                                             DITRON_LDS(stage + area + pass * T::ROWS_PER_PASS * T::ROW_BYTES + wave_lds), 16,
+                                             dead ? kOutOfRange : off[I], kt * 128, 0, 0);
+#else
+    (void)dead; (void)stage;
+#endif
+  }
+  template <int LO, int HI>
+  __device__ __forceinline__ void issue_range(int kt, int K, char* stage) const {
+    static_for<LO, HI>([&](auto i) { issue_one<decltype(i)::value>(kt, K, stage); });
   }
   template <int I>
   __device__ __forceinline__ void fetch_one(int kt, int K) { reg[I] = load_one<I>(kt, K); }
@@ -264,6 +294,46 @@ __device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[T::NI][T::MI], con
   const int kt_last = kt_all - 1;
   Stager4W<T> st;
   st.init(a_base, a_row, b_base, b_row);
+  if constexpr (Stager4W<T>::kDirect) {
+    // Operands go from global memory straight into the LDS stages.  K tiles 0 and 1 are requested together;
+    // inside the loop the loads of a K tile are issued over the 2 PAIRS slots that follow the barrier which
+    // frees its stage (the last step of iteration kt: tile kt+2 into the stage of tile kt; the first step of
+    // the next iteration: the rest of that tile), and have to be there at the next barrier.
+    st.template issue_range<0, LOADS>(0, K, lds);
+    st.template issue_range<0, LOADS>(min(1, kt_last), K, lds + T::STAGE_BYTES);
+    wait_vmcnt<LOADS>();
+    barrier_no_drain();
+    Frags4W<T> f0, f1;
+    read_range<T, 0, 0, READS>(f0, lds, a_off, b_off, koff);
+    for (int kt = 0; kt < kt_all; ++kt) {
+      char* cur = lds + (kt & 1) * T::STAGE_BYTES;
+      char* nxt = lds + ((kt + 1) & 1) * T::STAGE_BYTES;
+      const int kf = min(kt + 2, kt_last), kg = min(kt + 1, kt_last);
+      static_for<0, SLOTS>([&](auto sl) {
+        constexpr int S = decltype(sl)::value, PART = S / PAIRS, J = S % PAIRS;
+        if constexpr (S == 3 * PAIRS) {
+          wait_vmcnt0();     // this wave's part of tile kt+1 has landed
+          wait_lgkmcnt0();   // every read of tile kt has returned
+          barrier_no_drain();
+        }
+        mma_pair<T, J>(acc, (PART & 1) ? f1 : f0);
+        if constexpr (PART == 0) read_range<T, 1, J * READS / PAIRS, (J + 1) * READS / PAIRS>(f1, cur, a_off, b_off, koff);
+        if constexpr (PART == 1) read_range<T, 2, J * READS / PAIRS, (J + 1) * READS / PAIRS>(f0, cur, a_off, b_off, koff);
+        if constexpr (PART == 2 && J < T::HALF)
+          read_range<T, 3, J * READS / T::HALF, (J + 1) * READS / T::HALF>(f1, cur, a_off, b_off, koff);
+        if constexpr (PART == 3 && J < T::HALF)
+          read_range<T, 0, J * READS / T::HALF, (J + 1) * READS / T::HALF>(f0, nxt, a_off, b_off, koff);
+        constexpr int W = S >= 3 * PAIRS ? S - 3 * PAIRS : S + PAIRS;   // position in the issue window
+        if constexpr (W < 2 * PAIRS) {
+          constexpr int LO = W * LOADS / (2 * PAIRS), HI = (W + 1) * LOADS / (2 * PAIRS);
+          if constexpr (S >= 3 * PAIRS) st.template issue_range<LO, HI>(kf, K, cur);
+          else st.template issue_range<LO, HI>(kg, K, nxt);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      });
+    }
+    return;
+  }
   // the first two K tiles are requested together (the second into registers that are free until the
   // loop starts), so the tile pays for one cold round trip to memory, not two in a row
   st.template fetch_range<0, LOADS>(0, K);
