@@ -31,8 +31,8 @@ PEAK_HBM_GBS = 8000.0
 # the bytes read, WRITE_SIZE 1.000 of the bytes written).  Reads include those served by the
 # memory-side cache.
 MEASURED_TRAFFIC = {
-    "cfg2": 956.6e6 + 192.9e6,   # ag_gemm_kernel, fused launch (GEMM-only launch: 822.3e6 + 58.7e6); algorithmic 251.7e6 (+ 268.4e6 emulated gather)
-    "cfg3": 822.4e6 + 253.8e6,   # gemm_rs_kernel (reduce_slots_kernel: 134.3e6 + 16.8e6 = its algorithmic 151.0e6)
+    "cfg2": 956.9e6 + 192.9e6,   # ag_gemm_kernel, fused launch (GEMM-only launch: 822.3e6 + 58.7e6); algorithmic 251.7e6 (+ 268.4e6 emulated gather)
+    "cfg3": 822.4e6 + 253.9e6,   # gemm_rs_kernel (reduce_slots_kernel: 134.3e6 + 16.8e6 = its algorithmic 151.0e6)
     "cfg4": 327.6e6 + 6.2e6,     # moe_grouped_gemm_kernel (the emulated gather, in the routing launch: 67.3e6 + 67.1e6)
     "gemm_ar": 1999.3e6 + 268.8e6,   # gemm_ar_kernel, fused launch: operand panels ~0.9e9 + eight partials 1.07e9 read; partial + output written
     "cfg5": 76.8e6 + 3.1e6,      # ag_gemm_decode_kernel (fp8); algorithmic 70.3e6
