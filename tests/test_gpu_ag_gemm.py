@@ -69,6 +69,9 @@ def _check_schedule(B, cfg, rank, sched, kn=False):
     (2, 128, 256, 256),      # one small tile row per shard
     (4, 200, 264, 328),      # ragged rows, columns and contraction tail (328 = 5*64 + 8)
     (8, 505, 3080, 200),     # 256x256 tiles with ragged edges on every side, 208 tiles
+    (8, 505, 3080, 192),     # the same with a contraction of whole K tiles: operands staged straight into LDS
+    (8, 505, 3080, 64),      # ... a single K tile
+    (8, 505, 3080, 128),     # ... two K tiles
     (8, 250, 2056, 136),     # 128x128 tiles of the tile engine (too many for the decode kernel, too few 256x256 ones)
     (3, 64, 8, 8),           # minimum contraction and width
 ])

@@ -77,6 +77,8 @@ def _check_schedule(B, cfg, rank, sched):
     (4, 128, 256, 64, 1, True),
     (4, 100, 264, 72, 2, True),       # segments that straddle tiles, ragged everything
     (8, 505, 3080, 200, 5, True),     # 256x256 tiles, ragged edges
+    (8, 505, 3080, 192, 5, True),     # the same with whole K tiles: operands staged straight into LDS
+    (8, 505, 3080, 64, 5, True),      # ... a single K tile
     (2, 192, 384, 512, 3, False),
     (1, 256, 256, 128, 1, True),      # world 1: plain GEMM
 ])
