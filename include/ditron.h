@@ -111,7 +111,8 @@ ditron_status_t ditron_tile_row_order(int op, int m, int block_m, int world, int
  * [n, k] use the 128 x 32 tile of the decode kernel, which the [k, n] layout does not).
  * out[0]=BLOCK_M out[1]=BLOCK_N out[2]=GROUP_SIZE_M out[3]=chiplets used by the work-group
  * remap (0 = no remap) out[4]=tiles per chiplet per block out[5]=number of tiles
- * (ag_gemm / gemm_rs) out[6]=threads per work-group out[7]=reserved (0). */
+ * (ag_gemm / gemm_rs) out[6]=threads per work-group out[7]=operand staging of the tile engine (0 = through
+ * registers, 1 = global memory straight into LDS; op 1 and 3 report the choice for B stored [n, k]). */
 ditron_status_t ditron_tile_config(int op, int m, int n, int k, int dtype, int out[8]);
 
 /*

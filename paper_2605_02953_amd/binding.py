@@ -120,7 +120,7 @@ def tile_row_order(op, m, block_m, world, nnodes, rank):
 def tile_config(op, m, n, k, dtype=BF16):
     out = (ctypes.c_int * 8)()
     st = lib.ditron_tile_config(op, m, n, k, dtype, out)
-    keys = ("block_m", "block_n", "group_m", "num_xcd", "per_xcd", "ntiles", "threads", "reserved")
+    keys = ("block_m", "block_n", "group_m", "num_xcd", "per_xcd", "ntiles", "threads", "direct_staging")
     return st, dict(zip(keys, list(out)))
 
 
