@@ -266,6 +266,8 @@ struct Stager4W {
 //   every other slot         : global loads of tile kt+2, each after the LDS store that frees
 //                               its register
 // The body is branch-free (past the end the last tile is staged again into a free stage).
+// On entry the LDS stages must be idle (every wave of the work-group past its last access to them): the
+// direct-to-LDS staging starts writing them with its first instruction.
 template <class T, class ARow, class BRow>
 __device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[T::NI][T::MI], const char* a_base, ARow a_row,
                                                  const char* b_base, BRow b_row, int K, char* lds) {
