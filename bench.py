@@ -89,14 +89,12 @@ def bench_ag_gemm(args, cfg_id):
 
     # the same kernel with every shard already in place (flags preset): the GEMM alone
     for _ in range(3):
-        run.signals[:cfg.world] = run.epoch + 1
-        run(None, bd, cfg.rank, flags=B.EXTERNAL_PRODUCER)
+        run(None, bd, cfg.rank, flags=B.FLAGS_PRESET)
     torch.cuda.synchronize()
     pe = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     for i in range(args.steps):
-        run.signals[:cfg.world] = run.epoch + 1
         pe[i][0].record()
-        run(None, bd, cfg.rank, flags=B.EXTERNAL_PRODUCER)
+        run(None, bd, cfg.rank, flags=B.FLAGS_PRESET)
         pe[i][1].record()
     torch.cuda.synchronize()
     preset_ms = sum(a.elapsed_time(b_) for a, b_ in pe) / args.steps
@@ -225,16 +223,13 @@ def bench_gemm_rs(args):
 
     # the same call with the peers' blocks already in the scatter buffer and their flags preset: the GEMM
     # kernel without the emulated-peer work-groups, then the gated reduction
-    W, C = cfg.world, run.chunks
     for _ in range(3):
-        run.signals[2 * W:2 * W + W * C] = run.epoch + 1
-        run(ad, bd, None, d, flags=B.EXTERNAL_PRODUCER)
+        run(ad, bd, None, d, flags=B.FLAGS_PRESET)
     torch.cuda.synchronize()
     pe = _events(torch, args.steps)
     for i in range(args.steps):
-        run.signals[2 * W:2 * W + W * C] = run.epoch + 1
         pe[i][0].record()
-        run(ad, bd, None, d, flags=B.EXTERNAL_PRODUCER)
+        run(ad, bd, None, d, flags=B.FLAGS_PRESET)
         pe[i][1].record()
     torch.cuda.synchronize()
     preset_ms = sum(a.elapsed_time(b) for a, b in pe) / args.steps
@@ -498,8 +493,7 @@ def bench_sweep(args):
             assert run(sh, bd, 0) == B.OK
 
         def preset(run=run, bd=bd):
-            run.signals[:world] = run.epoch + 1
-            return lambda: run(None, bd, 0, flags=B.EXTERNAL_PRODUCER)
+            return lambda: run(None, bd, 0, flags=B.FLAGS_PRESET)
 
         problems.append(("ag_gemm", name, n, k, fused, preset, run))
     for name, n, k in SWEEP_RS:
@@ -511,8 +505,7 @@ def bench_sweep(args):
             assert run(a, bd, peers, 0) == B.OK
 
         def preset(run=run, a=a, bd=bd):
-            run.signals[2 * world:2 * world + world * run.chunks] = run.epoch + 1
-            return lambda: run(a, bd, None, 0, flags=B.EXTERNAL_PRODUCER)
+            return lambda: run(a, bd, None, 0, flags=B.FLAGS_PRESET)
 
         problems.append(("gemm_rs", name, n, k, fused, preset, run))
 
@@ -725,8 +718,7 @@ def bench_yardstick(args):
 
         def ours(run=run, bs=bs, cnt=cnt):
             cnt[0] += 1
-            run.signals[:world] = run.epoch + 1
-            assert run(None, bs[cnt[0] % 3].view(torch.int16), 0, flags=B.EXTERNAL_PRODUCER) == B.OK
+            assert run(None, bs[cnt[0] % 3].view(torch.int16), 0, flags=B.FLAGS_PRESET) == B.OK
 
         def vendor(a=a, bs=bs, cnt=cnt):
             cnt[0] += 1

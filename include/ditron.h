@@ -17,8 +17,8 @@
  * Conventions common to every entry point
  *   - "device" pointers are GPU global memory (or pinned host memory mapped into the GPU),
  *     "host" pointers are ordinary host memory read during the call.  All device buffers are
- *     owned by the caller; the library allocates no device memory and keeps no state
- *     between calls apart from the process-wide spin limit below.
+ *     owned by the caller; the library allocates no device memory and keeps no mutable state
+ *     between calls (per-call options travel in ditron_tuning_t).
  *   - All device pointers must be 16-byte aligned.  Matrices are row-major and dense
  *     (leading dimension = number of columns).  bf16 is the upper half of an IEEE binary32;
  *     fp8 is OCP e4m3 (finite only, max 448).  The contraction length k must be a multiple
@@ -36,6 +36,12 @@
  *     never spin forever: a wait that exceeds the spin limit stores DITRON_ERR_TIMEOUT in
  *     status[0] (and the flag index in status[1]) and the work-group carries on, so the
  *     result is then undefined but the kernel terminates.
+ *   - Who delivers the remote data is chosen by exactly one of three mode bits in `flags`:
+ *     DITRON_EMULATE_PRODUCER (the call copies the peers' data itself and raises the flags, in the
+ *     order the peers would), DITRON_EXTERNAL_PRODUCER (somebody else does, the kernels only wait)
+ *     or DITRON_FLAGS_PRESET (everything is already in place: nothing is copied, no flag is
+ *     looked at; the kernels alone, e.g. to time them).
+ *   - `tuning` is a host pointer to per-call options, or NULL for the defaults.
  *   - Return value: DITRON_OK, or an error without any work having been enqueued.
  *     INVALID_ARG: null / misaligned pointer, non-positive size, rank outside [0, world),
  *     m not divisible by world, world > DITRON_MAX_WORLD, bad enum.  UNSUPPORTED: a
@@ -74,8 +80,24 @@ typedef enum {
 enum {
   DITRON_EMULATE_PRODUCER = 1u,  /* the call itself copies the shards and raises the flags */
   DITRON_EXTERNAL_PRODUCER = 2u, /* somebody else fills the workspace and raises the flags   */
+  DITRON_FLAGS_PRESET = 4u,      /* the remote data is resident: no copies, no flag waits    */
   DITRON_DUMP_SCHEDULE = 8u      /* write the tile schedule to `schedule_out`                */
 };
+
+/* Per-call options (host memory, read during the call).  A zero field means "default", so a
+ * zero-filled struct and a NULL pointer are the same thing. */
+typedef struct {
+  int num_nodes;       /* nodes the `world` ranks are spread over (must divide world); 0 = 1.  With
+                        * more than one node ditron_ag_gemm / ditron_gemm_rs visit the tile rows in
+                        * the order of the paper's multi-node listings (see ditron_tile_row_order);
+                        * a shape for which that order does not visit every tile row exactly once is
+                        * refused with DITRON_ERR_UNSUPPORTED */
+  unsigned spin_limit; /* flag polls per wait before DITRON_ERR_TIMEOUT; 0 = 1 << 20 (of the order
+                        * of a second).  A tiny value lets a test exercise the time-out path without
+                        * hanging a kernel */
+  int decode_variant;  /* decode-shaped ditron_ag_gemm only, see there; 0 = the library's choice */
+  int reserved[5];     /* must be zero */
+} ditron_tuning_t;
 
 #define DITRON_MAX_WORLD 32
 #define DITRON_STATUS_WORDS 4
@@ -90,17 +112,14 @@ size_t ditron_signal_words(int world, int chunks);
  * listing (GEMM-ReduceScatter): with `nnodes` nodes of world/nnodes ranks, the gather order
  * visits the own node's tile rows first and inside a node starts at the own local rank; the
  * scatter order starts with the next node and the next local rank; a tile row shared by two
- * nodes is visited once.  With one node (the default) these are the plain rotations.
- *
- * ditron_set_num_nodes: process-wide setting read by ditron_ag_gemm and ditron_gemm_rs at call
- * time; `world` must then be a multiple of it, and a shape for which the listing's order does
- * not visit every tile row exactly once is refused with DITRON_ERR_UNSUPPORTED.
+ * nodes is visited once: it belongs to whichever of the two nodes is visited later (gather: both
+ * nodes' rows must have arrived) or earlier (scatter: it is computed as early as possible for both).
+ * With one node these are the plain rotations.
  *
  * ditron_tile_row_order: evaluates the order on the host with the very function the kernels
  * use: out[t] (host int[ceil(m / block_m)]) = tile row visited at position t.  op 0 = gather
  * order, 1 = scatter order.  m = rows of the full matrix (a multiple of world).
  */
-ditron_status_t ditron_set_num_nodes(int nnodes);
 ditron_status_t ditron_tile_row_order(int op, int m, int block_m, int world, int nnodes, int rank, int* out);
 
 /* Tile shape and ordering parameters the library will use for a problem, so that a test can
@@ -114,6 +133,32 @@ ditron_status_t ditron_tile_row_order(int op, int m, int block_m, int world, int
  * (ag_gemm / gemm_rs) out[6]=threads per work-group out[7]=operand staging of the tile engine (0 = through
  * registers, 1 = global memory straight into LDS; op 1 and 3 report the choice for B stored [n, k]). */
 ditron_status_t ditron_tile_config(int op, int m, int n, int k, int dtype, int out[8]);
+
+/*
+ * Sizes of the buffers the launchers' contexts own in the paper (`ag_gemm(a, b, ctx)`: the
+ * symmetric workspace that receives the gathered A; the MoE launcher: the gathered tokens).
+ * Bytes of the `workspace` argument of ditron_ag_gemm ([world*m_per_rank, k] in `dtype`) and of
+ * ditron_moe_ag_grouped_gemm ([world*tokens_per_rank, hidden] bf16); 0 for invalid arguments.
+ * The other caller-sized arrays have closed forms given with their arguments (signals:
+ * ditron_signal_words; tile_records: ditron_moe_max_tiles).
+ */
+size_t ditron_ag_gemm_workspace_bytes(int m_per_rank, int k, int world, int dtype);
+size_t ditron_moe_workspace_bytes(int tokens_per_rank, int hidden, int world);
+
+/*
+ * The tile schedule of a call, evaluated on the host with the functions the kernels use (paper: the
+ * index arithmetic at the top of `kernel_consumer_gemm` and `kernel_gemm_rs_producer`: grouped order,
+ * rank rotation, wait set / segment span).  op: 0 = ditron_ag_gemm, 1 = ditron_gemm_rs,
+ * 3 = ditron_gemm_ar (m, n, k as passed to those calls; for op 0 m = world*m_per_rank).
+ * out (host int32[DITRON_SCHEDULE_WORDS * capacity]) receives one record per GEMM work-group, in
+ * work-group order: (pid_m, pid_n, first, last) with first..last the shards waited for (op 0) or the
+ * segments touched (op 1); op 3: the record of position t of the tile order is (pid_m, pid_n, 0, 0).
+ * *count receives the number of records.  DITRON_ERR_WORKSPACE (and *count set) if capacity is too
+ * small.  Identical, word for word, to what DITRON_DUMP_SCHEDULE makes the kernels write (op 3: to its
+ * first two words).
+ */
+ditron_status_t ditron_schedule_dump(int op, int m, int n, int k, int world, int rank, int dtype, int b_layout,
+                                     const ditron_tuning_t* tuning, int32_t* out, int capacity, int* count);
 
 /*
  * AllGather-GEMM:  C[world*m_per_rank, n] = concat_s(A_s) . B       (fp32 accumulate)
@@ -144,7 +189,7 @@ ditron_status_t ditron_ag_gemm(const void* const* a_shards, const void* b, int b
                                const float* a_scales, const float* b_scales, void* workspace,
                                int32_t* signals, int32_t* status, int32_t* schedule_out,
                                const int* arrival_order, int m_per_rank, int n, int k, int world,
-                               int rank, int dtype, int32_t epoch, unsigned flags, void* stream);
+                               int rank, int dtype, int32_t epoch, unsigned flags, const ditron_tuning_t* tuning, void* stream);
 
 /*
  * GEMM-ReduceScatter:  out[m/world, n] = rows_rank( sum_s P_s ),  P_rank = A . B computed here.
@@ -179,7 +224,7 @@ ditron_status_t ditron_gemm_rs(const void* a, const void* b, int b_layout, void*
                                int32_t* signals, int32_t* status, int32_t* schedule_out,
                                const int* arrival_order, int m, int n, int k_local, int world,
                                int rank, int chunks_per_slot, int32_t epoch, unsigned flags,
-                               void* stream);
+                               const ditron_tuning_t* tuning, void* stream);
 
 /*
  * GEMM-ReduceScatter with the scatter fused into the GEMM's stores.  Paper: the FUSE_SCATTER branch of
@@ -203,7 +248,7 @@ ditron_status_t ditron_gemm_rs_fuse_scatter(const void* a, const void* b, int b_
                                             int32_t* schedule_out, const int* arrival_order, int m,
                                             int n, int k_local, int world, int rank,
                                             int chunks_per_slot, int32_t epoch, unsigned flags,
-                                            void* stream);
+                                            const ditron_tuning_t* tuning, void* stream);
 
 /*
  * GEMM + AllReduce, one-shot:  out[m, n] = sum_s P_s,  P_rank = A . B computed here.
@@ -239,7 +284,7 @@ ditron_status_t ditron_gemm_rs_fuse_scatter(const void* a, const void* b, int b_
 ditron_status_t ditron_gemm_ar(const void* a, const void* b, int b_layout, void* gemm_out,
                                const void* const* peer_partials, void* out, int32_t* signals,
                                int32_t* status, int32_t* schedule_out, int m, int n, int k_local,
-                               int world, int rank, int32_t epoch, unsigned flags, void* stream);
+                               int world, int rank, int32_t epoch, unsigned flags, const ditron_tuning_t* tuning, void* stream);
 
 /*
  * GEMM + AllReduce, two-shot: the default branch of the same listings (USE_MULTIMEM_ST).  The tiles
@@ -267,7 +312,7 @@ ditron_status_t ditron_gemm_ar_two_shot(const void* a, const void* b, int b_layo
                                         const void* const* peer_reduced, int32_t* signals,
                                         int32_t* status, int32_t* schedule_out, int m, int n,
                                         int k_local, int world, int rank, int32_t epoch,
-                                        unsigned flags, void* stream);
+                                        unsigned flags, const ditron_tuning_t* tuning, void* stream);
 
 /*
  * The reduction step of GEMM-ReduceScatter on its own: out = bf16( sum_s fp32(slots[s]) ),
@@ -276,7 +321,7 @@ ditron_status_t ditron_gemm_ar_two_shot(const void* a, const void* b, int b_layo
  */
 ditron_status_t ditron_reduce_slots(const void* const* slots, void* out, const int32_t* signals,
                                     int32_t* status, int rows, int n, int world, int chunks,
-                                    int32_t epoch, void* stream);
+                                    int32_t epoch, const ditron_tuning_t* tuning, void* stream);
 
 /*
  * MoE: route -> (all-gathered) token rows grouped by expert -> grouped GEMM.
@@ -310,7 +355,10 @@ ditron_status_t ditron_reduce_slots(const void* const* slots, void* out, const i
  *  workspace     device [world*tokens_per_rank, hidden] bf16 gathered tokens
  *  signals       device int32[ditron_signal_words(world, 1)]
  *  If R exceeds max_rows, status[0] = DITRON_ERR_WORKSPACE, status[2] = R and no GEMM tile
- *  runs.  Limits: num_experts <= 256, num_local_experts <= 64, max_tiles <= 4096.
+ *  runs.  An expert id outside [0, num_experts) is an error, not a dropped assignment:
+ *  status[0] = DITRON_ERR_INVALID_ARG, status[1] = the smallest flat index f holding such an id,
+ *  and no GEMM tile runs (counts then holds the in-range ids only; expert_offsets and gather_idx
+ *  are not written).  Limits: num_experts <= 256, num_local_experts <= 64, max_tiles <= 4096.
  */
 ditron_status_t ditron_moe_ag_grouped_gemm(const void* const* x_shards, const int32_t* topk_ids,
                                            const void* w, int w_layout, void* y, int32_t* counts,
@@ -321,7 +369,7 @@ ditron_status_t ditron_moe_ag_grouped_gemm(const void* const* x_shards, const in
                                            int hidden, int inter, int num_experts, int top_k,
                                            int expert_begin, int num_local_experts, int max_rows,
                                            int world, int rank, int32_t epoch, unsigned flags,
-                                           void* stream);
+                                           const ditron_tuning_t* tuning, void* stream);
 
 /* Tile of the grouped GEMM for a call with these sizes (total_tokens = world * tokens_per_rank):
  * out[0] = BLOCK_M (128, or 256 when the experts are large), out[1] = BLOCK_N.  The tile schedule
@@ -342,10 +390,6 @@ ditron_status_t ditron_publish_chunks(void* const* dst, const void* const* src,
                                       const size_t* bytes, const int* flag_index,
                                       int32_t* signals, int n, int32_t epoch,
                                       unsigned delay_cycles, void* stream);
-
-/* Process-wide bound on flag polls per wait (default 1<<20, of the order of a second).  A tiny value
- * lets a test exercise the time-out path without hanging a kernel. */
-void ditron_set_spin_limit(unsigned polls);
 
 const char* ditron_status_string(int status);
 

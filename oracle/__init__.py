@@ -8,8 +8,12 @@ cpu_baseline leg may import this package; the product path must not.
 
 Parity pins (tests/test_oracle_*.py): brute-force loops on tiny inputs, closed forms,
 library special cases (torch dtype conversion, numpy stable argsort / bincount), the
-paper's worked tiling example, bijection / conservation invariants.
-Unpinned against the paper: the helper semantics of the MoE tile schedule (stage of a
-tile, bisect helper), whose bodies the paper does not print -- pinned by invariants only.
+paper's worked tiling example, bijection / conservation invariants, multi-node visiting orders
+worked by hand from the two swizzle listings (tests/golden/multinode_order_three_nodes.txt) and
+re-derived from the ownership rule of shared tile rows, the MoE tile stage tied to the producer's
+delivery order (ag_gemm.arrival_order) with hand-worked orders for 3 and 4 ranks.
+The bodies of the MoE schedule's helpers (stage of a tile, bisect) are not printed in the paper:
+the stage is read as the delivery position of the last shard a tile needs and the bisect as
+"entries <= x"; both readings are pinned by re-deriving every tile's source ranks from gather_idx.
 """
 from . import formats, ag_gemm, gemm_rs, gemm_ar, moe, schedule, compare  # noqa: F401

@@ -56,6 +56,13 @@ def bisect_right(sorted_vals, x):
     return c
 
 
+def stage_of_shard(s, rank, world):
+    """Delivery position of shard `s` at rank `rank`: the producer of the all-gather delivers the
+    rank's own shard first and then walks the ring upwards (rank, rank+1, ... mod world), so shard
+    s is the ((s - rank) mod world)-th to arrive."""
+    return (s - rank) % world
+
+
 def tile_schedule(count, expert_begin, num_local_experts, block_m, rank, world):
     """Tile list of the grouped GEMM, ordered by (expert, stage, original tile index).
 
@@ -88,7 +95,7 @@ def tile_schedule(count, expert_begin, num_local_experts, block_m, rank, world):
             cum.append(run_c)
         seg_start = bisect_right(cum, q0)
         seg_end = bisect_right(cum, q1 - 1)
-        stage = max((s - rank) % world for s in range(seg_start, seg_end + 1))
+        stage = max(stage_of_shard(s, rank, world) for s in range(seg_start, seg_end + 1))
         rec.append((j, stage, tau, off_by_expert, seg_start, seg_end))
     out = {k: [0] * ntiles for k in ("expert_id", "tiled_m", "segment_start", "segment_end", "stage")}
     for (j, stage, tau, off_by_expert, seg_start, seg_end) in rec:

@@ -19,8 +19,6 @@ struct AgGemmParams {
   char* workspace;
   const char* b;
   __bf16* c;
-  const float* a_scales;
-  const float* b_scales;
   int32_t* flags;      // [world]
   int32_t* arrivals;   // [world] producer arrival counters
   int32_t* status;
@@ -29,7 +27,8 @@ struct AgGemmParams {
   int32_t epoch;
   int num_producers, teams;
   unsigned spin_limit;
-  int group_m, num_xcd, per_xcd, npm, npn;
+  int wait;            // 0: every shard is resident, the flags are not looked at
+  TileOrder tiling;
 };
 
 template <class T>
@@ -45,20 +44,13 @@ __global__ __launch_bounds__(T::THREADS) void ag_gemm_kernel(const AgGemmParams 
     return;
   }
   const int wg = blockIdx.x - p.num_producers;
-  const int pid = xcd_remap(wg, p.npm * p.npn, p.num_xcd, p.per_xcd);
-  int pid_m, pid_n;
-  grouped_order(pid, p.npm, p.npn, p.group_m, pid_m, pid_n);
-  // start on the rows of the rank's own shard, then follow the ring (across nodes: own node first)
-  pid_m = p.nnodes > 1 ? tile_row_across_nodes(pid_m, p.m, p.rank, p.world, p.nnodes, T::BM, kOrderGather)
-                       : (pid_m + cdiv(p.m_per_rank * p.rank, T::BM)) % p.npm;
-  const int m0 = pid_m * T::BM, n0 = pid_n * T::BN;
-  const int rank_beg = m0 / p.m_per_rank;
-  const int rank_end = (min(m0 + T::BM, p.m) - 1) / p.m_per_rank;
+  const TileSpan t = tile_of_workgroup(wg, p.tiling, kOrderGather, p.m, p.m_per_rank, p.rank, p.world, p.nnodes, T::BM);
+  const int m0 = t.pid_m * T::BM, n0 = t.pid_n * T::BN;
   if (p.schedule && threadIdx.x == 0) {
     int32_t* rec = p.schedule + 4 * (size_t)wg;
-    rec[0] = pid_m; rec[1] = pid_n; rec[2] = rank_beg; rec[3] = rank_end;
+    rec[0] = t.pid_m; rec[1] = t.pid_n; rec[2] = t.first; rec[3] = t.last;
   }
-  flag_wait_block(p.flags, rank_beg, rank_end - rank_beg + 1, p.epoch, p.spin_limit, p.status);
+  if (p.wait) flag_wait_block(p.flags, t.first, t.last - t.first + 1, p.epoch, p.spin_limit, p.status);
 
   const uint32_t row_bytes = (uint32_t)p.k * 2u;
   const int M = p.m, N = p.n;
@@ -75,12 +67,11 @@ __global__ __launch_bounds__(T::THREADS) void ag_gemm_kernel(const AgGemmParams 
 
 template <class T>
 static ditron_status_t launch_ag(AgGemmParams& p, hipStream_t stream) {
-  p.npm = cdiv(p.m, T::BM);
-  p.npn = cdiv(p.n, T::BN);
-  auto kern = ag_gemm_kernel<T>;
-  if (!set_dynamic_lds((const void*)kern, T::LDS_BYTES)) return DITRON_ERR_HIP;
-  const unsigned grid = (unsigned)(p.num_producers + p.npm * p.npn);
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(T::THREADS), T::LDS_BYTES, stream, p);
+  p.tiling.npm = cdiv(p.m, T::BM);
+  p.tiling.npn = cdiv(p.n, T::BN);
+  if (!set_dynamic_lds<ag_gemm_kernel<T>>(T::LDS_BYTES)) return DITRON_ERR_HIP;
+  const unsigned grid = (unsigned)(p.num_producers + p.tiling.npm * p.tiling.npn);
+  hipLaunchKernelGGL(ag_gemm_kernel<T>, dim3(grid), dim3(T::THREADS), T::LDS_BYTES, stream, p);
   return hipGetLastError() == hipSuccess ? DITRON_OK : DITRON_ERR_HIP;
 }
 
@@ -92,15 +83,17 @@ extern "C" ditron_status_t ditron_ag_gemm(const void* const* a_shards, const voi
                                           const float* a_scales, const float* b_scales, void* workspace,
                                           int32_t* signals, int32_t* status, int32_t* schedule_out,
                                           const int* arrival_order, int m_per_rank, int n, int k, int world,
-                                          int rank, int dtype, int32_t epoch, unsigned flags, void* stream) {
+                                          int rank, int dtype, int32_t epoch, unsigned flags,
+                                          const ditron_tuning_t* tuning, void* stream) {
   if (world < 1 || world > DITRON_MAX_WORLD || rank < 0 || rank >= world) return DITRON_ERR_INVALID_ARG;
   if (m_per_rank <= 0 || n <= 0 || k <= 0) return DITRON_ERR_INVALID_ARG;
-  if (world % g_num_nodes != 0) return DITRON_ERR_INVALID_ARG;
+  const Tuning tune = resolve_tuning(tuning, world);
+  if (!tune.valid) return DITRON_ERR_INVALID_ARG;
   if (!b || !c || !workspace || !signals || !status) return DITRON_ERR_INVALID_ARG;
   if (!aligned16(b) || !aligned16(c) || !aligned16(workspace) || !aligned16(signals)) return DITRON_ERR_INVALID_ARG;
-  const bool emulate = (flags & DITRON_EMULATE_PRODUCER) != 0;
-  const bool external = (flags & DITRON_EXTERNAL_PRODUCER) != 0;
-  if (emulate == external) return DITRON_ERR_INVALID_ARG;
+  const Mode mode = producer_mode(flags);
+  if (mode == Mode::kInvalid) return DITRON_ERR_INVALID_ARG;
+  const bool emulate = mode == Mode::kEmulate;
   if ((flags & DITRON_DUMP_SCHEDULE) && !schedule_out) return DITRON_ERR_INVALID_ARG;
   if (b_layout != DITRON_B_KN && b_layout != DITRON_B_NK) return DITRON_ERR_INVALID_ARG;
   if (dtype != DITRON_BF16 && dtype != DITRON_FP8_E4M3) return DITRON_ERR_INVALID_ARG;
@@ -112,7 +105,7 @@ extern "C" ditron_status_t ditron_ag_gemm(const void* const* a_shards, const voi
   }
   if (dtype == DITRON_FP8_E4M3 || (b_layout == DITRON_B_NK && bf16_ag_is_decode_shaped(m_per_rank * world, n)))
     return ditron_ag_gemm_decode(a_shards, b, b_layout, c, a_scales, b_scales, workspace, signals, status, schedule_out,
-                                 arrival_order, m_per_rank, n, k, world, rank, dtype, epoch, flags, stream);
+                                 arrival_order, m_per_rank, n, k, world, rank, dtype, epoch, flags, tuning, stream);
   if (k % 8 != 0 || n % 8 != 0) return DITRON_ERR_UNSUPPORTED;
   if (!fits_32bit((size_t)m_per_rank * world, k, 2) || !fits_32bit(n, k, 2)) return DITRON_ERR_UNSUPPORTED;
 
@@ -124,8 +117,6 @@ extern "C" ditron_status_t ditron_ag_gemm(const void* const* a_shards, const voi
   p.workspace = (char*)workspace;
   p.b = (const char*)b;
   p.c = (__bf16*)c;
-  p.a_scales = nullptr;
-  p.b_scales = nullptr;
   p.flags = signals;
   p.arrivals = signals + world;
   p.status = status;
@@ -136,15 +127,16 @@ extern "C" ditron_status_t ditron_ag_gemm(const void* const* a_shards, const voi
   p.k = k;
   p.world = world;
   p.rank = rank;
-  p.nnodes = g_num_nodes;
+  p.nnodes = tune.num_nodes;
   p.epoch = epoch;
-  p.spin_limit = g_spin_limit;
+  p.spin_limit = tune.spin_limit;
+  p.wait = mode != Mode::kPreset;
   TileChoice tc = choose_tile(p.m, n, k);
   if (p.nnodes > 1 && !node_order_is_bijection(p.m, tc.block_m, world, p.nnodes, rank, kOrderGather))
     return DITRON_ERR_UNSUPPORTED;
-  p.group_m = tc.group_m;
-  p.num_xcd = tc.num_xcd;
-  p.per_xcd = tc.per_xcd;
+  p.tiling.group_m = tc.group_m;
+  p.tiling.num_xcd = tc.num_xcd;
+  p.tiling.per_xcd = tc.per_xcd;
   const ProducerPlan pl = plan_producers((size_t)p.m * k * 2, world);
   p.num_producers = emulate ? pl.producers : 0;
   p.teams = pl.teams;

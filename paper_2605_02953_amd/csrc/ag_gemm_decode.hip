@@ -45,6 +45,7 @@ struct AgGemmDecodeParams {
   int32_t epoch;
   int num_producers, teams;
   unsigned spin_limit;
+  int wait;   // 0: every shard is resident, the flags are not looked at
   int group_m, num_xcd, per_xcd, npm, npn;
 };
 
@@ -119,7 +120,7 @@ __global__ __launch_bounds__(DecodeTile::THREADS) void ag_gemm_decode_kernel(con
   };
 
   // wave 0 looks at the flags; the loaders start B at once (it does not depend on the gather)
-  if (wave == 0) flag_wait_wave(p.flags, rank_beg, rank_end - rank_beg + 1, p.epoch, p.spin_limit, p.status);
+  if (wave == 0 && p.wait) flag_wait_wave(p.flags, rank_beg, rank_end - rank_beg + 1, p.epoch, p.spin_limit, p.status);
   if (loader) {
 #pragma unroll 1
     for (int kt = 0; kt < T::NB - 1; ++kt) issue_b(kt);
@@ -226,8 +227,10 @@ extern "C" ditron_status_t ditron_ag_gemm_decode(const void* const* a_shards, co
                                                  const float* a_scales, const float* b_scales, void* workspace,
                                                  int32_t* signals, int32_t* status, int32_t* schedule_out,
                                                  const int* arrival_order, int m_per_rank, int n, int k, int world,
-                                                 int rank, int dtype, int32_t epoch, unsigned flags, void* stream) {
-  // pointer / enum checks were done by ditron_ag_gemm
+                                                 int rank, int dtype, int32_t epoch, unsigned flags,
+                                                 const ditron_tuning_t* tuning, void* stream) {
+  // pointer / enum / mode checks were done by ditron_ag_gemm
+  const Tuning tune = resolve_tuning(tuning, world);
   const bool bf16 = dtype == DITRON_BF16;
   if (b_layout != DITRON_B_NK) return DITRON_ERR_UNSUPPORTED;
   if (k % (bf16 ? 8 : 16) != 0 || n % 8 != 0) return DITRON_ERR_UNSUPPORTED;
@@ -252,9 +255,10 @@ extern "C" ditron_status_t ditron_ag_gemm_decode(const void* const* a_shards, co
   p.k = k;
   p.world = world;
   p.rank = rank;
-  p.nnodes = g_num_nodes;
+  p.nnodes = tune.num_nodes;
   p.epoch = epoch;
-  p.spin_limit = g_spin_limit;
+  p.spin_limit = tune.spin_limit;
+  p.wait = producer_mode(flags) != Mode::kPreset;
   TileChoice tc = choose_tile_decode(p.m, n, k);
   if (p.nnodes > 1 && !node_order_is_bijection(p.m, tc.block_m, world, p.nnodes, rank, kOrderGather))
     return DITRON_ERR_UNSUPPORTED;
@@ -267,7 +271,9 @@ extern "C" ditron_status_t ditron_ag_gemm_decode(const void* const* a_shards, co
   p.npm = cdiv(p.m, DecodeTile::BM);
   p.npn = cdiv(p.n, DecodeTile::BN);
   auto kern = bf16 ? ag_gemm_decode_kernel<true> : ag_gemm_decode_kernel<false>;
-  if (!set_dynamic_lds((const void*)kern, DecodeTile::LDS_BYTES)) return DITRON_ERR_HIP;
+  if (!(bf16 ? set_dynamic_lds<ag_gemm_decode_kernel<true>>(DecodeTile::LDS_BYTES)
+             : set_dynamic_lds<ag_gemm_decode_kernel<false>>(DecodeTile::LDS_BYTES)))
+    return DITRON_ERR_HIP;
   const unsigned grid = (unsigned)(p.num_producers + p.npm * p.npn);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(DecodeTile::THREADS), DecodeTile::LDS_BYTES, (hipStream_t)stream, p);
   return hipGetLastError() == hipSuccess ? DITRON_OK : DITRON_ERR_HIP;

@@ -4,8 +4,6 @@
 #include "launch.h"
 
 namespace ditron {
-unsigned g_spin_limit = 1u << 20;
-int g_num_nodes = 1;
 
 struct PublishParams {
   void* dst[64];
@@ -64,6 +62,52 @@ extern "C" ditron_status_t ditron_tile_config(int op, int m, int n, int k, int d
   return DITRON_OK;
 }
 
+extern "C" size_t ditron_ag_gemm_workspace_bytes(int m_per_rank, int k, int world, int dtype) {
+  if (m_per_rank <= 0 || k <= 0 || world < 1 || world > DITRON_MAX_WORLD) return 0;
+  if (dtype != DITRON_BF16 && dtype != DITRON_FP8_E4M3) return 0;
+  return (size_t)world * m_per_rank * k * (dtype == DITRON_BF16 ? 2 : 1);
+}
+
+extern "C" size_t ditron_moe_workspace_bytes(int tokens_per_rank, int hidden, int world) {
+  if (tokens_per_rank <= 0 || hidden <= 0 || world < 1 || world > DITRON_MAX_WORLD) return 0;
+  return (size_t)world * tokens_per_rank * hidden * 2;
+}
+
+extern "C" ditron_status_t ditron_schedule_dump(int op, int m, int n, int k, int world, int rank, int dtype, int b_layout,
+                                                const ditron_tuning_t* tuning, int32_t* out, int capacity, int* count) {
+  if ((op != 0 && op != 1 && op != 3) || m <= 0 || n <= 0 || k <= 0 || !count || capacity < 0 || (capacity && !out))
+    return DITRON_ERR_INVALID_ARG;
+  if (world < 1 || world > DITRON_MAX_WORLD || rank < 0 || rank >= world) return DITRON_ERR_INVALID_ARG;
+  if (op != 3 && m % world != 0) return DITRON_ERR_INVALID_ARG;
+  if (dtype != DITRON_BF16 && dtype != DITRON_FP8_E4M3) return DITRON_ERR_INVALID_ARG;
+  if (b_layout != DITRON_B_KN && b_layout != DITRON_B_NK) return DITRON_ERR_INVALID_ARG;
+  if (dtype == DITRON_FP8_E4M3 && (op != 0 || b_layout != DITRON_B_NK)) return DITRON_ERR_UNSUPPORTED;
+  const Tuning tune = resolve_tuning(tuning, op == 3 ? 1 : world);
+  if (!tune.valid) return DITRON_ERR_INVALID_ARG;
+  const bool decode = op == 0 && (dtype == DITRON_FP8_E4M3 || (b_layout == DITRON_B_NK && bf16_ag_is_decode_shaped(m, n)));
+  const TileChoice tc = decode ? choose_tile_decode(m, n, k) : choose_tile(m, n, k);
+  const TileOrder o{cdiv(m, tc.block_m), cdiv(n, tc.block_n), tc.group_m, tc.num_xcd, tc.per_xcd};
+  const int ntiles = o.npm * o.npn;
+  *count = ntiles;
+  if (ntiles > capacity) return DITRON_ERR_WORKSPACE;
+  if (op != 3 && tune.num_nodes > 1 &&
+      !node_order_is_bijection(m, tc.block_m, world, tune.num_nodes, rank, op == 0 ? kOrderGather : kOrderScatter))
+    return DITRON_ERR_UNSUPPORTED;
+  for (int wg = 0; wg < ntiles; ++wg) {
+    int32_t* rec = out + (size_t)DITRON_SCHEDULE_WORDS * wg;
+    if (op == 3) {
+      int pid_m, pid_n;
+      grouped_order(xcd_remap(wg, ntiles, o.num_xcd, o.per_xcd), o.npm, o.npn, o.group_m, pid_m, pid_n);
+      rec[0] = pid_m; rec[1] = pid_n; rec[2] = 0; rec[3] = 0;
+    } else {
+      const TileSpan t = tile_of_workgroup(wg, o, op == 0 ? kOrderGather : kOrderScatter, m, m / world, rank, world,
+                                           tune.num_nodes, tc.block_m);
+      rec[0] = t.pid_m; rec[1] = t.pid_n; rec[2] = t.first; rec[3] = t.last;
+    }
+  }
+  return DITRON_OK;
+}
+
 extern "C" ditron_status_t ditron_moe_tile_choice(int total_tokens, int top_k, int num_experts, int num_local_experts,
                                                   int inter, int out[2]) {
   if (!out || total_tokens <= 0 || top_k <= 0 || num_experts <= 0 || num_local_experts <= 0 ||
@@ -72,12 +116,6 @@ extern "C" ditron_status_t ditron_moe_tile_choice(int total_tokens, int top_k, i
   const MoeTile t = choose_moe_tile(moe_expected_rows(total_tokens, top_k, num_experts, num_local_experts), num_local_experts, inter);
   out[0] = t.block_m;
   out[1] = t.block_n;
-  return DITRON_OK;
-}
-
-extern "C" ditron_status_t ditron_set_num_nodes(int nnodes) {
-  if (nnodes < 1 || nnodes > DITRON_MAX_WORLD) return DITRON_ERR_INVALID_ARG;
-  g_num_nodes = nnodes;
   return DITRON_OK;
 }
 
@@ -90,8 +128,6 @@ extern "C" ditron_status_t ditron_tile_row_order(int op, int m, int block_m, int
     out[t] = tile_row_across_nodes(t, m, rank, world, nnodes, block_m, op == 0 ? kOrderGather : kOrderScatter);
   return DITRON_OK;
 }
-
-extern "C" void ditron_set_spin_limit(unsigned polls) { g_spin_limit = polls ? polls : 1u; }
 
 extern "C" const char* ditron_status_string(int status) {
   switch (status) {

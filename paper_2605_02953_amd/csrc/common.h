@@ -144,10 +144,12 @@ __device__ inline void produce_chunks(int nchunks, size_t chunk_bytes, int part,
 // ------------------------------------------------------------------ tile ordering
 // Linear tile id -> (pid_m, pid_n), tile rows in groups of group_m with the row index
 // running fastest inside a group (paper, first lines of the AllGather-GEMM consumer).
-__device__ inline void grouped_order(int pid, int npm, int npn, int group_m, int& pid_m, int& pid_n) {
+__host__ __device__ inline int imin(int a, int b) { return a < b ? a : b; }
+
+__host__ __device__ inline void grouped_order(int pid, int npm, int npn, int group_m, int& pid_m, int& pid_n) {
   const int in_group = group_m * npn;
   const int first_m = (pid / in_group) * group_m;
-  const int size_m = min(npm - first_m, group_m);
+  const int size_m = imin(npm - first_m, group_m);
   const int r = pid % in_group;
   pid_m = first_m + r % size_m;
   pid_n = r / size_m;
@@ -163,7 +165,11 @@ __device__ inline void grouped_order(int pid, int npm, int npn, int group_m, int
 // With one node both reduce to the plain rotations used by the kernels.
 enum { kOrderGather = 0, kOrderScatter = 1 };
 
-// Tile rows [t_lo, t_lo + size) of the node visited at position `pos`.
+// Tile rows [t_lo, t_lo + size) owned by the node visited at position `pos`.  A tile row that holds
+// rows of two neighbouring nodes is owned by the one visited later in gather order (the data of
+// both must have arrived) and by the one visited earlier in scatter order (it is computed as early
+// as possible for both).  The node below in id is visited right before this one, except at the
+// first position; the node above right after it, except at the last.
 __host__ __device__ inline void node_tile_rows(int pos, int m, int nnodes, int block_m, int node_start, int mode,
                                                int& t_lo, int& size) {
   const int m_node = m / nnodes;
@@ -171,16 +177,12 @@ __host__ __device__ inline void node_tile_rows(int pos, int m, int nnodes, int b
   const int lo = m_node * node, hi = m_node * (node + 1);
   t_lo = lo / block_m;
   int t_hi = (hi - 1) / block_m;
-  const bool shares_first = lo != 0 && (lo - 1) / block_m == t_lo;   // first tile row also holds rows of the node before
-  const int next_start = hi / block_m;
-  if (mode == kOrderGather) {
-    if (pos == 0 && shares_first) ++t_lo;
-    if (pos == 0 && hi != m && next_start == t_hi) --t_hi;
-    if (pos != nnodes - 1 && hi != m && next_start == t_hi) --t_hi;
-  } else {
-    if (pos != 0 && shares_first) ++t_lo;
-    if (pos == nnodes - 1 && hi != m && next_start == t_hi) --t_hi;
-  }
+  const bool shares_first = lo != 0 && (lo - 1) / block_m == t_lo;
+  const bool shares_last = hi != m && hi / block_m == t_hi;
+  const bool after_lower = pos != 0, after_upper = pos == nnodes - 1;
+  const bool later_owns = mode == kOrderGather;
+  if (shares_first && after_lower != later_owns) ++t_lo;
+  if (shares_last && after_upper != later_owns) --t_hi;
   size = t_hi - t_lo + 1;
 }
 
@@ -219,17 +221,47 @@ __host__ __device__ inline int tile_row_across_nodes(int position, int m, int ra
 // chiplets; inside every block of num_xcd*per_xcd tiles, chiplet x receives a run of
 // consecutive tile ids, so tiles that share operand panels share an L2, while blocks stay in
 // schedule order.
-__device__ inline int xcd_remap(int wg, int ntiles, int num_xcd, int per_xcd) {
+__host__ __device__ inline int xcd_remap(int wg, int ntiles, int num_xcd, int per_xcd) {
   if (num_xcd <= 1) return wg;
   const int block = num_xcd * per_xcd;
   const int base = (wg / block) * block;
-  const int size = min(block, ntiles - base);
+  const int size = imin(block, ntiles - base);
   const int local = wg - base;
   const int x = local % num_xcd, j = local / num_xcd;
   const int q = size / num_xcd, rem = size % num_xcd;
   // chiplets 0..rem-1 own q+1 work-groups of this block, the rest own q
-  const int start = x * q + min(x, rem);
+  const int start = x * q + imin(x, rem);
   return base + start + j;
+}
+
+// ------------------------------------------------------------------ work-group -> tile
+// The whole index arithmetic of a GEMM work-group, shared by the kernels and by the host evaluation
+// of the schedule: chiplet remap, grouped order, then the rank rotation (across nodes: the multi-node
+// order) and the span of shards (gather) or segments (scatter) the tile's rows touch.
+struct TileOrder {
+  int npm, npn, group_m, num_xcd, per_xcd;
+};
+struct TileSpan {
+  int pid_m, pid_n, first, last;
+};
+__host__ __device__ inline TileSpan tile_of_workgroup(int wg, const TileOrder& o, int mode, int m, int m_per_rank,
+                                                      int rank, int world, int nnodes, int block_m) {
+  const int pid = xcd_remap(wg, o.npm * o.npn, o.num_xcd, o.per_xcd);
+  TileSpan t;
+  grouped_order(pid, o.npm, o.npn, o.group_m, t.pid_m, t.pid_n);
+  if (nnodes > 1) {
+    t.pid_m = tile_row_across_nodes(t.pid_m, m, rank, world, nnodes, block_m, mode);
+  } else if (mode == kOrderGather) {
+    // start on the rows of the rank's own shard, then follow the ring
+    t.pid_m = (t.pid_m + cdiv(m_per_rank * rank, block_m)) % o.npm;
+  } else {
+    // the next rank's segment first, the own segment last
+    t.pid_m = (t.pid_m + ((rank + 1) * m_per_rank) / block_m) % o.npm;
+  }
+  const int m0 = t.pid_m * block_m;
+  t.first = m0 / m_per_rank;
+  t.last = (imin(m0 + block_m, m) - 1) / m_per_rank;
+  return t;
 }
 
 }  // namespace ditron

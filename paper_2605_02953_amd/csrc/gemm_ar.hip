@@ -55,6 +55,7 @@ struct GemmArParams {
   int num_producers;
   int head_tiles;        // tiles ahead of the early consumers
   int early, late;       // consumers behind the first round of tiles / behind the last tile
+  int peers_resident;    // flags preset: the peers' partials are complete, only the own tile flags are waited for
   int group_m, num_xcd, per_xcd, npm, npn;
 };
 
@@ -251,7 +252,7 @@ __global__ __launch_bounds__(T::THREADS) void gemm_ar_kernel(const GemmArParams 
     if (q >= ntiles) break;
     int pid_m, pid_n;
     ar_tile_at(p, q, ntiles, pid_m, pid_n);
-    if ((int)threadIdx.x < p.world)
+    if ((int)threadIdx.x < p.world && (!p.peers_resident || (int)threadIdx.x == p.rank))
       flag_wait_lane(p.tile_flags + (size_t)threadIdx.x * ntiles, pid_m * p.npn + pid_n, 1, p.epoch, p.spin_limit, p.status);
     __syncthreads();
     ar_reduce_tile<T, WORLD, (T::BM * T::BN / 8 / T::THREADS >= 32 ? 4 : 2), TWO>(p, pid_m * T::BM, pid_n * T::BN);
@@ -270,6 +271,11 @@ __global__ __launch_bounds__(T::THREADS) void gemm_ar_kernel(const GemmArParams 
     }
   }
 }
+
+template <auto Kernel>
+struct KernelConstant {
+  static constexpr auto value = Kernel;
+};
 
 template <class T>
 static ditron_status_t launch_ar(GemmArParams& p, int units, bool two_shot, hipStream_t stream) {
@@ -291,13 +297,15 @@ static ditron_status_t launch_ar(GemmArParams& p, int units, bool two_shot, hipS
   }
   p.late = std::min(units, ntiles);
   const unsigned grid = (unsigned)(p.num_producers + ntiles + p.early + p.late);
-  auto launch = [&](auto kern) {
-    if (!set_dynamic_lds((const void*)kern, T::LDS_BYTES)) return DITRON_ERR_HIP;
+  auto launch = [&](auto instance) {
+    constexpr auto kern = decltype(instance)::value;
+    if (!set_dynamic_lds<kern>(T::LDS_BYTES)) return DITRON_ERR_HIP;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(T::THREADS), T::LDS_BYTES, stream, p);
     return hipGetLastError() == hipSuccess ? DITRON_OK : DITRON_ERR_HIP;
   };
-  if (two_shot) return p.world == 8 ? launch(gemm_ar_kernel<T, 8, true>) : launch(gemm_ar_kernel<T, 0, true>);
-  return p.world == 8 ? launch(gemm_ar_kernel<T, 8, false>) : launch(gemm_ar_kernel<T, 0, false>);
+  if (two_shot)
+    return p.world == 8 ? launch(KernelConstant<gemm_ar_kernel<T, 8, true>>{}) : launch(KernelConstant<gemm_ar_kernel<T, 0, true>>{});
+  return p.world == 8 ? launch(KernelConstant<gemm_ar_kernel<T, 8, false>>{}) : launch(KernelConstant<gemm_ar_kernel<T, 0, false>>{});
 }
 
 }  // namespace ditron
@@ -308,7 +316,7 @@ static ditron_status_t gemm_ar_impl(const void* a, const void* b, int b_layout, 
                                     const void* const* peer_partials, void* out, void* const* out_dsts,
                                     const void* const* peer_reduced, int32_t* signals, int32_t* status,
                                     int32_t* schedule_out, int m, int n, int k_local, int world, int rank,
-                                    int32_t epoch, unsigned flags, void* stream) {
+                                    int32_t epoch, unsigned flags, const ditron_tuning_t* tuning, void* stream) {
   const bool two_shot = out_dsts != nullptr;
 
   if (world < 1 || world > DITRON_MAX_WORLD || rank < 0 || rank >= world) return DITRON_ERR_INVALID_ARG;
@@ -317,9 +325,11 @@ static ditron_status_t gemm_ar_impl(const void* a, const void* b, int b_layout, 
   if (world > 1 && !peer_partials) return DITRON_ERR_INVALID_ARG;
   if (!aligned16(a) || !aligned16(b) || !aligned16(gemm_out) || !aligned16(out) || !aligned16(signals))
     return DITRON_ERR_INVALID_ARG;
-  const bool emulate = (flags & DITRON_EMULATE_PRODUCER) != 0;
-  const bool external = (flags & DITRON_EXTERNAL_PRODUCER) != 0;
-  if (emulate == external) return DITRON_ERR_INVALID_ARG;
+  const Mode mode = producer_mode(flags);
+  const Tuning tune = resolve_tuning(tuning, 1);
+  if (mode == Mode::kInvalid || !tune.valid) return DITRON_ERR_INVALID_ARG;
+  if (mode == Mode::kPreset && two_shot) return DITRON_ERR_UNSUPPORTED;   // the peers' broadcasts are part of the call
+  const bool emulate = mode == Mode::kEmulate;
   if ((flags & DITRON_DUMP_SCHEDULE) && !schedule_out) return DITRON_ERR_INVALID_ARG;
   if (b_layout != DITRON_B_KN && b_layout != DITRON_B_NK) return DITRON_ERR_INVALID_ARG;
   if (k_local % 8 != 0 || n % 8 != 0) return DITRON_ERR_UNSUPPORTED;
@@ -370,7 +380,8 @@ static ditron_status_t gemm_ar_impl(const void* a, const void* b, int b_layout, 
   p.world = world;
   p.rank = rank;
   p.epoch = epoch;
-  p.spin_limit = g_spin_limit;
+  p.spin_limit = tune.spin_limit;
+  p.peers_resident = mode == Mode::kPreset;
   // one-shot: the emulated peers only raise flags; two-shot: they also copy the peers' broadcasts
   p.num_producers = (emulate && world > 1) ? (two_shot ? 64 : 8) : 0;
   p.group_m = tc.group_m;
@@ -385,9 +396,10 @@ static ditron_status_t gemm_ar_impl(const void* a, const void* b, int b_layout, 
 extern "C" ditron_status_t ditron_gemm_ar(const void* a, const void* b, int b_layout, void* gemm_out,
                                           const void* const* peer_partials, void* out, int32_t* signals,
                                           int32_t* status, int32_t* schedule_out, int m, int n, int k_local,
-                                          int world, int rank, int32_t epoch, unsigned flags, void* stream) {
+                                          int world, int rank, int32_t epoch, unsigned flags,
+                                          const ditron_tuning_t* tuning, void* stream) {
   return gemm_ar_impl(a, b, b_layout, gemm_out, peer_partials, out, nullptr, nullptr, signals, status, schedule_out, m, n,
-                      k_local, world, rank, epoch, flags, stream);
+                      k_local, world, rank, epoch, flags, tuning, stream);
 }
 
 extern "C" ditron_status_t ditron_gemm_ar_two_shot(const void* a, const void* b, int b_layout, void* gemm_out,
@@ -395,8 +407,8 @@ extern "C" ditron_status_t ditron_gemm_ar_two_shot(const void* a, const void* b,
                                                    const void* const* peer_reduced, int32_t* signals,
                                                    int32_t* status, int32_t* schedule_out, int m, int n,
                                                    int k_local, int world, int rank, int32_t epoch, unsigned flags,
-                                                   void* stream) {
+                                                   const ditron_tuning_t* tuning, void* stream) {
   if (!out_dsts || world < 1 || world > DITRON_MAX_WORLD || rank < 0 || rank >= world) return DITRON_ERR_INVALID_ARG;
   return gemm_ar_impl(a, b, b_layout, gemm_out, peer_partials, out_dsts[rank], out_dsts, peer_reduced, signals, status,
-                      schedule_out, m, n, k_local, world, rank, epoch, flags, stream);
+                      schedule_out, m, n, k_local, world, rank, epoch, flags, tuning, stream);
 }

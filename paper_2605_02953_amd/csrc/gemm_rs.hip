@@ -32,13 +32,13 @@ struct GemmRsParams {
   int m, n, k, world, rank, nnodes, m_per_rank, chunks, n_peers;
   int32_t epoch;
   int num_producers, teams;
-  int group_m, num_xcd, per_xcd, npm, npn;
+  TileOrder tiling;
 };
 
 template <class T>
 __global__ __launch_bounds__(T::THREADS) void gemm_rs_kernel(const GemmRsParams p) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
-  const int ntiles = p.npm * p.npn;
+  const int ntiles = p.tiling.npm * p.tiling.npn;
   if ((int)blockIdx.x >= ntiles) {
     // The emulated peers sit behind the GEMM tiles in the grid: nothing in this launch waits for
     // them (only the reduction does), so they fill compute units as the last tiles drain instead
@@ -56,18 +56,12 @@ __global__ __launch_bounds__(T::THREADS) void gemm_rs_kernel(const GemmRsParams 
     return;
   }
   const int wg = blockIdx.x;
-  const int pid = xcd_remap(wg, ntiles, p.num_xcd, p.per_xcd);
-  int pid_m, pid_n;
-  grouped_order(pid, p.npm, p.npn, p.group_m, pid_m, pid_n);
-  // scatter mode: the next rank's segment first, the own segment last
-  pid_m = p.nnodes > 1 ? tile_row_across_nodes(pid_m, p.m, p.rank, p.world, p.nnodes, T::BM, kOrderScatter)
-                       : (pid_m + ((p.rank + 1) * p.m_per_rank) / T::BM) % p.npm;
-  const int m0 = pid_m * T::BM, n0 = pid_n * T::BN;
-  const int seg_start = m0 / p.m_per_rank;
-  const int seg_end = (min(m0 + T::BM, p.m) - 1) / p.m_per_rank;
+  const TileSpan t = tile_of_workgroup(wg, p.tiling, kOrderScatter, p.m, p.m_per_rank, p.rank, p.world, p.nnodes, T::BM);
+  const int m0 = t.pid_m * T::BM, n0 = t.pid_n * T::BN;
+  const int seg_start = t.first, seg_end = t.last;
   if (p.schedule && threadIdx.x == 0) {
     int32_t* rec = p.schedule + 4 * (size_t)wg;
-    rec[0] = pid_m; rec[1] = pid_n; rec[2] = seg_start; rec[3] = seg_end;
+    rec[0] = t.pid_m; rec[1] = t.pid_n; rec[2] = seg_start; rec[3] = seg_end;
   }
   const uint32_t row_bytes = (uint32_t)p.k * 2u;
   const int M = p.m, N = p.n;
@@ -100,7 +94,7 @@ __global__ __launch_bounds__(T::THREADS) void gemm_rs_kernel(const GemmRsParams 
   if (seg <= seg_end) {
     const int first = (p.m_per_rank * seg) / T::BM;
     const int last = (p.m_per_rank * (seg + 1) - 1) / T::BM;
-    const int target = p.npn * (last - first + 1);
+    const int target = p.tiling.npn * (last - first + 1);
     // release-only arrivals; the tile that completes the segment adds the acquire (see publish_after_all)
     const int old = __hip_atomic_fetch_add(p.seg_counters + seg, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
     if (old == target - 1) {
@@ -125,18 +119,9 @@ struct ReduceParams {
   int wgs_per_chunk;
 };
 
-// Tunable build constants of the reduction kernel.
-#ifndef DITRON_REDUCE_THREADS
-#define DITRON_REDUCE_THREADS 1024
-#endif
-#ifndef DITRON_REDUCE_UNROLL
-#define DITRON_REDUCE_UNROLL 1
-#endif
-#ifndef DITRON_REDUCE_MAX_WGS
-#define DITRON_REDUCE_MAX_WGS 1024
-#endif
-constexpr int kReduceThreads = DITRON_REDUCE_THREADS;
-constexpr int kReduceUnroll = DITRON_REDUCE_UNROLL;   // 16-byte vectors per lane per slot in flight
+constexpr int kReduceThreads = 1024;
+constexpr int kReduceUnroll = 1;     // 16-byte vectors per lane per slot in flight
+constexpr int kReduceMaxWgs = 1024;
 
 __device__ __forceinline__ void set_bf16x8(float (&acc)[8], const u32x4_t v) {
 #pragma unroll
@@ -217,7 +202,7 @@ static ditron_status_t launch_reduce(ReduceParams& p, bool flags_pending, hipStr
   size_t want = (p.vec_per_chunk + per_wg - 1) / per_wg;
   bool gated = false;
   for (int s = 0; s < p.world; ++s) gated = gated || p.gate[s] != nullptr;
-  const int max_wgs = (gated && flags_pending) ? 256 : DITRON_REDUCE_MAX_WGS;
+  const int max_wgs = (gated && flags_pending) ? 256 : kReduceMaxWgs;
   const size_t cap = (size_t)(max_wgs / p.chunks > 0 ? max_wgs / p.chunks : 1);
   if (want > cap) want = cap;
   if (want < 1) want = 1;
@@ -232,12 +217,11 @@ static ditron_status_t launch_reduce(ReduceParams& p, bool flags_pending, hipStr
 
 template <class T>
 static ditron_status_t launch_rs(GemmRsParams& p, hipStream_t stream) {
-  p.npm = cdiv(p.m, T::BM);
-  p.npn = cdiv(p.n, T::BN);
-  auto kern = gemm_rs_kernel<T>;
-  if (!set_dynamic_lds((const void*)kern, T::LDS_BYTES)) return DITRON_ERR_HIP;
-  const unsigned grid = (unsigned)(p.num_producers + p.npm * p.npn);
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(T::THREADS), T::LDS_BYTES, stream, p);
+  p.tiling.npm = cdiv(p.m, T::BM);
+  p.tiling.npn = cdiv(p.n, T::BN);
+  if (!set_dynamic_lds<gemm_rs_kernel<T>>(T::LDS_BYTES)) return DITRON_ERR_HIP;
+  const unsigned grid = (unsigned)(p.num_producers + p.tiling.npm * p.tiling.npn);
+  hipLaunchKernelGGL(gemm_rs_kernel<T>, dim3(grid), dim3(T::THREADS), T::LDS_BYTES, stream, p);
   return hipGetLastError() == hipSuccess ? DITRON_OK : DITRON_ERR_HIP;
 }
 
@@ -247,8 +231,10 @@ using namespace ditron;
 
 extern "C" ditron_status_t ditron_reduce_slots(const void* const* slots, void* out, const int32_t* signals,
                                                int32_t* status, int rows, int n, int world, int chunks,
-                                               int32_t epoch, void* stream) {
+                                               int32_t epoch, const ditron_tuning_t* tuning, void* stream) {
   if (world < 1 || world > DITRON_MAX_WORLD || rows <= 0 || n <= 0 || chunks < 1) return DITRON_ERR_INVALID_ARG;
+  const Tuning tune = resolve_tuning(tuning, 1);
+  if (!tune.valid) return DITRON_ERR_INVALID_ARG;
   if (!slots || !out || !aligned16(out) || (signals && !status)) return DITRON_ERR_INVALID_ARG;
   if (n % 8 != 0) return DITRON_ERR_UNSUPPORTED;
   if (rows % chunks != 0) return DITRON_ERR_INVALID_ARG;
@@ -265,7 +251,7 @@ extern "C" ditron_status_t ditron_reduce_slots(const void* const* slots, void* o
   p.chunks = chunks;
   p.world = world;
   p.epoch = epoch;
-  p.spin_limit = g_spin_limit;
+  p.spin_limit = tune.spin_limit;
   return launch_reduce(p, /*flags_pending=*/signals != nullptr, (hipStream_t)stream);
 }
 
@@ -273,12 +259,14 @@ static ditron_status_t gemm_rs_impl(const void* a, const void* b, int b_layout, 
                                     void* const* scatter_dsts, const void* const* peer_partials, void* scatter_buf,
                                     void* out, int32_t* signals, int32_t* status, int32_t* schedule_out,
                                     const int* arrival_order, int m, int n, int k_local, int world, int rank,
-                                    int chunks_per_slot, int32_t epoch, unsigned flags, void* stream) {
+                                    int chunks_per_slot, int32_t epoch, unsigned flags,
+                                    const ditron_tuning_t* tuning, void* stream) {
   const bool fuse = scatter_dsts != nullptr;
 
   if (world < 1 || world > DITRON_MAX_WORLD || rank < 0 || rank >= world) return DITRON_ERR_INVALID_ARG;
   if (m <= 0 || n <= 0 || k_local <= 0 || m % world != 0 || chunks_per_slot < 1) return DITRON_ERR_INVALID_ARG;
-  if (world % g_num_nodes != 0) return DITRON_ERR_INVALID_ARG;
+  const Tuning tune = resolve_tuning(tuning, world);
+  if (!tune.valid) return DITRON_ERR_INVALID_ARG;
   const int m_r = m / world;
   if (m_r % chunks_per_slot != 0) return DITRON_ERR_INVALID_ARG;
   if (!a || !b || (!fuse && !gemm_out) || !out || !signals || !status) return DITRON_ERR_INVALID_ARG;
@@ -286,9 +274,9 @@ static ditron_status_t gemm_rs_impl(const void* a, const void* b, int b_layout, 
   if (!aligned16(a) || !aligned16(b) || !aligned16(gemm_out) || !aligned16(out) || !aligned16(scatter_buf) ||
       !aligned16(signals))
     return DITRON_ERR_INVALID_ARG;
-  const bool emulate = (flags & DITRON_EMULATE_PRODUCER) != 0;
-  const bool external = (flags & DITRON_EXTERNAL_PRODUCER) != 0;
-  if (emulate == external) return DITRON_ERR_INVALID_ARG;
+  const Mode mode = producer_mode(flags);
+  if (mode == Mode::kInvalid) return DITRON_ERR_INVALID_ARG;
+  const bool emulate = mode == Mode::kEmulate;
   if ((flags & DITRON_DUMP_SCHEDULE) && !schedule_out) return DITRON_ERR_INVALID_ARG;
   if (b_layout != DITRON_B_KN && b_layout != DITRON_B_NK) return DITRON_ERR_INVALID_ARG;
   if (k_local % 8 != 0 || n % 8 != 0) return DITRON_ERR_UNSUPPORTED;
@@ -330,16 +318,16 @@ static ditron_status_t gemm_rs_impl(const void* a, const void* b, int b_layout, 
   p.k = k_local;
   p.world = world;
   p.rank = rank;
-  p.nnodes = g_num_nodes;
+  p.nnodes = tune.num_nodes;
   p.m_per_rank = m_r;
   p.chunks = chunks_per_slot;
   p.epoch = epoch;
   TileChoice tc = choose_tile(m, n, k_local);
   if (p.nnodes > 1 && !node_order_is_bijection(m, tc.block_m, world, p.nnodes, rank, kOrderScatter))
     return DITRON_ERR_UNSUPPORTED;
-  p.group_m = tc.group_m;
-  p.num_xcd = tc.num_xcd;
-  p.per_xcd = tc.per_xcd;
+  p.tiling.group_m = tc.group_m;
+  p.tiling.num_xcd = tc.num_xcd;
+  p.tiling.per_xcd = tc.per_xcd;
   const ProducerPlan pl = plan_producers((size_t)(world - 1) * m_r * n * 2, (world - 1) * chunks_per_slot);
   p.num_producers = (emulate && world > 1) ? pl.producers : 0;
   p.teams = pl.teams;
@@ -362,7 +350,8 @@ static ditron_status_t gemm_rs_impl(const void* a, const void* b, int b_layout, 
       r.gate_stride[s] = 0;
     } else {
       r.slot[s] = (const char*)scatter_buf + (size_t)s * slot_bytes;
-      r.gate[s] = p.arr_flags + (size_t)s * chunks_per_slot;
+      // flags preset: the peers' blocks are resident, only the GEMM's own segment gates the sum
+      r.gate[s] = mode == Mode::kPreset ? nullptr : p.arr_flags + (size_t)s * chunks_per_slot;
       r.gate_stride[s] = 1;
     }
   }
@@ -372,18 +361,19 @@ static ditron_status_t gemm_rs_impl(const void* a, const void* b, int b_layout, 
   r.chunks = chunks_per_slot;
   r.world = world;
   r.epoch = epoch;
-  r.spin_limit = g_spin_limit;
-  // with emulated peers every flag was raised by the launch before this one
-  return launch_reduce(r, /*flags_pending=*/!emulate, (hipStream_t)stream);
+  r.spin_limit = tune.spin_limit;
+  // with emulated peers (or everything resident) every flag was raised by the launch before this one
+  return launch_reduce(r, /*flags_pending=*/mode == Mode::kExternal, (hipStream_t)stream);
 }
 
 extern "C" ditron_status_t ditron_gemm_rs(const void* a, const void* b, int b_layout, void* gemm_out,
                                           const void* const* peer_partials, void* scatter_buf, void* out,
                                           int32_t* signals, int32_t* status, int32_t* schedule_out,
                                           const int* arrival_order, int m, int n, int k_local, int world, int rank,
-                                          int chunks_per_slot, int32_t epoch, unsigned flags, void* stream) {
+                                          int chunks_per_slot, int32_t epoch, unsigned flags,
+                                          const ditron_tuning_t* tuning, void* stream) {
   return gemm_rs_impl(a, b, b_layout, gemm_out, nullptr, peer_partials, scatter_buf, out, signals, status, schedule_out,
-                      arrival_order, m, n, k_local, world, rank, chunks_per_slot, epoch, flags, stream);
+                      arrival_order, m, n, k_local, world, rank, chunks_per_slot, epoch, flags, tuning, stream);
 }
 
 extern "C" ditron_status_t ditron_gemm_rs_fuse_scatter(const void* a, const void* b, int b_layout,
@@ -391,8 +381,10 @@ extern "C" ditron_status_t ditron_gemm_rs_fuse_scatter(const void* a, const void
                                                        void* out, int32_t* signals, int32_t* status,
                                                        int32_t* schedule_out, const int* arrival_order, int m, int n,
                                                        int k_local, int world, int rank, int chunks_per_slot,
-                                                       int32_t epoch, unsigned flags, void* stream) {
+                                                       int32_t epoch, unsigned flags,
+                                                       const ditron_tuning_t* tuning, void* stream) {
   if (!scatter_dsts || world < 1 || world > DITRON_MAX_WORLD || rank < 0 || rank >= world) return DITRON_ERR_INVALID_ARG;
   return gemm_rs_impl(a, b, b_layout, nullptr, scatter_dsts, peer_partials, scatter_dsts[rank], out, signals, status,
-                      schedule_out, arrival_order, m, n, k_local, world, rank, chunks_per_slot, epoch, flags, stream);
+                      schedule_out, arrival_order, m, n, k_local, world, rank, chunks_per_slot, epoch, flags, tuning,
+                      stream);
 }

@@ -3,6 +3,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdlib.h>
+#include <algorithm>
+#include <atomic>
+#include <vector>
 #include "../../include/ditron.h"
 #include "gemm_core.h"
 
@@ -144,13 +147,50 @@ inline bool is_permutation(const int* v, int n) {
   return true;
 }
 
-// Kernels with more than 64 KiB of dynamic LDS need the limit raised once per function.
-inline bool set_dynamic_lds(const void* func, int bytes) {
-  return hipFuncSetAttribute(func, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) == hipSuccess;
+// Kernels with more than 64 KiB of dynamic LDS need the limit raised, once per (kernel, device): the
+// outcome is remembered per kernel (one bit per device), so the driver call is not paid on every launch.
+template <auto Kernel>
+inline bool set_dynamic_lds(int bytes) {
+  static std::atomic<uint64_t> configured{0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return false;
+  const uint64_t bit = 1ull << (dev & 63);
+  if (configured.load(std::memory_order_acquire) & bit) return true;
+  if (hipFuncSetAttribute((const void*)Kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess)
+    return false;
+  configured.fetch_or(bit, std::memory_order_release);
+  return true;
 }
 
-extern unsigned g_spin_limit;
-extern int g_num_nodes;
+// Per-call options with the defaults filled in.
+struct Tuning {
+  int num_nodes;
+  unsigned spin_limit;
+  int decode_variant;
+  bool valid;
+};
+inline Tuning resolve_tuning(const ditron_tuning_t* t, int world) {
+  Tuning r{1, 1u << 20, 0, true};
+  if (!t) return r;
+  if (t->num_nodes < 0 || t->num_nodes > DITRON_MAX_WORLD || t->decode_variant < 0) r.valid = false;
+  for (int v : t->reserved) r.valid = r.valid && v == 0;
+  if (t->num_nodes > 0) r.num_nodes = t->num_nodes;
+  if (t->spin_limit) r.spin_limit = t->spin_limit;
+  r.decode_variant = t->decode_variant;
+  if (world % r.num_nodes != 0) r.valid = false;
+  return r;
+}
+
+// Exactly one of the three producer modes.
+enum class Mode { kInvalid, kEmulate, kExternal, kPreset };
+inline Mode producer_mode(unsigned flags) {
+  switch (flags & (DITRON_EMULATE_PRODUCER | DITRON_EXTERNAL_PRODUCER | DITRON_FLAGS_PRESET)) {
+    case DITRON_EMULATE_PRODUCER: return Mode::kEmulate;
+    case DITRON_EXTERNAL_PRODUCER: return Mode::kExternal;
+    case DITRON_FLAGS_PRESET: return Mode::kPreset;
+    default: return Mode::kInvalid;
+  }
+}
 
 }  // namespace ditron
 
@@ -158,4 +198,5 @@ extern "C" ditron_status_t ditron_ag_gemm_decode(const void* const* a_shards, co
                                                  const float* a_scales, const float* b_scales, void* workspace,
                                                  int32_t* signals, int32_t* status, int32_t* schedule_out,
                                                  const int* arrival_order, int m_per_rank, int n, int k, int world,
-                                                 int rank, int dtype, int32_t epoch, unsigned flags, void* stream);
+                                                 int rank, int dtype, int32_t epoch, unsigned flags,
+                                                 const ditron_tuning_t* tuning, void* stream);

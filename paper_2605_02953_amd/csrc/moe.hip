@@ -50,6 +50,7 @@ __global__ __launch_bounds__(kRouteThreads) void moe_route_kernel(const MoeRoute
   __shared__ int s_tile_acc[kMaxLocalExperts + 1];               // exclusive prefix of tiles per expert
   __shared__ int s_cum[kMaxLocalExperts][DITRON_MAX_WORLD];      // inclusive per-rank cumulative rows per expert
   __shared__ int s_stage[kMaxTilesLds];
+  __shared__ int s_bad;                                          // smallest flat index holding an id outside [0, E)
   if (blockIdx.x > 0) {
     // streaming stores: the grouped GEMM that reads the workspace is a later launch
     produce_chunks<kRouteThreads, true>(
@@ -66,6 +67,7 @@ __global__ __launch_bounds__(kRouteThreads) void moe_route_kernel(const MoeRoute
 
   for (int i = tid; i < p.world * E; i += kRouteThreads) s_counts[i] = 0;
   for (int i = tid; i < kRouteWaves * kMaxLocalExperts; i += kRouteThreads) (&s_wave_base[0][0])[i] = 0;
+  if (tid == 0) s_bad = 0x7fffffff;
   __syncthreads();
 
   // histogram over (source rank, expert), and per-wave totals for the local experts.  A wave
@@ -84,15 +86,28 @@ __global__ __launch_bounds__(kRouteThreads) void moe_route_kernel(const MoeRoute
 #pragma unroll
     for (int b = 0; b < kBatch; ++b) {
       const int f = f0 + b * 64 + lane;
+      if (f >= w_end) continue;
       if (e[b] >= 0 && e[b] < E) {
         atomicAdd(&s_counts[(f / per_shard) * E + e[b]], 1);
         const int j = e[b] - p.expert_begin;
         if (j >= 0 && j < EL) atomicAdd(&s_wave_base[wave][j], 1);
+      } else {
+        atomicMin(&s_bad, f);
       }
     }
   }
   __syncthreads();
   for (int i = tid; i < p.world * E; i += kRouteThreads) p.counts[i] = s_counts[i];
+  if (s_bad != 0x7fffffff) {
+    // an id that names no expert: reported, never dropped silently (the counts would no longer sum to
+    // tokens * top_k); no tile is scheduled
+    if (tid == 0) {
+      p.status[0] = DITRON_ERR_INVALID_ARG;
+      p.status[1] = s_bad;
+      p.tile_records[0] = 0;
+    }
+    return;
+  }
 
   // totals of the local experts -> exclusive scan; per-rank cumulative rows
   if (tid < EL) {
@@ -142,9 +157,12 @@ __global__ __launch_bounds__(kRouteThreads) void moe_route_kernel(const MoeRoute
 
   // stable placement: 64 assignments at a time.  The lanes that hold the same local expert find
   // each other with one ballot per bit of the expert index (a lane keeps the lanes that agree with
-  // it on every bit), rank themselves by counting the lanes below them, and the last of them moves
-  // the wave's running output position of that expert (kept in LDS) past the group.  The cost per
-  // round does not grow with the number of local experts beyond the number of index bits.
+  // it on every bit) and rank themselves by counting the lanes below them.  The first lane of each
+  // group moves the wave's running output position of that expert past the group with one LDS atomic,
+  // whose return value is the group's first position; the others receive it by a lane shuffle.  The
+  // row of running positions is private to the wave and a wave's LDS atomics execute in order, so
+  // consecutive rounds see each other's advances.  The cost per round does not grow with the number
+  // of local experts beyond the number of index bits.
   const int nbits = EL > 1 ? 32 - __builtin_clz(EL - 1) : 0;
   const unsigned long long below = (1ull << lane) - 1ull;
   for (int fb = w_begin; fb < w_end; fb += 64 * kBatch) {
@@ -171,14 +189,11 @@ __global__ __launch_bounds__(kRouteThreads) void moe_route_kernel(const MoeRoute
         const unsigned long long m = __ballot(set);
         same &= set ? m : ~m;
       }
-      if (local) {
-        // LDS operations of one wave complete in order: every lane of the group reads the position
-        // before the group's last lane advances it, and the next round reads the advanced value
-        const int base = s_wave_base[wave][j];
-        const int rank = __popcll(same & below), count = __popcll(same);
-        p.gather_idx[base + rank] = f;
-        if (rank == count - 1) s_wave_base[wave][j] = base + count;
-      }
+      const int rank = __popcll(same & below), count = __popcll(same);
+      int base = 0;
+      if (local && rank == 0) base = atomicAdd(&s_wave_base[wave][j], count);
+      base = __shfl(base, local ? __ffsll((long long)same) - 1 : lane);
+      if (local) p.gather_idx[base + rank] = f;
     }
   }
 
@@ -232,6 +247,7 @@ struct MoeGemmParams {
   int tokens_per_rank, hidden, inter, top_k, world, max_tiles, npn;
   int32_t epoch;
   unsigned spin_limit;
+  int wait;   // 0: the token shards are resident, the flags are not looked at
 };
 
 template <class T>
@@ -245,7 +261,7 @@ __global__ __launch_bounds__(T::THREADS) void moe_grouped_gemm_kernel(const MoeG
   const int j = rec[0], seg_start = rec[2], seg_end = rec[3];
   const int p0 = p.tile_records[1 + 4 * p.max_tiles + pos];
   const int p_end = min(p0 + T::BM, p.expert_offsets[j + 1]);
-  flag_wait_block(p.flags, seg_start, seg_end - seg_start + 1, p.epoch, p.spin_limit, p.status);
+  if (p.wait) flag_wait_block(p.flags, seg_start, seg_end - seg_start + 1, p.epoch, p.spin_limit, p.status);
 
   const int n0 = pid_n * T::BN;
   const uint32_t row_bytes = (uint32_t)p.hidden * 2u;
@@ -277,10 +293,9 @@ extern "C" int ditron_moe_max_tiles(int max_rows, int num_local_experts) {
 template <class T>
 static ditron_status_t launch_moe_gemm(MoeGemmParams& g, int max_tiles, hipStream_t s) {
   g.npn = cdiv(g.inter, T::BN);
-  auto kern = moe_grouped_gemm_kernel<T>;
-  if (!set_dynamic_lds((const void*)kern, T::LDS_BYTES)) return DITRON_ERR_HIP;
+  if (!set_dynamic_lds<moe_grouped_gemm_kernel<T>>(T::LDS_BYTES)) return DITRON_ERR_HIP;
   const unsigned grid = (unsigned)(max_tiles * g.npn);
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(T::THREADS), T::LDS_BYTES, s, g);
+  hipLaunchKernelGGL(moe_grouped_gemm_kernel<T>, dim3(grid), dim3(T::THREADS), T::LDS_BYTES, s, g);
   return hipGetLastError() == hipSuccess ? DITRON_OK : DITRON_ERR_HIP;
 }
 
@@ -289,7 +304,7 @@ extern "C" ditron_status_t ditron_moe_ag_grouped_gemm(
     int32_t* expert_offsets, int32_t* gather_idx, int32_t* tile_records, void* workspace, int32_t* signals,
     int32_t* status, const int* arrival_order, int tokens_per_rank, int hidden, int inter, int num_experts,
     int top_k, int expert_begin, int num_local_experts, int max_rows, int world, int rank, int32_t epoch,
-    unsigned flags, void* stream) {
+    unsigned flags, const ditron_tuning_t* tuning, void* stream) {
   if (world < 1 || world > DITRON_MAX_WORLD || rank < 0 || rank >= world) return DITRON_ERR_INVALID_ARG;
   if (tokens_per_rank <= 0 || hidden <= 0 || inter <= 0 || num_experts <= 0 || top_k <= 0 || max_rows <= 0)
     return DITRON_ERR_INVALID_ARG;
@@ -299,9 +314,10 @@ extern "C" ditron_status_t ditron_moe_ag_grouped_gemm(
       !signals || !status)
     return DITRON_ERR_INVALID_ARG;
   if (!aligned16(w) || !aligned16(y) || !aligned16(workspace) || !aligned16(signals)) return DITRON_ERR_INVALID_ARG;
-  const bool emulate = (flags & DITRON_EMULATE_PRODUCER) != 0;
-  const bool external = (flags & DITRON_EXTERNAL_PRODUCER) != 0;
-  if (emulate == external) return DITRON_ERR_INVALID_ARG;
+  const Mode mode = producer_mode(flags);
+  const Tuning tune = resolve_tuning(tuning, 1);
+  if (mode == Mode::kInvalid || !tune.valid) return DITRON_ERR_INVALID_ARG;
+  const bool emulate = mode == Mode::kEmulate;
   if (w_layout != DITRON_B_KN && w_layout != DITRON_B_NK) return DITRON_ERR_INVALID_ARG;
   if (emulate) {
     if (!x_shards) return DITRON_ERR_INVALID_ARG;
@@ -371,7 +387,8 @@ extern "C" ditron_status_t ditron_moe_ag_grouped_gemm(
   g.world = world;
   g.max_tiles = max_tiles;
   g.epoch = epoch;
-  g.spin_limit = g_spin_limit;
+  g.spin_limit = tune.spin_limit;
+  g.wait = mode != Mode::kPreset;
   if (w_layout == DITRON_B_KN) {   // [hidden, inter] weights: the column block is 128 or 256 (a 192-column row does not split over the loading lanes)
     const bool wide = mt.block_n > 128;
     if (mt.block_m == 256) return wide ? launch_moe_gemm<GemmTile4W<256, 256, true>>(g, max_tiles, s) : launch_moe_gemm<GemmTile4W<256, 128, true>>(g, max_tiles, s);

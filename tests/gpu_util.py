@@ -36,7 +36,7 @@ class AgGemmRun:
         self.epoch = 0
 
     def __call__(self, shards_dev, b_dev, rank, order=None, flags=None, schedule=None, b_layout=None,
-                 dtype=None, a_scales=None, b_scales=None, stream=None):
+                 dtype=None, a_scales=None, b_scales=None, stream=None, tuning=None):
         B = self.B
         self.epoch += 1
         flags = B.EMULATE_PRODUCER if flags is None else flags
@@ -44,7 +44,7 @@ class AgGemmRun:
             flags |= B.DUMP_SCHEDULE
         st = B.ag_gemm(shards_dev, b_dev, B.B_NK if b_layout is None else b_layout, self.c, a_scales, b_scales,
                        self.workspace, self.signals, self.status, schedule, order, self.m_per_rank, self.n,
-                       self.k, self.world, rank, B.BF16 if dtype is None else dtype, self.epoch, flags, stream)
+                       self.k, self.world, rank, B.BF16 if dtype is None else dtype, self.epoch, flags, stream, tuning)
         return st
 
 
@@ -61,7 +61,7 @@ class GemmRsRun:
         self.status = torch.zeros(B.STATUS_WORDS, dtype=torch.int32, device="cuda")
         self.epoch = 0
 
-    def __call__(self, a_dev, b_dev, peers, rank, order=None, flags=None, schedule=None, stream=None, b_layout=None):
+    def __call__(self, a_dev, b_dev, peers, rank, order=None, flags=None, schedule=None, stream=None, b_layout=None, tuning=None):
         B = self.B
         self.epoch += 1
         flags = B.EMULATE_PRODUCER if flags is None else flags
@@ -69,7 +69,7 @@ class GemmRsRun:
             flags |= B.DUMP_SCHEDULE
         return B.gemm_rs(a_dev, b_dev, B.B_NK if b_layout is None else b_layout, self.gemm_out, peers, self.scatter, self.out, self.signals,
                          self.status, schedule, order, self.m, self.n, self.k, self.world, rank, self.chunks,
-                         self.epoch, flags, stream)
+                         self.epoch, flags, stream, tuning)
 
 
 class MoeRun:
@@ -90,7 +90,7 @@ class MoeRun:
         self.status = torch.zeros(B.STATUS_WORDS, **i32)
         self.epoch = 0
 
-    def __call__(self, x_dev, ids_dev, w_dev, expert_begin, rank, order=None, flags=None, stream=None, w_layout=None):
+    def __call__(self, x_dev, ids_dev, w_dev, expert_begin, rank, order=None, flags=None, stream=None, w_layout=None, tuning=None):
         B = self.B
         t_r, hidden, inter, ne, top_k, nl, max_rows, world = self.dims
         self.epoch += 1
@@ -98,7 +98,7 @@ class MoeRun:
         return B.moe_ag_grouped_gemm(x_dev, ids_dev, w_dev, B.B_NK if w_layout is None else w_layout, self.y, self.counts, self.offsets, self.gather,
                                      self.records, self.workspace, self.signals, self.status, order, t_r, hidden,
                                      inter, ne, top_k, expert_begin, nl, max_rows, world, rank, self.epoch, flags,
-                                     stream)
+                                     stream, tuning)
 
 
 class GemmArRun:
@@ -119,7 +119,7 @@ class GemmArRun:
     def flag_index(self, s, pid_m, pid_n):
         return 2 * self.world + s * self.ntiles + pid_m * self.npn + pid_n
 
-    def __call__(self, a_dev, b_dev, peers, rank, flags=None, schedule=None, stream=None, b_layout=None):
+    def __call__(self, a_dev, b_dev, peers, rank, flags=None, schedule=None, stream=None, b_layout=None, tuning=None):
         B = self.B
         self.epoch += 1
         flags = B.EMULATE_PRODUCER if flags is None else flags
@@ -127,4 +127,4 @@ class GemmArRun:
             flags |= B.DUMP_SCHEDULE
         return B.gemm_ar(a_dev, b_dev, B.B_NK if b_layout is None else b_layout, self.gemm_out, peers, self.out,
                          self.signals, self.status, schedule, self.m, self.n, self.k, self.world, rank, self.epoch,
-                         flags, stream)
+                         flags, stream, tuning)

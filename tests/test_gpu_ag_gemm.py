@@ -22,7 +22,7 @@ def B():
 from gpu_util import to_dev, bits, nk, AgGemmRun  # noqa: E402
 
 
-def _run(B, cfg, shards, b_kn, rank=None, order=None, want_schedule=False, kn=False):
+def _run(B, cfg, shards, b_kn, rank=None, order=None, want_schedule=False, kn=False, tuning=None):
     rank = cfg.rank if rank is None else rank
     run = AgGemmRun(B, cfg.world, cfg.m_per_rank, cfg.n, cfg.k)
     sh = [to_dev(s) for s in shards]
@@ -31,7 +31,7 @@ def _run(B, cfg, shards, b_kn, rank=None, order=None, want_schedule=False, kn=Fa
     if want_schedule:
         st, tc = B.tile_config(4 if kn else 0, cfg.m, cfg.n, cfg.k)
         sched = torch.full((4 * tc["ntiles"],), -1, dtype=torch.int32, device="cuda")
-    st = run(sh, bd, rank, order=order, schedule=sched, b_layout=B.B_KN if kn else B.B_NK)
+    st = run(sh, bd, rank, order=order, schedule=sched, b_layout=B.B_KN if kn else B.B_NK, tuning=tuning)
     assert st == B.OK, B.status_string(st)
     torch.cuda.synchronize()
     assert run.status.cpu().tolist()[0] == 0
@@ -151,14 +151,10 @@ def test_external_producer_and_timeout(B):
     assert np.array_equal(bits(run.c), want)
     # (b) nobody raises the flags: with a tiny spin limit every wait gives up, the kernel ends
     # and reports the time-out instead of hanging
-    B.set_spin_limit(64)
-    try:
-        assert run(None, bd, rank=0, flags=B.EXTERNAL_PRODUCER) == B.OK
-        torch.cuda.synchronize()
-        s = run.status.cpu().tolist()
-        assert s[0] == B.ERR_TIMEOUT and 0 <= s[1] < cfg.world
-    finally:
-        B.set_spin_limit(1 << 20)
+    assert run(None, bd, rank=0, flags=B.EXTERNAL_PRODUCER, tuning=B.tuning(spin_limit=64)) == B.OK
+    torch.cuda.synchronize()
+    s = run.status.cpu().tolist()
+    assert s[0] == B.ERR_TIMEOUT and 0 <= s[1] < cfg.world
     # (c) the buffers stay usable afterwards
     run.status.zero_()
     assert run(sh, bd, rank=2) == B.OK
@@ -193,21 +189,20 @@ def test_tile_rows_follow_the_multi_node_order(B, world, nnodes, m_r, n, k):
     want_c = formats.encode_bf16_rne(oag.ag_gemm(shards, b).astype(np.float32))
     st, tc = B.tile_config(0, cfg.m, n, k)
     npm, npn = osch.cdiv(cfg.m, tc["block_m"]), osch.cdiv(n, tc["block_n"])
-    assert B.set_num_nodes(nnodes) == B.OK
-    try:
-        for rank in (0, world // nnodes, world - 1):
-            c, ws, sched, _ = _run(B, cfg, shards, b, rank=rank, want_schedule=True)
-            assert np.array_equal(c, want_c)
-            want = []
-            for wg in range(tc["ntiles"]):
-                pid = osch.xcd_remap(wg, tc["ntiles"], tc["num_xcd"], tc["per_xcd"]) if tc["num_xcd"] else wg
-                pm, pn = osch.grouped_order(pid, npm, npn, tc["group_m"])
-                pm = osch.ag_swizzle_multinode(pm, cfg.m, rank, world, nnodes, tc["block_m"])
-                row0 = pm * tc["block_m"]
-                want.append((pm, pn, row0 // m_r, (min(row0 + tc["block_m"], cfg.m) - 1) // m_r))
-            assert np.array_equal(sched, np.asarray(want, dtype=np.int32))
-    finally:
-        B.set_num_nodes(1)
+    for rank in (0, world // nnodes, world - 1):
+        c, ws, sched, _ = _run(B, cfg, shards, b, rank=rank, want_schedule=True, tuning=B.tuning(num_nodes=nnodes))
+        assert np.array_equal(c, want_c)
+        want = []
+        for wg in range(tc["ntiles"]):
+            pid = osch.xcd_remap(wg, tc["ntiles"], tc["num_xcd"], tc["per_xcd"]) if tc["num_xcd"] else wg
+            pm, pn = osch.grouped_order(pid, npm, npn, tc["group_m"])
+            pm = osch.ag_swizzle_multinode(pm, cfg.m, rank, world, nnodes, tc["block_m"])
+            row0 = pm * tc["block_m"]
+            want.append((pm, pn, row0 // m_r, (min(row0 + tc["block_m"], cfg.m) - 1) // m_r))
+        assert np.array_equal(sched, np.asarray(want, dtype=np.int32))
+        # the host evaluation of the schedule is the same list
+        st, host = B.schedule_dump(0, cfg.m, n, k, world, rank, tuning=B.tuning(num_nodes=nnodes))
+        assert st == B.OK and host == want
 
 
 def test_multi_node_order_that_skips_rows_is_refused(B):
@@ -218,10 +213,59 @@ def test_multi_node_order_that_skips_rows_is_refused(B):
     assert st == B.OK and sorted(order) != list(range(len(order)))
     shards, b = synth.ag_gemm_inputs(cfg, integer=True)
     run = AgGemmRun(B, cfg.world, cfg.m_per_rank, cfg.n, cfg.k)
-    assert B.set_num_nodes(4) == B.OK
-    try:
-        assert run([to_dev(s) for s in shards], to_dev(nk(b)), 4) == B.ERR_UNSUPPORTED
-        assert run([to_dev(s) for s in shards], to_dev(nk(b)), 0) == B.OK      # rank 0's order is fine
-        torch.cuda.synchronize()
-    finally:
-        B.set_num_nodes(1)
+    four = B.tuning(num_nodes=4)
+    assert run([to_dev(s) for s in shards], to_dev(nk(b)), 4, tuning=four) == B.ERR_UNSUPPORTED
+    assert run([to_dev(s) for s in shards], to_dev(nk(b)), 0, tuning=four) == B.OK      # rank 0's order is fine
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("k", [8256, 16384])
+@pytest.mark.parametrize("kn", [False, True], ids=["b_nk", "b_kn"])
+def test_long_contraction_on_256_tiles_is_bit_exact(B, k, kn):
+    """The register-staged 256 x 256 tile (taken beyond 8192, and for a ragged last K tile: 8256 = 129 K
+    tiles) over a long contraction, small-integer inputs, both layouts of B: bit for bit."""
+    cfg = synth.CONFIGS[2].scaled(world=8, m_per_rank=505, n=3080, k=k, rank=3)
+    st, tc = B.tile_config(4 if kn else 0, cfg.m, cfg.n, cfg.k)
+    assert (tc["block_m"], tc["block_n"], tc["direct_staging"]) == (256, 256, 0)
+    shards, b = synth.ag_gemm_inputs(cfg, integer=True)
+    c, ws, _, _ = _run(B, cfg, shards, b, kn=kn)
+    want = formats.encode_bf16_rne(oag.ag_gemm(shards, b).astype(np.float32))
+    assert np.array_equal(c, want)
+
+
+def test_cfg2_full_size_other_rank_and_layout(B):
+    """cfg 2 at full size from the view of rank 5, B stored [n, k] and [k, n]; every 16th row plus the
+    rows around every shard boundary against the oracle, the schedule bit for bit."""
+    cfg = synth.CONFIGS[2]
+    shards, b = synth.ag_gemm_inputs(cfg)
+    rows = np.unique(np.concatenate([np.arange(0, cfg.m, 16)] +
+                                    [np.arange(s * cfg.m_per_rank - 2, s * cfg.m_per_rank + 2) % cfg.m for s in range(cfg.world)]))
+    ref = oag.ag_gemm(shards, b, rows=rows)
+    for kn in (False, True):
+        c, ws, sched, _ = _run(B, cfg, shards, b, rank=5, want_schedule=True, kn=kn)
+        _check_schedule(B, cfg, 5, sched, kn=kn)
+        assert compare.max_row_rel_error(formats.decode_bf16(c[rows]), ref) <= TOL_BF16
+
+
+def test_llama_405b_share_sampled(B):
+    """The LLaMA-3.1-405B share of the paper's AllGather+GEMM shape table (M 8192, N 53248 / 8, K 16384)
+    at full size: sampled rows of every shard against the oracle."""
+    cfg = synth.CONFIGS[2].scaled(world=8, m_per_rank=1024, n=6656, k=16384, rank=2)
+    shards, b = synth.ag_gemm_inputs(cfg)
+    rows = np.unique(np.concatenate([np.arange(0, cfg.m, 41), np.arange(cfg.m - 3, cfg.m)]))
+    c, ws, sched, _ = _run(B, cfg, shards, b, want_schedule=True)
+    _check_schedule(B, cfg, cfg.rank, sched)
+    assert compare.max_row_rel_error(formats.decode_bf16(c[rows]), oag.ag_gemm(shards, b, rows=rows)) <= TOL_BF16
+
+
+def test_flags_preset_runs_the_gemm_alone(B):
+    """DITRON_FLAGS_PRESET: the gathered operand is already in the workspace, nothing is copied and no
+    flag is looked at (the signal words are all zero here and stay so)."""
+    cfg = synth.CONFIGS[2].scaled(world=4, m_per_rank=200, n=264, k=328, rank=1)
+    shards, b = synth.ag_gemm_inputs(cfg, integer=True)
+    run = AgGemmRun(B, cfg.world, cfg.m_per_rank, cfg.n, cfg.k)
+    run.workspace.copy_(to_dev(oag.gather(shards)))
+    assert run(None, to_dev(nk(b)), cfg.rank, flags=B.FLAGS_PRESET) == B.OK
+    torch.cuda.synchronize()
+    assert run.status.cpu().tolist()[0] == 0 and not run.signals.any()
+    assert np.array_equal(bits(run.c), formats.encode_bf16_rne(oag.ag_gemm(shards, b).astype(np.float32)))

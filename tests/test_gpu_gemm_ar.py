@@ -117,15 +117,11 @@ def test_external_producer_and_timeout(B):
     assert np.array_equal(bits(run.out), want)
     # (b) nobody raises the peers' flags: with a tiny spin limit every wait gives up, the kernel ends and
     # reports the time-out instead of hanging, and leaves the queue counters at zero
-    B.set_spin_limit(64)
-    try:
-        assert run(a_dev, b_dev, peers, d, flags=B.EXTERNAL_PRODUCER) == B.OK
-        torch.cuda.synchronize()
-        s = run.status.cpu().tolist()
-        assert s[0] == B.ERR_TIMEOUT and 0 <= s[1] < run.ntiles
-        assert run.signals.cpu().numpy()[:2].tolist() == [0, 0]
-    finally:
-        B.set_spin_limit(1 << 20)
+    assert run(a_dev, b_dev, peers, d, flags=B.EXTERNAL_PRODUCER, tuning=B.tuning(spin_limit=64)) == B.OK
+    torch.cuda.synchronize()
+    s = run.status.cpu().tolist()
+    assert s[0] == B.ERR_TIMEOUT and 0 <= s[1] < run.ntiles
+    assert run.signals.cpu().numpy()[:2].tolist() == [0, 0]
     # (c) the buffers stay usable afterwards
     run.status.zero_()
     st = run(a_dev, b_dev, [None if s == d else src[s] for s in range(world)], d)
@@ -215,3 +211,20 @@ def test_gemm_ar_two_shot(B, world, m_r, n, k, integer):
         assert not sig[:2 * world].any()
         done = sig[2 * world + world * run.ntiles:2 * world + world * run.ntiles + world]
         assert [done[s] for s in range(world) if s != d] == [run.epoch] * (world - 1)
+
+
+def test_flags_preset_waits_for_own_tiles_only(B):
+    """DITRON_FLAGS_PRESET: the peers' partials are complete in memory; only this rank's tile flags are
+    raised and waited for."""
+    world, m_r, n, k, d = 4, 100, 264, 72, 3
+    cfg = synth.CONFIGS[3].scaled(world=world, m_per_rank=m_r, n=n, k=k)
+    a_list, b_list = synth.gemm_rs_inputs(cfg, integer=True)
+    parts = [to_dev(oar.partial_bits(a, b)) for a, b in zip(a_list, b_list)]
+    run = GemmArRun(B, world, cfg.m, n, k)
+    peers = [None if s == d else parts[s] for s in range(world)]
+    st = run(to_dev(a_list[d]), to_dev(nk(b_list[d])), peers, d, flags=B.FLAGS_PRESET)
+    _ok(B, st, run)
+    assert np.array_equal(bits(run.out), formats.encode_bf16_rne(oar.gemm_ar(a_list, b_list).astype(np.float32)))
+    flags = run.signals.cpu().numpy()[2 * world:2 * world + world * run.ntiles].reshape(world, run.ntiles)
+    for s in range(world):
+        assert flags[s].tolist() == [run.epoch if s == d else 0] * run.ntiles

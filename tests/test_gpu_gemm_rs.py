@@ -152,25 +152,21 @@ def test_gemm_rs_multi_node_order(B, world, nnodes, m_r, n, k, chunks):
     run = GemmRsRun(B, world, cfg.m, n, k, chunks)
     st, tc = B.tile_config(1, cfg.m, n, k)
     npm, npn = osch.cdiv(cfg.m, tc["block_m"]), osch.cdiv(n, tc["block_n"])
-    assert B.set_num_nodes(nnodes) == B.OK
-    try:
-        for d in (0, world // nnodes, world - 1):
-            peers = [parts[s][d * m_r:(d + 1) * m_r] for s in range(world)]
-            sched = torch.full((4 * tc["ntiles"],), -1, dtype=torch.int32, device="cuda")
-            st = run(to_dev(a_list[d]), to_dev(nk(b_list[d])), peers, d, schedule=sched)
-            _ok(B, st, run)
-            assert np.array_equal(bits(run.out), formats.encode_bf16_rne(ors.gemm_rs(a_list, b_list, d).astype(np.float32)))
-            want = []
-            for wg in range(tc["ntiles"]):
-                pid = osch.xcd_remap(wg, tc["ntiles"], tc["num_xcd"], tc["per_xcd"]) if tc["num_xcd"] else wg
-                pm, pn = osch.grouped_order(pid, npm, npn, tc["group_m"])
-                pm = osch.rs_swizzle_multinode(pm, cfg.m, d, world, nnodes, tc["block_m"])
-                want.append((pm, pn, (pm * tc["block_m"]) // m_r, (min((pm + 1) * tc["block_m"], cfg.m) - 1) // m_r))
-            assert np.array_equal(sched.cpu().numpy().reshape(-1, 4), np.asarray(want, dtype=np.int32))
-            sig = run.signals.cpu().numpy()
-            assert sig[:world].tolist() == [run.epoch] * world
-    finally:
-        B.set_num_nodes(1)
+    for d in (0, world // nnodes, world - 1):
+        peers = [parts[s][d * m_r:(d + 1) * m_r] for s in range(world)]
+        sched = torch.full((4 * tc["ntiles"],), -1, dtype=torch.int32, device="cuda")
+        st = run(to_dev(a_list[d]), to_dev(nk(b_list[d])), peers, d, schedule=sched, tuning=B.tuning(num_nodes=nnodes))
+        _ok(B, st, run)
+        assert np.array_equal(bits(run.out), formats.encode_bf16_rne(ors.gemm_rs(a_list, b_list, d).astype(np.float32)))
+        want = []
+        for wg in range(tc["ntiles"]):
+            pid = osch.xcd_remap(wg, tc["ntiles"], tc["num_xcd"], tc["per_xcd"]) if tc["num_xcd"] else wg
+            pm, pn = osch.grouped_order(pid, npm, npn, tc["group_m"])
+            pm = osch.rs_swizzle_multinode(pm, cfg.m, d, world, nnodes, tc["block_m"])
+            want.append((pm, pn, (pm * tc["block_m"]) // m_r, (min((pm + 1) * tc["block_m"], cfg.m) - 1) // m_r))
+        assert np.array_equal(sched.cpu().numpy().reshape(-1, 4), np.asarray(want, dtype=np.int32))
+        sig = run.signals.cpu().numpy()
+        assert sig[:world].tolist() == [run.epoch] * world
 
 
 @pytest.mark.parametrize("world,m_r,n,k,chunks,integer", [
@@ -219,3 +215,46 @@ def test_gemm_rs_fused_scatter(B, world, m_r, n, k, chunks, integer):
         else:
             assert compare.max_row_rel_error(formats.decode_bf16(got), ref) <= TOL_BF16
         assert np.array_equal(got, ors.reduce_slots_f32_ordered([bits(dsts[d][s]) for s in range(world)]))
+
+
+def test_flags_preset_skips_the_peers(B):
+    """DITRON_FLAGS_PRESET: the peers' blocks are already in the scatter buffer; only the GEMM's own
+    segment flag gates the reduction and no arrival flag is touched."""
+    cfg = synth.CONFIGS[3].scaled(world=4, m_per_rank=100, n=264, k=72)
+    a_list, b_list = synth.gemm_rs_inputs(cfg, integer=True)
+    parts = _all_partials(B, cfg, a_list, b_list)
+    d, m_r, world = 2, cfg.m_per_rank, cfg.world
+    run = GemmRsRun(B, world, cfg.m, cfg.n, cfg.k, chunks=2)
+    for s in range(world):
+        if s != d:
+            run.scatter[s].copy_(parts[s][d * m_r:(d + 1) * m_r])
+    st = run(to_dev(a_list[d]), to_dev(nk(b_list[d])), None, d, flags=B.FLAGS_PRESET)
+    _ok(B, st, run)
+    assert np.array_equal(bits(run.out), formats.encode_bf16_rne(ors.gemm_rs(a_list, b_list, d).astype(np.float32)))
+    sig = run.signals.cpu().numpy()
+    assert sig[:world].tolist() == [run.epoch] * world and not sig[world:].any()
+
+
+def test_llama_405b_share_sampled(B):
+    """The LLaMA-3.1-405B share of the paper's GEMM+ReduceScatter shape table (M 8192, N 16384, K 53248 / 8)
+    at full size: sampled rows of the partial product against the oracle, the reduction bit for bit
+    against the ordered fp32 sum of the blocks that were in the slots."""
+    cfg = synth.CONFIGS[3].scaled(world=8, m_per_rank=1024, n=16384, k=6656, rank=6)
+    d, m_r = cfg.rank, cfg.m_per_rank
+    rng = synth.rng_for(11, d, 405)
+    a = synth.normal_bf16(rng, (cfg.m, cfg.k), std=1.0)
+    b = synth.normal_bf16(rng, (cfg.k, cfg.n), std=cfg.k ** -0.5)
+    peers_np = [synth.normal_bf16(rng, (m_r, cfg.n), std=1.0) for _ in range(cfg.world)]
+    run = GemmRsRun(B, cfg.world, cfg.m, cfg.n, cfg.k, chunks=4)
+    st, tc = B.tile_config(1, cfg.m, cfg.n, cfg.k)
+    assert (tc["block_m"], tc["direct_staging"]) == (256, 0)
+    sched = torch.full((4 * tc["ntiles"],), -1, dtype=torch.int32, device="cuda")
+    st = run(to_dev(a), to_dev(nk(b)), [to_dev(p) for p in peers_np], d, schedule=sched)
+    _ok(B, st, run)
+    _check_schedule(B, cfg, d, sched.cpu().numpy().reshape(-1, 4))
+    rows = np.unique(np.concatenate([np.arange(0, cfg.m, 53), np.arange(d * m_r, d * m_r + 4)]))
+    pref = formats.decode_bf16(a[rows]) @ formats.decode_bf16(b)
+    gemm_out = bits(run.gemm_out)
+    assert compare.max_row_rel_error(formats.decode_bf16(gemm_out[rows]), pref) <= TOL_BF16
+    slots = [gemm_out[d * m_r:(d + 1) * m_r] if s == d else peers_np[s] for s in range(cfg.world)]
+    assert np.array_equal(bits(run.out), ors.reduce_slots_f32_ordered(slots))

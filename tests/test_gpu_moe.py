@@ -137,3 +137,39 @@ def test_cfg4_full_size(B):
     xs, ids, w = synth.moe_inputs(cfg)
     run, R = _run_and_check(B, cfg, xs, ids, w, max_rows=4096, integer=False)
     assert 1500 < R < 2600
+
+
+def test_moe_expert_id_out_of_range_is_reported(B):
+    """An id that names no expert is an error (the routing counts would no longer sum to tokens x top_k):
+    status says which assignment, no tile runs, and the buffers are usable again afterwards."""
+    cfg = synth.CONFIGS[4].scaled(world=4, tokens_per_rank=96, k=64, n=128, num_experts=8, top_k=2,
+                                  num_local_experts=4, rank=1)
+    xs, ids, w = synth.moe_inputs(cfg, integer=True)
+    run = MoeRun(B, 4, 96, 64, 128, 8, 2, 4, max_rows=4 * 96 * 2)
+    xd, wd = [to_dev(x) for x in xs], to_dev(w_nk(w))
+    for bad_value, where in ((8, 301), (-1, 17)):
+        bad = ids.copy()
+        bad.reshape(-1)[where] = bad_value
+        bad.reshape(-1)[where + 200] = bad_value        # the smallest offending index is the one reported
+        assert run(xd, to_dev(bad), wd, 4, 1) == B.OK
+        torch.cuda.synchronize()
+        s = run.status.cpu().tolist()
+        assert s[0] == B.ERR_INVALID_ARG and s[1] == where
+        assert run.records.cpu()[0] == 0 and (bits(run.y) == 0x7FC0).all()
+        run.status.zero_()
+    _run_and_check(B, cfg, xs, ids, w, 4 * 96 * 2, True)
+
+
+def test_moe_flags_preset(B):
+    """DITRON_FLAGS_PRESET: the gathered tokens are already in the workspace; nothing is copied, no flag is read."""
+    cfg = synth.CONFIGS[4].scaled(world=4, tokens_per_rank=100, k=72, n=136, num_experts=12, top_k=3,
+                                  num_local_experts=3, rank=2)
+    xs, ids, w = synth.moe_inputs(cfg, integer=True)
+    e0 = cfg.rank * cfg.num_local_experts
+    run = MoeRun(B, 4, 100, 72, 136, 12, 3, 3, max_rows=1200)
+    run.workspace.copy_(to_dev(np.concatenate(xs, axis=0)))
+    assert run(None, to_dev(ids), to_dev(w_nk(w)), e0, cfg.rank, flags=B.FLAGS_PRESET) == B.OK
+    torch.cuda.synchronize()
+    assert run.status.cpu().tolist()[0] == 0 and not run.signals.any()
+    ref = omoe.grouped_gemm(xs, ids, w, cfg.world, cfg.num_experts, e0)
+    assert np.array_equal(bits(run.y)[:ref.shape[0]], formats.encode_bf16_rne(ref.astype(np.float32)))

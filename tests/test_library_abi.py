@@ -32,6 +32,11 @@ def test_every_declared_symbol_is_exported(B):
 
 def test_sizes_and_strings(B):
     assert B.signal_words(8, 1) == 32 and B.signal_words(8, 4) == 80 and B.signal_words(0, 1) == 0
+    # the gathered operand: world * rows * k elements of the operand type
+    assert B.ag_gemm_workspace_bytes(1024, 8192, 8) == 8 * 1024 * 8192 * 2
+    assert B.ag_gemm_workspace_bytes(16, 8192, 8, B.FP8_E4M3) == 128 * 8192
+    assert B.ag_gemm_workspace_bytes(0, 8192, 8) == 0 and B.ag_gemm_workspace_bytes(16, 8192, 8, 5) == 0
+    assert B.moe_workspace_bytes(1024, 4096, 8) == 8 * 1024 * 4096 * 2 and B.moe_workspace_bytes(1024, 0, 8) == 0
     assert B.status_string(B.OK) == "ok" and "time" in B.status_string(B.ERR_TIMEOUT)
     assert B.moe_max_tiles(4096, 8) == 4096 // 128 + 8
 
@@ -95,7 +100,8 @@ def test_ag_gemm_argument_checks(B):
         return B.lib.ditron_ag_gemm(B._ptr_array(a["a_shards"]), B._ptr(a["b"]), a["b_layout"], B._ptr(a["c"]),
                                     None, None, B._ptr(a["workspace"]), B._ptr(a["signals"]), B._ptr(a["status"]),
                                     B._ptr(a["schedule_out"]), B._int_array(a["arrival_order"]), a["m_per_rank"],
-                                    a["n"], a["k"], a["world"], a["rank"], a["dtype"], a["epoch"], a["flags"], s)
+                                    a["n"], a["k"], a["world"], a["rank"], a["dtype"], a["epoch"], a["flags"],
+                                    B._tuning(a.get("tuning")), s)
 
     assert call(world=0) == B.ERR_INVALID_ARG
     assert call(world=B.MAX_WORLD + 1, a_shards=[fake] * 40) == B.ERR_INVALID_ARG
@@ -112,6 +118,12 @@ def test_ag_gemm_argument_checks(B):
     assert call(b_layout=7) == B.ERR_INVALID_ARG
     assert call(b_layout=B.B_KN, dtype=B.FP8_E4M3) == B.ERR_UNSUPPORTED   # the fp8 operator takes B as [n, k] only
     assert call(k=260) == B.ERR_UNSUPPORTED                          # contraction not a multiple of 8
+    assert call(flags=B.FLAGS_PRESET | B.EXTERNAL_PRODUCER) == B.ERR_INVALID_ARG    # one producer mode at a time
+    assert call(tuning=B.tuning(num_nodes=3)) == B.ERR_INVALID_ARG   # nodes must divide the ranks
+    assert call(tuning=B.tuning(num_nodes=-1)) == B.ERR_INVALID_ARG
+    bad = B.tuning()
+    bad.reserved[2] = 1
+    assert call(tuning=bad) == B.ERR_INVALID_ARG                     # reserved words must be zero
 
 
 def test_gemm_rs_and_moe_argument_checks(B):
@@ -119,11 +131,11 @@ def test_gemm_rs_and_moe_argument_checks(B):
     z = ctypes.c_void_p(0)
     st = B.lib.ditron_gemm_rs(B._ptr(fake), B._ptr(fake), B.B_NK, B._ptr(fake), None, B._ptr(fake), B._ptr(fake),
                               B._ptr(fake), B._ptr(fake), None, None, 1000, 256, 64, 8, 0, 1, 1,
-                              B.EMULATE_PRODUCER, z)
+                              B.EMULATE_PRODUCER, None, z)
     assert st == B.ERR_INVALID_ARG          # m not divisible by world
     st = B.lib.ditron_gemm_rs(B._ptr(fake), B._ptr(fake), B.B_NK, B._ptr(fake), None, B._ptr(fake), B._ptr(fake),
                               B._ptr(fake), B._ptr(fake), None, None, 1024, 256, 64, 8, 0, 3, 1,
-                              B.EMULATE_PRODUCER, z)
+                              B.EMULATE_PRODUCER, None, z)
     assert st == B.ERR_INVALID_ARG          # chunks do not divide the rows per rank
     st = B.gemm_rs_fuse_scatter(fake, fake, B.B_NK, None, None, fake, fake, fake, None, None, 1024, 256, 64, 8, 0, 1, 1,
                                 B.EMULATE_PRODUCER, stream=_S())
@@ -131,7 +143,7 @@ def test_gemm_rs_and_moe_argument_checks(B):
     st = B.gemm_rs_fuse_scatter(fake, fake, B.B_NK, [fake] * 7 + [None], [fake] * 8, fake, fake, fake, None, None, 1024,
                                 256, 64, 8, 0, 1, 1, B.EMULATE_PRODUCER, stream=_S())
     assert st == B.ERR_INVALID_ARG          # a destination is missing
-    st = B.lib.ditron_reduce_slots(None, B._ptr(fake), None, None, 8, 8, 2, 1, 1, z)
+    st = B.lib.ditron_reduce_slots(None, B._ptr(fake), None, None, 8, 8, 2, 1, 1, None, z)
     assert st == B.ERR_INVALID_ARG
     st = B.moe_ag_grouped_gemm([fake] * 8, fake, fake, B.B_NK, fake, fake, fake, fake, fake, fake, fake, fake, None,
                                1024, 4096, 1536, 64, 2, 60, 8, 4096, 8, 0, 1, B.EMULATE_PRODUCER, stream=_S())
@@ -166,6 +178,43 @@ def test_gemm_ar_argument_checks(B):
     assert call(n=100) == B.ERR_UNSUPPORTED
     st, tc = B.tile_config(3, 8192, 8192, 3584)
     assert st == B.OK and (tc["block_m"], tc["block_n"], tc["ntiles"]) == (256, 256, 1024)
+
+
+def test_schedule_dump_on_the_host(B):
+    """The host evaluation of the schedule against the oracle's statement of the same arithmetic."""
+    from oracle import schedule as S
+    for op, m, n, k, world, rank, tile in [(0, 8192, 3584, 8192, 8, 3, S.ag_tile), (1, 8192, 8192, 3584, 8, 5, S.rs_tile),
+                                           (0, 1616, 2056, 136, 8, 7, S.ag_tile), (1, 800, 264, 72, 4, 1, S.rs_tile)]:
+        st, tc = B.tile_config(op, m, n, k)
+        st, got = B.schedule_dump(op, m, n, k, world, rank)
+        assert st == B.OK and len(got) == tc["ntiles"]
+        want = [tile(S.xcd_remap(wg, tc["ntiles"], tc["num_xcd"], tc["per_xcd"]), m, n, tc["block_m"], tc["block_n"],
+                     tc["group_m"], rank, world) for wg in range(tc["ntiles"])]
+        assert got == want
+    # GEMM + AllReduce: position -> tile, no rotation
+    from oracle import gemm_ar as oar
+    st, tc = B.tile_config(3, 1024, 2048, 64)
+    st, got = B.schedule_dump(3, 1024, 2048, 64, 4, 2)
+    assert st == B.OK and [g[:2] for g in got] == [oar.tile_at_position(t, 1024, 2048, tc["block_m"], tc["block_n"], tc["group_m"],
+                                                                         tc["num_xcd"], tc["per_xcd"]) for t in range(tc["ntiles"])]
+    # across nodes the order comes from the multi-node listings; a shape they do not cover is refused
+    st, got = B.schedule_dump(0, 8 * 505, 3080, 64, 8, 5, tuning=B.tuning(num_nodes=4))
+    st2, tc = B.tile_config(0, 8 * 505, 3080, 64)
+    assert st == B.OK
+    rows_in_order = []
+    for g in got:
+        if g[0] not in rows_in_order:
+            rows_in_order.append(g[0])
+    assert sorted(rows_in_order) == list(range(S.cdiv(8 * 505, tc["block_m"])))
+    assert B.schedule_dump(0, 8 * 37, 128, 64, 8, 4, b_layout=B.B_KN, tuning=B.tuning(num_nodes=4))[0] == B.ERR_UNSUPPORTED
+    # capacity too small: the count is still reported
+    import ctypes as C
+    cnt = C.c_int(0)
+    out = (C.c_int32 * 4)()
+    assert B.lib.ditron_schedule_dump(0, 8192, 3584, 8192, 8, 0, B.BF16, B.B_NK, None, out, 1, C.byref(cnt)) == B.ERR_WORKSPACE
+    assert cnt.value == 448
+    assert B.lib.ditron_schedule_dump(2, 8192, 3584, 8192, 8, 0, B.BF16, B.B_NK, None, out, 1, C.byref(cnt)) == B.ERR_INVALID_ARG
+    assert B.lib.ditron_schedule_dump(0, 8192, 3584, 8192, 8, 8, B.BF16, B.B_NK, None, out, 1, C.byref(cnt)) == B.ERR_INVALID_ARG
 
 
 class _S:

@@ -59,6 +59,3 @@ def test_argument_checks(B):
     assert B.tile_row_order(0, 1024, 256, 8, 3, 0)[0] == B.ERR_INVALID_ARG       # world not a multiple of nnodes
     assert B.tile_row_order(0, 1000, 256, 8, 2, 8)[0] == B.ERR_INVALID_ARG       # rank out of range
     assert B.tile_row_order(0, 1001, 256, 8, 2, 0)[0] == B.ERR_INVALID_ARG       # rows not a multiple of world
-    assert B.set_num_nodes(0) == B.ERR_INVALID_ARG
-    assert B.set_num_nodes(2) == B.OK
-    assert B.set_num_nodes(1) == B.OK

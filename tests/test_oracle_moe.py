@@ -6,6 +6,7 @@ import pytest
 
 import synth
 from oracle import moe, formats
+from oracle import ag_gemm as oag
 from oracle.schedule import cdiv
 
 
@@ -81,7 +82,9 @@ def test_tile_schedule_invariants(rank, bm):
             src = (gather[offsets[j] + q0: offsets[j] + q1] // top_k) // t_r
             assert sch["segment_start"][pos] == src[0] == src.min()
             assert sch["segment_end"][pos] == src[-1] == src.max()
-            assert sch["stage"][pos] == max((int(s) - rank) % world for s in src)
+            # the stage is the delivery position, in the producer's order, of the last shard needed
+            ring = oag.arrival_order(rank, world)
+            assert sch["stage"][pos] == max(ring.index(int(s)) for s in src)
             stages.append((sch["stage"][pos], tau))
             pos += 1
         assert stages == sorted(stages)      # ascending stage, ties by original index
@@ -102,6 +105,41 @@ def test_tile_schedule_tiny_by_hand():
     count = np.array([[0, 1], [0, 1]])
     sch = moe.tile_schedule(count, 0, 2, 4, rank=0, world=2)
     assert sch["ntiles"] == 1 and sch["expert_id"] == [1] and sch["segment_start"] == [0] and sch["segment_end"] == [1]
+
+
+def test_tile_stage_follows_the_producers_delivery_order_by_hand():
+    """The all-gather producer delivers to rank r in the order r, r+1, ... (mod W).  With 3 ranks and
+    rank 1 the order is 1, 2, 0, which a ring walked the other way (1, 0, 2) does not share."""
+    assert oag.arrival_order(1, 3) == [1, 2, 0]
+    # one local expert, 2 rows from every rank, tiles of 2 rows: tile t holds exactly rank t's rows
+    count = np.array([[2], [2], [2]])
+    sch = moe.tile_schedule(count, 0, 1, 2, rank=1, world=3)
+    # rank 1's own rows are there first (stage 0), then rank 2's (stage 1), rank 0's last (stage 2)
+    assert sch["tiled_m"] == [1, 2, 0]
+    assert sch["stage"] == [0, 1, 2]
+    assert sch["segment_start"] == [1, 2, 0] and sch["segment_end"] == [1, 2, 0]
+    # 4 ranks, rank 2 (delivery order 2, 3, 0, 1); rows per rank 3, 1, 2, 2; tiles of 3 rows:
+    #   tile 0 = rows 0..2  (rank 0)          -> waits for delivery position 2
+    #   tile 1 = rows 3..5  (ranks 1, 2, 2)   -> ranks 1..2, the later of positions 3 and 0 = 3
+    #   tile 2 = rows 6..7  (ranks 3, 3)      -> position 1
+    assert oag.arrival_order(2, 4) == [2, 3, 0, 1]
+    count = np.array([[3], [1], [2], [2]])
+    sch = moe.tile_schedule(count, 0, 1, 3, rank=2, world=4)
+    assert sch["tiled_m"] == [2, 0, 1]
+    assert sch["stage"] == [1, 2, 3]
+    assert sch["segment_start"] == [3, 0, 1] and sch["segment_end"] == [3, 0, 2]
+
+
+def test_reversed_ring_is_caught(monkeypatch):
+    """Planting the mistake: with the ring walked backwards the stage is still a permutation of
+    0..W-1 over the shards, every invariant test still holds, but the hand-worked orders differ."""
+    for rank, world in [(1, 3), (2, 4), (5, 8)]:
+        assert [moe.stage_of_shard(s, rank, world) for s in oag.arrival_order(rank, world)] == list(range(world))
+    monkeypatch.setattr(moe, "stage_of_shard", lambda s, rank, world: (rank - s) % world)
+    sch = moe.tile_schedule(np.array([[2], [2], [2]]), 0, 1, 2, rank=1, world=3)
+    assert sch["tiled_m"] == [1, 0, 2] != [1, 2, 0]
+    with pytest.raises(AssertionError):
+        test_tile_stage_follows_the_producers_delivery_order_by_hand()
 
 
 def test_grouped_gemm_brute_force_tiny():

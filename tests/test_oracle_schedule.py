@@ -163,3 +163,85 @@ def test_multinode_perfect_tiling_properties():
     for step in range(npm):
         dests = {(S.rs_swizzle_multinode(step, m, r, world, nnodes, bm) * bm) // m_r for r in range(world)}
         assert len(dests) == world
+
+
+# ---------------------------------------------------------------- ownership of shared tile rows
+def _golden_orders():
+    for ln in open(os.path.join(GOLD, "multinode_order_three_nodes.txt")):
+        if ln.startswith("#") or not ln.strip():
+            continue
+        head, tail = ln.split(":")
+        mode, world, nnodes, m_r, bm, rank = head.split()
+        yield (mode,) + tuple(map(int, (world, nnodes, m_r, bm, rank))) + (list(map(int, tail.split())),)
+
+
+def _oracle_order(mode, world, nnodes, m_r, bm, rank):
+    f = S.ag_swizzle_multinode if mode == "gather" else S.rs_swizzle_multinode
+    m = world * m_r
+    return [f(t, m, rank, world, nnodes, bm) for t in range(S.cdiv(m, bm))]
+
+
+def test_multinode_orders_worked_by_hand_three_nodes():
+    """Seven orders worked by hand from the two listings for a shape whose node boundaries cut
+    tile rows 3 and 6 (3 nodes, so the first, a middle and the last visit position all occur)."""
+    cases = list(_golden_orders())
+    assert len(cases) == 7
+    for mode, world, nnodes, m_r, bm, rank, want in cases:
+        assert _oracle_order(mode, world, nnodes, m_r, bm, rank) == want, (mode, rank)
+
+
+def _order_from_ownership_rule(mode, world, nnodes, m_r, bm, rank):
+    """The same order stated through sets instead of per-lane arithmetic.  Every tile row is owned
+    by one node: a row holding rows of two nodes goes to the one visited LATER in gather order
+    (both nodes' data must have arrived) and to the one visited EARLIER in scatter order (it is
+    computed as early as possible for both).  Nodes are visited starting at the own node (gather)
+    or the next one (scatter); inside a node's block of rows the visit starts at the tile row of
+    the own local rank's first row (gather: first tile row starting at or after it; scatter: the
+    tile row holding the next local rank's first row), never before the block's first row, and
+    wraps around the block."""
+    m = world * m_r
+    m_node, local_world = m // nnodes, world // nnodes
+    node_id, local_rank = rank // local_world, rank % local_world
+    first = node_id if mode == "gather" else node_id + 1
+    visit = [(first + p) % nnodes for p in range(nnodes)]
+    when = {node: p for p, node in enumerate(visit)}
+    owned = {node: [] for node in visit}
+    for t in range(S.cdiv(m, bm)):
+        touching = sorted({row // m_node for row in range(t * bm, min((t + 1) * bm, m))})
+        assert len(touching) <= 2
+        pick = max if mode == "gather" else min
+        owned[pick(touching, key=lambda nd: when[nd])].append(t)
+    order = []
+    for node in visit:
+        rows = owned[node]
+        if mode == "gather":
+            start = S.cdiv(m_node * node + m_r * local_rank, bm)
+        else:
+            start = (m_node * node + m_r * (local_rank + 1)) // bm
+        shift = max(0, start - rows[0]) % len(rows)
+        order += rows[shift:] + rows[:shift]
+    return order
+
+
+@pytest.mark.parametrize("world,nnodes,m_r,bm", [(8, 1, 997, 256), (16, 2, 997, 256), (32, 4, 997, 256), (6, 3, 100, 64),
+                                                (12, 3, 77, 32), (16, 4, 1000, 128), (8, 2, 505, 256), (20, 5, 333, 128)])
+def test_multinode_orders_follow_the_ownership_rule(world, nnodes, m_r, bm):
+    for rank in range(world):
+        for mode in ("gather", "scatter"):
+            assert _oracle_order(mode, world, nnodes, m_r, bm, rank) == \
+                _order_from_ownership_rule(mode, world, nnodes, m_r, bm, rank), (mode, rank)
+
+
+def test_swapped_ownership_is_caught(monkeypatch):
+    """Planting the mistake the pins exist for: with the gather and scatter ownership conditions
+    exchanged the orders are still permutations, but neither the hand-worked table nor the
+    ownership rule agrees any more."""
+    real = S._node_blocks
+    monkeypatch.setattr(S, "_node_blocks", lambda m, nn, bm, ns, mode: real(m, nn, bm, ns, "rs" if mode == "ag" else "ag"))
+    wrong = 0
+    for mode, world, nnodes, m_r, bm, rank, want in _golden_orders():
+        got = _oracle_order(mode, world, nnodes, m_r, bm, rank)
+        assert sorted(got) == list(range(len(want)))
+        wrong += got != want
+    assert wrong >= 5
+    assert _oracle_order("gather", 16, 2, 997, 256, 3) != _order_from_ownership_rule("gather", 16, 2, 997, 256, 3)
