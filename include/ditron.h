@@ -192,6 +192,24 @@ ditron_status_t ditron_ag_gemm(const void* const* a_shards, const void* b, int b
                                int rank, int dtype, int32_t epoch, unsigned flags, const ditron_tuning_t* tuning, void* stream);
 
 /*
+ * ditron_ag_gemm for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  The scratch of ditron_ag_gemm (the `workspace` that
+ * receives the gathered A and the `signals` words) comes from a fixed array inside the library's device
+ * image (DITRON_STATIC_WORKSPACE_BYTES + 4 KiB, one copy per GPU the library has been called on, held
+ * until the process ends); the call allocates nothing and frees nothing.  Always in
+ * DITRON_EMULATE_PRODUCER mode (nobody else can reach the workspace); arguments as for ditron_ag_gemm.
+ * DITRON_ERR_WORKSPACE if ditron_ag_gemm_workspace_bytes(m_per_rank, k, world, dtype) exceeds
+ * DITRON_STATIC_WORKSPACE_BYTES, before anything is enqueued.  The signal words are cleared on the
+ * stream at the start of every call (by a small kernel, so the call may be captured).  Every call on
+ * a GPU uses that GPU's one array: calls that overlap on one GPU (two streams, two threads) race.
+ */
+#define DITRON_STATIC_WORKSPACE_BYTES (32u << 20)
+ditron_status_t ditron_ag_gemm_static(const void* const* a_shards, const void* b, int b_layout, void* c,
+                                      const float* a_scales, const float* b_scales, int32_t* status,
+                                      const int* arrival_order, int m_per_rank, int n, int k, int world,
+                                      int rank, int dtype, const ditron_tuning_t* tuning, void* stream);
+
+/*
  * GEMM-ReduceScatter:  out[m/world, n] = rows_rank( sum_s P_s ),  P_rank = A . B computed here.
  *
  * Paper: `gemm_rs_op`, `kernel_gemm_rs_producer` and the reduce-scatter launchers of Appendix

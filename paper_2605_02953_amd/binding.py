@@ -54,6 +54,8 @@ lib.ditron_status_string.argtypes = [_i]
 lib.ditron_ag_gemm.restype = _i
 lib.ditron_ag_gemm.argtypes = [_pp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _ip,
                                _i, _i, _i, _i, _i, _i, _i32, _u, _tp, _vp]
+lib.ditron_ag_gemm_static.restype = _i
+lib.ditron_ag_gemm_static.argtypes = [_pp, _vp, _i, _vp, _vp, _vp, _vp, _ip, _i, _i, _i, _i, _i, _i, _tp, _vp]
 lib.ditron_gemm_rs.restype = _i
 lib.ditron_gemm_rs.argtypes = [_vp, _vp, _i, _vp, _pp, _vp, _vp, _vp, _vp, _vp, _ip,
                                _i, _i, _i, _i, _i, _i, _i32, _u, _tp, _vp]
@@ -166,6 +168,16 @@ def ag_gemm(a_shards, b, b_layout, c, a_scales, b_scales, workspace, signals, st
                               _ptr(workspace), _ptr(signals), _ptr(status), _ptr(schedule_out),
                               _int_array(arrival_order), m_per_rank, n, k, world, rank, dtype, epoch, flags,
                               _tuning(tuning), _stream(stream))
+
+
+STATIC_WORKSPACE_BYTES = 32 << 20
+
+
+def ag_gemm_static(a_shards, b, b_layout, c, a_scales, b_scales, status, arrival_order, m_per_rank, n, k, world,
+                   rank, dtype, stream=None, tuning=None):
+    return lib.ditron_ag_gemm_static(_ptr_array(a_shards), _ptr(b), b_layout, _ptr(c), _ptr(a_scales), _ptr(b_scales),
+                                     _ptr(status), _int_array(arrival_order), m_per_rank, n, k, world, rank, dtype,
+                                     _tuning(tuning), _stream(stream))
 
 
 def gemm_rs(a, b, b_layout, gemm_out, peer_partials, scatter_buf, out, signals, status, schedule_out,

@@ -5,7 +5,6 @@
 #include <stdlib.h>
 #include <algorithm>
 #include <atomic>
-#include <vector>
 #include "../../include/ditron.h"
 #include "gemm_core.h"
 
@@ -129,11 +128,13 @@ inline bool fits_32bit(size_t rows, size_t cols, size_t esize) { return rows * c
 // for which they do not visit every tile row exactly once is refused.
 inline bool node_order_is_bijection(int m, int block_m, int world, int nnodes, int rank, int mode) {
   const int npm = cdiv(m, block_m);
-  std::vector<char> seen((size_t)npm, 0);
+  constexpr int kMaxRows = 1 << 16;   // one bit per tile row on the stack: the check allocates nothing
+  if (npm > kMaxRows) return false;
+  uint64_t seen[kMaxRows / 64] = {0};
   for (int t = 0; t < npm; ++t) {
     const int r = tile_row_across_nodes(t, m, rank, world, nnodes, block_m, mode);
-    if (r < 0 || r >= npm || seen[(size_t)r]) return false;
-    seen[(size_t)r] = 1;
+    if (r < 0 || r >= npm || (seen[r >> 6] >> (r & 63)) & 1) return false;
+    seen[r >> 6] |= 1ull << (r & 63);
   }
   return true;
 }
