@@ -658,18 +658,47 @@ def bench_fp8(args):
     nsets = 5
     bds = [to_dev(nk(b)) for _ in range(nsets)]
     sad, sbd = to_dev(sa), to_dev(sb)
-    run = AgGemmRun(B, cfg.world, cfg.m_per_rank, cfg.n, cfg.k, esize=1)
+    run = AgGemmRun(B, cfg.world, cfg.m_per_rank, cfg.n, cfg.k, esize=1, tuning=B.tuning(decode_variant=args.decode_variant))
     it = [0]
 
-    def step():
-        it[0] += 1
-        st = run(ad, bds[it[0] % nsets], cfg.rank, dtype=B.FP8_E4M3, a_scales=sad, b_scales=sbd)
-        if st != B.OK:
-            raise RuntimeError(B.status_string(st))
+    def make_step(r, flags=None):
+        def step():
+            it[0] += 1
+            st = r(ad if flags is None else None, bds[it[0] % nsets], cfg.rank, dtype=B.FP8_E4M3, a_scales=sad, b_scales=sbd, flags=flags)
+            if st != B.OK:
+                raise RuntimeError(B.status_string(st))
+        return step
 
+    step = make_step(run)
     ms_per_step, ev_ms = _timed(torch, args, step)
     if run.status.cpu().tolist()[0] != 0:
         raise RuntimeError("kernel reported a signal time-out")
+    quant = LAST_QUANTILES
+    # the same call with the gathered operand resident (no emulated peers, no waits), and every kernel variant
+    # of the decode path, each timed the same way (events around each call, B rotating)
+    def events_us(fn, n=200):
+        for _ in range(20):
+            fn()
+        torch.cuda.synchronize()
+        ev = _events(torch, n)
+        for a_, b_ in ev:
+            a_.record()
+            fn()
+            b_.record()
+        torch.cuda.synchronize()
+        return _quantiles_us(ev)
+
+    preset = events_us(make_step(run, B.FLAGS_PRESET))
+    variants = {}
+    names = {1: "128x32 tiles, whole contraction", 2: "128x128 tiles, split contraction", 3: "128x64 tiles, split contraction",
+             4: "16-row tiles, one per shard"}
+    for v in (1, 2, 3, 4):
+        rv = AgGemmRun(B, cfg.world, cfg.m_per_rank, cfg.n, cfg.k, esize=1, tuning=B.tuning(decode_variant=v))
+        st, tc = B.tile_config(0, cfg.m, cfg.n, cfg.k, B.FP8_E4M3, B.tuning(decode_variant=v))
+        variants[str(v)] = {"what": names[v], "splits": tc["splits"], "emulated_peers_us": events_us(make_step(rv)),
+                            "flags_preset_us": events_us(make_step(rv, B.FLAGS_PRESET))}
+        if rv.status.cpu().tolist()[0] != 0:
+            raise RuntimeError("kernel reported a signal time-out")
     flops = 2.0 * cfg.m * cfg.n * cfg.k
     alg_bytes = cfg.k * cfg.n + cfg.m * cfg.k + cfg.m * cfg.n * 2
     gbs = alg_bytes / (ev_ms * 1e-3) / 1e9
@@ -682,9 +711,12 @@ def bench_fp8(args):
                                f"-> C [{cfg.m},{cfg.n}] bf16; weights rotated over {nsets} copies", "latency_us": ev_ms * 1e3,
                    "tflops": flops / (ev_ms * 1e-3) / 1e12},
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
-                     "traffic": MEASURED_TRAFFIC.get("cfg5"), "kernel": "ag_gemm_decode_kernel (fp8)", "kernel_ms": ev_ms,
+                     "traffic": MEASURED_TRAFFIC.get("cfg5"), "kernel": "ag_gemm_splitk_kernel (fp8)", "kernel_ms": ev_ms,
                      "bytes": alg_bytes},
+        "flags_preset_us": preset,
+        "decode_variants": variants,
     }
+    out["config"]["latency_us_quantiles"] = quant
     if not args.no_cpu:
         from oracle import ag_gemm as oag
         t0 = time.perf_counter()
@@ -779,6 +811,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--decode-variant", type=int, default=0, help="cfg5: kernel variant of the decode path (0 = library's choice)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU's share on one GPU; --gpus must be 1", file=sys.stderr)

@@ -102,6 +102,7 @@ typedef struct {
 #define DITRON_MAX_WORLD 32
 #define DITRON_STATUS_WORDS 4
 #define DITRON_SCHEDULE_WORDS 4 /* int32 words per tile record in a schedule dump */
+#define DITRON_TILE_CONFIG_WORDS 10
 
 /* Number of int32 words the `signals` array of any entry point must have for `world`
  * ranks and `chunks` flags per rank (chunks = 1 except for ditron_gemm_rs). */
@@ -131,18 +132,25 @@ ditron_status_t ditron_tile_row_order(int op, int m, int block_m, int world, int
  * out[0]=BLOCK_M out[1]=BLOCK_N out[2]=GROUP_SIZE_M out[3]=chiplets used by the work-group
  * remap (0 = no remap) out[4]=tiles per chiplet per block out[5]=number of tiles
  * (ag_gemm / gemm_rs) out[6]=threads per work-group out[7]=operand staging of the tile engine (0 = through
- * registers, 1 = global memory straight into LDS; op 1 and 3 report the choice for B stored [n, k]). */
-ditron_status_t ditron_tile_config(int op, int m, int n, int k, int dtype, int out[8]);
+ * registers, 1 = global memory straight into LDS; op 1 and 3 report the choice for B stored [n, k])
+ * out[8]=work-groups that share the contraction of one output tile (decode-shaped ag_gemm; else 1): a
+ * schedule dump then holds that many identical records per tile, tile after tile.  out[9]=0.
+ * `tuning`: only decode_variant matters. */
+ditron_status_t ditron_tile_config(int op, int m, int n, int k, int dtype, const ditron_tuning_t* tuning,
+                                   int out[DITRON_TILE_CONFIG_WORDS]);
 
 /*
  * Sizes of the buffers the launchers' contexts own in the paper (`ag_gemm(a, b, ctx)`: the
  * symmetric workspace that receives the gathered A; the MoE launcher: the gathered tokens).
- * Bytes of the `workspace` argument of ditron_ag_gemm ([world*m_per_rank, k] in `dtype`) and of
- * ditron_moe_ag_grouped_gemm ([world*tokens_per_rank, hidden] bf16); 0 for invalid arguments.
+ * Bytes of the `workspace` argument of ditron_ag_gemm (the gathered [world*m_per_rank, k] in `dtype`;
+ * for decode-shaped problems, whose contraction is split over several work-groups, followed at the next
+ * multiple of 256 bytes by the fp32 partial tiles) and of ditron_moe_ag_grouped_gemm
+ * ([world*tokens_per_rank, hidden] bf16); 0 for invalid arguments.
  * The other caller-sized arrays have closed forms given with their arguments (signals:
  * ditron_signal_words; tile_records: ditron_moe_max_tiles).
  */
-size_t ditron_ag_gemm_workspace_bytes(int m_per_rank, int k, int world, int dtype);
+size_t ditron_ag_gemm_workspace_bytes(int m_per_rank, int n, int k, int world, int dtype, int b_layout,
+                                      const ditron_tuning_t* tuning);
 size_t ditron_moe_workspace_bytes(int tokens_per_rank, int hidden, int world);
 
 /*
@@ -176,14 +184,20 @@ ditron_status_t ditron_schedule_dump(int op, int m, int n, int k, int world, int
  *  a_scales      device float[world] (fp8: one scale per shard) or NULL
  *  b_scales      device float[n]     (fp8: one scale per output column) or NULL
  *                fp8 result is (sum_k a*b) * a_scales[row / m_per_rank] * b_scales[col]
- *  workspace     device, [world*m_per_rank, k] in `dtype`: the gathered A (written by the
- *                producer, read by the GEMM)
+ *  workspace     device, ditron_ag_gemm_workspace_bytes(...) bytes; starts with the gathered A,
+ *                [world*m_per_rank, k] in `dtype` (written by the producer, read by the GEMM)
  *  signals       device int32[ditron_signal_words(world, 1)]; flag s is word s
  *  status        device int32[DITRON_STATUS_WORDS]
  *  schedule_out  device int32[4 * tiles] or NULL; with DITRON_DUMP_SCHEDULE the GEMM
  *                work-group with index w writes (pid_m, pid_n, rank_beg, rank_end) at 4*w
  *  arrival_order host int[world] or NULL: the order in which the emulated producer delivers
  *                shards; NULL = rank, rank+1, ... (mod world) as in the paper's producer
+ *  tuning->decode_variant (fp8, and bf16 problems of at most 128 tiles of 128 x 128 with B stored
+ *                [n, k]; the latency variants of the paper's Section "Kernel library"): 0 = library's
+ *                choice; 1 = 128 x 32 tiles over the whole contraction; 2 = 128 x 128 tiles, the
+ *                contraction split over up to 8 work-groups whose fp32 partials are summed in split
+ *                order by the last to finish; 3 = the same with 128 x 64 tiles; 4 = 16-row tiles,
+ *                one shard's rows at the decode shape, each waiting for its own shard only
  */
 ditron_status_t ditron_ag_gemm(const void* const* a_shards, const void* b, int b_layout, void* c,
                                const float* a_scales, const float* b_scales, void* workspace,
@@ -198,7 +212,7 @@ ditron_status_t ditron_ag_gemm(const void* const* a_shards, const void* b, int b
  * image (DITRON_STATIC_WORKSPACE_BYTES + 4 KiB, one copy per GPU the library has been called on, held
  * until the process ends); the call allocates nothing and frees nothing.  Always in
  * DITRON_EMULATE_PRODUCER mode (nobody else can reach the workspace); arguments as for ditron_ag_gemm.
- * DITRON_ERR_WORKSPACE if ditron_ag_gemm_workspace_bytes(m_per_rank, k, world, dtype) exceeds
+ * DITRON_ERR_WORKSPACE if ditron_ag_gemm_workspace_bytes(m_per_rank, n, k, world, dtype, b_layout, tuning) exceeds
  * DITRON_STATIC_WORKSPACE_BYTES, before anything is enqueued.  The signal words are cleared on the
  * stream at the start of every call (by a small kernel, so the call may be captured).  Every call on
  * a GPU uses that GPU's one array: calls that overlap on one GPU (two streams, two threads) race.

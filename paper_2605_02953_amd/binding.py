@@ -40,7 +40,7 @@ _tp = ctypes.POINTER(Tuning)
 lib.ditron_signal_words.restype = ctypes.c_size_t
 lib.ditron_signal_words.argtypes = [_i, _i]
 lib.ditron_ag_gemm_workspace_bytes.restype = ctypes.c_size_t
-lib.ditron_ag_gemm_workspace_bytes.argtypes = [_i, _i, _i, _i]
+lib.ditron_ag_gemm_workspace_bytes.argtypes = [_i, _i, _i, _i, _i, _i, _tp]
 lib.ditron_moe_workspace_bytes.restype = ctypes.c_size_t
 lib.ditron_moe_workspace_bytes.argtypes = [_i, _i, _i]
 lib.ditron_schedule_dump.restype = _i
@@ -48,7 +48,7 @@ lib.ditron_schedule_dump.argtypes = [_i, _i, _i, _i, _i, _i, _i, _i, _tp, ctypes
 lib.ditron_tile_row_order.restype = _i
 lib.ditron_tile_row_order.argtypes = [_i, _i, _i, _i, _i, _i, _ip]
 lib.ditron_tile_config.restype = _i
-lib.ditron_tile_config.argtypes = [_i, _i, _i, _i, _i, _ip]
+lib.ditron_tile_config.argtypes = [_i, _i, _i, _i, _i, _tp, _ip]
 lib.ditron_status_string.restype = ctypes.c_char_p
 lib.ditron_status_string.argtypes = [_i]
 lib.ditron_ag_gemm.restype = _i
@@ -125,8 +125,8 @@ def _tuning(t):
     return None if t is None else ctypes.byref(t)
 
 
-def ag_gemm_workspace_bytes(m_per_rank, k, world, dtype=BF16):
-    return int(lib.ditron_ag_gemm_workspace_bytes(m_per_rank, k, world, dtype))
+def ag_gemm_workspace_bytes(m_per_rank, n, k, world, dtype=BF16, b_layout=B_NK, tuning=None):
+    return int(lib.ditron_ag_gemm_workspace_bytes(m_per_rank, n, k, world, dtype, b_layout, _tuning(tuning)))
 
 
 def moe_workspace_bytes(tokens_per_rank, hidden, world):
@@ -155,10 +155,10 @@ def tile_row_order(op, m, block_m, world, nnodes, rank):
     return st, list(out)
 
 
-def tile_config(op, m, n, k, dtype=BF16):
-    out = (ctypes.c_int * 8)()
-    st = lib.ditron_tile_config(op, m, n, k, dtype, out)
-    keys = ("block_m", "block_n", "group_m", "num_xcd", "per_xcd", "ntiles", "threads", "direct_staging")
+def tile_config(op, m, n, k, dtype=BF16, tuning=None):
+    out = (ctypes.c_int * 10)()
+    st = lib.ditron_tile_config(op, m, n, k, dtype, _tuning(tuning), out)
+    keys = ("block_m", "block_n", "group_m", "num_xcd", "per_xcd", "ntiles", "threads", "direct_staging", "splits")
     return st, dict(zip(keys, list(out)))
 
 

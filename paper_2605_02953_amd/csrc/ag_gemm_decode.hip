@@ -47,6 +47,10 @@ struct AgGemmDecodeParams {
   unsigned spin_limit;
   int wait;   // 0: every shard is resident, the flags are not looked at
   int group_m, num_xcd, per_xcd, npm, npn;
+  // split-K kernel
+  int splits, kt_per_split;   // K splits per output tile; 128-byte K tiles per split
+  float* partials;            // [tile][split][BM x BN] fp32, in the lanes' own order
+  int32_t* tile_counters;     // [tiles] splits that have delivered their partial; left at zero
 };
 
 template <bool BF16>
@@ -219,9 +223,275 @@ __global__ __launch_bounds__(DecodeTile::THREADS) void ag_gemm_decode_kernel(con
   }
 }
 
+
+// ------------------------------------------------------------------ split-K form
+// The 128 x 32 tile above makes every work-group stream all of A through its compute unit (1 MiB
+// for 256 KiB of B at the decode shape), and the path from the L2 into a compute unit is what bounds
+// it.  Here a work-group owns a BM x BN tile over 1/S of the contraction: per 128-byte K tile it
+// loads BM + BN rows instead of 128 + 32, so with 128 x 128 tiles and S = 4 a unit moves 512 KiB
+// where the form above moves 1.25 MiB.  The S partial tiles (fp32, written in the lanes' own order so
+// that every store and load is a contiguous KiB per wave) meet in memory: each work-group stores its
+// partial, then draws a ticket from the tile's counter; the one that draws the last ticket adds the S
+// partials in split order 0..S-1 (its own from registers, so the order and hence the bits do not depend
+// on who came last), applies the scales and writes C.  No work-group waits for another, so the grid may
+// be of any size.  Waves 0-3 fetch A and compute, waves 4-7 fetch B, one barrier per K tile, as above.
+// BM = 16 is the per-shard form: a tile is one shard's rows and waits for that shard's flag only.
+template <int BM_, int BN_>
+struct SplitKTile {
+  static constexpr int BM = BM_, BN = BN_, BK = 128, THREADS = 512;
+  static constexpr int WM = BM >= 128 ? 2 : 1, WN = 4 / WM;          // the four computing waves as WM x WN
+  static constexpr int WTM = BM / WM, WTN = BN / WN;
+  static constexpr int MB = WTM / 16, NB = WTN / 16;                  // 16 x 16 blocks per wave
+  static constexpr int A_STAGE = BM * 128, B_STAGE = BN * 128;
+  static constexpr int A_GROUPS = BM / 8;                             // wave-wide loads (8 rows each) per K tile of A
+  static constexpr int A_LOADS = (A_GROUPS + 3) / 4;                  // per computing wave
+  static constexpr int B_LOADS = BN / 32;                             // per loading wave
+  static constexpr int NA = BM >= 128 ? 4 : 6;                        // ring depths: A comes from the L2, B from HBM
+  static constexpr int NBR_FIT = (160 * 1024 - NA * A_STAGE) / B_STAGE;
+  static constexpr int NBR = NBR_FIT > 10 ? 10 : NBR_FIT;
+  static constexpr int LDS_BYTES = NA * A_STAGE + NBR * B_STAGE;
+  static constexpr int PENDING_A = (NA - 2) * A_LOADS, PENDING_B = (NBR - 2) * B_LOADS;
+  static constexpr int TILE_WORDS = BM * BN;                          // fp32 words of one partial tile
+  static_assert(MB >= 1 && NB >= 1 && PENDING_B <= 63 && PENDING_A <= 63, "tile shape");
+};
+
+template <bool BF16, class T>
+__global__ __launch_bounds__(T::THREADS) void ag_gemm_splitk_kernel(const AgGemmDecodeParams p) {
+  const int K = p.k * (BF16 ? 2 : 1);   // bytes per row of A and of B
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  if ((int)blockIdx.x < p.num_producers) {
+    const size_t shard_bytes = (size_t)p.m_per_rank * K;
+    produce_chunks<T::THREADS>(
+        p.world, shard_bytes, blockIdx.x, p.num_producers, p.teams, p.epoch,
+        [&](int i) { return (void*)(p.workspace + (size_t)p.order[i] * shard_bytes); },
+        [&](int i) { return p.shard[p.order[i]]; }, [&](int i) { return p.flags + p.order[i]; },
+        [&](int i) { return p.arrivals + p.order[i]; });
+    return;
+  }
+  // work-group -> (tile, split): tiles are dealt to the chiplets in turn and the S splits of a tile are S
+  // consecutive work-groups of one chiplet, so the partials of a tile meet in one L2
+  const int wg = blockIdx.x - p.num_producers;
+  const int slot = wg / p.num_xcd;
+  const int tile = (slot / p.splits) * p.num_xcd + wg % p.num_xcd, ks = slot % p.splits;
+  const int ntiles = p.npm * p.npn;
+  if (tile >= ntiles) return;
+  const TileOrder order{p.npm, p.npn, p.group_m, 0, 0};
+  const TileSpan t = tile_of_workgroup(tile, order, kOrderGather, p.m, p.m_per_rank, p.rank, p.world, p.nnodes, T::BM);
+  const int m0 = t.pid_m * T::BM, n0 = t.pid_n * T::BN;
+  if (p.schedule && threadIdx.x == 0) {
+    int32_t* rec = p.schedule + 4 * ((size_t)tile * p.splits + ks);
+    rec[0] = t.pid_m; rec[1] = t.pid_n; rec[2] = t.first; rec[3] = t.last;
+  }
+
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int kt_begin = ks * p.kt_per_split;
+  const int kt_n = min((K + T::BK - 1) / T::BK, kt_begin + p.kt_per_split) - kt_begin;   // >= 1 by the host's choice of S
+  char* lds_a = lds;
+  char* lds_b = lds + T::NA * T::A_STAGE;
+  const bool loader = wave >= 4;
+  const int lw = wave - 4;
+
+  // per-lane source addresses at this split's first K tile, and the byte offset of the lane's chunk in a K tile
+  const char* src_ptr[T::A_LOADS > T::B_LOADS ? T::A_LOADS : T::B_LOADS];
+  int src_kc[T::A_LOADS > T::B_LOADS ? T::A_LOADS : T::B_LOADS];
+  if (loader) {
+#pragma unroll
+    for (int i = 0; i < T::B_LOADS; ++i) {
+      const int r = (lw * T::B_LOADS + i) * 8 + (lane >> 3);
+      const int c = (lane & 7) ^ swz128(r);
+      src_kc[i] = c * 16;
+      src_ptr[i] = p.b + (size_t)min(n0 + r, p.n - 1) * K + (size_t)kt_begin * T::BK + c * 16;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < T::A_LOADS; ++i) {
+      const int r = (wave * T::A_LOADS + i) * 8 + (lane >> 3);
+      const int c = (lane & 7) ^ swz128(r);
+      src_kc[i] = c * 16;
+      src_ptr[i] = p.workspace + (size_t)min(m0 + r, p.m - 1) * K + (size_t)kt_begin * T::BK + c * 16;
+    }
+  }
+  // K tile i of this split (tiles past its end re-load its last tile into a free stage: the number of
+  // loads per iteration stays fixed, which the in-order wait counts rely on)
+  auto issue_a = [&](int i) {
+    const int kt = min(i, kt_n - 1);
+    char* stage = lds_a + (i % T::NA) * T::A_STAGE;
+#pragma unroll
+    for (int j = 0; j < T::A_LOADS; ++j) {
+      const int group = wave * T::A_LOADS + j;
+      if (group >= T::A_GROUPS) break;   // fewer row groups than waves (16-row tiles)
+      const char* src = src_ptr[j] + (size_t)kt * T::BK;
+      if ((kt_begin + kt) * T::BK + src_kc[j] >= K) src = (const char*)&kZeroChunk;
+      __builtin_amdgcn_global_load_lds(src, DITRON_LDS(stage + group * 1024), 16, 0, 0);
+    }
+  };
+  auto issue_b = [&](int i) {
+    const int kt = min(i, kt_n - 1);
+    char* stage = lds_b + (i % T::NBR) * T::B_STAGE;
+#pragma unroll
+    for (int j = 0; j < T::B_LOADS; ++j) {
+      const char* src = src_ptr[j] + (size_t)kt * T::BK;
+      if ((kt_begin + kt) * T::BK + src_kc[j] >= K) src = (const char*)&kZeroChunk;
+      __builtin_amdgcn_global_load_lds(src, DITRON_LDS(stage + (lw * T::B_LOADS + j) * 1024), 16, 0, 0);
+    }
+  };
+
+  // wave 0 looks at the flags; the loaders start B at once (it does not depend on the gather)
+  if (wave == 0 && p.wait) flag_wait_wave(p.flags, t.first, t.last - t.first + 1, p.epoch, p.spin_limit, p.status);
+  if (loader) {
+#pragma unroll 1
+    for (int i = 0; i < T::NBR - 1; ++i) issue_b(i);
+  }
+  barrier_no_drain();                           // flags seen by wave 0 -> A may be read by everyone
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+
+  f32x4_t acc[T::NB][T::MB];
+#pragma unroll
+  for (int nb = 0; nb < T::NB; ++nb)
+#pragma unroll
+    for (int mb = 0; mb < T::MB; ++mb) acc[nb][mb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  const int wm = loader ? 0 : wave / T::WN, wn = loader ? 0 : wave % T::WN;
+  const int l16 = lane & 15, g = lane >> 4;
+
+  if (loader) {
+#pragma unroll 1
+    for (int i = 0; i < kt_n; ++i) {
+      // B(i) has landed once at most PENDING_B younger loads of this wave are outstanding
+      __builtin_amdgcn_s_waitcnt(0x0F70 | (T::PENDING_B & 0xF) | ((T::PENDING_B >> 4) << 14));
+      barrier_no_drain();
+      issue_b(i + T::NBR - 1);                  // into the stage every wave finished reading before this barrier
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < T::NA - 1; ++j) issue_a(j);
+    const int sw = swz128(l16);
+    const int off0 = ((2 * g) ^ sw) * 16, off1 = ((2 * g + 1) ^ sw) * 16;
+#pragma unroll 1
+    for (int i = 0; i < kt_n; ++i) {
+      __builtin_amdgcn_s_waitcnt(0x0F70 | (T::PENDING_A & 0xF) | ((T::PENDING_A >> 4) << 14));
+      barrier_no_drain();
+      issue_a(i + T::NA - 1);
+      const char* sa = lds_a + (i % T::NA) * T::A_STAGE + (wm * T::WTM + l16) * 128;
+      const char* sb = lds_b + (i % T::NBR) * T::B_STAGE + (wn * T::WTN + l16) * 128;
+      if constexpr (BF16) {
+        // MFMA j of the K tile takes k = 32 j + 8 g .. + 7 of the lane's row: 16-byte chunk 4 j + g
+        bf16x8_t af[T::MB][2], bf[T::NB][2];
+#pragma unroll
+        for (int mb = 0; mb < T::MB; ++mb)
+#pragma unroll
+          for (int j = 0; j < 2; ++j) af[mb][j] = *(const bf16x8_t*)(sa + mb * 16 * 128 + (((4 * j + g) ^ sw) * 16));
+#pragma unroll
+        for (int nb = 0; nb < T::NB; ++nb)
+#pragma unroll
+          for (int j = 0; j < 2; ++j) bf[nb][j] = *(const bf16x8_t*)(sb + nb * 16 * 128 + (((4 * j + g) ^ sw) * 16));
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int nb = 0; nb < T::NB; ++nb)
+#pragma unroll
+            for (int mb = 0; mb < T::MB; ++mb)
+              acc[nb][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bf[nb][j], af[mb][j], acc[nb][mb], 0, 0, 0);
+      } else {
+        i32x8_t af[T::MB], bf[T::NB];
+#pragma unroll
+        for (int mb = 0; mb < T::MB; ++mb) {
+          const u32x4_t lo = *(const u32x4_t*)(sa + mb * 16 * 128 + off0);
+          const u32x4_t hi = *(const u32x4_t*)(sa + mb * 16 * 128 + off1);
+          af[mb] = i32x8_t{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+        }
+#pragma unroll
+        for (int nb = 0; nb < T::NB; ++nb) {
+          const u32x4_t lo = *(const u32x4_t*)(sb + nb * 16 * 128 + off0);
+          const u32x4_t hi = *(const u32x4_t*)(sb + nb * 16 * 128 + off1);
+          bf[nb] = i32x8_t{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+        }
+#pragma unroll
+        for (int nb = 0; nb < T::NB; ++nb)
+#pragma unroll
+          for (int mb = 0; mb < T::MB; ++mb)
+            acc[nb][mb] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bf[nb], af[mb], acc[nb][mb], 0, 0, 0, 0, 0, 0);
+      }
+    }
+  }
+  // the redundant tail loads land before the LDS is used for anything else
+  wait_vmcnt0();
+
+  constexpr int BLOCKS = T::MB * T::NB;
+  if (p.splits > 1) {
+    // partial tile -> memory, in the lanes' own order: block (nb, mb) of wave w is 64 lanes x 16 bytes
+    f32x4_t* mine = (f32x4_t*)p.partials + (((size_t)tile * p.splits + ks) * 4 + wave) * (BLOCKS * 64);
+    if (!loader) {
+#pragma unroll
+      for (int nb = 0; nb < T::NB; ++nb)
+#pragma unroll
+        for (int mb = 0; mb < T::MB; ++mb) mine[(nb * T::MB + mb) * 64 + lane] = acc[nb][mb];
+    }
+    __syncthreads();   // every wave's stores have completed (the barrier waits for them) and the LDS is idle
+    int* s_last = (int*)lds;
+    if (threadIdx.x == 0) {
+      // release-only ticket; only the work-group that draws the last one pays for the acquire
+      const int old = __hip_atomic_fetch_add(p.tile_counters + tile, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+      const int last = old == p.splits - 1;
+      if (last) {
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        __hip_atomic_store(p.tile_counters + tile, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      *s_last = last;
+    }
+    __syncthreads();
+    if (!*s_last || loader) return;
+    // sum in split order; the own partial comes from the registers it is still in
+    const f32x4_t* first = (const f32x4_t*)p.partials + (((size_t)tile * p.splits) * 4 + wave) * (BLOCKS * 64);
+    f32x4_t tot[T::NB][T::MB];
+#pragma unroll 1
+    for (int s = 0; s < p.splits; ++s) {
+      const f32x4_t* part = first + (size_t)s * 4 * (BLOCKS * 64);
+#pragma unroll
+      for (int nb = 0; nb < T::NB; ++nb)
+#pragma unroll
+        for (int mb = 0; mb < T::MB; ++mb) {
+          const f32x4_t v = s == ks ? acc[nb][mb] : part[(nb * T::MB + mb) * 64 + lane];
+          tot[nb][mb] = s == 0 ? v : tot[nb][mb] + v;
+        }
+    }
+#pragma unroll
+    for (int nb = 0; nb < T::NB; ++nb)
+#pragma unroll
+      for (int mb = 0; mb < T::MB; ++mb) acc[nb][mb] = tot[nb][mb];
+  } else if (loader) {
+    return;
+  }
+
+#pragma unroll
+  for (int mb = 0; mb < T::MB; ++mb) {
+    const int m = m0 + wm * T::WTM + mb * 16 + l16;
+    if (m >= p.m) continue;
+    const float rs = p.a_scales ? p.a_scales[m / p.m_per_rank] : 1.f;
+#pragma unroll
+    for (int nb = 0; nb < T::NB; ++nb) {
+      const int n = n0 + wn * T::WTN + nb * 16 + g * 4;
+      if (n >= p.n) continue;   // n is a multiple of 4 and p.n of 8: all four columns are inside
+      float x[4];
+#pragma unroll
+      for (int v = 0; v < 4; ++v) x[v] = acc[nb][mb][v] * rs * (p.b_scales ? p.b_scales[n + v] : 1.f);
+      bf16x4_t o = {(__bf16)x[0], (__bf16)x[1], (__bf16)x[2], (__bf16)x[3]};
+      *(bf16x4_t*)(p.c + (size_t)m * p.n + n) = o;
+    }
+  }
+}
+
 }  // namespace ditron
 
 using namespace ditron;
+
+template <bool BF16, class T>
+static ditron_status_t launch_splitk(AgGemmDecodeParams& p, hipStream_t stream) {
+  if (!set_dynamic_lds<ag_gemm_splitk_kernel<BF16, T>>(T::LDS_BYTES)) return DITRON_ERR_HIP;
+  const int per_xcd = cdiv(p.npm * p.npn, p.num_xcd) * p.splits;   // work-groups of one chiplet
+  const unsigned grid = (unsigned)(p.num_producers + per_xcd * p.num_xcd);
+  hipLaunchKernelGGL((ag_gemm_splitk_kernel<BF16, T>), dim3(grid), dim3(T::THREADS), T::LDS_BYTES, stream, p);
+  return hipGetLastError() == hipSuccess ? DITRON_OK : DITRON_ERR_HIP;
+}
 
 extern "C" ditron_status_t ditron_ag_gemm_decode(const void* const* a_shards, const void* b, int b_layout, void* c,
                                                  const float* a_scales, const float* b_scales, void* workspace,
@@ -259,22 +529,36 @@ extern "C" ditron_status_t ditron_ag_gemm_decode(const void* const* a_shards, co
   p.epoch = epoch;
   p.spin_limit = tune.spin_limit;
   p.wait = producer_mode(flags) != Mode::kPreset;
-  TileChoice tc = choose_tile_decode(p.m, n, k);
-  if (p.nnodes > 1 && !node_order_is_bijection(p.m, tc.block_m, world, p.nnodes, rank, kOrderGather))
+  const size_t a_bytes = (size_t)p.m * k * (bf16 ? 2 : 1);
+  const DecodePlan plan = plan_decode(p.m, n, k * (bf16 ? 2 : 1), tune.decode_variant);
+  if (p.nnodes > 1 && !node_order_is_bijection(p.m, plan.block_m, world, p.nnodes, rank, kOrderGather))
     return DITRON_ERR_UNSUPPORTED;
+  const TileChoice tc = choose_tile_decode(p.m, n, k);
   p.group_m = tc.group_m;
   p.num_xcd = tc.num_xcd;
   p.per_xcd = tc.per_xcd;
-  const ProducerPlan pl = plan_producers((size_t)p.m * k * (bf16 ? 2 : 1), world);
+  const ProducerPlan pl = plan_producers(a_bytes, world);
   p.num_producers = emulate ? pl.producers : 0;
   p.teams = pl.teams;
-  p.npm = cdiv(p.m, DecodeTile::BM);
-  p.npn = cdiv(p.n, DecodeTile::BN);
-  auto kern = bf16 ? ag_gemm_decode_kernel<true> : ag_gemm_decode_kernel<false>;
+  p.npm = cdiv(p.m, plan.block_m);
+  p.npn = cdiv(p.n, plan.block_n);
+  p.splits = plan.splits;
+  p.kt_per_split = plan.kt_per_split;
+  p.partials = (float*)((char*)workspace + align256(a_bytes));
+  p.tile_counters = signals + 4 * world;
+  if (plan.splits > 1 && plan.ntiles > kTileCounterWords) return DITRON_ERR_UNSUPPORTED;   // cannot happen: S > 1 needs ntiles <= 128
+  const hipStream_t s = (hipStream_t)stream;
+  switch (plan.variant) {
+    case 2: return bf16 ? launch_splitk<true, SplitKTile<128, 128>>(p, s) : launch_splitk<false, SplitKTile<128, 128>>(p, s);
+    case 3: return bf16 ? launch_splitk<true, SplitKTile<128, 64>>(p, s) : launch_splitk<false, SplitKTile<128, 64>>(p, s);
+    case 4: return bf16 ? launch_splitk<true, SplitKTile<16, 128>>(p, s) : launch_splitk<false, SplitKTile<16, 128>>(p, s);
+    default: break;
+  }
   if (!(bf16 ? set_dynamic_lds<ag_gemm_decode_kernel<true>>(DecodeTile::LDS_BYTES)
              : set_dynamic_lds<ag_gemm_decode_kernel<false>>(DecodeTile::LDS_BYTES)))
     return DITRON_ERR_HIP;
+  auto kern = bf16 ? ag_gemm_decode_kernel<true> : ag_gemm_decode_kernel<false>;
   const unsigned grid = (unsigned)(p.num_producers + p.npm * p.npn);
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(DecodeTile::THREADS), DecodeTile::LDS_BYTES, (hipStream_t)stream, p);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(DecodeTile::THREADS), DecodeTile::LDS_BYTES, s, p);
   return hipGetLastError() == hipSuccess ? DITRON_OK : DITRON_ERR_HIP;
 }

@@ -45,7 +45,7 @@ extern "C" ditron_status_t ditron_ag_gemm_static(const void* const* a_shards, co
                                                  const int* arrival_order, int m_per_rank, int n, int k, int world,
                                                  int rank, int dtype, const ditron_tuning_t* tuning, void* stream) {
   if (world < 1 || world > DITRON_MAX_WORLD || m_per_rank <= 0 || n <= 0 || k <= 0) return DITRON_ERR_INVALID_ARG;
-  const size_t need = ditron_ag_gemm_workspace_bytes(m_per_rank, k, world, dtype);
+  const size_t need = ditron_ag_gemm_workspace_bytes(m_per_rank, n, k, world, dtype, b_layout, tuning);
   if (need == 0) return DITRON_ERR_INVALID_ARG;
   if (need > (size_t)DITRON_STATIC_WORKSPACE_BYTES || ditron_signal_words(world, 1) > kStaticSignalWords)
     return DITRON_ERR_WORKSPACE;

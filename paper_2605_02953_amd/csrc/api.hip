@@ -35,15 +35,27 @@ using namespace ditron;
 extern "C" size_t ditron_signal_words(int world, int chunks) {
   if (world < 1 || chunks < 1) return 0;
   // flags [world] + per-rank counters [world] + chunk flags [world*chunks] + chunk counters [world*chunks]
-  return (size_t)world * 2 + (size_t)world * chunks * 2;
+  // + the ticket counters of split output tiles
+  return (size_t)world * 2 + (size_t)world * chunks * 2 + kTileCounterWords;
 }
 
-extern "C" ditron_status_t ditron_tile_config(int op, int m, int n, int k, int dtype, int out[8]) {
+extern "C" ditron_status_t ditron_tile_config(int op, int m, int n, int k, int dtype, const ditron_tuning_t* tuning,
+                                              int out[DITRON_TILE_CONFIG_WORDS]) {
   if (!out || m <= 0 || n <= 0 || k <= 0 || op < 0 || op > 4) return DITRON_ERR_INVALID_ARG;
   if (dtype != DITRON_BF16 && dtype != DITRON_FP8_E4M3) return DITRON_ERR_INVALID_ARG;
   if (dtype == DITRON_FP8_E4M3 && op != 0) return DITRON_ERR_UNSUPPORTED;
+  const Tuning tune = resolve_tuning(tuning, 1);
+  if (!tune.valid) return DITRON_ERR_INVALID_ARG;
   const bool decode = dtype == DITRON_FP8_E4M3 || (op == 0 && bf16_ag_is_decode_shaped(m, n));
   TileChoice t = decode ? choose_tile_decode(m, n, k) : choose_tile(m, n, k);
+  int splits = 1;
+  if (decode) {
+    const DecodePlan plan = plan_decode(m, n, k * (dtype == DITRON_BF16 ? 2 : 1), tune.decode_variant);
+    t.block_m = plan.block_m;
+    t.block_n = plan.block_n;
+    splits = plan.splits;
+    if (plan.variant != 1) t.num_xcd = t.per_xcd = 0;   // the split-K kernel applies no remap to the tile ids
+  }
   if (op == 2) {  // the grouped GEMM has its own row tile; its column block is chosen per call; m is max_rows
     t.big = false;
     t.block_m = kMoeBlockM;
@@ -59,13 +71,26 @@ extern "C" ditron_status_t ditron_tile_config(int op, int m, int n, int k, int d
   out[6] = t.threads;
   // operand staging of the tile engine: 1 = straight into LDS (256 x 256 tiles, B stored [n, k], whole K tiles, K <= 8192)
   out[7] = (!decode && op != 2 && op != 4 && t.big && use_direct_staging(k)) ? 1 : 0;
+  out[8] = splits;
+  out[9] = 0;
   return DITRON_OK;
 }
 
-extern "C" size_t ditron_ag_gemm_workspace_bytes(int m_per_rank, int k, int world, int dtype) {
-  if (m_per_rank <= 0 || k <= 0 || world < 1 || world > DITRON_MAX_WORLD) return 0;
+extern "C" size_t ditron_ag_gemm_workspace_bytes(int m_per_rank, int n, int k, int world, int dtype, int b_layout,
+                                                 const ditron_tuning_t* tuning) {
+  if (m_per_rank <= 0 || n <= 0 || k <= 0 || world < 1 || world > DITRON_MAX_WORLD) return 0;
   if (dtype != DITRON_BF16 && dtype != DITRON_FP8_E4M3) return 0;
-  return (size_t)world * m_per_rank * k * (dtype == DITRON_BF16 ? 2 : 1);
+  if (b_layout != DITRON_B_KN && b_layout != DITRON_B_NK) return 0;
+  const Tuning tune = resolve_tuning(tuning, world);
+  if (!tune.valid) return 0;
+  const int esize = dtype == DITRON_BF16 ? 2 : 1;
+  const int m = world * m_per_rank;
+  const size_t gathered = (size_t)m * k * esize;
+  const bool decode = dtype == DITRON_FP8_E4M3 || (b_layout == DITRON_B_NK && bf16_ag_is_decode_shaped(m, n));
+  if (!decode) return gathered;
+  // decode-shaped problems: the fp32 partial tiles of the split contraction follow the gathered operand
+  const DecodePlan plan = plan_decode(m, n, k * esize, tune.decode_variant);
+  return plan.partial_bytes ? align256(gathered) + plan.partial_bytes : gathered;
 }
 
 extern "C" size_t ditron_moe_workspace_bytes(int tokens_per_rank, int hidden, int world) {
@@ -85,16 +110,24 @@ extern "C" ditron_status_t ditron_schedule_dump(int op, int m, int n, int k, int
   const Tuning tune = resolve_tuning(tuning, op == 3 ? 1 : world);
   if (!tune.valid) return DITRON_ERR_INVALID_ARG;
   const bool decode = op == 0 && (dtype == DITRON_FP8_E4M3 || (b_layout == DITRON_B_NK && bf16_ag_is_decode_shaped(m, n)));
-  const TileChoice tc = decode ? choose_tile_decode(m, n, k) : choose_tile(m, n, k);
+  TileChoice tc = decode ? choose_tile_decode(m, n, k) : choose_tile(m, n, k);
+  int splits = 1;
+  if (decode) {
+    const DecodePlan plan = plan_decode(m, n, k * (dtype == DITRON_BF16 ? 2 : 1), tune.decode_variant);
+    tc.block_m = plan.block_m;
+    tc.block_n = plan.block_n;
+    splits = plan.splits;
+    if (plan.variant != 1) tc.num_xcd = tc.per_xcd = 0;
+  }
   const TileOrder o{cdiv(m, tc.block_m), cdiv(n, tc.block_n), tc.group_m, tc.num_xcd, tc.per_xcd};
   const int ntiles = o.npm * o.npn;
-  *count = ntiles;
-  if (ntiles > capacity) return DITRON_ERR_WORKSPACE;
+  *count = ntiles * splits;
+  if (*count > capacity) return DITRON_ERR_WORKSPACE;
   if (op != 3 && tune.num_nodes > 1 &&
       !node_order_is_bijection(m, tc.block_m, world, tune.num_nodes, rank, op == 0 ? kOrderGather : kOrderScatter))
     return DITRON_ERR_UNSUPPORTED;
   for (int wg = 0; wg < ntiles; ++wg) {
-    int32_t* rec = out + (size_t)DITRON_SCHEDULE_WORDS * wg;
+    int32_t* rec = out + (size_t)DITRON_SCHEDULE_WORDS * wg * splits;
     if (op == 3) {
       int pid_m, pid_n;
       grouped_order(xcd_remap(wg, ntiles, o.num_xcd, o.per_xcd), o.npm, o.npn, o.group_m, pid_m, pid_n);
@@ -102,7 +135,11 @@ extern "C" ditron_status_t ditron_schedule_dump(int op, int m, int n, int k, int
     } else {
       const TileSpan t = tile_of_workgroup(wg, o, op == 0 ? kOrderGather : kOrderScatter, m, m / world, rank, world,
                                            tune.num_nodes, tc.block_m);
-      rec[0] = t.pid_m; rec[1] = t.pid_n; rec[2] = t.first; rec[3] = t.last;
+      // the splits of a tile share its record
+      for (int ks = 0; ks < splits; ++ks) {
+        int32_t* r = rec + DITRON_SCHEDULE_WORDS * ks;
+        r[0] = t.pid_m; r[1] = t.pid_n; r[2] = t.first; r[3] = t.last;
+      }
     }
   }
   return DITRON_OK;

@@ -100,6 +100,32 @@ inline TileChoice choose_tile_decode(int /*m*/, int /*n*/, int /*k*/) {
   return t;
 }
 
+// Decode-shaped problems: which kernel, tile and K split.  Variant 1 is the 128 x 32 tile over the whole
+// contraction; 2 / 3 are 128 x 128 / 128 x 64 tiles with the contraction split over S work-groups; 4 is the
+// per-shard form, 16-row tiles (one shard's rows at the decode shape: a tile waits for that shard only).
+// S doubles while the grid stays within one work-group per compute unit, at most 8, and every split keeps at
+// least four 128-byte K tiles.
+constexpr int kTileCounterWords = 128;   // signal words behind the flags: one ticket counter per split tile
+struct DecodePlan {
+  int variant, block_m, block_n, splits, kt_per_split, ntiles;
+  size_t partial_bytes;   // fp32 partial tiles, behind the gathered operand in the workspace
+};
+inline DecodePlan plan_decode(int m, int n, int k_bytes, int variant) {
+  DecodePlan d{};
+  d.variant = variant == 0 ? 2 : variant;
+  d.block_m = d.variant == 4 ? 16 : 128;
+  d.block_n = d.variant == 1 ? 32 : (d.variant == 3 ? 64 : 128);
+  d.ntiles = cdiv(m, d.block_m) * cdiv(n, d.block_n);
+  const int kt = cdiv(k_bytes, 128);
+  d.splits = 1;
+  if (d.variant != 1)
+    while ((long)d.ntiles * d.splits * 2 <= 256 && d.splits * 2 <= 8 && kt / (d.splits * 2) >= 4) d.splits *= 2;
+  d.kt_per_split = cdiv(kt, d.splits);
+  d.partial_bytes = d.splits > 1 ? (size_t)d.ntiles * d.splits * d.block_m * d.block_n * sizeof(float) : 0;
+  return d;
+}
+inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
 // How many work-groups play the peers, and into how many teams they split (= chunks in flight
 // at once).  On one GPU the copies are compute-unit work, so the cheapest emulation delivers
 // everything as early and as fast as possible: enough work-groups to saturate HBM for a large
@@ -173,7 +199,7 @@ struct Tuning {
 inline Tuning resolve_tuning(const ditron_tuning_t* t, int world) {
   Tuning r{1, 1u << 20, 0, true};
   if (!t) return r;
-  if (t->num_nodes < 0 || t->num_nodes > DITRON_MAX_WORLD || t->decode_variant < 0) r.valid = false;
+  if (t->num_nodes < 0 || t->num_nodes > DITRON_MAX_WORLD || t->decode_variant < 0 || t->decode_variant > 4) r.valid = false;
   for (int v : t->reserved) r.valid = r.valid && v == 0;
   if (t->num_nodes > 0) r.num_nodes = t->num_nodes;
   if (t->spin_limit) r.spin_limit = t->spin_limit;

@@ -25,11 +25,17 @@ def nk(b_kn):
 class AgGemmRun:
     """Buffers for repeated ditron_ag_gemm calls on one problem shape."""
 
-    def __init__(self, B, world, m_per_rank, n, k, esize=2):
+    def __init__(self, B, world, m_per_rank, n, k, esize=2, b_layout=None, tuning=None):
         self.B, self.world, self.m_per_rank, self.n, self.k = B, world, m_per_rank, n, k
         m = world * m_per_rank
         dt = torch.int16 if esize == 2 else torch.uint8
-        self.workspace = torch.zeros((m, k), dtype=dt, device="cuda")
+        # the library says how large the workspace is; it starts with the gathered operand
+        nbytes = B.ag_gemm_workspace_bytes(m_per_rank, n, k, world, B.BF16 if esize == 2 else B.FP8_E4M3,
+                                           B.B_NK if b_layout is None else b_layout, tuning)
+        assert nbytes >= m * k * esize
+        self.ws_raw = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+        self.workspace = self.ws_raw[:m * k * esize].view(dt).view(m, k)
+        self.tuning = tuning
         self.c = torch.zeros((m, n), dtype=torch.int16, device="cuda")
         self.signals = torch.zeros(B.signal_words(world, 1), dtype=torch.int32, device="cuda")
         self.status = torch.zeros(B.STATUS_WORDS, dtype=torch.int32, device="cuda")
@@ -43,8 +49,9 @@ class AgGemmRun:
         if schedule is not None:
             flags |= B.DUMP_SCHEDULE
         st = B.ag_gemm(shards_dev, b_dev, B.B_NK if b_layout is None else b_layout, self.c, a_scales, b_scales,
-                       self.workspace, self.signals, self.status, schedule, order, self.m_per_rank, self.n,
-                       self.k, self.world, rank, B.BF16 if dtype is None else dtype, self.epoch, flags, stream, tuning)
+                       self.ws_raw, self.signals, self.status, schedule, order, self.m_per_rank, self.n,
+                       self.k, self.world, rank, B.BF16 if dtype is None else dtype, self.epoch, flags, stream,
+                       self.tuning if tuning is None else tuning)
         return st
 
 

@@ -30,7 +30,7 @@ def _run(B, cfg, shards, b_kn, rank=None, order=None, want_schedule=False, kn=Fa
     sched = None
     if want_schedule:
         st, tc = B.tile_config(4 if kn else 0, cfg.m, cfg.n, cfg.k)
-        sched = torch.full((4 * tc["ntiles"],), -1, dtype=torch.int32, device="cuda")
+        sched = torch.full((4 * tc["ntiles"] * tc["splits"],), -1, dtype=torch.int32, device="cuda")
     st = run(sh, bd, rank, order=order, schedule=sched, b_layout=B.B_KN if kn else B.B_NK, tuning=tuning)
     assert st == B.OK, B.status_string(st)
     torch.cuda.synchronize()
@@ -61,7 +61,8 @@ def _check_schedule(B, cfg, rank, sched, kn=False):
     want = []
     for wg in range(nt):
         pid = osch.xcd_remap(wg, nt, tc["num_xcd"], tc["per_xcd"]) if tc["num_xcd"] else wg
-        want.append(osch.ag_tile(pid, cfg.m, cfg.n, tc["block_m"], tc["block_n"], tc["group_m"], rank, cfg.world))
+        # work-groups that share a tile's contraction share its record
+        want += [osch.ag_tile(pid, cfg.m, cfg.n, tc["block_m"], tc["block_n"], tc["group_m"], rank, cfg.world)] * tc["splits"]
     assert np.array_equal(sched, np.asarray(want, dtype=np.int32))
 
 
@@ -198,7 +199,7 @@ def test_tile_rows_follow_the_multi_node_order(B, world, nnodes, m_r, n, k):
             pm, pn = osch.grouped_order(pid, npm, npn, tc["group_m"])
             pm = osch.ag_swizzle_multinode(pm, cfg.m, rank, world, nnodes, tc["block_m"])
             row0 = pm * tc["block_m"]
-            want.append((pm, pn, row0 // m_r, (min(row0 + tc["block_m"], cfg.m) - 1) // m_r))
+            want += [(pm, pn, row0 // m_r, (min(row0 + tc["block_m"], cfg.m) - 1) // m_r)] * tc["splits"]
         assert np.array_equal(sched, np.asarray(want, dtype=np.int32))
         # the host evaluation of the schedule is the same list
         st, host = B.schedule_dump(0, cfg.m, n, k, world, rank, tuning=B.tuning(num_nodes=nnodes))

@@ -21,14 +21,15 @@ def B():
 from gpu_util import to_dev, bits, nk, AgGemmRun  # noqa: E402
 
 
-def _run(B, cfg, a, sa, b, sb, rank=None, order=None, want_schedule=False):
+def _run(B, cfg, a, sa, b, sb, rank=None, order=None, want_schedule=False, variant=0):
     rank = cfg.rank if rank is None else rank
-    run = AgGemmRun(B, cfg.world, cfg.m_per_rank, cfg.n, cfg.k, esize=1)
+    tuning = B.tuning(decode_variant=variant)
+    run = AgGemmRun(B, cfg.world, cfg.m_per_rank, cfg.n, cfg.k, esize=1, tuning=tuning)
     sched = None
-    st, tc = B.tile_config(0, cfg.m, cfg.n, cfg.k, B.FP8_E4M3)
+    st, tc = B.tile_config(0, cfg.m, cfg.n, cfg.k, B.FP8_E4M3, tuning)
     assert st == B.OK
     if want_schedule:
-        sched = torch.full((4 * tc["ntiles"],), -1, dtype=torch.int32, device="cuda")
+        sched = torch.full((4 * tc["ntiles"] * tc["splits"],), -1, dtype=torch.int32, device="cuda")
     st = run([to_dev(x) for x in a], to_dev(nk(b)), rank, order=order, schedule=sched, dtype=B.FP8_E4M3,
              a_scales=None if sa is None else to_dev(sa), b_scales=None if sb is None else to_dev(sb))
     assert st == B.OK, B.status_string(st)
@@ -36,10 +37,17 @@ def _run(B, cfg, a, sa, b, sb, rank=None, order=None, want_schedule=False):
     assert run.status.cpu().tolist()[0] == 0
     assert np.array_equal(run.workspace.cpu().numpy(), oag.gather(a))
     if want_schedule:
+        # one record per (tile, split of the contraction): the splits of a tile share the tile's record
         nt = tc["ntiles"]
-        want = [osch.ag_tile(osch.xcd_remap(w, nt, tc["num_xcd"], tc["per_xcd"]), cfg.m, cfg.n, tc["block_m"],
-                             tc["block_n"], tc["group_m"], rank, cfg.world) for w in range(nt)]
+        want = []
+        for w in range(nt):
+            pid = osch.xcd_remap(w, nt, tc["num_xcd"], tc["per_xcd"]) if tc["num_xcd"] else w
+            want += [osch.ag_tile(pid, cfg.m, cfg.n, tc["block_m"], tc["block_n"], tc["group_m"], rank, cfg.world)] * tc["splits"]
         assert np.array_equal(sched.cpu().numpy().reshape(-1, 4), np.asarray(want, dtype=np.int32))
+        st, host = B.schedule_dump(0, cfg.m, cfg.n, cfg.k, cfg.world, rank, B.FP8_E4M3, tuning=tuning)
+        assert st == B.OK and host == want
+        # the ticket counters of the split tiles are back at zero
+        assert not run.signals.cpu().numpy()[cfg.world:].any()
     return bits(run.c)
 
 
@@ -61,12 +69,15 @@ def _integer_fp8(cfg, seed):
     (8, 256, 2048, 384),     # many tiles
     (2, 640, 2560, 512),     # several row tiles per shard
 ])
-def test_fp8_integer_inputs_bit_exact(B, world, m_r, n, k):
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4])
+def test_fp8_integer_inputs_bit_exact(B, world, m_r, n, k, variant):
     cfg = synth.CONFIGS[5].scaled(world=world, m_per_rank=m_r, n=n, k=k, rank=world - 1)
     a, b = _integer_fp8(cfg, 3)
-    got = _run(B, cfg, a, None, b, None, want_schedule=True)
+    got = _run(B, cfg, a, None, b, None, want_schedule=True, variant=variant)
     want = formats.encode_bf16_rne(oag.ag_gemm(a, b, dtype="e4m3").astype(np.float32))
     assert np.array_equal(got, want)
+    if variant:
+        return
     # power-of-two scales keep everything exact as well
     sa = np.array([2.0 ** (s % 3 - 1) for s in range(world)], dtype=np.float32)
     sb = np.array([2.0 ** (j % 4 - 2) for j in range(n)], dtype=np.float32)
@@ -79,8 +90,10 @@ def test_fp8_rank_and_order_independent(B):
     cfg = synth.CONFIGS[5].scaled(world=4, m_per_rank=48, n=512, k=768)
     a, sa, b, sb = synth.fp8_ag_gemm_inputs(cfg)
     ref = None
-    for rank, order in [(0, None), (3, None), (1, [2, 0, 3, 1]), (2, [3, 2, 1, 0])]:
-        got = _run(B, cfg, a, sa, b, sb, rank=rank, order=order)
+    # every variant too: the split contraction is summed in split order whoever finishes last, so even
+    # the variants that split agree with themselves bit for bit from run to run
+    for rank, order, variant in [(0, None, 0), (3, None, 0), (1, [2, 0, 3, 1], 0), (2, [3, 2, 1, 0], 0)]:
+        got = _run(B, cfg, a, sa, b, sb, rank=rank, order=order, variant=variant)
         if ref is None:
             ref = got
             err = compare.max_row_rel_error(formats.decode_bf16(got),
@@ -89,10 +102,11 @@ def test_fp8_rank_and_order_independent(B):
         assert np.array_equal(got, ref)
 
 
-def test_cfg5_full_size(B):
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4])
+def test_cfg5_full_size(B, variant):
     cfg = synth.CONFIGS[5]
     a, sa, b, sb = synth.fp8_ag_gemm_inputs(cfg)
-    got = _run(B, cfg, a, sa, b, sb, want_schedule=True)
+    got = _run(B, cfg, a, sa, b, sb, want_schedule=True, variant=variant)
     ref = oag.ag_gemm(a, b, dtype="e4m3", a_scales=sa, b_scales=sb)
     err = compare.max_row_rel_error(formats.decode_bf16(got), ref)
     assert err <= TOL_FP8, err

@@ -31,11 +31,13 @@ def test_every_declared_symbol_is_exported(B):
 
 
 def test_sizes_and_strings(B):
-    assert B.signal_words(8, 1) == 32 and B.signal_words(8, 4) == 80 and B.signal_words(0, 1) == 0
+    assert B.signal_words(8, 1) == 32 + 128 and B.signal_words(8, 4) == 80 + 128 and B.signal_words(0, 1) == 0
     # the gathered operand: world * rows * k elements of the operand type
-    assert B.ag_gemm_workspace_bytes(1024, 8192, 8) == 8 * 1024 * 8192 * 2
-    assert B.ag_gemm_workspace_bytes(16, 8192, 8, B.FP8_E4M3) == 128 * 8192
-    assert B.ag_gemm_workspace_bytes(0, 8192, 8) == 0 and B.ag_gemm_workspace_bytes(16, 8192, 8, 5) == 0
+    assert B.ag_gemm_workspace_bytes(1024, 3584, 8192, 8) == 8 * 1024 * 8192 * 2
+    # decode shape: the gathered fp8 operand, then 64 tiles x 4 splits of 128 x 128 fp32 partials
+    assert B.ag_gemm_workspace_bytes(16, 8192, 8192, 8, B.FP8_E4M3) == 128 * 8192 + 64 * 4 * 128 * 128 * 4
+    assert B.ag_gemm_workspace_bytes(16, 8192, 8192, 8, B.FP8_E4M3, tuning=B.tuning(decode_variant=1)) == 128 * 8192
+    assert B.ag_gemm_workspace_bytes(0, 8, 8192, 8) == 0 and B.ag_gemm_workspace_bytes(16, 8, 8192, 8, 5) == 0
     assert B.moe_workspace_bytes(1024, 4096, 8) == 8 * 1024 * 4096 * 2 and B.moe_workspace_bytes(1024, 0, 8) == 0
     assert B.status_string(B.OK) == "ok" and "time" in B.status_string(B.ERR_TIMEOUT)
     assert B.moe_max_tiles(4096, 8) == 4096 // 128 + 8
@@ -44,14 +46,20 @@ def test_sizes_and_strings(B):
 def test_tile_config(B):
     st, tc = B.tile_config(0, 8192, 3584, 8192)
     assert st == B.OK and (tc["block_m"], tc["block_n"], tc["ntiles"]) == (256, 256, 448)
-    st, tc = B.tile_config(0, 256, 256, 256)           # few tiles, B stored [n, k]: the decode kernel's 128 x 32 tile
-    assert st == B.OK and (tc["block_m"], tc["block_n"], tc["ntiles"]) == (128, 32, 16)
+    st, tc = B.tile_config(0, 256, 256, 256)           # few tiles, B stored [n, k]: the decode kernel's 128 x 128 tile
+    assert st == B.OK and (tc["block_m"], tc["block_n"], tc["ntiles"], tc["splits"]) == (128, 128, 4, 1)
+    st, tc = B.tile_config(0, 256, 256, 256, tuning=B.tuning(decode_variant=1))
+    assert st == B.OK and (tc["block_m"], tc["block_n"], tc["ntiles"], tc["splits"]) == (128, 32, 16, 1)
     st, tc = B.tile_config(4, 256, 256, 256)           # B stored [k, n]: the tile engine
     assert st == B.OK and (tc["block_m"], tc["block_n"], tc["ntiles"]) == (128, 128, 4)
     st, tc = B.tile_config(0, 2048, 2048, 256)
     assert st == B.OK and (tc["block_m"], tc["block_n"], tc["ntiles"]) == (128, 128, 256)
-    st, tc = B.tile_config(0, 128, 8192, 8192, B.FP8_E4M3)
-    assert st == B.OK and (tc["block_m"], tc["block_n"], tc["ntiles"]) == (128, 32, 256)
+    st, tc = B.tile_config(0, 128, 8192, 8192, B.FP8_E4M3)     # the decode shape: 64 tiles, the contraction split in 4
+    assert st == B.OK and (tc["block_m"], tc["block_n"], tc["ntiles"], tc["splits"]) == (128, 128, 64, 4)
+    st, tc = B.tile_config(0, 128, 8192, 8192, B.FP8_E4M3, B.tuning(decode_variant=3))
+    assert st == B.OK and (tc["block_m"], tc["block_n"], tc["ntiles"], tc["splits"]) == (128, 64, 128, 2)
+    st, tc = B.tile_config(0, 128, 8192, 8192, B.FP8_E4M3, B.tuning(decode_variant=4))     # one tile per shard and column block
+    assert st == B.OK and (tc["block_m"], tc["block_n"], tc["ntiles"], tc["splits"]) == (16, 128, 512, 1)
     assert B.tile_config(7, 1, 1, 1)[0] == B.ERR_INVALID_ARG
 
 
