@@ -662,9 +662,15 @@ def bench_fp8(args):
     it = [0]
 
     def make_step(r, flags=None):
+        # the arguments are marshalled once per weight copy; a step only advances the epoch
+        calls = [B.PreparedAgGemm(ad if flags is None else None, bd_, B.B_NK, r.c, sad, sbd, r.ws_raw, r.signals, r.status, None,
+                                  None, cfg.m_per_rank, cfg.n, cfg.k, cfg.world, cfg.rank, B.FP8_E4M3,
+                                  B.EMULATE_PRODUCER if flags is None else flags, tuning=r.tuning) for bd_ in bds]
+
         def step():
             it[0] += 1
-            st = r(ad if flags is None else None, bds[it[0] % nsets], cfg.rank, dtype=B.FP8_E4M3, a_scales=sad, b_scales=sbd, flags=flags)
+            r.epoch += 1
+            st = calls[it[0] % nsets](r.epoch)
             if st != B.OK:
                 raise RuntimeError(B.status_string(st))
         return step
@@ -686,9 +692,22 @@ def bench_fp8(args):
             fn()
             b_.record()
         torch.cuda.synchronize()
-        return _quantiles_us(ev)
+        q = _quantiles_us(ev)
+        # 100 calls between one pair of events: launches queue up behind one another, so this is the
+        # kernel's own duration plus the gap between two dispatches
+        e0, e1 = _events(torch, 1)[0]
+        e0.record()
+        for _ in range(100):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        q["back_to_back"] = e0.elapsed_time(e1) * 10.0
+        return q
 
     preset = events_us(make_step(run, B.FLAGS_PRESET))
+    # what one tiny launch costs between two events on this machine (the floor of any single-call latency)
+    tiny = torch.zeros((1, 8), dtype=torch.int16, device="cuda")
+    floor_us = events_us(lambda: B.reduce_slots([tiny], tiny.clone(), None, run.status, 1, 8, 1, 1, 1))
     variants = {}
     names = {1: "128x32 tiles, whole contraction", 2: "128x128 tiles, split contraction", 3: "128x64 tiles, split contraction",
              4: "16-row tiles, one per shard"}
@@ -714,6 +733,7 @@ def bench_fp8(args):
                      "traffic": MEASURED_TRAFFIC.get("cfg5"), "kernel": "ag_gemm_splitk_kernel (fp8)", "kernel_ms": ev_ms,
                      "bytes": alg_bytes},
         "flags_preset_us": preset,
+        "tiny_launch_us": floor_us,
         "decode_variants": variants,
     }
     out["config"]["latency_us_quantiles"] = quant

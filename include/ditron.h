@@ -185,7 +185,11 @@ ditron_status_t ditron_schedule_dump(int op, int m, int n, int k, int world, int
  *  b_scales      device float[n]     (fp8: one scale per output column) or NULL
  *                fp8 result is (sum_k a*b) * a_scales[row / m_per_rank] * b_scales[col]
  *  workspace     device, ditron_ag_gemm_workspace_bytes(...) bytes; starts with the gathered A,
- *                [world*m_per_rank, k] in `dtype` (written by the producer, read by the GEMM)
+ *                [world*m_per_rank, k] in `dtype` (written by the producer, read by the GEMM).
+ *                For decode-shaped problems the partial tiles behind it are exchanged flag-in-data:
+ *                every 8-byte word carries the call's epoch, so like `signals` the workspace must be
+ *                zero-filled once before its first use, and the epoch must be nonzero and must not
+ *                repeat an earlier call's on the same workspace
  *  signals       device int32[ditron_signal_words(world, 1)]; flag s is word s
  *  status        device int32[DITRON_STATUS_WORDS]
  *  schedule_out  device int32[4 * tiles] or NULL; with DITRON_DUMP_SCHEDULE the GEMM
@@ -214,7 +218,9 @@ ditron_status_t ditron_ag_gemm(const void* const* a_shards, const void* b, int b
  * DITRON_EMULATE_PRODUCER mode (nobody else can reach the workspace); arguments as for ditron_ag_gemm.
  * DITRON_ERR_WORKSPACE if ditron_ag_gemm_workspace_bytes(m_per_rank, n, k, world, dtype, b_layout, tuning) exceeds
  * DITRON_STATIC_WORKSPACE_BYTES, before anything is enqueued.  The signal words are cleared on the
- * stream at the start of every call (by a small kernel, so the call may be captured).  Every call on
+ * stream at the start of every call (by a small kernel, so the call may be captured), and the call's
+ * epoch comes from a per-GPU call count kept on the host (a captured graph replays the epoch it was
+ * captured with: replay a captured call of a decode-shaped problem at most once per capture).  Every call on
  * a GPU uses that GPU's one array: calls that overlap on one GPU (two streams, two threads) race.
  */
 #define DITRON_STATIC_WORKSPACE_BYTES (32u << 20)

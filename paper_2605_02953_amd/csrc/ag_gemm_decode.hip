@@ -49,8 +49,7 @@ struct AgGemmDecodeParams {
   int group_m, num_xcd, per_xcd, npm, npn;
   // split-K kernel
   int splits, kt_per_split;   // K splits per output tile; 128-byte K tiles per split
-  float* partials;            // [tile][split][BM x BN] fp32, in the lanes' own order
-  int32_t* tile_counters;     // [tiles] splits that have delivered their partial; left at zero
+  char* partials;             // [tile][split][BM x BN] words of 8 bytes (fp32 value, epoch), in the lanes' own order
 };
 
 template <bool BF16>
@@ -103,7 +102,7 @@ __global__ __launch_bounds__(DecodeTile::THREADS) void ag_gemm_decode_kernel(con
   const int b_kc = cb * 16;
   const char* b_ptr = p.b + (size_t)min(n0 + rb, p.n - 1) * K + cb * 16;
 
-  // tile indices past the end re-load the last tile into a free stage: the number of loads per
+  // tile indices past the end fetch 16 constant bytes into a free stage: the number of loads per
   // iteration stays fixed, which is what the in-order wait counts below rely on
   auto issue_a = [&](int kt) {
     const int kte = min(kt, kt_all - 1);
@@ -111,7 +110,7 @@ __global__ __launch_bounds__(DecodeTile::THREADS) void ag_gemm_decode_kernel(con
 #pragma unroll
     for (int i = 0; i < T::A_LOADS; ++i) {
       const char* src = a_ptr[i] + (size_t)kte * T::BK;
-      if (kte * T::BK + a_kc[i] >= K) src = (const char*)&kZeroChunk;
+      if (kt >= kt_all || kte * T::BK + a_kc[i] >= K) src = (const char*)&kZeroChunk;
       __builtin_amdgcn_global_load_lds(src, DITRON_LDS(stage + (wave * T::A_LOADS + i) * 1024), 16, 0, 0);
     }
   };
@@ -119,7 +118,7 @@ __global__ __launch_bounds__(DecodeTile::THREADS) void ag_gemm_decode_kernel(con
     const int kte = min(kt, kt_all - 1);
     char* stage = lds_b + (kt % T::NB) * T::B_STAGE;
     const char* src = b_ptr + (size_t)kte * T::BK;
-    if (kte * T::BK + b_kc >= K) src = (const char*)&kZeroChunk;
+    if (kt >= kt_all || kte * T::BK + b_kc >= K) src = (const char*)&kZeroChunk;
     __builtin_amdgcn_global_load_lds(src, DITRON_LDS(stage + lw * 1024), 16, 0, 0);
   };
 
@@ -311,8 +310,9 @@ __global__ __launch_bounds__(T::THREADS) void ag_gemm_splitk_kernel(const AgGemm
       src_ptr[i] = p.workspace + (size_t)min(m0 + r, p.m - 1) * K + (size_t)kt_begin * T::BK + c * 16;
     }
   }
-  // K tile i of this split (tiles past its end re-load its last tile into a free stage: the number of
-  // loads per iteration stays fixed, which the in-order wait counts rely on)
+  // K tile i of this split (requests past its end fetch 16 constant bytes into a free stage: the number of
+  // loads per iteration stays fixed, which the in-order wait counts rely on, and nothing more is asked of
+  // memory: re-reading real tiles there kept 5 stale tiles per unit in the queues the partial exchange needs)
   auto issue_a = [&](int i) {
     const int kt = min(i, kt_n - 1);
     char* stage = lds_a + (i % T::NA) * T::A_STAGE;
@@ -321,7 +321,7 @@ __global__ __launch_bounds__(T::THREADS) void ag_gemm_splitk_kernel(const AgGemm
       const int group = wave * T::A_LOADS + j;
       if (group >= T::A_GROUPS) break;   // fewer row groups than waves (16-row tiles)
       const char* src = src_ptr[j] + (size_t)kt * T::BK;
-      if ((kt_begin + kt) * T::BK + src_kc[j] >= K) src = (const char*)&kZeroChunk;
+      if (i >= kt_n || (kt_begin + kt) * T::BK + src_kc[j] >= K) src = (const char*)&kZeroChunk;
       __builtin_amdgcn_global_load_lds(src, DITRON_LDS(stage + group * 1024), 16, 0, 0);
     }
   };
@@ -331,16 +331,18 @@ __global__ __launch_bounds__(T::THREADS) void ag_gemm_splitk_kernel(const AgGemm
 #pragma unroll
     for (int j = 0; j < T::B_LOADS; ++j) {
       const char* src = src_ptr[j] + (size_t)kt * T::BK;
-      if ((kt_begin + kt) * T::BK + src_kc[j] >= K) src = (const char*)&kZeroChunk;
+      if (i >= kt_n || (kt_begin + kt) * T::BK + src_kc[j] >= K) src = (const char*)&kZeroChunk;
       __builtin_amdgcn_global_load_lds(src, DITRON_LDS(stage + (lw * T::B_LOADS + j) * 1024), 16, 0, 0);
     }
   };
 
   // wave 0 looks at the flags; the loaders start B at once (it does not depend on the gather)
+  // (two tiles only before the barrier: a deeper burst fills the unit's miss queue and the first loads
+  // of A, issued after the barrier, would wait behind it)
   if (wave == 0 && p.wait) flag_wait_wave(p.flags, t.first, t.last - t.first + 1, p.epoch, p.spin_limit, p.status);
   if (loader) {
-#pragma unroll 1
-    for (int i = 0; i < T::NBR - 1; ++i) issue_b(i);
+    issue_b(0);
+    issue_b(1);
   }
   barrier_no_drain();                           // flags seen by wave 0 -> A may be read by everyone
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
@@ -354,6 +356,8 @@ __global__ __launch_bounds__(T::THREADS) void ag_gemm_splitk_kernel(const AgGemm
   const int l16 = lane & 15, g = lane >> 4;
 
   if (loader) {
+#pragma unroll 1
+    for (int i = 2; i < T::NBR - 1; ++i) issue_b(i);
 #pragma unroll 1
     for (int i = 0; i < kt_n; ++i) {
       // B(i) has landed once at most PENDING_B younger loads of this wave are outstanding
@@ -418,49 +422,79 @@ __global__ __launch_bounds__(T::THREADS) void ag_gemm_splitk_kernel(const AgGemm
 
   constexpr int BLOCKS = T::MB * T::NB;
   if (p.splits > 1) {
-    // partial tile -> memory, in the lanes' own order: block (nb, mb) of wave w is 64 lanes x 16 bytes
-    f32x4_t* mine = (f32x4_t*)p.partials + (((size_t)tile * p.splits + ks) * 4 + wave) * (BLOCKS * 64);
+    // The S partial tiles meet in memory, flag-in-data (the low-latency protocol of the paper's kernel
+    // library, applied where this kernel's latency is): every 8-byte word carries one fp32 value and the
+    // call's epoch, so a reader needs no counter and no fence; it reads the words it needs and reads them
+    // again until they all carry this call's epoch.  Stores are written through and loads go past the
+    // caches (sc0 sc1 on both), so this holds wherever the dispatcher put the work-groups.
+    constexpr int kCoherent = 17;                                  // sc0 | sc1 on the load / store
+    constexpr int UNITS = 4 * BLOCKS;                              // (wave, block) pieces per partial tile, 2 KiB each
+    const size_t tile_bytes = (size_t)T::TILE_WORDS * 2 * sizeof(float);
+    const __amdgpu_buffer_rsrc_t part = __builtin_amdgcn_make_buffer_rsrc(
+        (char*)p.partials + (size_t)tile * p.splits * tile_bytes, 0, (int)(p.splits * tile_bytes), 0x00020000);
+    const uint32_t tag = (uint32_t)p.epoch;
     if (!loader) {
-#pragma unroll
-      for (int nb = 0; nb < T::NB; ++nb)
-#pragma unroll
-        for (int mb = 0; mb < T::MB; ++mb) mine[(nb * T::MB + mb) * 64 + lane] = acc[nb][mb];
-    }
-    __syncthreads();   // every wave's stores have completed (the barrier waits for them) and the LDS is idle
-    int* s_last = (int*)lds;
-    if (threadIdx.x == 0) {
-      // release-only ticket; only the work-group that draws the last one pays for the acquire
-      const int old = __hip_atomic_fetch_add(p.tile_counters + tile, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-      const int last = old == p.splits - 1;
-      if (last) {
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
-        __hip_atomic_store(p.tile_counters + tile, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      }
-      *s_last = last;
-    }
-    __syncthreads();
-    if (!*s_last || loader) return;
-    // sum in split order; the own partial comes from the registers it is still in
-    const f32x4_t* first = (const f32x4_t*)p.partials + (((size_t)tile * p.splits) * 4 + wave) * (BLOCKS * 64);
-    f32x4_t tot[T::NB][T::MB];
-#pragma unroll 1
-    for (int s = 0; s < p.splits; ++s) {
-      const f32x4_t* part = first + (size_t)s * 4 * (BLOCKS * 64);
+      // in the lanes' own order: half h of block (nb, mb) of wave w is 64 lanes x 16 contiguous bytes
 #pragma unroll
       for (int nb = 0; nb < T::NB; ++nb)
 #pragma unroll
         for (int mb = 0; mb < T::MB; ++mb) {
-          const f32x4_t v = s == ks ? acc[nb][mb] : part[(nb * T::MB + mb) * 64 + lane];
-          tot[nb][mb] = s == 0 ? v : tot[nb][mb] + v;
+          const u32x4_t v = __builtin_bit_cast(u32x4_t, acc[nb][mb]);
+          const int off = ((ks * 4 + wave) * BLOCKS + nb * T::MB + mb) * 2048 + lane * 16;
+          __builtin_amdgcn_raw_buffer_store_b128(u32x4_t{v[0], tag, v[1], tag}, part, off, 0, kCoherent);
+          __builtin_amdgcn_raw_buffer_store_b128(u32x4_t{v[2], tag, v[3], tag}, part, off + 1024, 0, kCoherent);
         }
     }
+    // This work-group finishes 1/S of the tile: pieces [ks U / S, (ks + 1) U / S), dealt to its eight waves;
+    // the S partials of a piece are added in split order, whoever wrote them last.  The other splits of the
+    // tile are neighbours in the grid: work-groups are dispatched in index order, so whenever some of them
+    // are polling here the rest is running or next in line.
+    const int u_hi = (ks + 1) * UNITS / p.splits;
+    for (int u = ks * UNITS / p.splits + wave; u < u_hi; u += 8) {
+      u32x4_t v[8][2];
+      unsigned polls = 0;
+      for (;;) {
+        bool ok = true;
 #pragma unroll
-    for (int nb = 0; nb < T::NB; ++nb)
+        for (int sp = 0; sp < 8; ++sp)
+          if (sp < p.splits) {
+            v[sp][0] = __builtin_amdgcn_raw_buffer_load_b128(part, (sp * UNITS + u) * 2048 + lane * 16, 0, kCoherent);
+            v[sp][1] = __builtin_amdgcn_raw_buffer_load_b128(part, (sp * UNITS + u) * 2048 + 1024 + lane * 16, 0, kCoherent);
+          }
 #pragma unroll
-      for (int mb = 0; mb < T::MB; ++mb) acc[nb][mb] = tot[nb][mb];
-  } else if (loader) {
+        for (int sp = 0; sp < 8; ++sp)
+          if (sp < p.splits) ok = ok && v[sp][0][1] == tag && v[sp][0][3] == tag && v[sp][1][1] == tag && v[sp][1][3] == tag;
+        if (__all(ok)) break;
+        if (++polls >= p.spin_limit) {
+          if (lane == 0) {
+            p.status[1] = 4 * p.world + tile;
+            p.status[0] = DITRON_ERR_TIMEOUT;
+          }
+          break;
+        }
+      }
+      f32x4_t tot;
+#pragma unroll
+      for (int sp = 0; sp < 8; ++sp)
+        if (sp < p.splits) {
+          const f32x4_t lo = __builtin_bit_cast(f32x4_t, v[sp][0]), hi = __builtin_bit_cast(f32x4_t, v[sp][1]);
+          const f32x4_t x = __builtin_shufflevector(lo, hi, 0, 2, 4, 6);
+          tot = sp == 0 ? x : tot + x;
+        }
+      const int w = u / BLOCKS, blk = u % BLOCKS, nb = blk / T::MB, mb = blk % T::MB;
+      const int m = m0 + (w / T::WN) * T::WTM + mb * 16 + l16;
+      const int n = n0 + (w % T::WN) * T::WTN + nb * 16 + g * 4;
+      if (m >= p.m || n >= p.n) continue;   // n is a multiple of 4 and p.n of 8: all four columns are inside
+      const float rs = p.a_scales ? p.a_scales[m / p.m_per_rank] : 1.f;
+      float x[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) x[q] = tot[q] * rs * (p.b_scales ? p.b_scales[n + q] : 1.f);
+      bf16x4_t o = {(__bf16)x[0], (__bf16)x[1], (__bf16)x[2], (__bf16)x[3]};
+      *(bf16x4_t*)(p.c + (size_t)m * p.n + n) = o;
+    }
     return;
   }
+  if (loader) return;
 
 #pragma unroll
   for (int mb = 0; mb < T::MB; ++mb) {
@@ -544,9 +578,7 @@ extern "C" ditron_status_t ditron_ag_gemm_decode(const void* const* a_shards, co
   p.npn = cdiv(p.n, plan.block_n);
   p.splits = plan.splits;
   p.kt_per_split = plan.kt_per_split;
-  p.partials = (float*)((char*)workspace + align256(a_bytes));
-  p.tile_counters = signals + 4 * world;
-  if (plan.splits > 1 && plan.ntiles > kTileCounterWords) return DITRON_ERR_UNSUPPORTED;   // cannot happen: S > 1 needs ntiles <= 128
+  p.partials = (char*)workspace + align256(a_bytes);
   const hipStream_t s = (hipStream_t)stream;
   switch (plan.variant) {
     case 2: return bf16 ? launch_splitk<true, SplitKTile<128, 128>>(p, s) : launch_splitk<false, SplitKTile<128, 128>>(p, s);

@@ -17,10 +17,10 @@ static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 static std::mutex g_scratch_mutex;
 static unsigned char* g_scratch_ptr[64] = {nullptr};
+static std::atomic<int32_t> g_calls[64];   // calls so far on each device: the next call's epoch
 
 // The calling thread's current device's copy of `scratch` (looked up once per device), or null.
-static unsigned char* scratch_on_current_device() {
-  int dev = 0;
+static unsigned char* scratch_on_current_device(int& dev) {
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
   std::lock_guard<std::mutex> lock(g_scratch_mutex);
   if (!g_scratch_ptr[dev]) {
@@ -49,13 +49,20 @@ extern "C" ditron_status_t ditron_ag_gemm_static(const void* const* a_shards, co
   if (need == 0) return DITRON_ERR_INVALID_ARG;
   if (need > (size_t)DITRON_STATIC_WORKSPACE_BYTES || ditron_signal_words(world, 1) > kStaticSignalWords)
     return DITRON_ERR_WORKSPACE;
-  unsigned char* base = scratch_on_current_device();
+  int dev = 0;
+  unsigned char* base = scratch_on_current_device(dev);
   if (!base) return DITRON_ERR_HIP;
   int32_t* signals = (int32_t*)(base + DITRON_STATIC_WORKSPACE_BYTES);
-  // the array keeps the previous call's flags: they start at zero again, and the call's epoch is 1
+  // the array keeps the previous call's contents: the flags start at zero again, and the epoch (which the
+  // partial tiles of decode-shaped problems carry in every word) is one no earlier call on this GPU used
+  int32_t epoch = g_calls[dev].fetch_add(1) + 1;
+  if (epoch <= 0) {   // wrapped: fall back into the positive range (two billion calls apart)
+    g_calls[dev].store(1);
+    epoch = 1;
+  }
   const int words = (int)ditron_signal_words(world, 1);
   hipLaunchKernelGGL(zero_words_kernel, dim3(1), dim3(256), 0, (hipStream_t)stream, signals, words);
   if (hipGetLastError() != hipSuccess) return DITRON_ERR_HIP;
   return ditron_ag_gemm(a_shards, b, b_layout, c, a_scales, b_scales, base, signals, status, nullptr, arrival_order,
-                        m_per_rank, n, k, world, rank, dtype, /*epoch=*/1, DITRON_EMULATE_PRODUCER, tuning, stream);
+                        m_per_rank, n, k, world, rank, dtype, epoch, DITRON_EMULATE_PRODUCER, tuning, stream);
 }

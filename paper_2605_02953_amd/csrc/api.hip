@@ -35,8 +35,7 @@ using namespace ditron;
 extern "C" size_t ditron_signal_words(int world, int chunks) {
   if (world < 1 || chunks < 1) return 0;
   // flags [world] + per-rank counters [world] + chunk flags [world*chunks] + chunk counters [world*chunks]
-  // + the ticket counters of split output tiles
-  return (size_t)world * 2 + (size_t)world * chunks * 2 + kTileCounterWords;
+  return (size_t)world * 2 + (size_t)world * chunks * 2;
 }
 
 extern "C" ditron_status_t ditron_tile_config(int op, int m, int n, int k, int dtype, const ditron_tuning_t* tuning,
@@ -88,7 +87,7 @@ extern "C" size_t ditron_ag_gemm_workspace_bytes(int m_per_rank, int n, int k, i
   const size_t gathered = (size_t)m * k * esize;
   const bool decode = dtype == DITRON_FP8_E4M3 || (b_layout == DITRON_B_NK && bf16_ag_is_decode_shaped(m, n));
   if (!decode) return gathered;
-  // decode-shaped problems: the fp32 partial tiles of the split contraction follow the gathered operand
+  // decode-shaped problems: the partial tiles of the split contraction follow the gathered operand
   const DecodePlan plan = plan_decode(m, n, k * esize, tune.decode_variant);
   return plan.partial_bytes ? align256(gathered) + plan.partial_bytes : gathered;
 }

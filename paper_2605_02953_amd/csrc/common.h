@@ -111,6 +111,10 @@ __device__ inline void copy_slice(void* __restrict__ dst, const void* __restrict
 // agent-scope acquire invalidates the chiplet's L2, which the GEMM tiles next door live on).
 __device__ inline void publish_after_all(int32_t* counter, int nparts, int32_t* flag, int32_t value) {
   __syncthreads();
+  if (nparts == 1) {   // nobody to wait for: the flag's release covers the work-group's stores
+    if (threadIdx.x == 0) flag_raise(flag, value);
+    return;
+  }
   if (threadIdx.x == 0) {
     int old = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
     if (old == nparts - 1) {

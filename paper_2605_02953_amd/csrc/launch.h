@@ -105,10 +105,9 @@ inline TileChoice choose_tile_decode(int /*m*/, int /*n*/, int /*k*/) {
 // per-shard form, 16-row tiles (one shard's rows at the decode shape: a tile waits for that shard only).
 // S doubles while the grid stays within one work-group per compute unit, at most 8, and every split keeps at
 // least four 128-byte K tiles.
-constexpr int kTileCounterWords = 128;   // signal words behind the flags: one ticket counter per split tile
 struct DecodePlan {
   int variant, block_m, block_n, splits, kt_per_split, ntiles;
-  size_t partial_bytes;   // fp32 partial tiles, behind the gathered operand in the workspace
+  size_t partial_bytes;   // partial tiles (8 bytes per element: fp32 value + epoch), behind the gathered operand in the workspace
 };
 inline DecodePlan plan_decode(int m, int n, int k_bytes, int variant) {
   DecodePlan d{};
@@ -121,7 +120,7 @@ inline DecodePlan plan_decode(int m, int n, int k_bytes, int variant) {
   if (d.variant != 1)
     while ((long)d.ntiles * d.splits * 2 <= 256 && d.splits * 2 <= 8 && kt / (d.splits * 2) >= 4) d.splits *= 2;
   d.kt_per_split = cdiv(kt, d.splits);
-  d.partial_bytes = d.splits > 1 ? (size_t)d.ntiles * d.splits * d.block_m * d.block_n * sizeof(float) : 0;
+  d.partial_bytes = d.splits > 1 ? (size_t)d.ntiles * d.splits * d.block_m * d.block_n * 2 * sizeof(float) : 0;
   return d;
 }
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }

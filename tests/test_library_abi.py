@@ -31,11 +31,11 @@ def test_every_declared_symbol_is_exported(B):
 
 
 def test_sizes_and_strings(B):
-    assert B.signal_words(8, 1) == 32 + 128 and B.signal_words(8, 4) == 80 + 128 and B.signal_words(0, 1) == 0
+    assert B.signal_words(8, 1) == 32 and B.signal_words(8, 4) == 80 and B.signal_words(0, 1) == 0
     # the gathered operand: world * rows * k elements of the operand type
     assert B.ag_gemm_workspace_bytes(1024, 3584, 8192, 8) == 8 * 1024 * 8192 * 2
-    # decode shape: the gathered fp8 operand, then 64 tiles x 4 splits of 128 x 128 fp32 partials
-    assert B.ag_gemm_workspace_bytes(16, 8192, 8192, 8, B.FP8_E4M3) == 128 * 8192 + 64 * 4 * 128 * 128 * 4
+    # decode shape: the gathered fp8 operand, then 64 tiles x 4 splits of 128 x 128 partials of 8 bytes (value, epoch)
+    assert B.ag_gemm_workspace_bytes(16, 8192, 8192, 8, B.FP8_E4M3) == 128 * 8192 + 64 * 4 * 128 * 128 * 8
     assert B.ag_gemm_workspace_bytes(16, 8192, 8192, 8, B.FP8_E4M3, tuning=B.tuning(decode_variant=1)) == 128 * 8192
     assert B.ag_gemm_workspace_bytes(0, 8, 8192, 8) == 0 and B.ag_gemm_workspace_bytes(16, 8, 8192, 8, 5) == 0
     assert B.moe_workspace_bytes(1024, 4096, 8) == 8 * 1024 * 4096 * 2 and B.moe_workspace_bytes(1024, 0, 8) == 0
