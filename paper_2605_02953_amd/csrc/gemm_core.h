@@ -173,10 +173,15 @@ struct Stager4W {
 
   template <class ARow, class BRow>
   __device__ __forceinline__ void init(const char* a_base, ARow a_row, const char* b_base, BRow b_row) {
-    const int r = threadIdx.x >> 3;
+    init(a_base, a_row, b_base, b_row, (int)threadIdx.x);
+  }
+  // tid: the thread's index among the T::THREADS threads that stage (the whole work-group, or its loading waves)
+  template <class ARow, class BRow>
+  __device__ __forceinline__ void init(const char* a_base, ARow a_row, const char* b_base, BRow b_row, int tid) {
+    const int r = tid >> 3;
     // direct-to-LDS form: the lane's LDS position is chunk (lane & 7) of its row, which holds global chunk c
-    const int c = kDirect ? ((threadIdx.x & 7) ^ swz128(r)) : (threadIdx.x & 7);
-    wave_lds = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6) * 1024;
+    const int c = kDirect ? ((tid & 7) ^ swz128(r)) : (tid & 7);
+    wave_lds = __builtin_amdgcn_readfirstlane(tid >> 6) * 1024;
     a_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)a_base, 0, kOutOfRange, 0x00020000);
     b_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)b_base, 0, kOutOfRange, 0x00020000);
     kc = c * 8;
@@ -185,8 +190,8 @@ struct Stager4W {
     for (int i = 0; i < T::A_LOADS; ++i) off[i] = (int)(a_row(r + i * T::ROWS_PER_PASS) + (uint32_t)(c * 16));
     if constexpr (T::B_KN) {
       // lane (k row, group of 8 columns): 16 bytes = 8 columns of one k; a wave covers whole rows of the tile
-      kn_row = threadIdx.x / KN_LANES;
-      const int n8 = threadIdx.x % KN_LANES;
+      kn_row = tid / KN_LANES;
+      const int n8 = tid % KN_LANES;
       const int col = b_row.n0 + n8 * 8;
       kn_lds_off = kn_row * T::PB + n8 * 16;
       kn_tile_bytes = (int)(b_row.ld_bytes * 64u);
@@ -374,6 +379,114 @@ __device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[T::NI][T::MI], con
       __builtin_amdgcn_sched_barrier(0);
     });
   }
+}
+
+// Mainloop for tiles whose operands stream from HBM rather than from the L2 (the grouped GEMM's expert
+// weights): what bounds such a tile is the bytes a compute unit has in flight, so the two stages above
+// (one K tile requested ahead: 32 KiB at the 128 x 128 tile, about 32 GB/s per unit at 2 us of memory
+// latency) become a ring of NST stages filled by direct-to-LDS loads, NST - 1 K tiles ahead, one barrier
+// per K tile; the matrix work of a K tile (512 cycles at 128 x 128) is short against its loads.
+// Requests past the last K tile are out of the buffers' range: zeros are written, memory is not asked.
+template <class T, int NST, class ARow, class BRow>
+__device__ __forceinline__ void gemm_mainloop_ring(f32x16_t (&acc)[T::NI][T::MI], const char* a_base, ARow a_row,
+                                                      const char* b_base, BRow b_row, int K, char* lds) {
+  static_assert(T::DIRECT && !T::B_KN, "ring staging is written for [N, K] operands loaded straight into LDS");
+  constexpr int PAIRS = T::PAIRS, READS = T::READS, LOADS = T::LOADS;
+  static_assert((NST - 2) * LOADS <= 63 && NST >= 3, "wait-count immediate");
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int wm = wave / 2, wn = wave % 2;
+  const int lr = lane & 31, lh = lane >> 5;
+  const int a_off = (wm * T::WTM + lr) * T::ROW_BYTES;
+  const int b_off = T::A_BYTES + (wn * T::WTN + lr) * T::ROW_BYTES;
+  int koff[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) koff[ks] = ((ks * 2 + lh) ^ swz128(lr)) * 16;
+#pragma unroll
+  for (int ni = 0; ni < T::NI; ++ni)
+#pragma unroll
+    for (int mi = 0; mi < T::MI; ++mi)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[ni][mi][v] = 0.f;
+  const int kt_all = (K + 63) / 64;
+  Stager4W<T> st;
+  st.init(a_base, a_row, b_base, b_row);
+#pragma unroll
+  for (int j = 0; j < NST - 1; ++j) st.template issue_range<0, LOADS>(j, K, lds + j * T::STAGE_BYTES);
+#pragma unroll 1
+  for (int kt = 0; kt < kt_all; ++kt) {
+    wait_vmcnt<(NST - 2) * LOADS>();   // this wave's part of tile kt has landed (loads return in order)
+    barrier_no_drain();                // ... everybody's, and every wave is past its reads of tile kt - 1
+    st.template issue_range<0, LOADS>(kt + NST - 1, K, lds + ((kt + NST - 1) % NST) * T::STAGE_BYTES);
+    const char* cur = lds + (kt % NST) * T::STAGE_BYTES;
+    Frags4W<T> f0, f1;
+    read_range<T, 0, 0, READS>(f0, cur, a_off, b_off, koff);
+    read_range<T, 1, 0, READS>(f1, cur, a_off, b_off, koff);
+    static_for<0, PAIRS>([&](auto j) { mma_pair<T, decltype(j)::value>(acc, f0); });
+    read_range<T, 2, 0, READS>(f0, cur, a_off, b_off, koff);
+    static_for<0, PAIRS>([&](auto j) { mma_pair<T, decltype(j)::value>(acc, f1); });
+    read_range<T, 3, 0, READS>(f1, cur, a_off, b_off, koff);
+    static_for<0, PAIRS>([&](auto j) { mma_pair<T, decltype(j)::value>(acc, f0); });
+    static_for<0, PAIRS>([&](auto j) { mma_pair<T, decltype(j)::value>(acc, f1); });
+  }
+  wait_vmcnt0();   // the requests past the end have completed before the stages are used for anything else
+}
+
+// The same ring with the two jobs given to different waves: a work-group of eight waves, waves 0-3 (one per
+// SIMD) only read fragments and issue MFMAs, waves 4-7 only issue the loads.  A wave issues in order, so in
+// the form above the eight load instructions of a K tile (512 cycles of address-unit time per compute unit)
+// and its 512 cycles of matrix work follow one another; here they overlap.  Returns true in the computing
+// waves (which hold the accumulators) and false in the loading waves, whose requests have all completed.
+template <class T, int NST, class ARow, class BRow>
+__device__ __forceinline__ bool gemm_mainloop_ring_split(f32x16_t (&acc)[T::NI][T::MI], const char* a_base, ARow a_row,
+                                                            const char* b_base, BRow b_row, int K, char* lds) {
+  static_assert(T::DIRECT && !T::B_KN, "ring staging is written for [N, K] operands loaded straight into LDS");
+  constexpr int PAIRS = T::PAIRS, READS = T::READS, LOADS = T::LOADS;
+  static_assert((NST - 2) * LOADS <= 63 && NST >= 3, "wait-count immediate");
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int kt_all = (K + 63) / 64;
+  if (wave >= T::NWAVES) {
+    Stager4W<T> st;
+    st.init(a_base, a_row, b_base, b_row, (int)threadIdx.x - T::THREADS);
+#pragma unroll
+    for (int j = 0; j < NST - 1; ++j) st.template issue_range<0, LOADS>(j, K, lds + j * T::STAGE_BYTES);
+#pragma unroll 1
+    for (int kt = 0; kt < kt_all; ++kt) {
+      wait_vmcnt<(NST - 2) * LOADS>();   // this wave's part of tile kt has landed (loads return in order)
+      barrier_no_drain();                // ... everybody's, and the computing waves are past tile kt - 1
+      st.template issue_range<0, LOADS>(kt + NST - 1, K, lds + ((kt + NST - 1) % NST) * T::STAGE_BYTES);
+    }
+    wait_vmcnt0();
+    return false;
+  }
+  const int wm = wave / 2, wn = wave % 2;
+  const int lr = lane & 31, lh = lane >> 5;
+  const int a_off = (wm * T::WTM + lr) * T::ROW_BYTES;
+  const int b_off = T::A_BYTES + (wn * T::WTN + lr) * T::ROW_BYTES;
+  int koff[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) koff[ks] = ((ks * 2 + lh) ^ swz128(lr)) * 16;
+#pragma unroll
+  for (int ni = 0; ni < T::NI; ++ni)
+#pragma unroll
+    for (int mi = 0; mi < T::MI; ++mi)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[ni][mi][v] = 0.f;
+#pragma unroll 1
+  for (int kt = 0; kt < kt_all; ++kt) {
+    barrier_no_drain();
+    const char* cur = lds + (kt % NST) * T::STAGE_BYTES;
+    Frags4W<T> f0, f1;
+    read_range<T, 0, 0, READS>(f0, cur, a_off, b_off, koff);
+    read_range<T, 1, 0, READS>(f1, cur, a_off, b_off, koff);
+    static_for<0, PAIRS>([&](auto j) { mma_pair<T, decltype(j)::value>(acc, f0); });
+    read_range<T, 2, 0, READS>(f0, cur, a_off, b_off, koff);
+    static_for<0, PAIRS>([&](auto j) { mma_pair<T, decltype(j)::value>(acc, f1); });
+    read_range<T, 3, 0, READS>(f1, cur, a_off, b_off, koff);
+    static_for<0, PAIRS>([&](auto j) { mma_pair<T, decltype(j)::value>(acc, f0); });
+    static_for<0, PAIRS>([&](auto j) { mma_pair<T, decltype(j)::value>(acc, f1); });
+    wait_lgkmcnt0();   // every read of tile kt has returned before the next barrier frees its stage
+  }
+  return true;
 }
 
 // Epilogue: each wave turns its accumulators into bf16, parks them in its

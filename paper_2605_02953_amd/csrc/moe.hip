@@ -244,19 +244,43 @@ struct MoeGemmParams {
   const int32_t* tile_records;
   const int32_t* flags;
   int32_t* status;
-  int tokens_per_rank, hidden, inter, top_k, world, max_tiles, npn;
+  int tokens_per_rank, hidden, inter, top_k, world, max_tiles, npn, num_local, num_xcd;
   int32_t epoch;
   unsigned spin_limit;
   int wait;   // 0: the token shards are resident, the flags are not looked at
 };
 
-template <class T>
-__global__ __launch_bounds__(T::THREADS) void moe_grouped_gemm_kernel(const MoeGemmParams p) {
+// NST > 0: operands through a ring of NST LDS stages filled by four extra waves (expert weights stream from
+// HBM: see gemm_mainloop_ring_split)
+template <class T, int NST = 0>
+__global__ __launch_bounds__(NST > 0 ? 2 * T::THREADS : T::THREADS) void moe_grouped_gemm_kernel(const MoeGemmParams p) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
+  // Work-group -> (row tile, column block).  All (row tile, column block) items are put in one list, expert
+  // after expert, inside an expert column block after column block, the expert's row tiles (one to three) of
+  // a column block next to each other; the list is cut into as many equal runs as there are chiplets and
+  // chiplet x (the work-groups with index = x mod 8) takes run x.  Neighbours in the list share a block of the
+  // expert's weights (same column block) or the gathered rows (same row tile), so each comes from memory about
+  // once, and every chiplet has the same number of tiles (an expert per chiplet moves as few bytes but leaves
+  // the chiplets of small experts idle while the large ones run two rounds).  The row tiles of expert j are
+  // the positions [first_j, first_j + ceil(n_j / BLOCK_M)) of the tile list, in arrival-stage order.
   const int wg = blockIdx.x;
-  const int pos = wg / p.npn, pid_n = wg % p.npn;
   const int ntiles = p.tile_records[0];
-  if (pos >= ntiles) return;
+  if (ntiles <= 0) return;   // nothing routed here, or the routing launch reported an error
+  const int per_xcd = cdiv(ntiles * p.npn, p.num_xcd);
+  const int slot = wg / p.num_xcd;
+  int item = (wg % p.num_xcd) * per_xcd + slot;
+  if (slot >= per_xcd || item >= ntiles * p.npn) return;
+  int pos = 0, pid_n = 0;
+  for (int j = 0; j < p.num_local; ++j) {
+    const int nt = cdiv(p.expert_offsets[j + 1] - p.expert_offsets[j], T::BM);
+    if (item < nt * p.npn) {
+      pid_n = item / nt;
+      pos += item % nt;
+      break;
+    }
+    item -= nt * p.npn;
+    pos += nt;
+  }
   const int32_t* rec = p.tile_records + 1 + 4 * pos;
   const int j = rec[0], seg_start = rec[2], seg_end = rec[3];
   const int p0 = p.tile_records[1 + 4 * p.max_tiles + pos];
@@ -275,7 +299,14 @@ __global__ __launch_bounds__(T::THREADS) void moe_grouped_gemm_kernel(const MoeG
     gemm_mainloop<T>(acc, p.workspace, a_row, wj, BColumns{(uint32_t)N * 2u, n0, N}, p.hidden, lds);
   } else {
     auto b_row = [=](int r) { return (uint32_t)min(n0 + r, N - 1) * row_bytes; };
-    gemm_mainloop<T>(acc, p.workspace, a_row, wj, b_row, p.hidden, lds);
+    if constexpr (NST > 0) {
+      if (!gemm_mainloop_ring_split<T, NST>(acc, p.workspace, a_row, wj, b_row, p.hidden, lds)) {
+        __syncthreads();   // the loading waves meet the barrier at the head of the epilogue and leave
+        return;
+      }
+    } else {
+      gemm_mainloop<T>(acc, p.workspace, a_row, wj, b_row, p.hidden, lds);
+    }
   }
   store_tile_bf16<T>(acc, p.y, (size_t)p.inter, p0, n0, p_end, N, lds);
 }
@@ -290,12 +321,15 @@ extern "C" int ditron_moe_max_tiles(int max_rows, int num_local_experts) {
   return cdiv(max_rows, kMoeBlockM) + num_local_experts;
 }
 
-template <class T>
+template <class T, int NST = 0>
 static ditron_status_t launch_moe_gemm(MoeGemmParams& g, int max_tiles, hipStream_t s) {
   g.npn = cdiv(g.inter, T::BN);
-  if (!set_dynamic_lds<moe_grouped_gemm_kernel<T>>(T::LDS_BYTES)) return DITRON_ERR_HIP;
-  const unsigned grid = (unsigned)(max_tiles * g.npn);
-  hipLaunchKernelGGL(moe_grouped_gemm_kernel<T>, dim3(grid), dim3(T::THREADS), T::LDS_BYTES, s, g);
+  constexpr int kLds = NST > 0 ? NST * T::STAGE_BYTES : T::LDS_BYTES;
+  static_assert(kLds <= 160 * 1024, "LDS of one compute unit");
+  if (!set_dynamic_lds<moe_grouped_gemm_kernel<T, NST>>(kLds)) return DITRON_ERR_HIP;
+  // every chiplet takes an equal share of the (row tile, column block) items
+  const unsigned grid = (unsigned)(g.num_xcd * cdiv(max_tiles * g.npn, g.num_xcd));
+  hipLaunchKernelGGL((moe_grouped_gemm_kernel<T, NST>), dim3(grid), dim3(NST > 0 ? 2 * T::THREADS : T::THREADS), kLds, s, g);
   return hipGetLastError() == hipSuccess ? DITRON_OK : DITRON_ERR_HIP;
 }
 
@@ -386,6 +420,8 @@ extern "C" ditron_status_t ditron_moe_ag_grouped_gemm(
   g.top_k = top_k;
   g.world = world;
   g.max_tiles = max_tiles;
+  g.num_local = num_local_experts;
+  g.num_xcd = 8;
   g.epoch = epoch;
   g.spin_limit = tune.spin_limit;
   g.wait = mode != Mode::kPreset;
@@ -398,9 +434,11 @@ extern "C" ditron_status_t ditron_moe_ag_grouped_gemm(
     if (mt.block_n == 128) return launch_moe_gemm<GemmTile4W<256, 128>>(g, max_tiles, s);
     return launch_moe_gemm<GemmTile4W<256, 256>>(g, max_tiles, s);
   }
+  // 128-row tiles: their operands are streamed (an expert's weights are read by one or two row tiles), so
+  // they go through as deep a ring of LDS stages as fits
   switch (mt.block_n) {
-    case 128: return launch_moe_gemm<GemmTile4W<128, 128>>(g, max_tiles, s);
-    case 192: return launch_moe_gemm<GemmTile4W<128, 192>>(g, max_tiles, s);
-    default: return launch_moe_gemm<GemmTile4W<128, 256>>(g, max_tiles, s);
+    case 128: return launch_moe_gemm<GemmTile4W<128, 128, false, true>, 5>(g, max_tiles, s);
+    case 192: return launch_moe_gemm<GemmTile4W<128, 192, false, true>, 4>(g, max_tiles, s);
+    default: return launch_moe_gemm<GemmTile4W<128, 256, false, true>, 3>(g, max_tiles, s);
   }
 }
