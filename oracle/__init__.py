@@ -16,4 +16,4 @@ The bodies of the MoE schedule's helpers (stage of a tile, bisect) are not print
 the stage is read as the delivery position of the last shard a tile needs and the bisect as
 "entries <= x"; both readings are pinned by re-deriving every tile's source ranks from gather_idx.
 """
-from . import formats, ag_gemm, gemm_rs, gemm_ar, moe, schedule, compare  # noqa: F401
+from . import formats, ag_gemm, gemm_rs, gemm_ar, moe, moe_rs, schedule, compare  # noqa: F401
