@@ -10,6 +10,7 @@
  *   ditron_gemm_rs_fuse_scatter the same with the scatter fused into the GEMM's stores
  *   ditron_moe_ag_grouped_gemm  AllGather + grouped GEMM over local experts
  *                               (paper, kernel list "ag_group_gemm"; Appendix "Swizzle", third listing)
+ *   ditron_moe_grouped_gemm_rs  MoE down-projection (grouped GEMM + top-k combine) + ReduceScatter
  *   ditron_gemm_ar              GEMM + AllReduce, every tile reduced on every rank
  *   ditron_gemm_ar_two_shot     GEMM + AllReduce, tiles dealt to the ranks and broadcast
  *                               (paper, Appendix "GEMM All-Reduce")
@@ -407,6 +408,48 @@ ditron_status_t ditron_moe_ag_grouped_gemm(const void* const* x_shards, const in
                                            int hidden, int inter, int num_experts, int top_k,
                                            int expert_begin, int num_local_experts, int max_rows,
                                            int world, int rank, int32_t epoch, unsigned flags,
+                                           const ditron_tuning_t* tuning, void* stream);
+
+/*
+ * MoE down-projection + ReduceScatter:  out[tokens_per_rank, hidden] = rows_rank( sum_s z_s ),
+ *   z_rank[t, :] = sum_j gate[t, j] * ( h[pos(t*top_k + j), :] . W2_expert(t, j) )   computed here.
+ *
+ * Paper: the workload "MoE+ReduceScatter" of the evaluation (tensor-parallel placement: every rank holds
+ * its slice of the intermediate dimension of every expert); the paper prints its shape, not a listing, so
+ * the steps are the plain ones.  The activations are grouped by expert already (row p belongs to the
+ * assignment gather_idx[p]: the output order of ditron_moe_ag_grouped_gemm), the grouped GEMM multiplies
+ * each expert's rows by its down-projection, the combine adds a token's top_k rows (fp32 fused multiply-add
+ * in the order j = 0..top_k-1, one rounding to bf16; an assignment whose expert is not on the rank adds
+ * nothing), and the reduce-scatter is that of ditron_gemm_rs: the peers' blocks arrive in the scatter
+ * buffer (emulated: copied there in the order rank-1, rank-2, ...), the `world` slots are added in fp32 in
+ * slot order and rounded once.
+ *
+ *  h             device [R, inter] bf16, R = expert_offsets[num_local_experts] <= max_rows
+ *  w, w_layout   device, per expert logical [inter, hidden] bf16 (DITRON_B_NK = [E_l, hidden, inter],
+ *                DITRON_B_KN = [E_l, inter, hidden])
+ *  topk_weights  device float[world*tokens_per_rank*top_k] or NULL (all ones)
+ *  gather_idx, expert_offsets   device, as written by ditron_moe_ag_grouped_gemm
+ *  y             device scratch [max_rows, hidden] bf16: the grouped GEMM's output
+ *  inverse_idx   device scratch int32[world*tokens_per_rank*top_k]
+ *  tile_records  device scratch int32[1 + 5*ditron_moe_max_tiles(max_rows, num_local_experts)]
+ *  combined      device out [world*tokens_per_rank, hidden] bf16: this rank's partial z_rank
+ *  peer_partials host array of `world` device pointers; entry s != rank is the [tokens_per_rank, hidden]
+ *                bf16 block rank s contributes to this rank (EMULATE_PRODUCER)
+ *  scatter_buf   device [world, tokens_per_rank, hidden] bf16 (slot `rank` unused)
+ *  out           device out [tokens_per_rank, hidden] bf16
+ *  signals       device int32[ditron_signal_words(world, chunks_per_slot)], laid out as for ditron_gemm_rs:
+ *                the arrival flag of (slot s, row chunk c) is word 2*world + s*chunks_per_slot + c; the
+ *                own slot's flags are raised by the combine
+ *  If R exceeds max_rows: status[0] = DITRON_ERR_WORKSPACE, status[2] = R, and `out` is undefined.
+ */
+ditron_status_t ditron_moe_grouped_gemm_rs(const void* h, const void* w, int w_layout, const float* topk_weights,
+                                           const int32_t* gather_idx, const int32_t* expert_offsets, void* y,
+                                           int32_t* inverse_idx, int32_t* tile_records, void* combined,
+                                           const void* const* peer_partials, void* scatter_buf, void* out,
+                                           int32_t* signals, int32_t* status, const int* arrival_order,
+                                           int tokens_per_rank, int hidden, int inter, int num_experts, int top_k,
+                                           int num_local_experts, int max_rows, int world, int rank,
+                                           int chunks_per_slot, int32_t epoch, unsigned flags,
                                            const ditron_tuning_t* tuning, void* stream);
 
 /* Tile of the grouped GEMM for a call with these sizes (total_tokens = world * tokens_per_rank):

@@ -71,6 +71,9 @@ lib.ditron_reduce_slots.argtypes = [_pp, _vp, _vp, _vp, _i, _i, _i, _i, _i32, _t
 lib.ditron_moe_ag_grouped_gemm.restype = _i
 lib.ditron_moe_ag_grouped_gemm.argtypes = [_pp, _vp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _ip,
                                            _i, _i, _i, _i, _i, _i, _i, _i, _i, _i, _i32, _u, _tp, _vp]
+lib.ditron_moe_grouped_gemm_rs.restype = _i
+lib.ditron_moe_grouped_gemm_rs.argtypes = [_vp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _pp, _vp, _vp, _vp, _vp, _ip,
+                                           _i, _i, _i, _i, _i, _i, _i, _i, _i, _i, _i32, _u, _tp, _vp]
 lib.ditron_moe_tile_choice.restype = _i
 lib.ditron_moe_tile_choice.argtypes = [_i, _i, _i, _i, _i, _ip]
 lib.ditron_moe_max_tiles.restype = _i
@@ -252,6 +255,18 @@ def moe_ag_grouped_gemm(x_shards, topk_ids, w, w_layout, y, counts, expert_offse
                                           _int_array(arrival_order), tokens_per_rank, hidden, inter,
                                           num_experts, top_k, expert_begin, num_local_experts, max_rows, world,
                                           rank, epoch, flags, _tuning(tuning), _stream(stream))
+
+
+def moe_grouped_gemm_rs(h, w, w_layout, topk_weights, gather_idx, expert_offsets, y, inverse_idx, tile_records, combined,
+                        peer_partials, scatter_buf, out, signals, status, arrival_order, tokens_per_rank, hidden, inter,
+                        num_experts, top_k, num_local_experts, max_rows, world, rank, chunks_per_slot, epoch, flags,
+                        stream=None, tuning=None):
+    return lib.ditron_moe_grouped_gemm_rs(_ptr(h), _ptr(w), w_layout, _ptr(topk_weights), _ptr(gather_idx),
+                                          _ptr(expert_offsets), _ptr(y), _ptr(inverse_idx), _ptr(tile_records),
+                                          _ptr(combined), _ptr_array(peer_partials), _ptr(scatter_buf), _ptr(out),
+                                          _ptr(signals), _ptr(status), _int_array(arrival_order), tokens_per_rank,
+                                          hidden, inter, num_experts, top_k, num_local_experts, max_rows, world, rank,
+                                          chunks_per_slot, epoch, flags, _tuning(tuning), _stream(stream))
 
 
 def publish_chunks(dst, src, nbytes, flag_index, signals, epoch, delay_cycles=0, stream=None):

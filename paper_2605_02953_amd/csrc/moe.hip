@@ -244,7 +244,8 @@ struct MoeGemmParams {
   const int32_t* tile_records;
   const int32_t* flags;
   int32_t* status;
-  int tokens_per_rank, hidden, inter, top_k, world, max_tiles, npn, num_local, num_xcd;
+  int tokens_per_rank, hidden, inter, top_k, world, max_tiles, npn, num_local, num_xcd;   // hidden: contraction length, inter: output width
+  int rows_in_place;   // 1: row p of the left operand is row p of `workspace` (already grouped by expert), no gather
   int32_t epoch;
   unsigned spin_limit;
   int wait;   // 0: the token shards are resident, the flags are not looked at
@@ -293,7 +294,11 @@ __global__ __launch_bounds__(NST > 0 ? 2 * T::THREADS : T::THREADS) void moe_gro
   const int32_t* gidx = p.gather_idx;
   const int top_k = p.top_k, N = p.inter;
   // the gather happens here: a tile row is fetched from the token its assignment belongs to
-  auto a_row = [=](int r) { return (uint32_t)(gidx[min(p0 + r, p_end - 1)] / top_k) * row_bytes; };
+  const int in_place = p.rows_in_place;
+  auto a_row = [=](int r) {
+    const int row = min(p0 + r, p_end - 1);
+    return (uint32_t)(in_place ? row : gidx[row] / top_k) * row_bytes;
+  };
   f32x16_t acc[T::NI][T::MI];
   if constexpr (T::B_KN) {   // expert weights stored [hidden, inter]: same bytes per expert, inter contiguous
     gemm_mainloop<T>(acc, p.workspace, a_row, wj, BColumns{(uint32_t)N * 2u, n0, N}, p.hidden, lds);
@@ -441,4 +446,278 @@ extern "C" ditron_status_t ditron_moe_ag_grouped_gemm(
     case 192: return launch_moe_gemm<GemmTile4W<128, 192, false, true>, 4>(g, max_tiles, s);
     default: return launch_moe_gemm<GemmTile4W<128, 256, false, true>, 3>(g, max_tiles, s);
   }
+}
+
+
+// ====================================================================== MoE down-projection + ReduceScatter
+// (paper: workload "MoE+ReduceScatter" of the evaluation; tensor-parallel placement.)  The activations are
+// already grouped by expert (the output order of the AllGather + grouped GEMM above), so the grouped GEMM
+// reads its rows in place; a top-k combine brings the rows back to token order (fp32 fma over the token's
+// assignments in order, one rounding), and the reduce-scatter is the one of GEMM-ReduceScatter: the peers'
+// blocks arrive in the scatter buffer, the slots are added in fp32 in slot order.
+namespace ditron {
+
+__global__ __launch_bounds__(1024) void fill_i32_kernel(int32_t* dst, int n, int32_t value) {
+  for (int i = blockIdx.x * 1024 + threadIdx.x; i < n; i += gridDim.x * 1024) dst[i] = value;
+}
+
+struct MoeRsPrepareParams {
+  const int32_t* expert_offsets;
+  const int32_t* gather_idx;
+  int32_t* inverse_idx;    // [assignments], pre-filled with -1
+  int32_t* tile_records;
+  int32_t* status;
+  int num_local, block_m, max_rows, max_tiles, assignments;
+};
+
+// Work-group 0: the tile list (expert after expert, no arrival stage: every row is local).  The others:
+// inverse_idx[gather_idx[p]] = p.
+__global__ __launch_bounds__(1024) void moe_rs_prepare_kernel(const MoeRsPrepareParams p) {
+  const int R = p.expert_offsets[p.num_local];
+  if (blockIdx.x == 0) {
+    __shared__ int s_first[kMaxLocalExperts + 1];
+    if (threadIdx.x == 0) {
+      int tiles = 0;
+      for (int j = 0; j < p.num_local; ++j) {
+        s_first[j] = tiles;
+        tiles += cdiv(p.expert_offsets[j + 1] - p.expert_offsets[j], p.block_m);
+      }
+      s_first[p.num_local] = tiles;
+      const bool fits = R <= p.max_rows && tiles <= p.max_tiles;
+      if (!fits) {
+        p.status[0] = DITRON_ERR_WORKSPACE;
+        p.status[2] = R;
+      }
+      p.tile_records[0] = fits ? tiles : 0;
+    }
+    __syncthreads();
+    if (R > p.max_rows || s_first[p.num_local] > p.max_tiles) return;
+    for (int j = 0; j < p.num_local; ++j)
+      for (int t = s_first[j] + (int)threadIdx.x; t < s_first[j + 1]; t += 1024) {
+        int32_t* rec = p.tile_records + 1 + 4 * t;
+        rec[0] = j; rec[1] = t; rec[2] = 0; rec[3] = 0;
+        p.tile_records[1 + 4 * p.max_tiles + t] = p.expert_offsets[j] + (t - s_first[j]) * p.block_m;
+      }
+    return;
+  }
+  for (int q = (blockIdx.x - 1) * 1024 + threadIdx.x; q < min(R, p.max_rows); q += (gridDim.x - 1) * 1024) {
+    const int f = p.gather_idx[q];
+    if (f >= 0 && f < p.assignments) p.inverse_idx[f] = q;
+  }
+}
+
+struct MoeCombineParams {
+  const __bf16* y;             // [rows, hidden] grouped by expert
+  const int32_t* inverse_idx;  // [tokens * top_k]
+  const float* gate;           // [tokens * top_k] or null
+  __bf16* combined;            // [tokens, hidden]
+  int tokens, top_k, hidden, combine_wgs;
+  // own-slot flags and the emulated peers (work-groups behind the combine)
+  int32_t* done;               // work-groups of the combine that have finished
+  int32_t* own_flags;          // [chunks]
+  const void* peer[DITRON_MAX_WORLD];
+  int order[DITRON_MAX_WORLD];
+  char* scatter_buf;
+  int32_t* arr_flags;
+  int32_t* arr_counters;
+  size_t slot_bytes;
+  int chunks, n_peers, num_producers, teams;
+  int32_t epoch;
+};
+
+__global__ __launch_bounds__(1024) void moe_combine_kernel(const MoeCombineParams p) {
+  if ((int)blockIdx.x >= p.combine_wgs) {
+    const size_t chunk_bytes = p.slot_bytes / p.chunks;
+    produce_chunks<1024>(
+        p.n_peers * p.chunks, chunk_bytes, blockIdx.x - p.combine_wgs, p.num_producers, p.teams, p.epoch,
+        [&](int i) { return (void*)(p.scatter_buf + p.order[i / p.chunks] * p.slot_bytes + (i % p.chunks) * chunk_bytes); },
+        [&](int i) { return (const void*)((const char*)p.peer[p.order[i / p.chunks]] + (i % p.chunks) * chunk_bytes); },
+        [&](int i) { return p.arr_flags + p.order[i / p.chunks] * p.chunks + i % p.chunks; },
+        [&](int i) { return p.arr_counters + p.order[i / p.chunks] * p.chunks + i % p.chunks; });
+    return;
+  }
+  // one lane per 8 columns of one token: top_k rows of 16 bytes in, one out
+  const int vpr = p.hidden >> 3;
+  const long total = (long)p.tokens * vpr;
+  for (long v = (long)blockIdx.x * 1024 + threadIdx.x; v < total; v += (long)p.combine_wgs * 1024) {
+    const int t = (int)(v / vpr), c = (int)(v - (long)t * vpr);
+    float acc[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) acc[q] = 0.f;
+    for (int j = 0; j < p.top_k; ++j) {
+      const int pos = p.inverse_idx[t * p.top_k + j];
+      if (pos < 0) continue;   // the assignment's expert is not on this rank
+      const float g = p.gate ? p.gate[t * p.top_k + j] : 1.f;
+      const u32x4_t x = __builtin_nontemporal_load((const u32x4_t*)(p.y + (size_t)pos * p.hidden) + c);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        acc[2 * q] = __builtin_fmaf(g, __builtin_bit_cast(float, x[q] << 16), acc[2 * q]);
+        acc[2 * q + 1] = __builtin_fmaf(g, __builtin_bit_cast(float, x[q] & 0xFFFF0000u), acc[2 * q + 1]);
+      }
+    }
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    u32x4_t r;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      bf16x2_t o = {(__bf16)acc[2 * q], (__bf16)acc[2 * q + 1]};
+      r[q] = __builtin_bit_cast(uint32_t, o);
+    }
+    *((u32x4_t*)(p.combined + (size_t)t * p.hidden) + c) = r;
+  }
+  // the last work-group of the combine to finish raises the flags of the own slot
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int old = __hip_atomic_fetch_add(p.done, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    if (old == p.combine_wgs - 1) {
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+      __hip_atomic_store(p.done, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      for (int c = 0; c < p.chunks; ++c) flag_raise(p.own_flags + c, p.epoch);
+    }
+  }
+}
+
+}  // namespace ditron
+
+extern "C" ditron_status_t ditron_moe_grouped_gemm_rs(
+    const void* h, const void* w, int w_layout, const float* topk_weights, const int32_t* gather_idx,
+    const int32_t* expert_offsets, void* y, int32_t* inverse_idx, int32_t* tile_records, void* combined,
+    const void* const* peer_partials, void* scatter_buf, void* out, int32_t* signals, int32_t* status,
+    const int* arrival_order, int tokens_per_rank, int hidden, int inter, int num_experts, int top_k,
+    int num_local_experts, int max_rows, int world, int rank, int chunks_per_slot, int32_t epoch, unsigned flags,
+    const ditron_tuning_t* tuning, void* stream) {
+  if (world < 1 || world > DITRON_MAX_WORLD || rank < 0 || rank >= world) return DITRON_ERR_INVALID_ARG;
+  if (tokens_per_rank <= 0 || hidden <= 0 || inter <= 0 || num_experts <= 0 || top_k <= 0 || max_rows <= 0)
+    return DITRON_ERR_INVALID_ARG;
+  if (num_local_experts <= 0 || num_local_experts > num_experts || chunks_per_slot < 1 ||
+      tokens_per_rank % chunks_per_slot != 0)
+    return DITRON_ERR_INVALID_ARG;
+  if (!h || !w || !gather_idx || !expert_offsets || !y || !inverse_idx || !tile_records || !combined || !out ||
+      !signals || !status)
+    return DITRON_ERR_INVALID_ARG;
+  if (world > 1 && !scatter_buf) return DITRON_ERR_INVALID_ARG;
+  if (!aligned16(h) || !aligned16(w) || !aligned16(y) || !aligned16(combined) || !aligned16(out) ||
+      !aligned16(scatter_buf) || !aligned16(signals))
+    return DITRON_ERR_INVALID_ARG;
+  const Mode mode = producer_mode(flags);
+  const Tuning tune = resolve_tuning(tuning, 1);
+  if (mode == Mode::kInvalid || !tune.valid) return DITRON_ERR_INVALID_ARG;
+  const bool emulate = mode == Mode::kEmulate;
+  if (w_layout != DITRON_B_KN && w_layout != DITRON_B_NK) return DITRON_ERR_INVALID_ARG;
+  if (hidden % 8 != 0 || inter % 8 != 0) return DITRON_ERR_UNSUPPORTED;
+  if (!fits_32bit((size_t)max_rows, inter, 2) || !fits_32bit(hidden, inter, 2)) return DITRON_ERR_UNSUPPORTED;
+  if (num_local_experts > kMaxLocalExperts) return DITRON_ERR_UNSUPPORTED;
+  const long assignments = (long)world * tokens_per_rank * top_k;
+  if (assignments > 0x7fffffffL) return DITRON_ERR_UNSUPPORTED;
+  const int max_tiles = ditron_moe_max_tiles(max_rows, num_local_experts);
+  hipStream_t s = (hipStream_t)stream;
+
+  int order[DITRON_MAX_WORLD] = {0};
+  if (emulate && world > 1) {
+    if (!peer_partials) return DITRON_ERR_INVALID_ARG;
+    bool seen[DITRON_MAX_WORLD] = {false};
+    for (int i = 0; i < world - 1; ++i) {
+      const int sr = arrival_order ? arrival_order[i] : ((rank - 1 - i) % world + world) % world;
+      if (sr < 0 || sr >= world || sr == rank || seen[sr]) return DITRON_ERR_INVALID_ARG;
+      seen[sr] = true;
+      order[i] = sr;
+      if (!peer_partials[sr] || !aligned16(peer_partials[sr])) return DITRON_ERR_INVALID_ARG;
+    }
+  }
+
+  // 1. inverse index starts at "not on this rank"
+  hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)std::min<long>(256, (assignments + 1023) / 1024)), dim3(1024), 0, s,
+                     inverse_idx, (int)assignments, -1);
+  // 2. tile list + inverse index
+  const MoeTile mt = choose_moe_tile(moe_expected_rows((long)world * tokens_per_rank, top_k, num_experts, num_local_experts),
+                                     num_local_experts, hidden);
+  MoeRsPrepareParams pr{};
+  pr.expert_offsets = expert_offsets;
+  pr.gather_idx = gather_idx;
+  pr.inverse_idx = inverse_idx;
+  pr.tile_records = tile_records;
+  pr.status = status;
+  pr.num_local = num_local_experts;
+  pr.block_m = mt.block_m;
+  pr.max_rows = max_rows;
+  pr.max_tiles = max_tiles;
+  pr.assignments = (int)assignments;
+  hipLaunchKernelGGL(moe_rs_prepare_kernel, dim3(1 + (unsigned)std::min(64, cdiv(max_rows, 1024))), dim3(1024), 0, s, pr);
+  if (hipGetLastError() != hipSuccess) return DITRON_ERR_HIP;
+
+  // 3. grouped GEMM y[p, :] = h[p, :] . W2_expert(p): contraction over the intermediate size, hidden columns
+  MoeGemmParams g{};
+  g.workspace = (const char*)h;
+  g.w = (const char*)w;
+  g.y = (__bf16*)y;
+  g.expert_offsets = expert_offsets;
+  g.gather_idx = gather_idx;
+  g.tile_records = tile_records;
+  g.flags = signals;
+  g.status = status;
+  g.tokens_per_rank = tokens_per_rank;
+  g.hidden = inter;
+  g.inter = hidden;
+  g.top_k = top_k;
+  g.world = world;
+  g.max_tiles = max_tiles;
+  g.num_local = num_local_experts;
+  g.num_xcd = 8;
+  g.rows_in_place = 1;
+  g.epoch = epoch;
+  g.spin_limit = tune.spin_limit;
+  g.wait = 0;
+  ditron_status_t st;
+  if (w_layout == DITRON_B_KN) {
+    const bool wide = mt.block_n > 128;
+    if (mt.block_m == 256) st = wide ? launch_moe_gemm<GemmTile4W<256, 256, true>>(g, max_tiles, s) : launch_moe_gemm<GemmTile4W<256, 128, true>>(g, max_tiles, s);
+    else st = wide ? launch_moe_gemm<GemmTile4W<128, 256, true>>(g, max_tiles, s) : launch_moe_gemm<GemmTile4W<128, 128, true>>(g, max_tiles, s);
+  } else if (mt.block_m == 256) {
+    st = mt.block_n == 128 ? launch_moe_gemm<GemmTile4W<256, 128>>(g, max_tiles, s) : launch_moe_gemm<GemmTile4W<256, 256>>(g, max_tiles, s);
+  } else {
+    switch (mt.block_n) {
+      case 128: st = launch_moe_gemm<GemmTile4W<128, 128, false, true>, 5>(g, max_tiles, s); break;
+      case 192: st = launch_moe_gemm<GemmTile4W<128, 192, false, true>, 4>(g, max_tiles, s); break;
+      default: st = launch_moe_gemm<GemmTile4W<128, 256, false, true>, 3>(g, max_tiles, s); break;
+    }
+  }
+  if (st != DITRON_OK) return st;
+
+  // 4. top-k combine into token order; the emulated peers' blocks arrive beside it
+  const size_t slot_bytes = (size_t)tokens_per_rank * hidden * 2;
+  MoeCombineParams c{};
+  c.y = (const __bf16*)y;
+  c.inverse_idx = inverse_idx;
+  c.gate = topk_weights;
+  c.combined = (__bf16*)combined;
+  c.tokens = world * tokens_per_rank;
+  c.top_k = top_k;
+  c.hidden = hidden;
+  c.combine_wgs = (int)std::min<long>(512, ((long)c.tokens * (hidden / 8) + 1023) / 1024);
+  c.done = signals + world;                                   // the counter word of segment 0 (unused here otherwise)
+  c.own_flags = signals + 2 * world + rank * chunks_per_slot;
+  for (int i = 0; i < world; ++i) {
+    c.peer[i] = (emulate && i != rank && world > 1) ? peer_partials[i] : nullptr;
+    c.order[i] = order[i];
+  }
+  c.scatter_buf = (char*)scatter_buf;
+  c.arr_flags = signals + 2 * world;
+  c.arr_counters = signals + 2 * world + world * chunks_per_slot;
+  c.slot_bytes = slot_bytes;
+  c.chunks = chunks_per_slot;
+  c.n_peers = world - 1;
+  const ProducerPlan pl = plan_producers((size_t)(world - 1) * slot_bytes, (world - 1) * chunks_per_slot);
+  c.num_producers = (emulate && world > 1) ? std::min(pl.producers, 128) : 0;
+  c.teams = std::min(pl.teams, std::max(1, c.num_producers));
+  c.epoch = epoch;
+  hipLaunchKernelGGL(moe_combine_kernel, dim3((unsigned)(c.combine_wgs + c.num_producers)), dim3(1024), 0, s, c);
+  if (hipGetLastError() != hipSuccess) return DITRON_ERR_HIP;
+
+  // 5. the reduction of GEMM-ReduceScatter over the `world` slots (own slot: the rank's rows of `combined`)
+  const void* slots[DITRON_MAX_WORLD];
+  for (int i = 0; i < world; ++i)
+    slots[i] = i == rank ? (const void*)((const char*)combined + (size_t)rank * slot_bytes)
+                         : (const void*)((const char*)scatter_buf + (size_t)i * slot_bytes);
+  // flags preset: the peers' blocks are resident and nothing gates the sum but the stream order
+  return ditron_reduce_slots(slots, out, mode == Mode::kPreset ? nullptr : signals + 2 * world, status, tokens_per_rank,
+                             hidden, world, chunks_per_slot, epoch, tuning, stream);
 }
