@@ -119,6 +119,13 @@ def bench_ag_gemm(args, cfg_id):
                       "frac": flops / (preset_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
                       "note": "same kernel, all shards resident and flags preset"},
     }
+    gather_bytes = 2.0 * cfg.m * cfg.k * 2
+    if kernel_ms > preset_ms:
+        gbs = gather_bytes / ((kernel_ms - preset_ms) * 1e-3) / 1e9
+        out["gather"] = {"bound": "hbm", "bytes": gather_bytes, "us": (kernel_ms - preset_ms) * 1e3, "achieved": gbs,
+                         "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
+                         "note": "the emulated all-gather (read + write of the eight shards by the producer work-groups of the "
+                                 "same launch): its bytes over the time it adds to the launch (fused minus flags preset)"}
     if not args.no_cpu:
         out["cpu_baseline"] = _cpu_baseline_ag(cfg, shards, b)
     return out
@@ -160,6 +167,20 @@ def _ramp(torch, step):
         for _ in range(20):
             step()
         torch.cuda.synchronize()
+
+
+def _events_us(torch, fn, n=100, warm=10):
+    """Quantiles (us) of n calls of fn, events around each."""
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    ev = _events(torch, n)
+    for a, b in ev:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    return _quantiles_us(ev)
 
 
 def _quantiles_us(ev):
@@ -434,6 +455,13 @@ def bench_moe(args):
     if run.status.cpu().tolist()[0] != 0:
         raise RuntimeError("kernel reported an error")
     R = int(run.offsets.cpu()[-1])
+    # the gather on its own: the same call with a routing that sends nothing to the local experts, so the grouped
+    # GEMM launch has no tile and the step is the routing launch (routing scan beside the emulated all-gather)
+    nowhere = torch.full_like(idd, (e0 + cfg.num_local_experts) % cfg.num_experts)
+    gather_us = _events_us(torch, lambda: run(xd, nowhere, wds[0], e0, cfg.rank))["median"]
+    gather_bytes = 2.0 * cfg.world * cfg.tokens_per_rank * cfg.k * 2
+    step()          # leave the buffers as the timed steps had them
+    torch.cuda.synchronize()
     flops = 2.0 * R * cfg.k * cfg.n
     w_bytes = w.size * 2
     alg_bytes = w_bytes + R * cfg.k * 2 + R * cfg.n * 2
@@ -449,6 +477,10 @@ def bench_moe(args):
                      "traffic": MEASURED_TRAFFIC.get("cfg4"),
                      "kernel": "moe_route_kernel + moe_grouped_gemm_kernel (whole step between events)", "kernel_ms": ev_ms,
                      "bytes": alg_bytes},
+        "gather": {"bound": "hbm", "bytes": gather_bytes, "us": gather_us, "achieved": gather_bytes / gather_us / 1e3,
+                   "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gather_bytes / gather_us / 1e3 / PEAK_HBM_GBS,
+                   "note": "the emulated all-gather of the token shards (read + write) beside the routing scan: the call with a "
+                           "routing that sends nothing to the local experts, events around it (includes the launch of both kernels)"},
     }
     if not args.no_cpu:
         from oracle import moe as omoe
@@ -597,7 +629,16 @@ def bench_moe_sweep(args):
             if st != B.OK:
                 raise RuntimeError(B.status_string(st))
 
-        problems.append((name, hidden, inter, experts, top_k, rows, call, run))
+        # the same call with nothing routed to the one local expert it is given: the gather + routing launch alone
+        ids_none = torch.zeros_like(ids)
+        run_g = MoeRun(B, world, t_r, hidden, inter, experts, top_k, 1, 1024)
+
+        def gather_only(run_g=run_g, xs=xs, ids_none=ids_none, w=w):
+            st = run_g(xs, ids_none, w, 1, 0)
+            if st != B.OK:
+                raise RuntimeError(B.status_string(st))
+
+        problems.append((name, hidden, inter, experts, top_k, rows, call, run, gather_only))
 
     def step():
         for pr in problems:
@@ -620,16 +661,19 @@ def bench_moe_sweep(args):
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     rows_out, total_flops, logs = [], 0.0, []
-    for i, (name, hidden, inter, experts, top_k, rows, _, run) in enumerate(problems):
+    for i, (name, hidden, inter, experts, top_k, rows, _, run, gather_only) in enumerate(problems):
         if run.status.cpu().tolist()[0] != 0:
             raise RuntimeError("kernel reported an error")
+        g_us = _events_us(torch, gather_only, n=30, warm=5)["median"]
+        g_bytes = 2.0 * world * t_r * hidden * 2
         assert int(run.offsets.cpu()[-1]) == rows
         flops = 2.0 * rows * hidden * inter
         total_flops += flops
         us = _quantiles_us(per[i])["median"]
         alg_bytes = experts * inter * hidden * 2 + world * t_r * hidden * 2 + rows * inter * 2
         rows_out.append({"model": name, "tokens": world * t_r, "hidden": hidden, "inter": inter, "experts": experts, "top_k": top_k,
-                         "rows": rows, "us": us, "tflops": flops / us / 1e6, "algorithmic_gbs": alg_bytes / us / 1e3})
+                         "rows": rows, "us": us, "tflops": flops / us / 1e6, "algorithmic_gbs": alg_bytes / us / 1e3,
+                         "gather_bytes": g_bytes, "gather_us": g_us, "gather_gbs": g_bytes / g_us / 1e3})
         logs.append(math.log(flops / us / 1e6))
     ms_per_step = wall * 1e3 / reps
     geo = math.exp(sum(logs) / len(logs))
