@@ -26,17 +26,29 @@ PEAK_FP8_TFLOPS = 5000.0
 PEAK_HBM_GBS = 8000.0
 
 # Bytes per launch of the dominant kernel between the L2s and memory, from two rocprofv3 --pmc runs
-# (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch) of the commands given in profiles/, each scaled by
-# what the same counter reads for this script's 256 MiB calibration copy (FETCH_SIZE reports 0.500 of
-# the bytes read, WRITE_SIZE 1.000 of the bytes written).  Reads include those served by the
-# memory-side cache.
+# (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch) of the commands given in the profile named with each
+# entry, each scaled by what the same counter reads for this script's 256 MiB calibration copy
+# (FETCH_SIZE reports 0.500 of the bytes read, WRITE_SIZE 1.000 of the bytes written).  Reads include
+# those served by the memory-side cache.  A run cannot collect these itself (the counters need the
+# profiler), so every entry says which build it was measured on; re-measure after changing the kernel.
 MEASURED_TRAFFIC = {
-    "cfg2": 956.9e6 + 192.9e6,   # ag_gemm_kernel, fused launch (GEMM-only launch: 822.3e6 + 58.7e6); algorithmic 251.7e6 (+ 268.4e6 emulated gather)
-    "cfg3": 822.4e6 + 253.9e6,   # gemm_rs_kernel (reduce_slots_kernel: 134.3e6 + 16.8e6 = its algorithmic 151.0e6)
-    "cfg4": 327.6e6 + 6.2e6,     # moe_grouped_gemm_kernel (the emulated gather, in the routing launch: 67.3e6 + 67.1e6)
-    "gemm_ar": 1999.3e6 + 268.8e6,   # gemm_ar_kernel, fused launch: operand panels ~0.9e9 + eight partials 1.07e9 read; partial + output written
-    "cfg5": 76.8e6 + 3.1e6,      # ag_gemm_decode_kernel (fp8); algorithmic 70.3e6
+    # workload: (bytes read + bytes written, profile, kernels as of commit)
+    "cfg2": (956.9e6 + 192.9e6, "profiles/ag_gemm_kernel_cfg2.md", "f7bf4c3"),   # fused launch; GEMM-only launch 822.3e6 + 58.7e6; algorithmic 251.7e6 (+ 268.4e6 emulated gather)
+    "cfg3": (822.4e6 + 253.8e6, "profiles/gemm_rs_kernel_reduce_slots_kernel_cfg3.md", "f7bf4c3"),   # gemm_rs_kernel fused; reduce_slots_kernel 134.3e6 + 16.8e6 = its algorithmic 151.0e6
+    "cfg4": (141.7e6 + 6.2e6, "profiles/moe_kernels_cfg4.md", "f7bf4c3"),   # moe_grouped_gemm_kernel (algorithmic 123.2e6); the gather in the routing launch: 67.4e6 + 67.2e6
+    "gemm_ar": (1999.3e6 + 268.8e6, "profiles/gemm_ar_kernel_table_shape3.md", "41de86f"),   # fused launch: operand panels ~0.9e9 + eight partials 1.07e9 read; partial + output written
+    "cfg5": (110.5e6 + 37.0e6, "profiles/ag_gemm_splitk_kernel_cfg5.md", "f7bf4c3"),   # ag_gemm_splitk_kernel (fp8) with emulated peers: B 67.1e6 + A + the partial tiles out and back; algorithmic 70.3e6
 }
+
+
+def _traffic(key):
+    t = MEASURED_TRAFFIC.get(key)
+    return None if t is None else t[0]
+
+
+def _traffic_source(key):
+    t = MEASURED_TRAFFIC.get(key)
+    return None if t is None else {"profile": t[1], "kernels_as_of_commit": t[2]}
 
 
 def _cpu_baseline_ag(cfg, shards, b):
@@ -112,7 +124,7 @@ def bench_ag_gemm(args, cfg_id):
                                f"B [{cfg.k},{cfg.n}] stored [n,k] -> C [{cfg.m},{cfg.n}] bf16, fp32 accumulate",
                    "latency_us": kernel_ms * 1e3, "latency_us_quantiles": _quantiles_us(ev)},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": MEASURED_TRAFFIC.get(f"cfg{cfg_id}"),
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": _traffic(f"cfg{cfg_id}"), "traffic_source": _traffic_source(f"cfg{cfg_id}"),
                      "kernel": "ag_gemm_kernel (producer work-groups + GEMM tiles in one launch)",
                      "kernel_ms": kernel_ms},
         "gemm_only": {"ms": preset_ms, "us_quantiles": _quantiles_us(pe), "achieved": flops / (preset_ms * 1e-3) / 1e12,
@@ -284,7 +296,7 @@ def bench_gemm_rs(args):
         "config": {"workload": f"cfg3: GEMM-RS world={cfg.world} rank={d} A [{cfg.m},{cfg.k}] B [{cfg.k},{cfg.n}] stored [n,k], "
                                f"7 peer blocks [{m_r},{cfg.n}] bf16, 4 row chunks per block", "latency_us": ev_ms * 1e3},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": MEASURED_TRAFFIC.get("cfg3"),
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": _traffic("cfg3"), "traffic_source": _traffic_source("cfg3"),
                      "kernel": "gemm_rs_kernel + reduce_slots_kernel (whole step between events)", "kernel_ms": ev_ms},
         "flags_preset": {"ms": preset_ms, "us_quantiles": _quantiles_us(pe), "achieved": flops / (preset_ms * 1e-3) / 1e12,
                          "frac": flops / (preset_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
@@ -402,7 +414,7 @@ def bench_gemm_ar(args):
         "config": {"workload": f"gemm_ar: GEMM-AR world={cfg.world} rank={d} A [{cfg.m},{cfg.k}] B [{cfg.k},{cfg.n}] stored [n,k], "
                                f"7 peer partials [{cfg.m},{cfg.n}] bf16 resident -> out [{cfg.m},{cfg.n}] bf16", "latency_us": ev_ms * 1e3},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": MEASURED_TRAFFIC.get("gemm_ar"),
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": _traffic("gemm_ar"), "traffic_source": _traffic_source("gemm_ar"),
                      "kernel": "gemm_ar_kernel (GEMM tiles + all-reduce consumers in one launch)", "kernel_ms": ev_ms},
         "two_shot": {"ms": two_ms, "achieved": flops / (two_ms * 1e-3) / 1e12, "us_quantiles": _quantiles_us(ev2),
                      "note": "ditron_gemm_ar_two_shot on the same operands: 1/8 of the tiles reduced here and stored to eight outputs, "
@@ -474,7 +486,7 @@ def bench_moe(args):
         "config": {"workload": f"cfg4: MoE world={cfg.world} rank={cfg.rank} tokens 8x{cfg.tokens_per_rank} hidden {cfg.k} inter {cfg.n} "
                                f"{cfg.num_experts} experts top-{cfg.top_k}, {cfg.num_local_experts} local, R={R}", "latency_us": ev_ms * 1e3},
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
-                     "traffic": MEASURED_TRAFFIC.get("cfg4"),
+                     "traffic": _traffic("cfg4"), "traffic_source": _traffic_source("cfg4"),
                      "kernel": "moe_route_kernel + moe_grouped_gemm_kernel (whole step between events)", "kernel_ms": ev_ms,
                      "bytes": alg_bytes},
         "gather": {"bound": "hbm", "bytes": gather_bytes, "us": gather_us, "achieved": gather_bytes / gather_us / 1e3,
@@ -774,7 +786,7 @@ def bench_fp8(args):
                                f"-> C [{cfg.m},{cfg.n}] bf16; weights rotated over {nsets} copies", "latency_us": ev_ms * 1e3,
                    "tflops": flops / (ev_ms * 1e-3) / 1e12},
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
-                     "traffic": MEASURED_TRAFFIC.get("cfg5"), "kernel": "ag_gemm_splitk_kernel (fp8)", "kernel_ms": ev_ms,
+                     "traffic": _traffic("cfg5"), "traffic_source": _traffic_source("cfg5"), "kernel": "ag_gemm_splitk_kernel (fp8)", "kernel_ms": ev_ms,
                      "bytes": alg_bytes},
         "flags_preset_us": preset,
         "tiny_launch_us": floor_us,
