@@ -131,6 +131,14 @@ def bench_ag_gemm(args, cfg_id):
                       "frac": flops / (preset_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
                       "note": "same kernel, all shards resident and flags preset"},
     }
+    st, tc = B.tile_config(0, cfg.m, cfg.n, cfg.k)
+    stamps = torch.zeros(4 * tc["ntiles"] * tc["splits"], dtype=torch.int32, device="cuda")
+    run.epoch += 1
+    st = B.ag_gemm(sh, bd, B.B_NK, run.c, None, None, run.ws_raw, run.signals, run.status, stamps, None, cfg.m_per_rank, cfg.n,
+                   cfg.k, cfg.world, cfg.rank, B.BF16, run.epoch, B.EMULATE_PRODUCER | B.DUMP_TIMING)
+    torch.cuda.synchronize()
+    if st == B.OK:
+        out["flag_wait"] = _wait_share(torch, B, stamps)
     gather_bytes = 2.0 * cfg.m * cfg.k * 2
     if kernel_ms > preset_ms:
         gbs = gather_bytes / ((kernel_ms - preset_ms) * 1e-3) / 1e9
@@ -193,6 +201,22 @@ def _events_us(torch, fn, n=100, warm=10):
         b.record()
     torch.cuda.synchronize()
     return _quantiles_us(ev)
+
+
+def _wait_share(torch, B, records):
+    """From the time stamps a DITRON_DUMP_TIMING call wrote (start, wait entered, wait left, end per GEMM
+    work-group, 100 MHz ticks): the share of the work-groups' time spent waiting for shard flags."""
+    r = records.cpu().numpy().reshape(-1, 4).astype("int64")
+    r = r[(r[:, 3] != 0) & (r[:, 0] != 0)]
+    if not len(r):
+        return None
+    wait = (r[:, 2] - r[:, 1]) % (1 << 31)
+    busy = (r[:, 3] - r[:, 0]) % (1 << 31)
+    span = (r[:, 3].max() - r[:, 0].min()) % (1 << 31)
+    return {"work_groups": int(len(r)), "wait_share": float(wait.sum() / busy.sum()), "mean_wait_us": float(wait.mean() / 100.0),
+            "mean_work_group_us": float(busy.mean() / 100.0), "first_start_to_last_end_us": float(span / 100.0),
+            "note": "in-kernel time stamps of one launch with emulated peers: time between entering and leaving the shard-flag wait over "
+                    "the work-group's lifetime, summed over the GEMM work-groups"}
 
 
 def _quantiles_us(ev):
@@ -761,6 +785,13 @@ def bench_fp8(args):
         return q
 
     preset = events_us(make_step(run, B.FLAGS_PRESET))
+    st, tc0 = B.tile_config(0, cfg.m, cfg.n, cfg.k, B.FP8_E4M3, run.tuning)
+    stamps = torch.zeros(4 * tc0["ntiles"] * tc0["splits"], dtype=torch.int32, device="cuda")
+    run.epoch += 1
+    st = B.ag_gemm(ad, bds[0], B.B_NK, run.c, sad, sbd, run.ws_raw, run.signals, run.status, stamps, None, cfg.m_per_rank, cfg.n,
+                   cfg.k, cfg.world, cfg.rank, B.FP8_E4M3, run.epoch, B.EMULATE_PRODUCER | B.DUMP_TIMING, tuning=run.tuning)
+    torch.cuda.synchronize()
+    wait_share = _wait_share(torch, B, stamps) if st == B.OK else None
     # what one tiny launch costs between two events on this machine (the floor of any single-call latency)
     tiny = torch.zeros((1, 8), dtype=torch.int16, device="cuda")
     floor_us = events_us(lambda: B.reduce_slots([tiny], tiny.clone(), None, run.status, 1, 8, 1, 1, 1))
@@ -789,6 +820,7 @@ def bench_fp8(args):
                      "traffic": _traffic("cfg5"), "traffic_source": _traffic_source("cfg5"), "kernel": "ag_gemm_splitk_kernel (fp8)", "kernel_ms": ev_ms,
                      "bytes": alg_bytes},
         "flags_preset_us": preset,
+        "flag_wait": wait_share,
         "tiny_launch_us": floor_us,
         "decode_variants": variants,
     }

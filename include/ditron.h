@@ -82,7 +82,13 @@ enum {
   DITRON_EMULATE_PRODUCER = 1u,  /* the call itself copies the shards and raises the flags */
   DITRON_EXTERNAL_PRODUCER = 2u, /* somebody else fills the workspace and raises the flags   */
   DITRON_FLAGS_PRESET = 4u,      /* the remote data is resident: no copies, no flag waits    */
-  DITRON_DUMP_SCHEDULE = 8u      /* write the tile schedule to `schedule_out`                */
+  DITRON_DUMP_SCHEDULE = 8u,     /* write the tile schedule to `schedule_out`                */
+  DITRON_DUMP_TIMING = 16u       /* ditron_ag_gemm: write per-work-group time stamps to `schedule_out`
+                                  * instead (not together with DITRON_DUMP_SCHEDULE): the record of a GEMM
+                                  * work-group, at the index its schedule record would have, is (start,
+                                  * flag wait entered, flag wait left, end) in ticks of the GPU's constant
+                                  * 100 MHz clock, low 31 bits: where a launch's time goes between waiting
+                                  * for shards and computing (decode_variant 1 writes nothing) */
 };
 
 /* Per-call options (host memory, read during the call).  A zero field means "default", so a

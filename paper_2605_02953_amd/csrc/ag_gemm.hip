@@ -23,6 +23,7 @@ struct AgGemmParams {
   int32_t* arrivals;   // [world] producer arrival counters
   int32_t* status;
   int32_t* schedule;   // or null
+  int timing;          // schedule records hold time stamps instead
   int m_per_rank, m, n, k, world, rank, nnodes;
   int32_t epoch;
   int num_producers, teams;
@@ -46,11 +47,13 @@ __global__ __launch_bounds__(T::THREADS) void ag_gemm_kernel(const AgGemmParams 
   const int wg = blockIdx.x - p.num_producers;
   const TileSpan t = tile_of_workgroup(wg, p.tiling, kOrderGather, p.m, p.m_per_rank, p.rank, p.world, p.nnodes, T::BM);
   const int m0 = t.pid_m * T::BM, n0 = t.pid_n * T::BN;
-  if (p.schedule && threadIdx.x == 0) {
+  const unsigned long long ts_start = p.timing ? wall_clock64() : 0;
+  if (p.schedule && !p.timing && threadIdx.x == 0) {
     int32_t* rec = p.schedule + 4 * (size_t)wg;
     rec[0] = t.pid_m; rec[1] = t.pid_n; rec[2] = t.first; rec[3] = t.last;
   }
   if (p.wait) flag_wait_block(p.flags, t.first, t.last - t.first + 1, p.epoch, p.spin_limit, p.status);
+  const unsigned long long ts_ready = p.timing ? wall_clock64() : 0;
 
   const uint32_t row_bytes = (uint32_t)p.k * 2u;
   const int M = p.m, N = p.n;
@@ -63,6 +66,11 @@ __global__ __launch_bounds__(T::THREADS) void ag_gemm_kernel(const AgGemmParams 
     gemm_mainloop<T>(acc, p.workspace, a_row, p.b, b_row, p.k, lds);
   }
   store_tile_bf16<T>(acc, p.c, (size_t)p.n, m0, n0, M, N, lds);
+  if (p.timing && threadIdx.x == 0) {
+    int32_t* rec = p.schedule + 4 * (size_t)wg;
+    rec[0] = (int32_t)(ts_start & 0x7fffffff); rec[1] = rec[0];
+    rec[2] = (int32_t)(ts_ready & 0x7fffffff); rec[3] = (int32_t)(wall_clock64() & 0x7fffffff);
+  }
 }
 
 template <class T>
@@ -94,7 +102,8 @@ extern "C" ditron_status_t ditron_ag_gemm(const void* const* a_shards, const voi
   const Mode mode = producer_mode(flags);
   if (mode == Mode::kInvalid) return DITRON_ERR_INVALID_ARG;
   const bool emulate = mode == Mode::kEmulate;
-  if ((flags & DITRON_DUMP_SCHEDULE) && !schedule_out) return DITRON_ERR_INVALID_ARG;
+  if ((flags & (DITRON_DUMP_SCHEDULE | DITRON_DUMP_TIMING)) && !schedule_out) return DITRON_ERR_INVALID_ARG;
+  if ((flags & DITRON_DUMP_SCHEDULE) && (flags & DITRON_DUMP_TIMING)) return DITRON_ERR_INVALID_ARG;
   if (b_layout != DITRON_B_KN && b_layout != DITRON_B_NK) return DITRON_ERR_INVALID_ARG;
   if (dtype != DITRON_BF16 && dtype != DITRON_FP8_E4M3) return DITRON_ERR_INVALID_ARG;
   if (emulate) {
@@ -120,7 +129,8 @@ extern "C" ditron_status_t ditron_ag_gemm(const void* const* a_shards, const voi
   p.flags = signals;
   p.arrivals = signals + world;
   p.status = status;
-  p.schedule = (flags & DITRON_DUMP_SCHEDULE) ? schedule_out : nullptr;
+  p.schedule = (flags & (DITRON_DUMP_SCHEDULE | DITRON_DUMP_TIMING)) ? schedule_out : nullptr;
+  p.timing = (flags & DITRON_DUMP_TIMING) != 0;
   p.m_per_rank = m_per_rank;
   p.m = m_per_rank * world;
   p.n = n;

@@ -46,6 +46,7 @@ struct AgGemmDecodeParams {
   int num_producers, teams;
   unsigned spin_limit;
   int wait;   // 0: every shard is resident, the flags are not looked at
+  int timing; // schedule records hold time stamps instead
   int group_m, num_xcd, per_xcd, npm, npn;
   // split-K kernel
   int splits, kt_per_split;   // K splits per output tile; 128-byte K tiles per split
@@ -75,7 +76,7 @@ __global__ __launch_bounds__(DecodeTile::THREADS) void ag_gemm_decode_kernel(con
   const int m0 = pid_m * T::BM, n0 = pid_n * T::BN;
   const int rank_beg = m0 / p.m_per_rank;
   const int rank_end = (min(m0 + T::BM, p.m) - 1) / p.m_per_rank;
-  if (p.schedule && threadIdx.x == 0) {
+  if (p.schedule && !p.timing && threadIdx.x == 0) {
     int32_t* rec = p.schedule + 4 * (size_t)wg;
     rec[0] = pid_m; rec[1] = pid_n; rec[2] = rank_beg; rec[3] = rank_end;
   }
@@ -277,7 +278,9 @@ __global__ __launch_bounds__(T::THREADS) void ag_gemm_splitk_kernel(const AgGemm
   const TileOrder order{p.npm, p.npn, p.group_m, 0, 0};
   const TileSpan t = tile_of_workgroup(tile, order, kOrderGather, p.m, p.m_per_rank, p.rank, p.world, p.nnodes, T::BM);
   const int m0 = t.pid_m * T::BM, n0 = t.pid_n * T::BN;
-  if (p.schedule && threadIdx.x == 0) {
+  const unsigned long long ts_start = p.timing ? wall_clock64() : 0;
+  unsigned long long ts_wait = 0, ts_ready = 0;
+  if (p.schedule && !p.timing && threadIdx.x == 0) {
     int32_t* rec = p.schedule + 4 * ((size_t)tile * p.splits + ks);
     rec[0] = t.pid_m; rec[1] = t.pid_n; rec[2] = t.first; rec[3] = t.last;
   }
@@ -339,7 +342,9 @@ __global__ __launch_bounds__(T::THREADS) void ag_gemm_splitk_kernel(const AgGemm
   // wave 0 looks at the flags; the loaders start B at once (it does not depend on the gather)
   // (two tiles only before the barrier: a deeper burst fills the unit's miss queue and the first loads
   // of A, issued after the barrier, would wait behind it)
+  if (p.timing) ts_wait = wall_clock64();
   if (wave == 0 && p.wait) flag_wait_wave(p.flags, t.first, t.last - t.first + 1, p.epoch, p.spin_limit, p.status);
+  if (p.timing) ts_ready = wall_clock64();
   if (loader) {
     issue_b(0);
     issue_b(1);
@@ -492,7 +497,17 @@ __global__ __launch_bounds__(T::THREADS) void ag_gemm_splitk_kernel(const AgGemm
       bf16x4_t o = {(__bf16)x[0], (__bf16)x[1], (__bf16)x[2], (__bf16)x[3]};
       *(bf16x4_t*)(p.c + (size_t)m * p.n + n) = o;
     }
+    if (p.timing && threadIdx.x == 0) {
+      int32_t* rec = p.schedule + 4 * ((size_t)tile * p.splits + ks);
+      rec[0] = (int32_t)(ts_start & 0x7fffffff); rec[1] = (int32_t)(ts_wait & 0x7fffffff);
+      rec[2] = (int32_t)(ts_ready & 0x7fffffff); rec[3] = (int32_t)(wall_clock64() & 0x7fffffff);
+    }
     return;
+  }
+  if (p.timing && threadIdx.x == 0) {   // the contraction was not split: stamped before the stores below are issued
+    int32_t* rec = p.schedule + 4 * ((size_t)tile * p.splits + ks);
+    rec[0] = (int32_t)(ts_start & 0x7fffffff); rec[1] = (int32_t)(ts_wait & 0x7fffffff);
+    rec[2] = (int32_t)(ts_ready & 0x7fffffff); rec[3] = (int32_t)(wall_clock64() & 0x7fffffff);
   }
   if (loader) return;
 
@@ -552,7 +567,8 @@ extern "C" ditron_status_t ditron_ag_gemm_decode(const void* const* a_shards, co
   p.flags = signals;
   p.arrivals = signals + world;
   p.status = status;
-  p.schedule = (flags & DITRON_DUMP_SCHEDULE) ? schedule_out : nullptr;
+  p.schedule = (flags & (DITRON_DUMP_SCHEDULE | DITRON_DUMP_TIMING)) ? schedule_out : nullptr;
+  p.timing = (flags & DITRON_DUMP_TIMING) != 0;
   p.m_per_rank = m_per_rank;
   p.m = m_per_rank * world;
   p.n = n;

@@ -270,3 +270,29 @@ def test_flags_preset_runs_the_gemm_alone(B):
     torch.cuda.synchronize()
     assert run.status.cpu().tolist()[0] == 0 and not run.signals.any()
     assert np.array_equal(bits(run.c), formats.encode_bf16_rne(oag.ag_gemm(shards, b).astype(np.float32)))
+
+
+@pytest.mark.parametrize("shape", [(4, 200, 264, 328), (8, 505, 3080, 192), (8, 16, 1024, 2048)])
+def test_timing_dump_is_ordered_and_leaves_the_result_alone(B, shape):
+    """DITRON_DUMP_TIMING: every GEMM work-group writes (start, wait entered, wait left, end), in that order in
+    time; the product is what it is without the flag; the two dump flags exclude each other."""
+    world, m_r, n, k = shape
+    cfg = synth.CONFIGS[2].scaled(world=world, m_per_rank=m_r, n=n, k=k, rank=1)
+    shards, b = synth.ag_gemm_inputs(cfg, integer=True)
+    st, tc = B.tile_config(0, cfg.m, n, k)
+    run = AgGemmRun(B, world, m_r, n, k)
+    stamps = torch.zeros(4 * tc["ntiles"] * tc["splits"], dtype=torch.int32, device="cuda")
+    sh, bd = [to_dev(s) for s in shards], to_dev(nk(b))
+    assert run(sh, bd, 1, flags=B.EMULATE_PRODUCER | B.DUMP_TIMING | B.DUMP_SCHEDULE, schedule=stamps) == B.ERR_INVALID_ARG
+    run.epoch += 1
+    st = B.ag_gemm(sh, bd, B.B_NK, run.c, None, None, run.ws_raw, run.signals, run.status, stamps, None, m_r, n, k, world, 1,
+                   B.BF16, run.epoch, B.EMULATE_PRODUCER | B.DUMP_TIMING)
+    assert st == B.OK
+    torch.cuda.synchronize()
+    assert run.status.cpu().tolist()[0] == 0
+    assert np.array_equal(bits(run.c), formats.encode_bf16_rne(oag.ag_gemm(shards, b).astype(np.float32)))
+    r = stamps.cpu().numpy().reshape(-1, 4).astype(np.int64)
+    assert (r != 0).all()
+    d = np.diff(r, axis=1) % (1 << 31)
+    assert (d < (1 << 30)).all()                 # start <= wait entered <= wait left <= end (modulo the 31-bit wrap)
+    assert ((r[:, 3] - r[:, 0]) % (1 << 31) < 100 * 1000 * 100).all()      # no work-group lives for 100 ms
