@@ -103,16 +103,20 @@ typedef struct {
                         * of a second).  A tiny value lets a test exercise the time-out path without
                         * hanging a kernel */
   int decode_variant;  /* decode-shaped ditron_ag_gemm only, see there; 0 = the library's choice */
-  int reserved[5];     /* must be zero */
+  int moe_route_groups; /* ditron_moe_ag_grouped_gemm only: work-groups that share the routing scan, 1..8;
+                        * 0 = one per 4096 assignments.  The outputs do not depend on it */
+  int reserved[4];     /* must be zero */
 } ditron_tuning_t;
 
 #define DITRON_MAX_WORLD 32
 #define DITRON_STATUS_WORDS 4
 #define DITRON_SCHEDULE_WORDS 4 /* int32 words per tile record in a schedule dump */
 #define DITRON_TILE_CONFIG_WORDS 10
+#define DITRON_MOE_ROUTE_SCRATCH_BYTES 266240u /* 8 work-groups x (32 x 256 + 128) int32 */
 
 /* Number of int32 words the `signals` array of any entry point must have for `world`
- * ranks and `chunks` flags per rank (chunks = 1 except for ditron_gemm_rs). */
+ * ranks and `chunks` flags per rank (chunks = 1 except for ditron_gemm_rs): flags and arrival
+ * counters per rank and per (rank, chunk), plus 16 words for the work-groups of the MoE routing. */
 size_t ditron_signal_words(int world, int chunks);
 
 /*
@@ -152,7 +156,9 @@ ditron_status_t ditron_tile_config(int op, int m, int n, int k, int dtype, const
  * Bytes of the `workspace` argument of ditron_ag_gemm (the gathered [world*m_per_rank, k] in `dtype`;
  * for decode-shaped problems, whose contraction is split over several work-groups, followed at the next
  * multiple of 256 bytes by the fp32 partial tiles) and of ditron_moe_ag_grouped_gemm
- * ([world*tokens_per_rank, hidden] bf16); 0 for invalid arguments.
+ * ([world*tokens_per_rank, hidden] bf16, followed at the next multiple of 256 bytes by
+ * DITRON_MOE_ROUTE_SCRATCH_BYTES through which the routing work-groups exchange their histograms;
+ * that part needs no initialisation); 0 for invalid arguments.
  * The other caller-sized arrays have closed forms given with their arguments (signals:
  * ditron_signal_words; tile_records: ditron_moe_max_tiles).
  */
@@ -397,8 +403,12 @@ ditron_status_t ditron_reduce_slots(const void* const* slots, void* out, const i
  *                order (expert_id counted from expert_begin, tiled_m = index of the tile in
  *                the unsorted per-expert order); the last max_tiles words are internal
  *                (first output row of each tile)
- *  workspace     device [world*tokens_per_rank, hidden] bf16 gathered tokens
- *  signals       device int32[ditron_signal_words(world, 1)]
+ *  workspace     device, ditron_moe_workspace_bytes(tokens_per_rank, hidden, world) bytes: the gathered
+ *                tokens [world*tokens_per_rank, hidden] bf16, then scratch of the routing scan
+ *  signals       device int32[ditron_signal_words(world, 1)]: shard flags and arrival counters in
+ *                the first 2*world words; the last 16 words are the routing work-groups' flags
+ *  The routing scan is shared by tuning->moe_route_groups work-groups (contiguous ranges of the flat
+ *  assignment index; they exchange their histograms through the scratch, one bounded wait each).
  *  If R exceeds max_rows, status[0] = DITRON_ERR_WORKSPACE, status[2] = R and no GEMM tile
  *  runs.  An expert id outside [0, num_experts) is an error, not a dropped assignment:
  *  status[0] = DITRON_ERR_INVALID_ARG, status[1] = the smallest flat index f holding such an id,

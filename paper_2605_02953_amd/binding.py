@@ -32,7 +32,7 @@ _ip = ctypes.POINTER(ctypes.c_int)
 class Tuning(ctypes.Structure):
     """ditron_tuning_t: per-call options; zero fields mean the defaults."""
     _fields_ = [("num_nodes", ctypes.c_int), ("spin_limit", ctypes.c_uint), ("decode_variant", ctypes.c_int),
-                ("reserved", ctypes.c_int * 5)]
+                ("moe_route_groups", ctypes.c_int), ("reserved", ctypes.c_int * 4)]
 
 
 _tp = ctypes.POINTER(Tuning)
@@ -119,9 +119,9 @@ def signal_words(world, chunks=1):
     return int(lib.ditron_signal_words(world, chunks))
 
 
-def tuning(num_nodes=0, spin_limit=0, decode_variant=0):
+def tuning(num_nodes=0, spin_limit=0, decode_variant=0, moe_route_groups=0):
     """A ditron_tuning_t to pass as `tuning=`."""
-    return Tuning(num_nodes, spin_limit, decode_variant)
+    return Tuning(num_nodes, spin_limit, decode_variant, moe_route_groups)
 
 
 def _tuning(t):
@@ -192,6 +192,7 @@ class PreparedAgGemm:
 
 
 STATIC_WORKSPACE_BYTES = 32 << 20
+MOE_ROUTE_SCRATCH_BYTES = 266240
 
 
 def ag_gemm_static(a_shards, b, b_layout, c, a_scales, b_scales, status, arrival_order, m_per_rank, n, k, world,

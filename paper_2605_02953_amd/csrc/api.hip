@@ -35,7 +35,8 @@ using namespace ditron;
 extern "C" size_t ditron_signal_words(int world, int chunks) {
   if (world < 1 || chunks < 1) return 0;
   // flags [world] + per-rank counters [world] + chunk flags [world*chunks] + chunk counters [world*chunks]
-  return (size_t)world * 2 + (size_t)world * chunks * 2;
+  // + the flags of the MoE routing work-groups (which sit behind a one-chunk layout)
+  return (size_t)world * 2 + (size_t)world * chunks * 2 + 16;
 }
 
 extern "C" ditron_status_t ditron_tile_config(int op, int m, int n, int k, int dtype, const ditron_tuning_t* tuning,
@@ -94,7 +95,7 @@ extern "C" size_t ditron_ag_gemm_workspace_bytes(int m_per_rank, int n, int k, i
 
 extern "C" size_t ditron_moe_workspace_bytes(int tokens_per_rank, int hidden, int world) {
   if (tokens_per_rank <= 0 || hidden <= 0 || world < 1 || world > DITRON_MAX_WORLD) return 0;
-  return (size_t)world * tokens_per_rank * hidden * 2;
+  return align256((size_t)world * tokens_per_rank * hidden * 2) + DITRON_MOE_ROUTE_SCRATCH_BYTES;
 }
 
 extern "C" ditron_status_t ditron_schedule_dump(int op, int m, int n, int k, int world, int rank, int dtype, int b_layout,

@@ -24,8 +24,7 @@ typedef GemmTile4W<128, 128> TileSmall;
 typedef GemmTile4W<256, 256, true> TileBigKN;
 typedef GemmTile4W<128, 128, true> TileSmallKN;
 // The MoE grouped GEMM: 4 waves as 2 x 2.  An expert's rows are padded to whole row tiles, so the row
-// tile is 128 unless the experts are large (1024 rows or more each under even routing), where the
-// 256-row tile's fewer loads per MFMA are worth more than the padding.
+// tile is 128 unless the experts are large or the 128-row tiles would need more rounds (choose_moe_tile).
 constexpr int kMoeBlockM = 128;   // the smallest row tile: what the upper bound on the tile count assumes
 struct MoeTile {
   int block_m, block_n;
@@ -48,16 +47,22 @@ inline int choose_moe_block_n(long expected_rows, int num_local_experts, int int
     if (cdiv(inter, w) * w < cdiv(inter, best) * best || (cdiv(inter, w) * w == cdiv(inter, best) * best && w > best)) best = w;
   return best;
 }
+// Row tile.  What a tile costs is the bytes its compute unit loads, (rows + columns) * K, times the rounds
+// the launch needs on 256 units; the 256-row tile has two LDS stages instead of a ring fed by loading waves,
+// which makes its loads about 1.3 times slower (measured: 64 experts x 768 rows x 256 columns, 416 tiles of
+// 128 rows in two rounds against 224 of 256 rows in one: 100 against 85 us for the whole call; 60 experts x
+// 546 rows x 176 columns: 97 against 94 us).  From 1024 rows per expert on the 256-row tile is also ahead
+// on matrix work (fewer loads per MFMA, little padding).
 inline MoeTile choose_moe_tile(long expected_rows, int num_local_experts, int inter) {
-  MoeTile t{};
-  if (expected_rows / num_local_experts >= 1024) {
-    t.block_m = 256;
-    t.block_n = inter <= 128 ? 128 : 256;
-  } else {
-    t.block_m = kMoeBlockM;
-    t.block_n = choose_moe_block_n(expected_rows, num_local_experts, inter);
-  }
-  return t;
+  const MoeTile small{kMoeBlockM, choose_moe_block_n(expected_rows, num_local_experts, inter)};
+  const MoeTile big{256, inter <= 128 ? 128 : 256};
+  if (expected_rows / num_local_experts >= 1024) return big;
+  const long rows = std::min<long>(expected_rows, 1 << 30);
+  auto per_unit = [&](const MoeTile& t) {
+    const long tiles = ((rows + t.block_m - 1) / t.block_m + (num_local_experts + 1) / 2) * cdiv(inter, t.block_n);
+    return ((tiles + 255) / 256) * (t.block_m + std::min(t.block_n, inter));
+  };
+  return 13 * per_unit(big) < 10 * per_unit(small) ? big : small;
 }
 // rows routed to the local experts if every expert received the same number of assignments
 inline long moe_expected_rows(long total_tokens, int top_k, int num_experts, int num_local_experts) {
@@ -193,16 +198,19 @@ struct Tuning {
   int num_nodes;
   unsigned spin_limit;
   int decode_variant;
+  int moe_route_groups;
   bool valid;
 };
 inline Tuning resolve_tuning(const ditron_tuning_t* t, int world) {
-  Tuning r{1, 1u << 20, 0, true};
+  Tuning r{1, 1u << 20, 0, 0, true};
   if (!t) return r;
   if (t->num_nodes < 0 || t->num_nodes > DITRON_MAX_WORLD || t->decode_variant < 0 || t->decode_variant > 4) r.valid = false;
+  if (t->moe_route_groups < 0 || t->moe_route_groups > 8) r.valid = false;
   for (int v : t->reserved) r.valid = r.valid && v == 0;
   if (t->num_nodes > 0) r.num_nodes = t->num_nodes;
   if (t->spin_limit) r.spin_limit = t->spin_limit;
   r.decode_variant = t->decode_variant;
+  r.moe_route_groups = t->moe_route_groups;
   if (world % r.num_nodes != 0) r.valid = false;
   return r;
 }

@@ -22,6 +22,14 @@ constexpr int kRouteWaves = kRouteThreads / 64;
 constexpr int kMaxExperts = 256;       // experts (global) the routing kernel can histogram
 constexpr int kMaxLocalExperts = 64;
 constexpr int kMaxTilesLds = 4096;     // tile stages kept in LDS by the schedule step
+constexpr int kRouteGroupsMax = 8;     // work-groups that share the routing scan
+// what a routing work-group hands to the others: its (rank, expert) histogram, its totals of the local
+// experts, and the smallest flat index at which it met an id that names no expert
+constexpr int kPartLocal = DITRON_MAX_WORLD * kMaxExperts;
+constexpr int kPartBad = kPartLocal + kMaxLocalExperts;
+constexpr int kRoutePartWords = kPartBad + 64;
+static_assert(kRouteGroupsMax * kRoutePartWords * 4 == DITRON_MOE_ROUTE_SCRATCH_BYTES, "scratch size declared at the boundary");
+constexpr int kNoBadId = 0x7fffffff;
 
 struct MoeRouteParams {
   const int32_t* topk_ids;   // [tokens * top_k]
@@ -32,7 +40,12 @@ struct MoeRouteParams {
   int32_t* status;
   int tokens_per_rank, top_k, num_experts, expert_begin, num_local, max_rows, max_tiles;
   int world, rank, block_m;
-  // the emulated peers (work-groups 1 .. num_producers)
+  // routing work-groups 0 .. groups-1 and the scheduling work-group `groups`
+  int groups;
+  int32_t* route_flags;      // [groups]
+  int32_t* parts;            // [groups][kRoutePartWords]
+  unsigned spin_limit;
+  // the emulated peers (work-groups groups+1 .. groups+num_producers)
   const void* shard[DITRON_MAX_WORLD];
   int order[DITRON_MAX_WORLD];
   char* workspace;
@@ -43,18 +56,27 @@ struct MoeRouteParams {
   int num_producers, teams;
 };
 
+// Work-groups 0 .. G-1 share the scan of the assignments: each owns one contiguous range, cut into one
+// contiguous range per wave, so that positions inside an expert follow the flat assignment index whatever G
+// is.  A work-group histograms its range, hands its partial tables to the others through memory (one flag
+// per work-group, bounded wait), and then places its own assignments: the first output position of (work-
+// group, wave, expert) is the expert's offset plus what the ranges before it hold of that expert.
+// Work-group G sums the histograms and writes counts, offsets and the tile list.  All G + 1 have the lowest
+// indices of the launch, so they are resident before anything else and the waits end.
 __global__ __launch_bounds__(kRouteThreads) void moe_route_kernel(const MoeRouteParams p) {
   __shared__ int s_counts[DITRON_MAX_WORLD * kMaxExperts];       // [world][num_experts]
   __shared__ int s_offsets[kMaxLocalExperts + 1];
   __shared__ int s_wave_base[kRouteWaves][kMaxLocalExperts];     // running output position per (wave, expert)
   __shared__ int s_tile_acc[kMaxLocalExperts + 1];               // exclusive prefix of tiles per expert
   __shared__ int s_cum[kMaxLocalExperts][DITRON_MAX_WORLD];      // inclusive per-rank cumulative rows per expert
+  __shared__ int s_total[kMaxLocalExperts], s_before[kMaxLocalExperts];
   __shared__ int s_stage[kMaxTilesLds];
   __shared__ int s_bad;                                          // smallest flat index holding an id outside [0, E)
-  if (blockIdx.x > 0) {
+  const int G = p.groups;
+  if ((int)blockIdx.x > G) {
     // streaming stores: the grouped GEMM that reads the workspace is a later launch
     produce_chunks<kRouteThreads, true>(
-        p.world, p.shard_bytes, blockIdx.x - 1, p.num_producers, p.teams, p.epoch,
+        p.world, p.shard_bytes, blockIdx.x - G - 1, p.num_producers, p.teams, p.epoch,
         [&](int i) { return (void*)(p.workspace + (size_t)p.order[i] * p.shard_bytes); },
         [&](int i) { return p.shard[p.order[i]]; }, [&](int i) { return p.flags + p.order[i]; },
         [&](int i) { return p.arrivals + p.order[i]; });
@@ -63,19 +85,116 @@ __global__ __launch_bounds__(kRouteThreads) void moe_route_kernel(const MoeRoute
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int F = p.world * p.tokens_per_rank * p.top_k;
   const int per_shard = p.tokens_per_rank * p.top_k;
-  const int E = p.num_experts, EL = p.num_local;
+  const int E = p.num_experts, EL = p.num_local, WE = p.world * E;
 
-  for (int i = tid; i < p.world * E; i += kRouteThreads) s_counts[i] = 0;
+  if ((int)blockIdx.x == G) {
+    // ---------------------------------------------------------------- counts, offsets, tile list
+    flag_wait_block(p.route_flags, 0, G, p.epoch, p.spin_limit, p.status);
+    for (int i = tid; i < WE; i += kRouteThreads) {
+      int c = 0;
+      for (int g = 0; g < G; ++g) c += p.parts[g * kRoutePartWords + i];
+      s_counts[i] = c;
+      p.counts[i] = c;
+    }
+    if (tid == 0) {
+      int bad = kNoBadId;
+      for (int g = 0; g < G; ++g) bad = min(bad, p.parts[g * kRoutePartWords + kPartBad]);
+      s_bad = bad;
+    }
+    __syncthreads();
+    if (s_bad != kNoBadId) {
+      // an id that names no expert: reported, never dropped silently (the counts would no longer sum to
+      // tokens * top_k); no tile is scheduled
+      if (tid == 0) {
+        p.status[0] = DITRON_ERR_INVALID_ARG;
+        p.status[1] = s_bad;
+        p.tile_records[0] = 0;
+      }
+      return;
+    }
+    // per-rank cumulative rows of the local experts; exclusive scan of their totals
+    if (tid < EL) {
+      int run = 0;
+      for (int s = 0; s < p.world; ++s) {
+        run += s_counts[s * E + p.expert_begin + tid];
+        s_cum[tid][s] = run;
+      }
+    }
+    __syncthreads();
+    if (tid == 0) {
+      int run = 0, tiles = 0;
+      for (int j = 0; j < EL; ++j) {
+        s_offsets[j] = run;
+        s_tile_acc[j] = tiles;
+        const int n_j = s_cum[j][p.world - 1];
+        run += n_j;
+        tiles += cdiv(n_j, p.block_m);
+      }
+      s_offsets[EL] = run;
+      s_tile_acc[EL] = tiles;
+    }
+    __syncthreads();
+    for (int j = tid; j <= EL; j += kRouteThreads) p.expert_offsets[j] = s_offsets[j];
+    const int R = s_offsets[EL];
+    const int ntiles = s_tile_acc[EL];
+    if (R > p.max_rows || ntiles > p.max_tiles || ntiles > kMaxTilesLds) {
+      if (tid == 0) {
+        p.status[0] = DITRON_ERR_WORKSPACE;
+        p.status[2] = R;
+        p.tile_records[0] = 0;
+      }
+      return;
+    }
+    // stage of a tile: position in the ring order rank, rank+1, ... of the last source rank among its rows
+    for (int t = tid; t < ntiles; t += kRouteThreads) {
+      int j = 0;
+      while (s_tile_acc[j + 1] <= t) ++j;
+      const int q0 = (t - s_tile_acc[j]) * p.block_m;
+      const int q1 = min(q0 + p.block_m, s_cum[j][p.world - 1]);
+      int seg_start = 0, seg_end = 0;
+      for (int s = 0; s < p.world; ++s) {
+        seg_start += (s_cum[j][s] <= q0);
+        seg_end += (s_cum[j][s] <= q1 - 1);
+      }
+      int stage = 0;
+      for (int s = seg_start; s <= seg_end; ++s) stage = max(stage, (s - p.rank + p.world) % p.world);
+      s_stage[t] = stage | (seg_start << 8) | (seg_end << 16);
+    }
+    __syncthreads();
+    int32_t* rec = p.tile_records + 1;
+    int32_t* row0 = p.tile_records + 1 + 4 * p.max_tiles;
+    for (int t = tid; t < ntiles; t += kRouteThreads) {
+      int j = 0;
+      while (s_tile_acc[j + 1] <= t) ++j;
+      const int mine = s_stage[t] & 0xFF;
+      int before = 0;
+      for (int u = s_tile_acc[j]; u < s_tile_acc[j + 1]; ++u) {
+        const int other = s_stage[u] & 0xFF;
+        before += (other < mine) || (other == mine && u < t);
+      }
+      const int pos = s_tile_acc[j] + before;
+      rec[4 * pos + 0] = j;
+      rec[4 * pos + 1] = t;
+      rec[4 * pos + 2] = (s_stage[t] >> 8) & 0xFF;
+      rec[4 * pos + 3] = (s_stage[t] >> 16) & 0xFF;
+      row0[pos] = s_offsets[j] + (t - s_tile_acc[j]) * p.block_m;
+    }
+    if (tid == 0) p.tile_records[0] = ntiles;
+    return;
+  }
+
+  // ------------------------------------------------------------------ routing work-group g
+  const int g = blockIdx.x;
+  for (int i = tid; i < WE; i += kRouteThreads) s_counts[i] = 0;
   for (int i = tid; i < kRouteWaves * kMaxLocalExperts; i += kRouteThreads) (&s_wave_base[0][0])[i] = 0;
-  if (tid == 0) s_bad = 0x7fffffff;
+  if (tid == 0) s_bad = kNoBadId;
   __syncthreads();
 
-  // histogram over (source rank, expert), and per-wave totals for the local experts.  A wave
-  // owns one contiguous range of assignments so that ranks inside an expert follow f.  The ids
-  // are fetched kBatch steps at a time so that the loads overlap instead of queueing one by one.
+  // histogram over (source rank, expert), and per-wave totals for the local experts.  The ids are fetched
+  // kBatch steps at a time so that the loads overlap instead of queueing one by one.
   constexpr int kBatch = 16;
-  const int per_wave = cdiv(cdiv(F, kRouteWaves), 64) * 64;
-  const int w_begin = min(wave * per_wave, F), w_end = min(w_begin + per_wave, F);
+  const int per_wave = cdiv(cdiv(F, G * kRouteWaves), 64) * 64;
+  const int w_begin = (int)min((long)(g * kRouteWaves + wave) * per_wave, (long)F), w_end = min(w_begin + per_wave, F);
   for (int f0 = w_begin; f0 < w_end; f0 += 64 * kBatch) {
     int e[kBatch];
 #pragma unroll
@@ -97,56 +216,52 @@ __global__ __launch_bounds__(kRouteThreads) void moe_route_kernel(const MoeRoute
     }
   }
   __syncthreads();
-  for (int i = tid; i < p.world * E; i += kRouteThreads) p.counts[i] = s_counts[i];
-  if (s_bad != 0x7fffffff) {
-    // an id that names no expert: reported, never dropped silently (the counts would no longer sum to
-    // tokens * top_k); no tile is scheduled
-    if (tid == 0) {
-      p.status[0] = DITRON_ERR_INVALID_ARG;
-      p.status[1] = s_bad;
-      p.tile_records[0] = 0;
-    }
-    return;
-  }
-
-  // totals of the local experts -> exclusive scan; per-rank cumulative rows
+  int32_t* part = p.parts + g * kRoutePartWords;
+  for (int i = tid; i < WE; i += kRouteThreads) part[i] = s_counts[i];
   if (tid < EL) {
-    int run = 0;
-    for (int s = 0; s < p.world; ++s) {
-      run += s_counts[s * E + p.expert_begin + tid];
-      s_cum[tid][s] = run;
+    int c = 0;
+    for (int w = 0; w < kRouteWaves; ++w) c += s_wave_base[w][tid];
+    part[kPartLocal + tid] = c;
+  }
+  if (tid == 0) part[kPartBad] = s_bad;
+  __syncthreads();
+  if (tid == 0) flag_raise(p.route_flags + g, p.epoch);
+  flag_wait_block(p.route_flags, 0, G, p.epoch, p.spin_limit, p.status);
+
+  // every routing work-group takes the same decisions from the same tables
+  if (tid < EL) {
+    int total = 0, before = 0;
+    for (int h = 0; h < G; ++h) {
+      const int c = p.parts[h * kRoutePartWords + kPartLocal + tid];
+      total += c;
+      before += h < g ? c : 0;
     }
+    s_total[tid] = total;
+    s_before[tid] = before;
+  }
+  if (tid == 64) {
+    int bad = kNoBadId;
+    for (int h = 0; h < G; ++h) bad = min(bad, p.parts[h * kRoutePartWords + kPartBad]);
+    s_bad = bad;
   }
   __syncthreads();
+  if (s_bad != kNoBadId) return;
   if (tid == 0) {
     int run = 0, tiles = 0;
     for (int j = 0; j < EL; ++j) {
       s_offsets[j] = run;
-      s_tile_acc[j] = tiles;
-      const int n_j = s_cum[j][p.world - 1];
-      run += n_j;
-      tiles += cdiv(n_j, p.block_m);
+      run += s_total[j];
+      tiles += cdiv(s_total[j], p.block_m);
     }
     s_offsets[EL] = run;
     s_tile_acc[EL] = tiles;
   }
   __syncthreads();
-  for (int j = tid; j <= EL; j += kRouteThreads) p.expert_offsets[j] = s_offsets[j];
-  const int R = s_offsets[EL];
-  const int ntiles = s_tile_acc[EL];
-  const bool fits = R <= p.max_rows && ntiles <= p.max_tiles && ntiles <= kMaxTilesLds;
-  if (!fits) {
-    if (tid == 0) {
-      p.status[0] = DITRON_ERR_WORKSPACE;
-      p.status[2] = R;
-      p.tile_records[0] = 0;
-    }
-    return;
-  }
+  if (s_offsets[EL] > p.max_rows || s_tile_acc[EL] > p.max_tiles || s_tile_acc[EL] > kMaxTilesLds) return;
 
-  // wave totals -> first output position of every (wave, expert)
+  // first output position of every (wave, expert) of this work-group
   if (tid < EL) {
-    int run = s_offsets[tid];
+    int run = s_offsets[tid] + s_before[tid];
     for (int w = 0; w < kRouteWaves; ++w) {
       const int c = s_wave_base[w][tid];
       s_wave_base[w][tid] = run;
@@ -193,46 +308,10 @@ __global__ __launch_bounds__(kRouteThreads) void moe_route_kernel(const MoeRoute
       int base = 0;
       if (local && rank == 0) base = atomicAdd(&s_wave_base[wave][j], count);
       base = __shfl(base, local ? __ffsll((long long)same) - 1 : lane);
-      if (local) p.gather_idx[base + rank] = f;
+      // (the range test only matters after a timed-out wait, when the tables may be incomplete)
+      if (local && (unsigned)(base + rank) < (unsigned)p.max_rows) p.gather_idx[base + rank] = f;
     }
   }
-
-  // tile list.  stage of a tile: position in the ring order rank, rank+1, ... of the last
-  // source rank among its rows
-  for (int t = tid; t < ntiles; t += kRouteThreads) {
-    int j = 0;
-    while (s_tile_acc[j + 1] <= t) ++j;
-    const int q0 = (t - s_tile_acc[j]) * p.block_m;
-    const int q1 = min(q0 + p.block_m, s_cum[j][p.world - 1]);
-    int seg_start = 0, seg_end = 0;
-    for (int s = 0; s < p.world; ++s) {
-      seg_start += (s_cum[j][s] <= q0);
-      seg_end += (s_cum[j][s] <= q1 - 1);
-    }
-    int stage = 0;
-    for (int s = seg_start; s <= seg_end; ++s) stage = max(stage, (s - p.rank + p.world) % p.world);
-    s_stage[t] = stage | (seg_start << 8) | (seg_end << 16);
-  }
-  __syncthreads();
-  int32_t* rec = p.tile_records + 1;
-  int32_t* row0 = p.tile_records + 1 + 4 * p.max_tiles;
-  for (int t = tid; t < ntiles; t += kRouteThreads) {
-    int j = 0;
-    while (s_tile_acc[j + 1] <= t) ++j;
-    const int mine = s_stage[t] & 0xFF;
-    int before = 0;
-    for (int u = s_tile_acc[j]; u < s_tile_acc[j + 1]; ++u) {
-      const int other = s_stage[u] & 0xFF;
-      before += (other < mine) || (other == mine && u < t);
-    }
-    const int pos = s_tile_acc[j] + before;
-    rec[4 * pos + 0] = j;
-    rec[4 * pos + 1] = t;
-    rec[4 * pos + 2] = (s_stage[t] >> 8) & 0xFF;
-    rec[4 * pos + 3] = (s_stage[t] >> 16) & 0xFF;
-    row0[pos] = s_offsets[j] + (t - s_tile_acc[j]) * p.block_m;
-  }
-  if (tid == 0) p.tile_records[0] = ntiles;
 }
 
 struct MoeGemmParams {
@@ -400,6 +479,12 @@ extern "C" ditron_status_t ditron_moe_ag_grouped_gemm(
   r.workspace = (char*)workspace;
   r.flags = signals;
   r.arrivals = signals + world;
+  // one routing work-group per 4096 assignments (three or four rounds of 64 per wave), eight at most
+  const long assignments = (long)world * tokens_per_rank * top_k;
+  r.groups = tune.moe_route_groups ? tune.moe_route_groups : (int)std::min<long>(kRouteGroupsMax, std::max<long>(1, assignments / 4096));
+  r.route_flags = signals + 4 * world;   // behind the flags and counters of a one-chunk layout
+  r.parts = (int32_t*)((char*)workspace + align256((size_t)world * tokens_per_rank * hidden * 2));
+  r.spin_limit = tune.spin_limit;
   r.shard_bytes = (size_t)tokens_per_rank * hidden * 2;
   r.epoch = epoch;
   // as many work-groups (of 1024 threads here) as the plan for 256-thread producers: measured best of
@@ -407,7 +492,7 @@ extern "C" ditron_status_t ditron_moe_ag_grouped_gemm(
   const ProducerPlan pl = plan_producers((size_t)world * r.shard_bytes, world);
   r.num_producers = emulate ? pl.producers : 0;
   r.teams = std::min(pl.teams, std::max(1, r.num_producers));
-  hipLaunchKernelGGL(moe_route_kernel, dim3(1 + r.num_producers), dim3(kRouteThreads), 0, s, r);
+  hipLaunchKernelGGL(moe_route_kernel, dim3(r.groups + 1 + r.num_producers), dim3(kRouteThreads), 0, s, r);
   if (hipGetLastError() != hipSuccess) return DITRON_ERR_HIP;
 
   MoeGemmParams g{};

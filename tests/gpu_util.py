@@ -87,7 +87,12 @@ class MoeRun:
         self.dims = (tokens_per_rank, hidden, inter, num_experts, top_k, num_local, max_rows, world)
         self.max_tiles = B.moe_max_tiles(max_rows, num_local)
         i32 = dict(dtype=torch.int32, device="cuda")
-        self.workspace = torch.zeros((world * tokens_per_rank, hidden), dtype=torch.int16, device="cuda")
+        # the gathered tokens, then the routing work-groups' scratch, which needs no initialisation: fill it with a
+        # pattern so that nothing can rely on zeros
+        gathered = world * tokens_per_rank * hidden * 2
+        self.ws_raw = torch.full((B.moe_workspace_bytes(tokens_per_rank, hidden, world),), 0x5A, dtype=torch.uint8, device="cuda")
+        self.ws_raw[:gathered].zero_()
+        self.workspace = self.ws_raw[:gathered].view(torch.int16).view(world * tokens_per_rank, hidden)
         self.y = torch.full((max_rows, inter), 0x7FC0, dtype=torch.int16, device="cuda")   # NaN pattern: untouched rows stay visible
         self.counts = torch.full((world * num_experts,), -1, **i32)
         self.offsets = torch.full((num_local + 1,), -1, **i32)

@@ -26,7 +26,7 @@ def w_nk(w_ekn):
     return np.ascontiguousarray(np.transpose(w_ekn, (0, 2, 1)))
 
 
-def _run_and_check(B, cfg, xs, ids, w, max_rows, integer, order=None, block_m=128, kn=False):
+def _run_and_check(B, cfg, xs, ids, w, max_rows, integer, order=None, block_m=128, kn=False, tuning=None):
     st0, bm, bn = B.moe_tile_choice(cfg.world * cfg.tokens_per_rank, cfg.top_k, cfg.num_experts, cfg.num_local_experts, cfg.n)
     assert st0 == B.OK and bm == block_m and bn in (128, 192, 256)
     e0 = cfg.rank * cfg.num_local_experts if (cfg.rank + 1) * cfg.num_local_experts <= cfg.num_experts else 0
@@ -34,7 +34,7 @@ def _run_and_check(B, cfg, xs, ids, w, max_rows, integer, order=None, block_m=12
                  cfg.num_local_experts, max_rows)
     # kn: the weights handed over as they are stored logically, [E_l, hidden, inter]
     st = run([to_dev(x) for x in xs], to_dev(ids), to_dev(w if kn else w_nk(w)), e0, cfg.rank, order=order,
-             w_layout=B.B_KN if kn else B.B_NK)
+             w_layout=B.B_KN if kn else B.B_NK, tuning=tuning)
     assert st == B.OK, B.status_string(st)
     torch.cuda.synchronize()
     assert run.status.cpu().tolist()[0] == 0
@@ -109,6 +109,39 @@ def test_moe_large_experts_use_the_256_row_tile(B):
     _run_and_check(B, cfg, xs, ids, w, 8 * 512 * 2, integer=True, block_m=256, kn=True)
 
 
+@pytest.mark.parametrize("groups", [1, 2, 3, 8])
+@pytest.mark.parametrize("world,t_r,experts,top_k,local,rank", [
+    (4, 100, 12, 3, 3, 2),        # 1200 assignments: most waves of eight work-groups have nothing to scan
+    (8, 128, 64, 6, 64, 5),       # 6144 assignments over 64 local experts
+    (8, 520, 60, 4, 60, 1),       # 16640 assignments: ranges that end inside a rank's shard
+])
+def test_moe_routing_shared_by_several_work_groups(B, groups, world, t_r, experts, top_k, local, rank):
+    """counts, offsets, gather index and tile list do not depend on how many work-groups share the scan."""
+    cfg = synth.CONFIGS[4].scaled(world=world, tokens_per_rank=t_r, k=64, n=128, num_experts=experts,
+                                  top_k=top_k, num_local_experts=local, rank=rank)
+    xs, ids, w = synth.moe_inputs(cfg, integer=True)
+    _run_and_check(B, cfg, xs, ids, w, world * t_r * top_k, True, tuning=B.tuning(moe_route_groups=groups))
+
+
+def test_moe_route_groups_out_of_range_is_refused(B):
+    cfg = synth.CONFIGS[4].scaled(world=2, tokens_per_rank=64, k=64, n=128, num_experts=2, top_k=1,
+                                  num_local_experts=2, rank=0)
+    xs, ids, w = synth.moe_inputs(cfg, integer=True)
+    run = MoeRun(B, 2, 64, 64, 128, 2, 1, 2, max_rows=128)
+    st = run([to_dev(x) for x in xs], to_dev(ids), to_dev(w_nk(w)), 0, 0, tuning=B.tuning(moe_route_groups=9))
+    assert st == B.ERR_INVALID_ARG
+
+
+def test_moe_many_small_experts_use_the_256_row_tile_when_it_saves_a_round(B):
+    """64 experts x 576 rows x 248 columns: 320 tiles of 128 rows (two rounds on 256 units) against 176 of 256 rows."""
+    assert B.moe_tile_choice(8 * 768, 6, 64, 64, 248) == (B.OK, 256, 256)
+    assert B.moe_tile_choice(8 * 512, 6, 64, 64, 248)[1] == 128      # 224 tiles of 128 rows: a single round either way
+    cfg = synth.CONFIGS[4].scaled(world=8, tokens_per_rank=768, k=64, n=248, num_experts=64, top_k=6,
+                                  num_local_experts=64, rank=3)
+    xs, ids, w = synth.moe_inputs(cfg, integer=True)
+    _run_and_check(B, cfg, xs, ids, w, 8 * 768 * 6, integer=True, block_m=256)
+
+
 def test_moe_degenerate_routings(B):
     cfg = synth.CONFIGS[4].scaled(world=4, tokens_per_rank=96, k=64, n=128, num_experts=8, top_k=1,
                                   num_local_experts=4, rank=1)
@@ -147,11 +180,11 @@ def test_moe_expert_id_out_of_range_is_reported(B):
     xs, ids, w = synth.moe_inputs(cfg, integer=True)
     run = MoeRun(B, 4, 96, 64, 128, 8, 2, 4, max_rows=4 * 96 * 2)
     xd, wd = [to_dev(x) for x in xs], to_dev(w_nk(w))
-    for bad_value, where in ((8, 301), (-1, 17)):
+    for bad_value, where, groups in ((8, 301, 0), (-1, 17, 0), (8, 301, 3), (-1, 17, 8)):
         bad = ids.copy()
         bad.reshape(-1)[where] = bad_value
         bad.reshape(-1)[where + 200] = bad_value        # the smallest offending index is the one reported
-        assert run(xd, to_dev(bad), wd, 4, 1) == B.OK
+        assert run(xd, to_dev(bad), wd, 4, 1, tuning=B.tuning(moe_route_groups=groups)) == B.OK
         torch.cuda.synchronize()
         s = run.status.cpu().tolist()
         assert s[0] == B.ERR_INVALID_ARG and s[1] == where
@@ -170,6 +203,7 @@ def test_moe_flags_preset(B):
     run.workspace.copy_(to_dev(np.concatenate(xs, axis=0)))
     assert run(None, to_dev(ids), to_dev(w_nk(w)), e0, cfg.rank, flags=B.FLAGS_PRESET) == B.OK
     torch.cuda.synchronize()
-    assert run.status.cpu().tolist()[0] == 0 and not run.signals.any()
+    # (the only words written are the flags of the routing work-groups, behind the 4 x world shard words)
+    assert run.status.cpu().tolist()[0] == 0 and not run.signals[:4 * cfg.world].any()
     ref = omoe.grouped_gemm(xs, ids, w, cfg.world, cfg.num_experts, e0)
     assert np.array_equal(bits(run.y)[:ref.shape[0]], formats.encode_bf16_rne(ref.astype(np.float32)))

@@ -31,14 +31,14 @@ def test_every_declared_symbol_is_exported(B):
 
 
 def test_sizes_and_strings(B):
-    assert B.signal_words(8, 1) == 32 and B.signal_words(8, 4) == 80 and B.signal_words(0, 1) == 0
+    assert B.signal_words(8, 1) == 48 and B.signal_words(8, 4) == 96 and B.signal_words(0, 1) == 0
     # the gathered operand: world * rows * k elements of the operand type
     assert B.ag_gemm_workspace_bytes(1024, 3584, 8192, 8) == 8 * 1024 * 8192 * 2
     # decode shape: the gathered fp8 operand, then 64 tiles x 4 splits of 128 x 128 partials of 8 bytes (value, epoch)
     assert B.ag_gemm_workspace_bytes(16, 8192, 8192, 8, B.FP8_E4M3) == 128 * 8192 + 64 * 4 * 128 * 128 * 8
     assert B.ag_gemm_workspace_bytes(16, 8192, 8192, 8, B.FP8_E4M3, tuning=B.tuning(decode_variant=1)) == 128 * 8192
     assert B.ag_gemm_workspace_bytes(0, 8, 8192, 8) == 0 and B.ag_gemm_workspace_bytes(16, 8, 8192, 8, 5) == 0
-    assert B.moe_workspace_bytes(1024, 4096, 8) == 8 * 1024 * 4096 * 2 and B.moe_workspace_bytes(1024, 0, 8) == 0
+    assert B.moe_workspace_bytes(1024, 4096, 8) == 8 * 1024 * 4096 * 2 + B.MOE_ROUTE_SCRATCH_BYTES and B.moe_workspace_bytes(1024, 0, 8) == 0
     assert B.status_string(B.OK) == "ok" and "time" in B.status_string(B.ERR_TIMEOUT)
     assert B.moe_max_tiles(4096, 8) == 4096 // 128 + 8
 
@@ -76,16 +76,21 @@ def test_operand_staging_choice(B):
 
 
 def test_moe_tile_choice(B):
-    """Host rule for the grouped GEMM's tile: 256 rows when an expert expects 1024 rows or more; for
+    """Host rule for the grouped GEMM's tile: 256 rows when an expert expects 1024 rows or more, or when
+    rounds x (rows + columns) of the 256-row tiling is below that of the 128-row tiling by more than 1.3; for
     128-row tiles the narrowest column block that keeps one tile per compute unit (256 of them) with a
     row tile to spare, else the block that pads the intermediate size least, the wider on a tie."""
     # cfg 4: 8192 tokens, top-2 of 64 experts, 8 local -> 2048 rows, 16 + 4 row tiles; 21 x 12 blocks of 128 fit
     assert B.moe_tile_choice(8192, 2, 64, 8, 1536) == (B.OK, 128, 128)
     # one row tile more (22 x 12 = 264 > 256): 192 columns (22 x 8)
     assert B.moe_tile_choice(8192 + 128 * 4, 2, 64, 8, 1536) == (B.OK, 128, 192)
-    # many tiles, 176 columns: 192 pads least; 256 columns: 128 and 256 tie, the wider wins
-    assert B.moe_tile_choice(8192, 4, 60, 60, 176) == (B.OK, 128, 192)
-    assert B.moe_tile_choice(8192, 6, 64, 64, 256) == (B.OK, 128, 256)
+    # many tiles (two rounds with either row tile), 176 columns: 192 pads least; 256 columns: 128 and 256 tie,
+    # the wider wins
+    assert B.moe_tile_choice(14592, 4, 60, 60, 176) == (B.OK, 128, 192)
+    assert B.moe_tile_choice(14400, 4, 64, 64, 256) == (B.OK, 128, 256)
+    # the paper's two many-expert shapes: 286 / 416 tiles of 128 rows need two rounds, 256-row tiles one
+    assert B.moe_tile_choice(8192, 4, 60, 60, 176) == (B.OK, 256, 256)
+    assert B.moe_tile_choice(8192, 6, 64, 64, 256) == (B.OK, 256, 256)
     # 2048 rows per expert: the 256-row tile, 256 columns unless the intermediate size is at most 128
     assert B.moe_tile_choice(8192, 2, 8, 8, 512) == (B.OK, 256, 256)
     assert B.moe_tile_choice(8192, 2, 8, 8, 128) == (B.OK, 256, 128)
