@@ -229,7 +229,7 @@ __global__ __launch_bounds__(T::THREADS) void gemm_ar_kernel(const GemmArParams 
     const uint32_t row_bytes = (uint32_t)p.k * 2u;
     const int M = p.m, N = p.n;
     auto a_row = [=](int r) { return (uint32_t)min(m0 + r, M - 1) * row_bytes; };
-    f32x16_t acc[T::NI][T::MI];
+    typename T::Acc acc;
     if constexpr (T::B_KN) {
       gemm_mainloop<T>(acc, p.a, a_row, p.b, BColumns{(uint32_t)N * 2u, n0, N}, p.k, lds);
     } else {

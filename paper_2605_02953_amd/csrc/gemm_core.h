@@ -70,13 +70,20 @@ __device__ __forceinline__ void barrier_no_drain() {
 // reads (ds_read_b64_tr_b16: inside each group of 16 lanes, lane i receives element i % 4 of
 // the 8-byte chunks addressed by lanes i/4, 4 + i/4, 8 + i/4, 12 + i/4; measured).  The pitch
 // makes the four rows a group touches, and the two groups that share a cycle, hit distinct banks.
-template <int BM_, int BN_, bool B_KN_ = false, bool DIRECT_ = false>
+//
+// X16: the same tile fed to v_mfma_f32_16x16x32_bf16 (a wave's quarter is cut into 16 x 16 blocks, a fragment
+// is 16 rows x 32 k: the 16-byte chunk (lane / 16) of the 32-deep step of row (lane % 16)); written for the
+// direct-to-LDS staging.  The accumulator of a block is four registers instead of sixteen, so the instruction
+// moves a quarter of the accumulator registers per unit of matrix work.
+template <int BM_, int BN_, bool B_KN_ = false, bool DIRECT_ = false, bool X16_ = false>
 struct GemmTile4W {
   static_assert((BM_ == 256 || BM_ == 128) && (BN_ == 256 || BN_ == 192 || BN_ == 128), "supported tile sides");
   static_assert(!B_KN_ || BN_ != 192, "a [K, N] row of 192 elements does not split evenly over the loading lanes");
   static_assert(!DIRECT_ || !B_KN_, "the direct-to-LDS staging is written for [N, K] operands");
+  static_assert(!X16_ || DIRECT_, "the 16 x 16 x 32 loop is written for the direct-to-LDS staging");
   static constexpr bool B_KN = B_KN_;
   static constexpr bool DIRECT = DIRECT_;   // operands go from global memory straight into LDS (no staging registers)
+  static constexpr bool X16 = X16_;
   static constexpr int BM = BM_, BN = BN_, BK = 64, NSTAGE = 2;
   static constexpr int WAVES_M = 2, WAVES_N = 2, NWAVES = 4, THREADS = 256;
   static constexpr int WTM = BM / 2, WTN = BN / 2, MI = WTM / 32, NI = WTN / 32;
@@ -93,6 +100,11 @@ struct GemmTile4W {
   static constexpr int B_READS = B_KN ? 2 : 1;                // LDS reads per B fragment
   static constexpr int READS = MI + B_READS * NI;             // fragment reads per step
   static constexpr int HALF = (PAIRS + 1) / 2;                // slots of a step that take its reads when they must be early
+  static constexpr int MB = WTM / 16, NB = WTN / 16;          // X16: 16 x 16 blocks of a wave's quarter
+  // the accumulators of one wave: [column block][row block]
+  typedef f32x16_t Acc32[NI][MI];
+  typedef f32x4_t Acc16[NB][MB];
+  typedef std::conditional_t<X16_, Acc16, Acc32> Acc;
 };
 
 template <class T>
@@ -144,7 +156,7 @@ __device__ __forceinline__ void read_range(Frags4W<T>& f, const char* st, int a_
 }
 
 template <class T, int P>
-__device__ __forceinline__ void mma_pair(f32x16_t (&acc)[T::NI][T::MI], const Frags4W<T>& f) {
+__device__ __forceinline__ void mma_pair(typename T::Acc32& acc, const Frags4W<T>& f) {
   constexpr int ni = P / (T::MI / 2), mi = (P % (T::MI / 2)) * 2;
   const bf16x8_t b = __builtin_shufflevector(f.b[ni][0], f.b[ni][1], 0, 1, 2, 3, 4, 5, 6, 7);
   acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, f.a[mi], acc[ni][mi], 0, 0, 0);
@@ -260,6 +272,95 @@ struct Stager4W {
   }
 };
 
+// ------------------------------------------------------------------ 16 x 16 x 32 form
+template <class T>
+struct Frags16 {
+  bf16x8_t a[T::MB];
+  bf16x8_t b[T::NB];
+};
+
+// Fragment read J of the 32-deep step KS (0 or 1) of the K tile staged at `st`, in the order the slots
+// below consume them: b0, a0 .. a[MB-1], b1 .. b[NB-1].  koff[KS]: the lane's swizzled chunk offset.
+template <class T, int KS, int J>
+__device__ __forceinline__ void read_one16(Frags16<T>& f, const char* st, int a_off, int b_off, const int (&koff)[2]) {
+  if constexpr (J == 0) f.b[0] = *(const bf16x8_t*)(st + b_off + koff[KS]);
+  else if constexpr (J <= T::MB) f.a[J - 1] = *(const bf16x8_t*)(st + a_off + (J - 1) * 16 * 128 + koff[KS]);
+  else f.b[J - T::MB] = *(const bf16x8_t*)(st + b_off + (J - T::MB) * 16 * 128 + koff[KS]);
+}
+
+// Slot S of a step: four MFMAs of column block S / (MB / 4) on row blocks 4 (S % (MB / 4)) .. + 3.
+template <class T, int S>
+__device__ __forceinline__ void mma_quad16(typename T::Acc16& acc, const Frags16<T>& f) {
+  constexpr int nb = S / (T::MB / 4), mb = (S % (T::MB / 4)) * 4;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    acc[nb][mb + i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.b[nb], f.a[mb + i], acc[nb][mb + i], 0, 0, 0);
+}
+
+// K loop of the 16 x 16 x 32 form, operands loaded straight into two LDS stages.  A 64-deep K tile is two
+// 32-deep steps of MB x NB MFMAs each, written as slots of four MFMAs plus one fragment read and at most one
+// load.  All fragments of a step are read during the step before it, so the K tile's stage is no longer read
+// once its second step starts: the barrier sits between the two steps.
+//   step 0 of tile kt : fragment reads of step 1 (same stage)
+//   barrier           : every wave's part of tile kt+1 has landed, nobody reads tile kt's stage any more
+//   step 1 of tile kt : fragment reads of step 0 of tile kt+1 (other stage); loads of tile kt+2 into the
+//                       stage just freed, which have the whole of the next step 0 to land
+// On entry the LDS stages must be idle; on exit no load is in flight.
+template <class T, class ARow, class BRow>
+__device__ __forceinline__ void gemm_mainloop_x16(typename T::Acc16& acc, const char* a_base, ARow a_row,
+                                                     const char* b_base, BRow b_row, int K, char* lds) {
+  constexpr int MB = T::MB, NB = T::NB, READS = MB + NB, LOADS = T::LOADS;
+  constexpr int SLOTS = MB * NB / 4;   // per step
+  static_assert(MB % 4 == 0 && READS <= SLOTS && LOADS <= SLOTS, "one read and at most one load per slot");
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int wm = wave / 2, wn = wave % 2;
+  const int lr = lane & 15, lq = lane >> 4;
+  const int a_off = (wm * T::WTM + lr) * T::ROW_BYTES;
+  const int b_off = T::A_BYTES + (wn * T::WTN + lr) * T::ROW_BYTES;
+  int koff[2];
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) koff[ks] = ((ks * 4 + lq) ^ swz128(lr)) * 16;
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) acc[nb][mb][v] = 0.f;
+
+  const int kt_all = (K + 63) / 64;
+  const int kt_last = kt_all - 1;
+  Stager4W<T> st;
+  st.init(a_base, a_row, b_base, b_row);
+  st.template issue_range<0, LOADS>(0, K, lds);
+  st.template issue_range<0, LOADS>(min(1, kt_last), K, lds + T::STAGE_BYTES);
+  wait_vmcnt<LOADS>();
+  barrier_no_drain();
+  Frags16<T> f0, f1;
+  static_for<0, READS>([&](auto j) { read_one16<T, 0, decltype(j)::value>(f0, lds, a_off, b_off, koff); });
+  for (int kt = 0; kt < kt_all; ++kt) {
+    char* cur = lds + (kt & 1) * T::STAGE_BYTES;
+    const char* nxt = lds + ((kt + 1) & 1) * T::STAGE_BYTES;
+    const int kf = min(kt + 2, kt_last);
+    static_for<0, SLOTS>([&](auto sl) {
+      constexpr int S = decltype(sl)::value;
+      mma_quad16<T, S>(acc, f0);
+      if constexpr (S < READS) read_one16<T, 1, S>(f1, cur, a_off, b_off, koff);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    wait_vmcnt0();     // this wave's part of tile kt+1 has landed
+    wait_lgkmcnt0();   // every read of tile kt has returned
+    barrier_no_drain();
+    static_for<0, SLOTS>([&](auto sl) {
+      constexpr int S = decltype(sl)::value;
+      mma_quad16<T, S>(acc, f1);
+      if constexpr (S < READS) read_one16<T, 0, S>(f0, nxt, a_off, b_off, koff);
+      if constexpr (S < LOADS) st.template issue_range<S, S + 1>(kf, K, cur);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+  }
+  wait_vmcnt0();   // the last iteration's requests (the last K tile once more) are not left in flight
+}
+
 // One barrier per 64-deep K tile.  A single wave per SIMD has to keep the matrix pipe fed
 // while it also issues every memory instruction, so the loop body is written as slots of two
 // MFMAs plus a few memory instructions, each slot fenced so that the compiler keeps the
@@ -272,10 +373,15 @@ struct Stager4W {
 //                               its register
 // The body is branch-free (past the end the last tile is staged again into a free stage).
 // On entry the LDS stages must be idle (every wave of the work-group past its last access to them): the
-// direct-to-LDS staging starts writing them with its first instruction.
+// direct-to-LDS staging starts writing them with its first instruction.  On exit none of the wave's loads
+// is in flight; other waves may still be reading fragments, so a barrier precedes any reuse of the stages.
 template <class T, class ARow, class BRow>
-__device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[T::NI][T::MI], const char* a_base, ARow a_row,
+__device__ __forceinline__ void gemm_mainloop(typename T::Acc& acc, const char* a_base, ARow a_row,
                                                  const char* b_base, BRow b_row, int K, char* lds) {
+  if constexpr (T::X16) {
+    gemm_mainloop_x16<T>(acc, a_base, a_row, b_base, b_row, K, lds);
+    return;
+  } else {
   constexpr int PAIRS = T::PAIRS, SLOTS = T::SLOTS, READS = T::READS, LOADS = T::LOADS;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int wm = wave / 2, wn = wave % 2;
@@ -339,6 +445,7 @@ __device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[T::NI][T::MI], con
         __builtin_amdgcn_sched_barrier(0);
       });
     }
+    wait_vmcnt0();   // the last iteration's requests (the last K tile once more) are not left in flight
     return;
   }
   // the first two K tiles are requested together (the second into registers that are free until the
@@ -379,6 +486,7 @@ __device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[T::NI][T::MI], con
       __builtin_amdgcn_sched_barrier(0);
     });
   }
+  }
 }
 
 // Mainloop for tiles whose operands stream from HBM rather than from the L2 (the grouped GEMM's expert
@@ -388,7 +496,7 @@ __device__ __forceinline__ void gemm_mainloop(f32x16_t (&acc)[T::NI][T::MI], con
 // per K tile; the matrix work of a K tile (512 cycles at 128 x 128) is short against its loads.
 // Requests past the last K tile are out of the buffers' range: zeros are written, memory is not asked.
 template <class T, int NST, class ARow, class BRow>
-__device__ __forceinline__ void gemm_mainloop_ring(f32x16_t (&acc)[T::NI][T::MI], const char* a_base, ARow a_row,
+__device__ __forceinline__ void gemm_mainloop_ring(typename T::Acc32& acc, const char* a_base, ARow a_row,
                                                       const char* b_base, BRow b_row, int K, char* lds) {
   static_assert(T::DIRECT && !T::B_KN, "ring staging is written for [N, K] operands loaded straight into LDS");
   constexpr int PAIRS = T::PAIRS, READS = T::READS, LOADS = T::LOADS;
@@ -437,7 +545,7 @@ __device__ __forceinline__ void gemm_mainloop_ring(f32x16_t (&acc)[T::NI][T::MI]
 // and its 512 cycles of matrix work follow one another; here they overlap.  Returns true in the computing
 // waves (which hold the accumulators) and false in the loading waves, whose requests have all completed.
 template <class T, int NST, class ARow, class BRow>
-__device__ __forceinline__ bool gemm_mainloop_ring_split(f32x16_t (&acc)[T::NI][T::MI], const char* a_base, ARow a_row,
+__device__ __forceinline__ bool gemm_mainloop_ring_split(typename T::Acc32& acc, const char* a_base, ARow a_row,
                                                             const char* b_base, BRow b_row, int K, char* lds) {
   static_assert(T::DIRECT && !T::B_KN, "ring staging is written for [N, K] operands loaded straight into LDS");
   constexpr int PAIRS = T::PAIRS, READS = T::READS, LOADS = T::LOADS;
@@ -509,12 +617,28 @@ struct ParkedTile {
 
 // First half of the epilogue: accumulators -> bf16 -> the wave's piece of the operand stages.
 template <class T>
-__device__ __forceinline__ void park_tile_bf16(const f32x16_t (&acc)[T::NI][T::MI], char* lds) {
+__device__ __forceinline__ void park_tile_bf16(const typename T::Acc& acc, char* lds) {
   typedef ParkedTile<T> P;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-  const int lr = lane & 31, lh = lane >> 5;
   __syncthreads();   // every wave is done reading the operand stages
   char* park = lds + wave * (T::WTM * P::ROW);
+  if constexpr (T::X16) {
+    // a lane holds, per block, row (lane % 16) and the four columns 4 (lane / 16) .. + 3: half a 16-byte slot
+    const int lr = lane & 15, lq = lane >> 4;
+#pragma unroll
+    for (int mb = 0; mb < T::MB; ++mb) {
+      const int m = mb * 16 + lr;
+#pragma unroll
+      for (int nb = 0; nb < T::NB; ++nb) {
+        const int g = nb * 2 + (lq >> 1);
+        bf16x4_t v = {(__bf16)acc[nb][mb][0], (__bf16)acc[nb][mb][1], (__bf16)acc[nb][mb][2], (__bf16)acc[nb][mb][3]};
+        *(bf16x4_t*)(park + m * P::ROW + ((g ^ P::key(m)) * 16) + (lq & 1) * 8) = v;
+      }
+    }
+    wait_lgkmcnt0();
+    return;
+  } else {
+  const int lr = lane & 31, lh = lane >> 5;
 #pragma unroll
   for (int mi = 0; mi < T::MI; ++mi) {
     const int m = mi * 32 + lr;
@@ -531,6 +655,7 @@ __device__ __forceinline__ void park_tile_bf16(const f32x16_t (&acc)[T::NI][T::M
   }
   // the reads that follow are the same wave's: LDS operations of one wave complete in order
   wait_lgkmcnt0();
+  }
 }
 
 // Second half: the rows m_lo <= m < m_hi of the parked tile (global row numbers; the tile starts at row
@@ -558,7 +683,7 @@ __device__ __forceinline__ void store_parked_bf16(__bf16* c, size_t ldc, int m0,
 }
 
 template <class T, bool STREAM = false>
-__device__ __forceinline__ void store_tile_bf16(const f32x16_t (&acc)[T::NI][T::MI], __bf16* c, size_t ldc, int m0,
+__device__ __forceinline__ void store_tile_bf16(const typename T::Acc& acc, __bf16* c, size_t ldc, int m0,
                                                     int n0, int M, int N, char* lds) {
   park_tile_bf16<T>(acc, lds);
   store_parked_bf16<T, STREAM>(c, ldc, m0, n0, m0, M, N, lds);

@@ -12,10 +12,10 @@ namespace ditron {
 
 // 256x256 output tile: 128x128 per wave, 128 KiB of LDS.
 typedef GemmTile4W<256, 256> TileBig;
-// The same tile with operands loaded straight into LDS, and the contraction lengths for which that is the
-// faster staging (measured at 2048 ... 16384: 3 % faster up to 8192, even at 10240-12288, 1-4 % slower at
-// 16384; 7 % slower when the last K tile is ragged).
-typedef GemmTile4W<256, 256, false, true> TileBigDirect;
+// The same tile with operands loaded straight into LDS and the 16 x 16 x 32 MFMA form, and the contraction
+// lengths for which that is the faster one (measured against the tile above: 6-7 % faster at 3584 and 8192,
+// 7 % slower at 16384, 7 % slower when the last K tile is ragged).
+typedef GemmTile4W<256, 256, false, true, true> TileBigDirect;
 inline bool use_direct_staging(int k) { return k % 64 == 0 && k <= 8192; }
 // 128x128 output tile: 64x64 per wave, 64 KiB of LDS; for problems with too few 256x256 tiles
 // to fill the chip.

@@ -378,7 +378,7 @@ __global__ __launch_bounds__(NST > 0 ? 2 * T::THREADS : T::THREADS) void moe_gro
     const int row = min(p0 + r, p_end - 1);
     return (uint32_t)(in_place ? row : gidx[row] / top_k) * row_bytes;
   };
-  f32x16_t acc[T::NI][T::MI];
+  typename T::Acc acc;
   if constexpr (T::B_KN) {   // expert weights stored [hidden, inter]: same bytes per expert, inter contiguous
     gemm_mainloop<T>(acc, p.workspace, a_row, wj, BColumns{(uint32_t)N * 2u, n0, N}, p.hidden, lds);
   } else {
