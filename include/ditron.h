@@ -83,12 +83,20 @@ enum {
   DITRON_EXTERNAL_PRODUCER = 2u, /* somebody else fills the workspace and raises the flags   */
   DITRON_FLAGS_PRESET = 4u,      /* the remote data is resident: no copies, no flag waits    */
   DITRON_DUMP_SCHEDULE = 8u,     /* write the tile schedule to `schedule_out`                */
-  DITRON_DUMP_TIMING = 16u       /* ditron_ag_gemm: write per-work-group time stamps to `schedule_out`
+  DITRON_DUMP_TIMING = 16u,      /* ditron_ag_gemm: write per-work-group time stamps to `schedule_out`
                                   * instead (not together with DITRON_DUMP_SCHEDULE): the record of a GEMM
                                   * work-group, at the index its schedule record would have, is (start,
                                   * flag wait entered, flag wait left, end) in ticks of the GPU's constant
                                   * 100 MHz clock, low 31 bits: where a launch's time goes between waiting
                                   * for shards and computing (decode_variant 1 writes nothing) */
+  DITRON_EPOCH_IN_MEMORY = 32u,  /* decode-shaped ditron_ag_gemm (decode_variant 0, 2, 3, 4): the `epoch`
+                                  * argument is ignored; the call's epoch is 1 + the last word of `signals`,
+                                  * and the kernel's last work-group to finish stores it there (the word
+                                  * before it counts the finished work-groups and returns to zero).  The
+                                  * same recorded launch can then be replayed, e.g. from a HIP graph: the
+                                  * call makes no other host-side change between launches.  Calls with and
+                                  * without this flag must not share a `signals` array.  Elsewhere:
+                                  * DITRON_ERR_UNSUPPORTED */
 };
 
 /* Per-call options (host memory, read during the call).  A zero field means "default", so a

@@ -13,7 +13,7 @@ LIB_PATH = os.path.join(_HERE, "libditron.so")
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP, ERR_TIMEOUT = range(6)
 BF16, FP8_E4M3 = 0, 1
 B_KN, B_NK = 0, 1
-EMULATE_PRODUCER, EXTERNAL_PRODUCER, FLAGS_PRESET, DUMP_SCHEDULE, DUMP_TIMING = 1, 2, 4, 8, 16
+EMULATE_PRODUCER, EXTERNAL_PRODUCER, FLAGS_PRESET, DUMP_SCHEDULE, DUMP_TIMING, EPOCH_IN_MEMORY = 1, 2, 4, 8, 16, 32
 SCHEDULE_WORDS = 4
 MAX_WORLD = 32
 STATUS_WORDS = 4

@@ -112,7 +112,9 @@ extern "C" ditron_status_t ditron_ag_gemm(const void* const* a_shards, const voi
       if (!a_shards[s] || !aligned16(a_shards[s])) return DITRON_ERR_INVALID_ARG;
     if (arrival_order && !is_permutation(arrival_order, world)) return DITRON_ERR_INVALID_ARG;
   }
-  if (dtype == DITRON_FP8_E4M3 || (b_layout == DITRON_B_NK && bf16_ag_is_decode_shaped(m_per_rank * world, n)))
+  const bool decode_shaped = dtype == DITRON_FP8_E4M3 || (b_layout == DITRON_B_NK && bf16_ag_is_decode_shaped(m_per_rank * world, n));
+  if ((flags & DITRON_EPOCH_IN_MEMORY) && !decode_shaped) return DITRON_ERR_UNSUPPORTED;
+  if (decode_shaped)
     return ditron_ag_gemm_decode(a_shards, b, b_layout, c, a_scales, b_scales, workspace, signals, status, schedule_out,
                                  arrival_order, m_per_rank, n, k, world, rank, dtype, epoch, flags, tuning, stream);
   if (k % 8 != 0 || n % 8 != 0) return DITRON_ERR_UNSUPPORTED;

@@ -43,6 +43,8 @@ struct AgGemmDecodeParams {
   int32_t* schedule;
   int m_per_rank, m, n, k, world, rank, nnodes;   // k in elements
   int32_t epoch;
+  int32_t* epoch_word;   // if set: the call's epoch is 1 + this word, which the last work-group to finish advances
+  int32_t* finished;     // ... counting the work-groups that are done
   int num_producers, teams;
   unsigned spin_limit;
   int wait;   // 0: every shard is resident, the flags are not looked at
@@ -256,13 +258,12 @@ struct SplitKTile {
 };
 
 template <bool BF16, class T>
-__global__ __launch_bounds__(T::THREADS) void ag_gemm_splitk_kernel(const AgGemmDecodeParams p) {
+__device__ __forceinline__ void splitk_work_group(const AgGemmDecodeParams& p, const int32_t epoch, char* lds) {
   const int K = p.k * (BF16 ? 2 : 1);   // bytes per row of A and of B
-  extern __shared__ __attribute__((aligned(1024))) char lds[];
   if ((int)blockIdx.x < p.num_producers) {
     const size_t shard_bytes = (size_t)p.m_per_rank * K;
     produce_chunks<T::THREADS>(
-        p.world, shard_bytes, blockIdx.x, p.num_producers, p.teams, p.epoch,
+        p.world, shard_bytes, blockIdx.x, p.num_producers, p.teams, epoch,
         [&](int i) { return (void*)(p.workspace + (size_t)p.order[i] * shard_bytes); },
         [&](int i) { return p.shard[p.order[i]]; }, [&](int i) { return p.flags + p.order[i]; },
         [&](int i) { return p.arrivals + p.order[i]; });
@@ -343,7 +344,7 @@ __global__ __launch_bounds__(T::THREADS) void ag_gemm_splitk_kernel(const AgGemm
   // (two tiles only before the barrier: a deeper burst fills the unit's miss queue and the first loads
   // of A, issued after the barrier, would wait behind it)
   if (p.timing) ts_wait = wall_clock64();
-  if (wave == 0 && p.wait) flag_wait_wave(p.flags, t.first, t.last - t.first + 1, p.epoch, p.spin_limit, p.status);
+  if (wave == 0 && p.wait) flag_wait_wave(p.flags, t.first, t.last - t.first + 1, epoch, p.spin_limit, p.status);
   if (p.timing) ts_ready = wall_clock64();
   if (loader) {
     issue_b(0);
@@ -437,7 +438,7 @@ __global__ __launch_bounds__(T::THREADS) void ag_gemm_splitk_kernel(const AgGemm
     const size_t tile_bytes = (size_t)T::TILE_WORDS * 2 * sizeof(float);
     const __amdgpu_buffer_rsrc_t part = __builtin_amdgcn_make_buffer_rsrc(
         (char*)p.partials + (size_t)tile * p.splits * tile_bytes, 0, (int)(p.splits * tile_bytes), 0x00020000);
-    const uint32_t tag = (uint32_t)p.epoch;
+    const uint32_t tag = (uint32_t)epoch;
     if (!loader) {
       // in the lanes' own order: half h of block (nb, mb) of wave w is 64 lanes x 16 contiguous bytes
 #pragma unroll
@@ -529,6 +530,28 @@ __global__ __launch_bounds__(T::THREADS) void ag_gemm_splitk_kernel(const AgGemm
   }
 }
 
+// The epoch of a call is a launch argument, or, for callers that record the launch once and replay it (a HIP
+// graph), one more than a word in memory: every work-group reads the word when it starts, and the last one to
+// finish (they count themselves) writes the new epoch there, after every other work-group has read the old one.
+template <bool BF16, class T>
+__global__ __launch_bounds__(T::THREADS) void ag_gemm_splitk_kernel(const AgGemmDecodeParams p) {
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  int32_t epoch = p.epoch;
+  if (p.epoch_word)
+    epoch = __builtin_amdgcn_readfirstlane(__hip_atomic_load(p.epoch_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) + 1;
+  splitk_work_group<BF16, T>(p, epoch, lds);
+  if (p.epoch_word) {
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      const int old = __hip_atomic_fetch_add(p.finished, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (old == (int)gridDim.x - 1) {
+        __hip_atomic_store(p.finished, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(p.epoch_word, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+  }
+}
+
 }  // namespace ditron
 
 using namespace ditron;
@@ -577,6 +600,11 @@ extern "C" ditron_status_t ditron_ag_gemm_decode(const void* const* a_shards, co
   p.rank = rank;
   p.nnodes = tune.num_nodes;
   p.epoch = epoch;
+  if (flags & DITRON_EPOCH_IN_MEMORY) {
+    const size_t words = ditron_signal_words(world, 1);
+    p.epoch_word = signals + words - 1;
+    p.finished = signals + words - 2;
+  }
   p.spin_limit = tune.spin_limit;
   p.wait = producer_mode(flags) != Mode::kPreset;
   const size_t a_bytes = (size_t)p.m * k * (bf16 ? 2 : 1);
@@ -602,6 +630,7 @@ extern "C" ditron_status_t ditron_ag_gemm_decode(const void* const* a_shards, co
     case 4: return bf16 ? launch_splitk<true, SplitKTile<16, 128>>(p, s) : launch_splitk<false, SplitKTile<16, 128>>(p, s);
     default: break;
   }
+  if (p.epoch_word) return DITRON_ERR_UNSUPPORTED;   // the 128 x 32 kernel takes its epoch as an argument only
   if (!(bf16 ? set_dynamic_lds<ag_gemm_decode_kernel<true>>(DecodeTile::LDS_BYTES)
              : set_dynamic_lds<ag_gemm_decode_kernel<false>>(DecodeTile::LDS_BYTES)))
     return DITRON_ERR_HIP;

@@ -326,6 +326,7 @@ static ditron_status_t gemm_ar_impl(const void* a, const void* b, int b_layout, 
   if (!aligned16(a) || !aligned16(b) || !aligned16(gemm_out) || !aligned16(out) || !aligned16(signals))
     return DITRON_ERR_INVALID_ARG;
   const Mode mode = producer_mode(flags);
+  if (flags & DITRON_EPOCH_IN_MEMORY) return DITRON_ERR_UNSUPPORTED;
   const Tuning tune = resolve_tuning(tuning, 1);
   if (mode == Mode::kInvalid || !tune.valid) return DITRON_ERR_INVALID_ARG;
   if (mode == Mode::kPreset && two_shot) return DITRON_ERR_UNSUPPORTED;   // the peers' broadcasts are part of the call

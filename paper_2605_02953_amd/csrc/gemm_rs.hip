@@ -275,6 +275,7 @@ static ditron_status_t gemm_rs_impl(const void* a, const void* b, int b_layout, 
       !aligned16(signals))
     return DITRON_ERR_INVALID_ARG;
   const Mode mode = producer_mode(flags);
+  if (flags & DITRON_EPOCH_IN_MEMORY) return DITRON_ERR_UNSUPPORTED;
   if (mode == Mode::kInvalid) return DITRON_ERR_INVALID_ARG;
   const bool emulate = mode == Mode::kEmulate;
   if ((flags & DITRON_DUMP_SCHEDULE) && !schedule_out) return DITRON_ERR_INVALID_ARG;

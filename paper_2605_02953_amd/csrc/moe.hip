@@ -433,6 +433,7 @@ extern "C" ditron_status_t ditron_moe_ag_grouped_gemm(
     return DITRON_ERR_INVALID_ARG;
   if (!aligned16(w) || !aligned16(y) || !aligned16(workspace) || !aligned16(signals)) return DITRON_ERR_INVALID_ARG;
   const Mode mode = producer_mode(flags);
+  if (flags & DITRON_EPOCH_IN_MEMORY) return DITRON_ERR_UNSUPPORTED;
   const Tuning tune = resolve_tuning(tuning, 1);
   if (mode == Mode::kInvalid || !tune.valid) return DITRON_ERR_INVALID_ARG;
   const bool emulate = mode == Mode::kEmulate;
@@ -684,6 +685,7 @@ extern "C" ditron_status_t ditron_moe_grouped_gemm_rs(
       !aligned16(scatter_buf) || !aligned16(signals))
     return DITRON_ERR_INVALID_ARG;
   const Mode mode = producer_mode(flags);
+  if (flags & DITRON_EPOCH_IN_MEMORY) return DITRON_ERR_UNSUPPORTED;
   const Tuning tune = resolve_tuning(tuning, 1);
   if (mode == Mode::kInvalid || !tune.valid) return DITRON_ERR_INVALID_ARG;
   const bool emulate = mode == Mode::kEmulate;

@@ -111,3 +111,64 @@ def test_cfg5_full_size(B, variant):
     err = compare.max_row_rel_error(formats.decode_bf16(got), ref)
     assert err <= TOL_FP8, err
     assert err <= 1e-2          # what fp32 accumulation + one bf16 rounding should actually give
+
+
+def test_epoch_in_memory_and_graph_replay(B):
+    """DITRON_EPOCH_IN_MEMORY: the epoch lives in the last word of `signals` and the kernel advances it, so one
+    recorded launch can be replayed.  Eager calls first, then a captured graph replayed several times with eager
+    work and synchronisations in between; every result is compared with the call that takes its epoch as an
+    argument."""
+    cfg = synth.CONFIGS[5].scaled(world=8, m_per_rank=16, n=1024, k=2048, rank=3)
+    a, sa, b, sb = synth.fp8_ag_gemm_inputs(cfg)
+    ref = _run(B, cfg, a, sa, b, sb)
+    run = AgGemmRun(B, cfg.world, cfg.m_per_rank, cfg.n, cfg.k, esize=1)
+    xs, bd, sad, sbd = [to_dev(x) for x in a], to_dev(nk(b)), to_dev(sa), to_dev(sb)
+    flags = B.EMULATE_PRODUCER | B.EPOCH_IN_MEMORY
+    gathered = oag.gather(a)
+
+    def check(calls_so_far):
+        torch.cuda.synchronize()
+        sig = run.signals.cpu().numpy()
+        assert run.status.cpu().tolist()[0] == 0
+        assert sig[-1] == calls_so_far and sig[-2] == 0              # the epoch advanced once, the counter is back at zero
+        assert (sig[:cfg.world] == calls_so_far).all()               # every shard flag carries this call's epoch
+        assert np.array_equal(bits(run.c), ref)
+        assert np.array_equal(run.workspace.cpu().numpy(), gathered)
+
+    for i in range(3):
+        run.c.zero_()
+        run.workspace.zero_()
+        assert run(xs, bd, cfg.rank, flags=flags, dtype=B.FP8_E4M3, a_scales=sad, b_scales=sbd) == B.OK
+        check(i + 1)
+
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        try:
+            st = run(xs, bd, cfg.rank, flags=flags, dtype=B.FP8_E4M3, a_scales=sad, b_scales=sbd, stream=side)
+        finally:
+            graph.capture_end()
+    assert st == B.OK
+    scratch = torch.zeros(1 << 20, device="cuda")
+    for i in range(4):
+        run.c.zero_()
+        run.workspace.zero_()
+        scratch.add_(1.0)                       # the program's own eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        check(3 + i + 1)
+    assert float(scratch[0]) == 4.0
+
+
+def test_epoch_in_memory_is_refused_elsewhere(B):
+    cfg = synth.CONFIGS[5].scaled(world=8, m_per_rank=16, n=1024, k=2048)
+    a, sa, b, sb = synth.fp8_ag_gemm_inputs(cfg)
+    run = AgGemmRun(B, cfg.world, cfg.m_per_rank, cfg.n, cfg.k, esize=1, tuning=B.tuning(decode_variant=1))
+    st = run([to_dev(x) for x in a], to_dev(nk(b)), 0, flags=B.EMULATE_PRODUCER | B.EPOCH_IN_MEMORY, dtype=B.FP8_E4M3)
+    assert st == B.ERR_UNSUPPORTED            # the 128 x 32 kernel takes its epoch as an argument only
+    big = AgGemmRun(B, 2, 1024, 2048, 256)    # a bf16 problem of the tile engine
+    x = [torch.zeros((1024, 256), dtype=torch.int16, device="cuda") for _ in range(2)]
+    w = torch.zeros((2048, 256), dtype=torch.int16, device="cuda")
+    assert big(x, w, 0, flags=B.EMULATE_PRODUCER | B.EPOCH_IN_MEMORY) == B.ERR_UNSUPPORTED
