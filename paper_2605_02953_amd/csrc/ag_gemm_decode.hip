@@ -439,37 +439,46 @@ __device__ __forceinline__ void splitk_work_group(const AgGemmDecodeParams& p, c
     const __amdgpu_buffer_rsrc_t part = __builtin_amdgcn_make_buffer_rsrc(
         (char*)p.partials + (size_t)tile * p.splits * tile_bytes, 0, (int)(p.splits * tile_bytes), 0x00020000);
     const uint32_t tag = (uint32_t)epoch;
+    // This work-group finishes 1/S of the tile: pieces [u_lo, u_hi).  Its own partial of those pieces never
+    // leaves the compute unit: the wave that holds it parks it in the (now idle) operand rings.
+    const int u_lo = ks * UNITS / p.splits, u_hi = (ks + 1) * UNITS / p.splits;
+    __syncthreads();   // every wave is past its last fragment read
     if (!loader) {
       // in the lanes' own order: half h of block (nb, mb) of wave w is 64 lanes x 16 contiguous bytes
 #pragma unroll
       for (int nb = 0; nb < T::NB; ++nb)
 #pragma unroll
         for (int mb = 0; mb < T::MB; ++mb) {
-          const u32x4_t v = __builtin_bit_cast(u32x4_t, acc[nb][mb]);
-          const int off = ((ks * 4 + wave) * BLOCKS + nb * T::MB + mb) * 2048 + lane * 16;
-          __builtin_amdgcn_raw_buffer_store_b128(u32x4_t{v[0], tag, v[1], tag}, part, off, 0, kCoherent);
-          __builtin_amdgcn_raw_buffer_store_b128(u32x4_t{v[2], tag, v[3], tag}, part, off + 1024, 0, kCoherent);
+          const int blk = nb * T::MB + mb, u = wave * BLOCKS + blk;
+          if (u >= u_lo && u < u_hi) {
+            *(f32x4_t*)(lds + (u - u_lo) * 1024 + lane * 16) = acc[nb][mb];
+          } else {
+            const u32x4_t v = __builtin_bit_cast(u32x4_t, acc[nb][mb]);
+            const int off = ((ks * 4 + wave) * BLOCKS + blk) * 2048 + lane * 16;
+            __builtin_amdgcn_raw_buffer_store_b128(u32x4_t{v[0], tag, v[1], tag}, part, off, 0, kCoherent);
+            __builtin_amdgcn_raw_buffer_store_b128(u32x4_t{v[2], tag, v[3], tag}, part, off + 1024, 0, kCoherent);
+          }
         }
     }
-    // This work-group finishes 1/S of the tile: pieces [ks U / S, (ks + 1) U / S), dealt to its eight waves;
-    // the S partials of a piece are added in split order, whoever wrote them last.  The other splits of the
-    // tile are neighbours in the grid: work-groups are dispatched in index order, so whenever some of them
-    // are polling here the rest is running or next in line.
-    const int u_hi = (ks + 1) * UNITS / p.splits;
-    for (int u = ks * UNITS / p.splits + wave; u < u_hi; u += 8) {
+    __syncthreads();   // the parked partial is there
+    // The pieces are dealt to the eight waves; the S partials of a piece are added in split order, whoever
+    // wrote them last.  The other splits of the tile are neighbours in the grid: work-groups are dispatched in
+    // index order, so whenever some of them are polling here the rest is running or next in line.
+    for (int u = u_lo + wave; u < u_hi; u += 8) {
+      const f32x4_t own = *(const f32x4_t*)(lds + (u - u_lo) * 1024 + lane * 16);
       u32x4_t v[8][2];
       unsigned polls = 0;
       for (;;) {
         bool ok = true;
 #pragma unroll
         for (int sp = 0; sp < 8; ++sp)
-          if (sp < p.splits) {
+          if (sp < p.splits && sp != ks) {
             v[sp][0] = __builtin_amdgcn_raw_buffer_load_b128(part, (sp * UNITS + u) * 2048 + lane * 16, 0, kCoherent);
             v[sp][1] = __builtin_amdgcn_raw_buffer_load_b128(part, (sp * UNITS + u) * 2048 + 1024 + lane * 16, 0, kCoherent);
           }
 #pragma unroll
         for (int sp = 0; sp < 8; ++sp)
-          if (sp < p.splits) ok = ok && v[sp][0][1] == tag && v[sp][0][3] == tag && v[sp][1][1] == tag && v[sp][1][3] == tag;
+          if (sp < p.splits && sp != ks) ok = ok && v[sp][0][1] == tag && v[sp][0][3] == tag && v[sp][1][1] == tag && v[sp][1][3] == tag;
         if (__all(ok)) break;
         if (++polls >= p.spin_limit) {
           if (lane == 0) {
@@ -484,7 +493,7 @@ __device__ __forceinline__ void splitk_work_group(const AgGemmDecodeParams& p, c
       for (int sp = 0; sp < 8; ++sp)
         if (sp < p.splits) {
           const f32x4_t lo = __builtin_bit_cast(f32x4_t, v[sp][0]), hi = __builtin_bit_cast(f32x4_t, v[sp][1]);
-          const f32x4_t x = __builtin_shufflevector(lo, hi, 0, 2, 4, 6);
+          const f32x4_t x = sp == ks ? own : __builtin_shufflevector(lo, hi, 0, 2, 4, 6);
           tot = sp == 0 ? x : tot + x;
         }
       const int w = u / BLOCKS, blk = u % BLOCKS, nb = blk / T::MB, mb = blk % T::MB;
