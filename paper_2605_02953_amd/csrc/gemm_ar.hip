@@ -288,7 +288,7 @@ static ditron_status_t launch_ar(GemmArParams& p, int units, bool two_shot, hipS
     // balance the two.  Per GEMM tile the consumer moves (world + 1) tile-sized streams in the one-shot
     // form and 2 in the two-shot form (world reads and world writes for one tile in `world`), at ~40 GB/s
     // per unit (50 while streaming, less the waits).
-    constexpr double kUnitBytes = 40e9, kUnitFlops = 4.4e12;
+    constexpr double kUnitBytes = 40e9, kUnitFlops = 5.3e12;   // (measured at table shape 3: X = 40 / 56 / 64 / 72 / 80 -> 555 / 534 / 528 / 540 / 545 us)
     const double streams = two_shot ? 2.0 : p.world + 1.0;
     const double t_reduce = streams * T::BM * T::BN * 2 / kUnitBytes;   // unit-seconds per tile
     const double t_gemm = 2.0 * T::BM * T::BN * p.k / kUnitFlops;
