@@ -63,7 +63,7 @@ __device__ __forceinline__ void barrier_no_drain() {
 // each owning BM/2 x BN/2 (256 x 256: 128 x 128 per wave, 256 accumulator registers, every
 // fragment read from LDS feeds four MFMAs).  Operands are staged global -> registers -> LDS, or,
 // with DIRECT, global -> LDS (`buffer_load ... lds`; measured 3 % faster on 256 x 256 tiles for
-// contraction lengths up to 8192, slower beyond 12288, for contraction lengths that are not whole K
+// contraction lengths up to 12288, slower beyond, for contraction lengths that are not whole K
 // tiles, and on 128-row tiles, so the launch code picks per problem).  LDS
 // holds two stages of one 64-deep K tile each, rows of 128 bytes (measured free of bank
 // conflicts for both the fragment reads and the staging stores).

@@ -13,10 +13,11 @@ namespace ditron {
 // 256x256 output tile: 128x128 per wave, 128 KiB of LDS.
 typedef GemmTile4W<256, 256> TileBig;
 // The same tile with operands loaded straight into LDS and the 16 x 16 x 32 MFMA form, and the contraction
-// lengths for which that is the faster one (measured against the tile above: 6-7 % faster at 3584 and 8192,
-// 7 % slower at 16384, 7 % slower when the last K tile is ragged).
+// lengths for which that is the faster one (measured against the tile above: 6-7 % faster at 3584 and 8192, 3 %
+// faster at 10240 and 12288, 1-2 % slower at 14336, 16320 and 16448, 8 % slower at 16384, whose rows are 32 KiB
+// apart; 7 % slower when the last K tile is ragged).
 typedef GemmTile4W<256, 256, false, true, true> TileBigDirect;
-inline bool use_direct_staging(int k) { return k % 64 == 0 && k <= 8192; }
+inline bool use_direct_staging(int k) { return k % 64 == 0 && k <= 12288; }
 // 128x128 output tile: 64x64 per wave, 64 KiB of LDS; for problems with too few 256x256 tiles
 // to fill the chip.
 typedef GemmTile4W<128, 128> TileSmall;
