@@ -3,7 +3,8 @@
 // Both operands are read as rows that are contiguous along the contraction dimension.  A
 // K slice of 64 elements of BM + BN rows is staged in LDS as 128-byte rows (one cache line per
 // row) whose eight 16-byte chunks are XOR-swizzled by the row index.  Four waves, one per SIMD,
-// each own a quarter of the tile and feed v_mfma_f32_32x32x16_bf16 from 128-bit LDS reads.  The
+// each own a quarter of the tile and feed v_mfma_f32_32x32x16_bf16 (or, in the X16 form of the tile,
+// v_mfma_f32_16x16x32_bf16) from 128-bit LDS reads.  The
 // instruction's row operand is taken from the B rows and its column operand from the A rows,
 // so that a lane ends up with four consecutive output columns of one output row.
 #pragma once

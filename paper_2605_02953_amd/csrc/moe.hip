@@ -1,14 +1,14 @@
 // MoE AllGather + grouped GEMM, one rank's share (paper: "ag_group_gemm" of the kernel
 // list; tile ordering after `threadblock_swizzle_ag_moe_kernel`, Appendix "Swizzle").
 //
-// Launch 1.  Work-group 0 (integer only): per-(rank, expert) histogram, exclusive scan of
-// the local experts' totals, stable gather index, then the tile list: every local expert's
-// rows are cut into BLOCK_M row tiles, each tile learns the span of source ranks its rows
-// come from and the ring stage at which the last of them arrives, and tiles are emitted
-// grouped by expert, ascending stage, ties in original order.  The other work-groups are the
-// emulated peers: they copy the token shards into the workspace in delivery order and raise
-// one flag per shard.  The all-gather does not depend on the routing, so it starts with the
-// call and runs beside the routing work-group (which leaves the rest of the chip idle).
+// Launch 1.  The first work-groups (integer only, up to eight sharing the scan plus one for the
+// schedule): per-(rank, expert) histogram, exclusive scan of the local experts' totals, stable
+// gather index, then the tile list: every local expert's rows are cut into BLOCK_M row tiles, each
+// tile learns the span of source ranks its rows come from and the ring stage at which the last of
+// them arrives, and tiles are emitted grouped by expert, ascending stage, ties in original order.
+// The other work-groups are the emulated peers: they copy the token shards into the workspace in
+// delivery order and raise one flag per shard.  The all-gather does not depend on the routing, so
+// it starts with the call and runs beside the routing work-groups (which leave the rest of the chip idle).
 // Launch 2: every work-group takes one (tile, column block), waits for the shard flags of its
 // tile, gathers its rows through gather_idx while staging them in LDS and multiplies by its
 // expert's weights.
