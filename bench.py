@@ -640,6 +640,78 @@ SWEEP_MOE = [("Qwen1.5-MoE-A2.7B", 2048, 176, 60, 4), ("Mixtral-8x7B", 14336, 51
              ("Mixtral-8x22B", 16384, 768, 8, 2), ("DeepSeek-MoE", 1408, 256, 64, 6)]
 
 
+def bench_moe_rs(args):
+    """MoE down-projection + ReduceScatter at the shape of the paper's MoE+RS table (8192 tokens, hidden 2048,
+    intermediate 1536 over 8 ranks, 32 experts, top-2), tensor-parallel placement: every expert on the rank, its
+    slice of the intermediate size.  Routing tables are made with torch (stable sort by expert); activations and
+    weights N(0,1) / N(0,1/intermediate) bf16 made on the device."""
+    import torch
+    from paper_2605_02953_amd import binding as B
+
+    world, t_r, hidden, inter, experts, top_k, chunks = 8, 1024, 2048, 1536 // 8, 32, 2, 4
+    tokens, rows = world * t_r, world * t_r * top_k
+    g = torch.Generator(device="cuda").manual_seed(11)
+    i32 = dict(dtype=torch.int32, device="cuda")
+    ids = torch.rand((tokens, experts), device="cuda", generator=g).argsort(dim=1)[:, :top_k].reshape(-1)
+    order = torch.sort(ids, stable=True).indices.to(torch.int32).contiguous()          # gather_idx: assignments grouped by expert
+    offsets = torch.zeros(experts + 1, **i32)
+    offsets[1:] = torch.bincount(ids, minlength=experts).cumsum(0).to(torch.int32)
+    h = torch.randn((rows, inter), device="cuda", generator=g).to(torch.bfloat16).view(torch.int16)
+    nsets = 3
+    w2 = [(torch.randn((experts, hidden, inter), device="cuda", generator=g) * (inter * world) ** -0.5).to(torch.bfloat16).view(torch.int16)
+          for _ in range(nsets)]
+    gate = torch.rand((tokens * top_k,), device="cuda", generator=g)
+    peers = [None if s == 0 else torch.randn((t_r, hidden), device="cuda", generator=g).to(torch.bfloat16).view(torch.int16) for s in range(world)]
+    max_rows = rows
+    y = torch.zeros((max_rows, hidden), dtype=torch.int16, device="cuda")
+    inv = torch.zeros((tokens * top_k,), **i32)
+    rec = torch.zeros((1 + 5 * B.moe_max_tiles(max_rows, experts),), **i32)
+    combined = torch.zeros((tokens, hidden), dtype=torch.int16, device="cuda")
+    scatter = torch.zeros((world, t_r, hidden), dtype=torch.int16, device="cuda")
+    out_t = torch.zeros((t_r, hidden), dtype=torch.int16, device="cuda")
+    signals = torch.zeros(B.signal_words(world, chunks), **i32)
+    status = torch.zeros(B.STATUS_WORDS, **i32)
+    state = {"epoch": 0, "it": 0}
+
+    def make_step(flags):
+        def step():
+            state["epoch"] += 1
+            state["it"] += 1
+            st = B.moe_grouped_gemm_rs(h, w2[state["it"] % nsets], B.B_NK, gate, order, offsets, y, inv, rec, combined,
+                                       None if flags == B.FLAGS_PRESET else peers, scatter, out_t, signals, status, None, t_r, hidden,
+                                       inter, experts, top_k, experts, max_rows, world, 0, chunks, state["epoch"], flags)
+            if st != B.OK:
+                raise RuntimeError(B.status_string(st))
+        return step
+
+    step = make_step(B.EMULATE_PRODUCER)
+    ms_per_step, ev_ms = _timed(torch, args, step)
+    if status.cpu().tolist()[0] != 0:
+        raise RuntimeError("kernel reported an error")
+    quant = LAST_QUANTILES
+    preset = _events_us(torch, make_step(B.FLAGS_PRESET), n=100, warm=10)
+    flops = 2.0 * rows * inter * hidden
+    slot = t_r * hidden * 2
+    # h and the weights in, y out and back in, the combined block out, the reduction's world slots in and its result out
+    alg_bytes = rows * inter * 2 + experts * hidden * inter * 2 + 2 * rows * hidden * 2 + tokens * hidden * 2 + (world + 1) * slot
+    peer_bytes = 2.0 * (world - 1) * slot
+    gbs = (alg_bytes + peer_bytes) / (ev_ms * 1e-3) / 1e9
+    return {
+        "metric": "time (us) of one rank's MoE down-projection + ReduceScatter share (emulated peers)",
+        "value": ms_per_step * 1e3, "unit": "us",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"moe_rs: grouped GEMM [{rows}, {inter}] x [{experts}, {inter}, {hidden}] + top-{top_k} combine + reduce-scatter over "
+                               f"{world} slots of [{t_r}, {hidden}] ({chunks} row chunks): the paper's MoE+RS table shape at tensor parallel 8",
+                   "latency_us": ev_ms * 1e3, "latency_us_quantiles": quant, "tflops": flops / (ev_ms * 1e-3) / 1e12},
+        "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS, "traffic": None,
+                     "kernel": "fill + prepare + moe_grouped_gemm_kernel + moe_combine_kernel + reduce_slots_kernel (whole step between events)",
+                     "kernel_ms": ev_ms, "bytes": alg_bytes + peer_bytes,
+                     "note": "algorithmic bytes of the five launches plus the emulated peers' copies (read + write of 7 blocks)"},
+        "flags_preset_us": preset,
+    }
+
+
 def bench_moe_sweep(args):
     """MoE AllGather + grouped GEMM over the four shapes of the paper's MoE table, all experts local
     (expert_begin 0), 8 x 1024 tokens, uniform top-k routing, N(0,1) / N(0,1/hidden) bf16 made on the
@@ -979,6 +1051,8 @@ def main():
         out = bench_sweep(args)
     elif args.workload == "moe_sweep":
         out = bench_moe_sweep(args)
+    elif args.workload == "moe_rs":
+        out = bench_moe_rs(args)
     elif args.workload == "yardstick":
         out = bench_yardstick(args)
     else:
