@@ -630,15 +630,30 @@ __global__ __launch_bounds__(1024) void moe_combine_kernel(const MoeCombineParam
     float acc[8];
 #pragma unroll
     for (int q = 0; q < 8; ++q) acc[q] = 0.f;
-    for (int j = 0; j < p.top_k; ++j) {
-      const int pos = p.inverse_idx[t * p.top_k + j];
-      if (pos < 0) continue;   // the assignment's expert is not on this rank
-      const float g = p.gate ? p.gate[t * p.top_k + j] : 1.f;
-      const u32x4_t x = __builtin_nontemporal_load((const u32x4_t*)(p.y + (size_t)pos * p.hidden) + c);
+    // the token's assignments eight at a time: positions and gates first, then every row's 16 bytes, then the
+    // sum in the order j = 0, 1, ... (the loads of a batch are in flight together)
+    constexpr int kBatch = 8;
+    for (int j0 = 0; j0 < p.top_k; j0 += kBatch) {
+      int pos[kBatch];
+      float g[kBatch];
+      u32x4_t x[kBatch];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        acc[2 * q] = __builtin_fmaf(g, __builtin_bit_cast(float, x[q] << 16), acc[2 * q]);
-        acc[2 * q + 1] = __builtin_fmaf(g, __builtin_bit_cast(float, x[q] & 0xFFFF0000u), acc[2 * q + 1]);
+      for (int b = 0; b < kBatch; ++b) {
+        const bool in = j0 + b < p.top_k;
+        pos[b] = in ? p.inverse_idx[t * p.top_k + j0 + b] : -1;   // -1: the assignment's expert is not on this rank
+        g[b] = (in && p.gate) ? p.gate[t * p.top_k + j0 + b] : 1.f;
+      }
+#pragma unroll
+      for (int b = 0; b < kBatch; ++b)
+        if (pos[b] >= 0) x[b] = __builtin_nontemporal_load((const u32x4_t*)(p.y + (size_t)pos[b] * p.hidden) + c);
+#pragma unroll
+      for (int b = 0; b < kBatch; ++b) {
+        if (pos[b] < 0) continue;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          acc[2 * q] = __builtin_fmaf(g[b], __builtin_bit_cast(float, x[b][q] << 16), acc[2 * q]);
+          acc[2 * q + 1] = __builtin_fmaf(g[b], __builtin_bit_cast(float, x[b][q] & 0xFFFF0000u), acc[2 * q + 1]);
+        }
       }
     }
     typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
@@ -779,7 +794,10 @@ extern "C" ditron_status_t ditron_moe_grouped_gemm_rs(
   c.tokens = world * tokens_per_rank;
   c.top_k = top_k;
   c.hidden = hidden;
-  c.combine_wgs = (int)std::min<long>(512, ((long)c.tokens * (hidden / 8) + 1023) / 1024);
+  // one work-group of 1024 threads per compute unit, so that the emulated peers behind them are resident from the
+  // start (two such work-groups fit a unit); measured at the paper's MoE+RS shape: 256 / 384 / 512 / 2048 combine
+  // work-groups -> 117 / 122 / 124 / 166 us for the whole call
+  c.combine_wgs = (int)std::min<long>(256, ((long)c.tokens * (hidden / 8) + 1023) / 1024);
   c.done = signals + world;                                   // the counter word of segment 0 (unused here otherwise)
   c.own_flags = signals + 2 * world + rank * chunks_per_slot;
   for (int i = 0; i < world; ++i) {
