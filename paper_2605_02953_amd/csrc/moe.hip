@@ -325,6 +325,8 @@ struct MoeGemmParams {
   int32_t* status;
   int tokens_per_rank, hidden, inter, top_k, world, max_tiles, npn, num_local, num_xcd;   // hidden: contraction length, inter: output width
   int rows_in_place;   // 1: row p of the left operand is row p of `workspace` (already grouped by expert), no gather
+  int32_t* inverse_idx;   // if set: the work-groups of column block 0 also write inverse_idx[gather_idx[p]] = p for their rows
+  int assignments;
   int32_t epoch;
   unsigned spin_limit;
   int wait;   // 0: the token shards are resident, the flags are not looked at
@@ -366,6 +368,13 @@ __global__ __launch_bounds__(NST > 0 ? 2 * T::THREADS : T::THREADS) void moe_gro
   const int p0 = p.tile_records[1 + 4 * p.max_tiles + pos];
   const int p_end = min(p0 + T::BM, p.expert_offsets[j + 1]);
   if (p.wait) flag_wait_block(p.flags, seg_start, seg_end - seg_start + 1, p.epoch, p.spin_limit, p.status);
+  if (p.inverse_idx && pid_n == 0) {
+    // every row belongs to exactly one row tile, and every row tile has one work-group of column block 0
+    for (int row = p0 + (int)threadIdx.x; row < p_end; row += (int)blockDim.x) {
+      const int f = p.gather_idx[row];
+      if (f >= 0 && f < p.assignments) p.inverse_idx[f] = row;
+    }
+  }
 
   const int n0 = pid_n * T::BN;
   const uint32_t row_bytes = (uint32_t)p.hidden * 2u;
@@ -543,52 +552,49 @@ extern "C" ditron_status_t ditron_moe_ag_grouped_gemm(
 // blocks arrive in the scatter buffer, the slots are added in fp32 in slot order.
 namespace ditron {
 
-__global__ __launch_bounds__(1024) void fill_i32_kernel(int32_t* dst, int n, int32_t value) {
-  for (int i = blockIdx.x * 1024 + threadIdx.x; i < n; i += gridDim.x * 1024) dst[i] = value;
-}
-
 struct MoeRsPrepareParams {
   const int32_t* expert_offsets;
-  const int32_t* gather_idx;
-  int32_t* inverse_idx;    // [assignments], pre-filled with -1
+  int32_t* inverse_idx;    // [assignments]
   int32_t* tile_records;
   int32_t* status;
   int num_local, block_m, max_rows, max_tiles, assignments;
 };
 
-// Work-group 0: the tile list (expert after expert, no arrival stage: every row is local).  The others:
-// inverse_idx[gather_idx[p]] = p.
+// Work-group 0: the tile list (expert after expert, no arrival stage: every row is local).  The others start
+// the inverse index at "not on this rank"; the grouped GEMM that follows fills in the rows that are.
 __global__ __launch_bounds__(1024) void moe_rs_prepare_kernel(const MoeRsPrepareParams p) {
-  const int R = p.expert_offsets[p.num_local];
-  if (blockIdx.x == 0) {
-    __shared__ int s_first[kMaxLocalExperts + 1];
-    if (threadIdx.x == 0) {
-      int tiles = 0;
-      for (int j = 0; j < p.num_local; ++j) {
-        s_first[j] = tiles;
-        tiles += cdiv(p.expert_offsets[j + 1] - p.expert_offsets[j], p.block_m);
-      }
-      s_first[p.num_local] = tiles;
-      const bool fits = R <= p.max_rows && tiles <= p.max_tiles;
-      if (!fits) {
-        p.status[0] = DITRON_ERR_WORKSPACE;
-        p.status[2] = R;
-      }
-      p.tile_records[0] = fits ? tiles : 0;
-    }
-    __syncthreads();
-    if (R > p.max_rows || s_first[p.num_local] > p.max_tiles) return;
-    for (int j = 0; j < p.num_local; ++j)
-      for (int t = s_first[j] + (int)threadIdx.x; t < s_first[j + 1]; t += 1024) {
-        int32_t* rec = p.tile_records + 1 + 4 * t;
-        rec[0] = j; rec[1] = t; rec[2] = 0; rec[3] = 0;
-        p.tile_records[1 + 4 * p.max_tiles + t] = p.expert_offsets[j] + (t - s_first[j]) * p.block_m;
-      }
+  if (blockIdx.x > 0) {
+    for (int f = (blockIdx.x - 1) * 1024 + threadIdx.x; f < p.assignments; f += (gridDim.x - 1) * 1024) p.inverse_idx[f] = -1;
     return;
   }
-  for (int q = (blockIdx.x - 1) * 1024 + threadIdx.x; q < min(R, p.max_rows); q += (gridDim.x - 1) * 1024) {
-    const int f = p.gather_idx[q];
-    if (f >= 0 && f < p.assignments) p.inverse_idx[f] = q;
+  __shared__ int s_off[kMaxLocalExperts + 1];
+  __shared__ int s_first[kMaxLocalExperts + 1];
+  for (int j = threadIdx.x; j <= p.num_local; j += 1024) s_off[j] = p.expert_offsets[j];
+  __syncthreads();
+  const int R = s_off[p.num_local];
+  if (threadIdx.x == 0) {
+    int tiles = 0;
+    for (int j = 0; j < p.num_local; ++j) {
+      s_first[j] = tiles;
+      tiles += cdiv(s_off[j + 1] - s_off[j], p.block_m);
+    }
+    s_first[p.num_local] = tiles;
+    const bool fits = R <= p.max_rows && tiles <= p.max_tiles;
+    if (!fits) {
+      p.status[0] = DITRON_ERR_WORKSPACE;
+      p.status[2] = R;
+    }
+    p.tile_records[0] = fits ? tiles : 0;
+  }
+  __syncthreads();
+  if (R > p.max_rows || s_first[p.num_local] > p.max_tiles) return;
+  // one thread per tile: its expert by a walk over the (few) firsts
+  for (int t = threadIdx.x; t < s_first[p.num_local]; t += 1024) {
+    int j = 0;
+    while (s_first[j + 1] <= t) ++j;
+    int32_t* rec = p.tile_records + 1 + 4 * t;
+    rec[0] = j; rec[1] = t; rec[2] = 0; rec[3] = 0;
+    p.tile_records[1 + 4 * p.max_tiles + t] = s_off[j] + (t - s_first[j]) * p.block_m;
   }
 }
 
@@ -726,15 +732,11 @@ extern "C" ditron_status_t ditron_moe_grouped_gemm_rs(
     }
   }
 
-  // 1. inverse index starts at "not on this rank"
-  hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)std::min<long>(256, (assignments + 1023) / 1024)), dim3(1024), 0, s,
-                     inverse_idx, (int)assignments, -1);
-  // 2. tile list + inverse index
+  // 1. tile list; the inverse index starts at "not on this rank"
   const MoeTile mt = choose_moe_tile(moe_expected_rows((long)world * tokens_per_rank, top_k, num_experts, num_local_experts),
                                      num_local_experts, hidden);
   MoeRsPrepareParams pr{};
   pr.expert_offsets = expert_offsets;
-  pr.gather_idx = gather_idx;
   pr.inverse_idx = inverse_idx;
   pr.tile_records = tile_records;
   pr.status = status;
@@ -743,10 +745,11 @@ extern "C" ditron_status_t ditron_moe_grouped_gemm_rs(
   pr.max_rows = max_rows;
   pr.max_tiles = max_tiles;
   pr.assignments = (int)assignments;
-  hipLaunchKernelGGL(moe_rs_prepare_kernel, dim3(1 + (unsigned)std::min(64, cdiv(max_rows, 1024))), dim3(1024), 0, s, pr);
+  hipLaunchKernelGGL(moe_rs_prepare_kernel, dim3(1 + (unsigned)std::min<long>(64, (assignments + 1023) / 1024)), dim3(1024), 0, s, pr);
   if (hipGetLastError() != hipSuccess) return DITRON_ERR_HIP;
 
-  // 3. grouped GEMM y[p, :] = h[p, :] . W2_expert(p): contraction over the intermediate size, hidden columns
+  // 2. grouped GEMM y[p, :] = h[p, :] . W2_expert(p): contraction over the intermediate size, hidden columns; its
+  //    work-groups of column block 0 also write the inverse index of their rows
   MoeGemmParams g{};
   g.workspace = (const char*)h;
   g.w = (const char*)w;
@@ -765,6 +768,8 @@ extern "C" ditron_status_t ditron_moe_grouped_gemm_rs(
   g.num_local = num_local_experts;
   g.num_xcd = 8;
   g.rows_in_place = 1;
+  g.inverse_idx = inverse_idx;
+  g.assignments = (int)assignments;
   g.epoch = epoch;
   g.spin_limit = tune.spin_limit;
   g.wait = 0;
@@ -784,7 +789,7 @@ extern "C" ditron_status_t ditron_moe_grouped_gemm_rs(
   }
   if (st != DITRON_OK) return st;
 
-  // 4. top-k combine into token order; the emulated peers' blocks arrive beside it
+  // 3. top-k combine into token order; the emulated peers' blocks arrive beside it
   const size_t slot_bytes = (size_t)tokens_per_rank * hidden * 2;
   MoeCombineParams c{};
   c.y = (const __bf16*)y;
@@ -817,7 +822,7 @@ extern "C" ditron_status_t ditron_moe_grouped_gemm_rs(
   hipLaunchKernelGGL(moe_combine_kernel, dim3((unsigned)(c.combine_wgs + c.num_producers)), dim3(1024), 0, s, c);
   if (hipGetLastError() != hipSuccess) return DITRON_ERR_HIP;
 
-  // 5. the reduction of GEMM-ReduceScatter over the `world` slots (own slot: the rank's rows of `combined`)
+  // 4. the reduction of GEMM-ReduceScatter over the `world` slots (own slot: the rank's rows of `combined`)
   const void* slots[DITRON_MAX_WORLD];
   for (int i = 0; i < world; ++i)
     slots[i] = i == rank ? (const void*)((const char*)combined + (size_t)rank * slot_bytes)
