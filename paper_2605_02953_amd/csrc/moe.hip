@@ -334,8 +334,11 @@ struct MoeGemmParams {
 
 // NST > 0: operands through a ring of NST LDS stages filled by four extra waves (expert weights stream from
 // HBM: see gemm_mainloop_ring_split)
-template <class T, int NST = 0>
+// WALK: the launch has fewer work-groups than items and every work-group walks down its chiplet's run with the
+// stride of the grid (short tiles: a work-group start costs as much as the tile).
+template <class T, int NST = 0, bool WALK = false>
 __global__ __launch_bounds__(NST > 0 ? 2 * T::THREADS : T::THREADS) void moe_grouped_gemm_kernel(const MoeGemmParams p) {
+  static_assert(!WALK || NST == 0, "the loading waves of the ring leave the kernel after one item");
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   // Work-group -> (row tile, column block).  All (row tile, column block) items are put in one list, expert
   // after expert, inside an expert column block after column block, the expert's row tiles (one to three) of
@@ -345,13 +348,11 @@ __global__ __launch_bounds__(NST > 0 ? 2 * T::THREADS : T::THREADS) void moe_gro
   // once, and every chiplet has the same number of tiles (an expert per chiplet moves as few bytes but leaves
   // the chiplets of small experts idle while the large ones run two rounds).  The row tiles of expert j are
   // the positions [first_j, first_j + ceil(n_j / BLOCK_M)) of the tile list, in arrival-stage order.
-  // A launch with fewer work-groups than items (short tiles: a work-group start costs as much as the tile)
-  // lets every work-group walk down its chiplet's run with the stride of the grid.
   const int wg = blockIdx.x;
   const int ntiles = p.tile_records[0];
   if (ntiles <= 0) return;   // nothing routed here, or the routing launch reported an error
   const int per_xcd = cdiv(ntiles * p.npn, p.num_xcd);
-  const int slots_in_grid = gridDim.x / p.num_xcd;
+  const int slots_in_grid = WALK ? gridDim.x / p.num_xcd : per_xcd;
   for (int slot = wg / p.num_xcd; slot < per_xcd; slot += slots_in_grid) {
   int item = (wg % p.num_xcd) * per_xcd + slot;
   if (item >= ntiles * p.npn) return;
@@ -405,6 +406,7 @@ __global__ __launch_bounds__(NST > 0 ? 2 * T::THREADS : T::THREADS) void moe_gro
     }
   }
   store_tile_bf16<T>(acc, p.y, (size_t)p.inter, p0, n0, p_end, N, lds);
+  if constexpr (!WALK) return;
   __syncthreads();   // the parked tile has been read: the stages are idle for the next item
   }
 }
@@ -419,17 +421,26 @@ extern "C" int ditron_moe_max_tiles(int max_rows, int num_local_experts) {
   return cdiv(max_rows, kMoeBlockM) + num_local_experts;
 }
 
-// `resident`: 0 = one work-group per item; otherwise the number of work-groups to launch at most (they share the items)
 template <class T, int NST = 0>
-static ditron_status_t launch_moe_gemm(MoeGemmParams& g, int max_tiles, hipStream_t s, int resident = 0) {
+static ditron_status_t launch_moe_gemm(MoeGemmParams& g, int max_tiles, hipStream_t s) {
   g.npn = cdiv(g.inter, T::BN);
   constexpr int kLds = NST > 0 ? NST * T::STAGE_BYTES : T::LDS_BYTES;
   static_assert(kLds <= 160 * 1024, "LDS of one compute unit");
   if (!set_dynamic_lds<moe_grouped_gemm_kernel<T, NST>>(kLds)) return DITRON_ERR_HIP;
   // every chiplet takes an equal share of the (row tile, column block) items
-  unsigned grid = (unsigned)(g.num_xcd * cdiv(max_tiles * g.npn, g.num_xcd));
-  if (NST == 0 && resident > 0) grid = std::min(grid, (unsigned)(g.num_xcd * cdiv(resident, g.num_xcd)));
+  const unsigned grid = (unsigned)(g.num_xcd * cdiv(max_tiles * g.npn, g.num_xcd));
   hipLaunchKernelGGL((moe_grouped_gemm_kernel<T, NST>), dim3(grid), dim3(NST > 0 ? 2 * T::THREADS : T::THREADS), kLds, s, g);
+  return hipGetLastError() == hipSuccess ? DITRON_OK : DITRON_ERR_HIP;
+}
+
+// The same with at most `resident` work-groups, which share the items.
+template <class T>
+static ditron_status_t launch_moe_gemm_walk(MoeGemmParams& g, int max_tiles, int resident, hipStream_t s) {
+  g.npn = cdiv(g.inter, T::BN);
+  if (!set_dynamic_lds<moe_grouped_gemm_kernel<T, 0, true>>(T::LDS_BYTES)) return DITRON_ERR_HIP;
+  const unsigned items = (unsigned)(g.num_xcd * cdiv(max_tiles * g.npn, g.num_xcd));
+  const unsigned grid = std::min(items, (unsigned)(g.num_xcd * cdiv(resident, g.num_xcd)));
+  hipLaunchKernelGGL((moe_grouped_gemm_kernel<T, 0, true>), dim3(grid), dim3(T::THREADS), T::LDS_BYTES, s, g);
   return hipGetLastError() == hipSuccess ? DITRON_OK : DITRON_ERR_HIP;
 }
 
@@ -793,7 +804,7 @@ extern "C" ditron_status_t ditron_moe_grouped_gemm_rs(
     // work-groups as are resident at once, each walking down its share of the items (measured at the paper's
     // MoE+RS shape, whole call: 115 us with the ring tiles, 109 with these tiles, 106.5 with 512 resident
     // work-groups, 113.6 with 768; 256 x 256 tiles 108-118).
-    if (inter <= 256) st = launch_moe_gemm<GemmTile4W<128, 128>>(g, max_tiles, s, 512); else
+    if (inter <= 256) st = launch_moe_gemm_walk<GemmTile4W<128, 128>>(g, max_tiles, 512, s); else
     switch (mt.block_n) {
       case 128: st = launch_moe_gemm<GemmTile4W<128, 128, false, true>, 5>(g, max_tiles, s); break;
       case 192: st = launch_moe_gemm<GemmTile4W<128, 192, false, true>, 4>(g, max_tiles, s); break;
