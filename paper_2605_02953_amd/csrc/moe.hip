@@ -30,6 +30,7 @@ constexpr int kPartBad = kPartLocal + kMaxLocalExperts;
 constexpr int kRoutePartWords = kPartBad + 64;
 static_assert(kRouteGroupsMax * kRoutePartWords * 4 == DITRON_MOE_ROUTE_SCRATCH_BYTES, "scratch size declared at the boundary");
 constexpr int kNoBadId = 0x7fffffff;
+constexpr int kWalkExperts = 16;       // up to this many local experts a work-group finds its expert by a scalar walk
 
 struct MoeRouteParams {
   const int32_t* topk_ids;   // [tokens * top_k]
@@ -353,20 +354,44 @@ __global__ __launch_bounds__(NST > 0 ? 2 * T::THREADS : T::THREADS) void moe_gro
   if (ntiles <= 0) return;   // nothing routed here, or the routing launch reported an error
   const int per_xcd = cdiv(ntiles * p.npn, p.num_xcd);
   const int slots_in_grid = WALK ? gridDim.x / p.num_xcd : per_xcd;
-  for (int slot = wg / p.num_xcd; slot < per_xcd; slot += slots_in_grid) {
-  int item = (wg % p.num_xcd) * per_xcd + slot;
-  if (item >= ntiles * p.npn) return;
-  int pos = 0, pid_n = 0;
-  for (int j = 0; j < p.num_local; ++j) {
-    const int nt = cdiv(p.expert_offsets[j + 1] - p.expert_offsets[j], T::BM);
-    if (item < nt * p.npn) {
-      pid_n = item / nt;
-      pos += item % nt;
-      break;
+  // lane j of every wave: the row tiles of expert j and of the experts before it (at most 64 local experts)
+  const int lane_j = threadIdx.x & 63;
+  int nt_j = 0, before_j = 0;
+  if (WALK || p.num_local > kWalkExperts) {
+    nt_j = lane_j < p.num_local ? cdiv(p.expert_offsets[lane_j + 1] - p.expert_offsets[lane_j], T::BM) : 0;
+    before_j = nt_j;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const int v = __shfl_up(before_j, d);
+      if (lane_j >= d) before_j += v;
     }
-    item -= nt * p.npn;
-    pos += nt;
+    before_j -= nt_j;
   }
+  for (int slot = wg / p.num_xcd; slot < per_xcd; slot += slots_in_grid) {
+  const int item = (wg % p.num_xcd) * per_xcd + slot;
+  if (item >= ntiles * p.npn) return;
+  int nt, before;
+  if (WALK || p.num_local > kWalkExperts) {
+    // the expert whose items [before_j npn, (before_j + nt_j) npn) hold this one
+    const unsigned long long holds = __ballot(item >= before_j * p.npn && item < (before_j + nt_j) * p.npn);
+    if (holds == 0) return;
+    const int owner = __ffsll((long long)holds) - 1;
+    // (read into scalar registers: the tile's addresses derive from them and must stay wave-uniform)
+    nt = __builtin_amdgcn_readlane(nt_j, owner);
+    before = __builtin_amdgcn_readlane(before_j, owner);
+  } else {
+    // a handful of experts: a scalar walk over their offsets
+    nt = 0;
+    before = 0;
+    for (int j = 0; j < p.num_local; ++j) {
+      nt = cdiv(p.expert_offsets[j + 1] - p.expert_offsets[j], T::BM);
+      if (item < (before + nt) * p.npn) break;
+      before += nt;
+    }
+    if (nt == 0) return;
+  }
+  const int pid_n = (item - before * p.npn) / nt;
+  const int pos = before + (item - before * p.npn) % nt;
   const int32_t* rec = p.tile_records + 1 + 4 * pos;
   const int j = rec[0], seg_start = rec[2], seg_end = rec[3];
   const int p0 = p.tile_records[1 + 4 * p.max_tiles + pos];
