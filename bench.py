@@ -35,8 +35,9 @@ MEASURED_TRAFFIC = {
     # workload: (bytes read + bytes written, profile, kernels as of commit)
     "cfg2": (957.1e6 + 192.9e6, "profiles/ag_gemm_kernel_cfg2.md", "2377d5c"),   # fused launch; GEMM-only launch 822.4e6 + 58.7e6; algorithmic 251.7e6 (+ 268.4e6 emulated gather)
     "cfg3": (822.4e6 + 251.7e6, "profiles/gemm_rs_kernel_reduce_slots_kernel_cfg3.md", "2377d5c"),   # gemm_rs_kernel fused; reduce_slots_kernel 134.3e6 + 16.8e6 = its algorithmic 151.0e6
-    "cfg4": (143.1e6 + 6.2e6, "profiles/moe_kernels_cfg4.md", "1dccb1d"),   # moe_grouped_gemm_kernel (algorithmic 123.2e6); the gather in the routing launch: 67.4e6 + 67.2e6
+    "cfg4": (144.8e6 + 6.2e6, "profiles/moe_kernels_cfg4.md", "04f4682"),   # moe_grouped_gemm_kernel (algorithmic 123.2e6); the gather in the routing launch: 67.4e6 + 67.2e6
     "gemm_ar": (1999.4e6 + 268.8e6, "profiles/gemm_ar_kernel_table_shape3.md", "2377d5c"),   # fused launch: operand panels ~0.9e9 + eight partials 1.07e9 read; partial + output written
+    "moe_rs": (33.1e6 + 67.7e6 + 97.1e6 + 62.9e6 + 33.6e6 + 4.2e6 + 0.1e6, "profiles/moe_rs_kernels_table_shape.md", "04f4682"),   # grouped GEMM + combine (with the peers' copies) + reduction + preparation
     "cfg5": (102.1e6 + 28.5e6, "profiles/ag_gemm_splitk_kernel_cfg5.md", "431892f"),   # ag_gemm_splitk_kernel (fp8) with emulated peers: B 67.1e6 + A + three quarters of the partial tiles out and back; algorithmic 70.3e6
 }
 
@@ -704,10 +705,11 @@ def bench_moe_rs(args):
         "config": {"workload": f"moe_rs: grouped GEMM [{rows}, {inter}] x [{experts}, {inter}, {hidden}] + top-{top_k} combine + reduce-scatter over "
                                f"{world} slots of [{t_r}, {hidden}] ({chunks} row chunks): the paper's MoE+RS table shape at tensor parallel 8",
                    "latency_us": ev_ms * 1e3, "latency_us_quantiles": quant, "tflops": flops / (ev_ms * 1e-3) / 1e12},
-        "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS, "traffic": None,
-                     "kernel": "fill + prepare + moe_grouped_gemm_kernel + moe_combine_kernel + reduce_slots_kernel (whole step between events)",
+        "roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS, "traffic": _traffic("moe_rs"),
+                     "traffic_source": _traffic_source("moe_rs"),
+                     "kernel": "moe_rs_prepare_kernel + moe_grouped_gemm_kernel + moe_combine_kernel + reduce_slots_kernel (whole step between events)",
                      "kernel_ms": ev_ms, "bytes": alg_bytes + peer_bytes,
-                     "note": "algorithmic bytes of the five launches plus the emulated peers' copies (read + write of 7 blocks)"},
+                     "note": "algorithmic bytes of the four launches plus the emulated peers' copies (read + write of 7 blocks)"},
         "flags_preset_us": preset,
     }
 
