@@ -239,11 +239,11 @@ struct Stager4W {
   // contiguous in the stage (lane l lands at byte 16 l), so the swizzle is applied on the global side: `off`
   // was built for the chunk that belongs at the lane's LDS position.  A chunk past K is pushed out of the
   // buffer's range, for which zeros are written.
-  template <int I>
+  template <int I, bool WHOLE = false>
   __device__ __forceinline__ void issue_one(int kt, int K, char* stage) const {
     constexpr int area = I < T::A_LOADS ? 0 : T::A_BYTES;
     constexpr int pass = I < T::A_LOADS ? I : I - T::A_LOADS;
-    const bool dead = kt * 64 + kc >= K;
+    const bool dead = !WHOLE && kt * 64 + kc >= K;   // WHOLE: K is a whole number of K tiles, no chunk lies past it
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass does not know this builtin
     __builtin_amdgcn_raw_ptr_buffer_load_lds(I < T::A_LOADS ? a_rsrc : b_rsrc,
                                              DITRON_LDS(stage + area + pass * T::ROWS_PER_PASS * T::ROW_BYTES + wave_lds), 16,
@@ -293,23 +293,27 @@ __device__ __forceinline__ void read_one16(Frags16<T>& f, const char* st, int a_
   else f.b[J - T::MB] = *(const bf16x8_t*)(st + b_off + (J - T::MB) * 16 * 128 + koff[KS]);
 }
 
-// Slot S of a step: four MFMAs of column block S / (MB / 4) on row blocks 4 (S % (MB / 4)) .. + 3.
-template <class T, int S>
-__device__ __forceinline__ void mma_quad16(typename T::Acc16& acc, const Frags16<T>& f) {
-  constexpr int nb = S / (T::MB / 4), mb = (S % (T::MB / 4)) * 4;
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-    acc[nb][mb + i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.b[nb], f.a[mb + i], acc[nb][mb + i], 0, 0, 0);
+// MFMA I (0..3) of slot S of a step: column block S / (MB / 4), row block 4 (S % (MB / 4)) + I.
+template <class T, int S, int I>
+__device__ __forceinline__ void mma_one16(typename T::Acc16& acc, const Frags16<T>& f) {
+  constexpr int nb = S / (T::MB / 4), mb = (S % (T::MB / 4)) * 4 + I;
+  acc[nb][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.b[nb], f.a[mb], acc[nb][mb], 0, 0, 0);
 }
 
-// K loop of the 16 x 16 x 32 form, operands loaded straight into two LDS stages.  A 64-deep K tile is two
-// 32-deep steps of MB x NB MFMAs each, written as slots of four MFMAs plus one fragment read and at most one
-// load.  All fragments of a step are read during the step before it, so the K tile's stage is no longer read
-// once its second step starts: the barrier sits between the two steps.
+// K loop of the 16 x 16 x 32 form, operands loaded straight into two LDS stages; K must be a whole number of
+// 64-deep K tiles (the loads carry no range test).  A K tile is two 32-deep steps of MB x NB MFMAs each, written
+// as slots of four MFMAs plus one fragment read and at most one load.  All fragments of a step are read during
+// the step before it, so the K tile's stage is no longer read once its second step starts: the barrier sits
+// between the two steps.
 //   step 0 of tile kt : fragment reads of step 1 (same stage)
 //   barrier           : every wave's part of tile kt+1 has landed, nobody reads tile kt's stage any more
 //   step 1 of tile kt : fragment reads of step 0 of tile kt+1 (other stage); loads of tile kt+2 into the
 //                       stage just freed, which have the whole of the next step 0 to land
+// An MFMA of this form holds the matrix pipe for 16 cycles and the wave is alone on its SIMD, so whatever is
+// issued between two MFMAs has to fit into the 12 cycles the first one leaves: the read and the load of a slot
+// go behind different MFMAs, each MFMA fenced so that the compiler keeps them there (measured: with both behind
+// the slot's last MFMA the loads cost ~300 and the reads ~150 cycles of a K tile's 2048; spread like this the
+// cfg 2 GEMM takes 4 % less time).
 // On entry the LDS stages must be idle; on exit no load is in flight.
 template <class T, class ARow, class BRow>
 __device__ __forceinline__ void gemm_mainloop_x16(typename T::Acc16& acc, const char* a_base, ARow a_row,
@@ -336,8 +340,8 @@ __device__ __forceinline__ void gemm_mainloop_x16(typename T::Acc16& acc, const 
   const int kt_last = kt_all - 1;
   Stager4W<T> st;
   st.init(a_base, a_row, b_base, b_row);
-  st.template issue_range<0, LOADS>(0, K, lds);
-  st.template issue_range<0, LOADS>(min(1, kt_last), K, lds + T::STAGE_BYTES);
+  static_for<0, LOADS>([&](auto i) { st.template issue_one<decltype(i)::value, true>(0, K, lds); });
+  static_for<0, LOADS>([&](auto i) { st.template issue_one<decltype(i)::value, true>(min(1, kt_last), K, lds + T::STAGE_BYTES); });
   wait_vmcnt<LOADS>();
   barrier_no_drain();
   Frags16<T> f0, f1;
@@ -348,8 +352,14 @@ __device__ __forceinline__ void gemm_mainloop_x16(typename T::Acc16& acc, const 
     const int kf = min(kt + 2, kt_last);
     static_for<0, SLOTS>([&](auto sl) {
       constexpr int S = decltype(sl)::value;
-      mma_quad16<T, S>(acc, f0);
+      mma_one16<T, S, 0>(acc, f0);
       if constexpr (S < READS) read_one16<T, 1, S>(f1, cur, a_off, b_off, koff);
+      __builtin_amdgcn_sched_barrier(0);
+      mma_one16<T, S, 1>(acc, f0);
+      __builtin_amdgcn_sched_barrier(0);
+      mma_one16<T, S, 2>(acc, f0);
+      __builtin_amdgcn_sched_barrier(0);
+      mma_one16<T, S, 3>(acc, f0);
       __builtin_amdgcn_sched_barrier(0);
     });
     wait_vmcnt0();     // this wave's part of tile kt+1 has landed
@@ -357,9 +367,15 @@ __device__ __forceinline__ void gemm_mainloop_x16(typename T::Acc16& acc, const 
     barrier_no_drain();
     static_for<0, SLOTS>([&](auto sl) {
       constexpr int S = decltype(sl)::value;
-      mma_quad16<T, S>(acc, f1);
+      mma_one16<T, S, 0>(acc, f1);
       if constexpr (S < READS) read_one16<T, 0, S>(f0, nxt, a_off, b_off, koff);
-      if constexpr (S < LOADS) st.template issue_range<S, S + 1>(kf, K, cur);
+      __builtin_amdgcn_sched_barrier(0);
+      mma_one16<T, S, 1>(acc, f1);
+      __builtin_amdgcn_sched_barrier(0);
+      mma_one16<T, S, 2>(acc, f1);
+      if constexpr (S < LOADS) st.template issue_one<S, true>(kf, K, cur);
+      __builtin_amdgcn_sched_barrier(0);
+      mma_one16<T, S, 3>(acc, f1);
       __builtin_amdgcn_sched_barrier(0);
     });
   }
