@@ -65,6 +65,20 @@ def _cpu_baseline_ag(cfg, shards, b):
             "sample": f"all {cfg.m} rows x {cfg.n} columns of the workload (numpy fp64 GEMM on decoded inputs)"}
 
 
+class _Rotating:
+    """The weight operand of a step, rotating through `copies` device copies of the same values: layers follow
+    each other with different weights, so a call does not find its B in the caches (a single copy would stay in
+    the 256 MB memory-side cache from step to step)."""
+
+    def __init__(self, tensor, copies):
+        self.items = [tensor] + [tensor.clone() for _ in range(max(1, copies) - 1)]
+        self.i = 0
+
+    def next(self):
+        self.i += 1
+        return self.items[self.i % len(self.items)]
+
+
 def bench_ag_gemm(args, cfg_id):
     import torch
     import synth
@@ -75,11 +89,12 @@ def bench_ag_gemm(args, cfg_id):
     shards, b = synth.ag_gemm_inputs(cfg)
     sh = [to_dev(s) for s in shards]
     bd = to_dev(nk(b))
+    weights = _Rotating(bd, args.weight_copies)
     run = AgGemmRun(B, cfg.world, cfg.m_per_rank, cfg.n, cfg.k)
     flops = 2.0 * cfg.m * cfg.n * cfg.k
 
     def step():
-        st = run(sh, bd, cfg.rank)
+        st = run(sh, weights.next(), cfg.rank)
         if st != B.OK:
             raise RuntimeError(B.status_string(st))
 
@@ -102,12 +117,12 @@ def bench_ag_gemm(args, cfg_id):
 
     # the same kernel with every shard already in place (flags preset): the GEMM alone
     for _ in range(3):
-        run(None, bd, cfg.rank, flags=B.FLAGS_PRESET)
+        run(None, weights.next(), cfg.rank, flags=B.FLAGS_PRESET)
     torch.cuda.synchronize()
     pe = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     for i in range(args.steps):
         pe[i][0].record()
-        run(None, bd, cfg.rank, flags=B.FLAGS_PRESET)
+        run(None, weights.next(), cfg.rank, flags=B.FLAGS_PRESET)
         pe[i][1].record()
     torch.cuda.synchronize()
     preset_ms = sum(a.elapsed_time(b_) for a, b_ in pe) / args.steps
@@ -123,6 +138,7 @@ def bench_ag_gemm(args, cfg_id):
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"cfg{cfg_id}: AG-GEMM world={cfg.world} rank={cfg.rank} A {cfg.world}x[{cfg.m_per_rank},{cfg.k}] "
                                f"B [{cfg.k},{cfg.n}] stored [n,k] -> C [{cfg.m},{cfg.n}] bf16, fp32 accumulate",
+                   "weight_copies": args.weight_copies,
                    "latency_us": kernel_ms * 1e3, "latency_us_quantiles": _quantiles_us(ev)},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": _traffic(f"cfg{cfg_id}"), "traffic_source": _traffic_source(f"cfg{cfg_id}"),
@@ -268,9 +284,10 @@ def bench_gemm_rs(args):
         torch.cuda.synchronize()
         peers.append(run.gemm_out[d * m_r:(d + 1) * m_r].clone())
     ad, bd = to_dev(a_list[d]), to_dev(nk(b_list[d]))
+    weights = _Rotating(bd, args.weight_copies)
 
     def step():
-        st = run(ad, bd, peers, d)
+        st = run(ad, weights.next(), peers, d)
         if st != B.OK:
             raise RuntimeError(B.status_string(st))
 
@@ -282,12 +299,12 @@ def bench_gemm_rs(args):
     # the same call with the peers' blocks already in the scatter buffer and their flags preset: the GEMM
     # kernel without the emulated-peer work-groups, then the gated reduction
     for _ in range(3):
-        run(ad, bd, None, d, flags=B.FLAGS_PRESET)
+        run(ad, weights.next(), None, d, flags=B.FLAGS_PRESET)
     torch.cuda.synchronize()
     pe = _events(torch, args.steps)
     for i in range(args.steps):
         pe[i][0].record()
-        run(ad, bd, None, d, flags=B.FLAGS_PRESET)
+        run(ad, weights.next(), None, d, flags=B.FLAGS_PRESET)
         pe[i][1].record()
     torch.cuda.synchronize()
     preset_ms = sum(a.elapsed_time(b) for a, b in pe) / args.steps
@@ -319,7 +336,8 @@ def bench_gemm_rs(args):
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"cfg3: GEMM-RS world={cfg.world} rank={d} A [{cfg.m},{cfg.k}] B [{cfg.k},{cfg.n}] stored [n,k], "
-                               f"7 peer blocks [{m_r},{cfg.n}] bf16, 4 row chunks per block", "latency_us": ev_ms * 1e3},
+                               f"7 peer blocks [{m_r},{cfg.n}] bf16, 4 row chunks per block", "weight_copies": args.weight_copies,
+                   "latency_us": ev_ms * 1e3},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": _traffic("cfg3"), "traffic_source": _traffic_source("cfg3"),
                      "kernel": "gemm_rs_kernel + reduce_slots_kernel (whole step between events)", "kernel_ms": ev_ms},
@@ -366,8 +384,10 @@ def bench_gemm_ar(args):
     ad, bd = to_dev(a_list[d]), to_dev(nk(b_list[d]))
     run = GemmArRun(B, cfg.world, cfg.m, cfg.n, cfg.k)
 
+    weights = _Rotating(bd, args.weight_copies)
+
     def step():
-        st = run(ad, bd, peers, d)
+        st = run(ad, weights.next(), peers, d)
         if st != B.OK:
             raise RuntimeError(B.status_string(st))
 
@@ -437,7 +457,8 @@ def bench_gemm_ar(args):
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"gemm_ar: GEMM-AR world={cfg.world} rank={d} A [{cfg.m},{cfg.k}] B [{cfg.k},{cfg.n}] stored [n,k], "
-                               f"7 peer partials [{cfg.m},{cfg.n}] bf16 resident -> out [{cfg.m},{cfg.n}] bf16", "latency_us": ev_ms * 1e3},
+                               f"7 peer partials [{cfg.m},{cfg.n}] bf16 resident -> out [{cfg.m},{cfg.n}] bf16", "weight_copies": args.weight_copies,
+                   "latency_us": ev_ms * 1e3},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": _traffic("gemm_ar"), "traffic_source": _traffic_source("gemm_ar"),
                      "kernel": "gemm_ar_kernel (GEMM tiles + all-reduce consumers in one launch)", "kernel_ms": ev_ms},
@@ -1032,6 +1053,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--weight-copies", type=int, default=3,
+                    help="cfg2, cfg3, cfg5, gemm_ar: device copies of the weight operand B that the steps rotate through (1 = the same buffer every step)")
     ap.add_argument("--decode-variant", type=int, default=0, help="cfg5: kernel variant of the decode path (0 = library's choice)")
     args = ap.parse_args()
     if args.gpus != 1:

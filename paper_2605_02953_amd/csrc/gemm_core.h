@@ -63,10 +63,10 @@ __device__ __forceinline__ void barrier_no_drain() {
 // BM x BN output tile (BM 256 or 128, BN 256, 192 or 128) computed by four waves, one per SIMD,
 // each owning BM/2 x BN/2 (256 x 256: 128 x 128 per wave, 256 accumulator registers, every
 // fragment read from LDS feeds four MFMAs).  Operands are staged global -> registers -> LDS, or,
-// with DIRECT, global -> LDS (`buffer_load ... lds`; measured 3 % faster on 256 x 256 tiles for
-// contraction lengths up to 12288, slower beyond, for contraction lengths that are not whole K
-// tiles, and on 128-row tiles, so the launch code picks per problem).  LDS
-// holds two stages of one 64-deep K tile each, rows of 128 bytes (measured free of bank
+// with DIRECT, global -> LDS (`buffer_load ... lds`; measured faster on 256 x 256 tiles whose
+// contraction is a whole number of K tiles, slower for a ragged last K tile and on 128-row tiles,
+// so the launch code picks per problem).  LDS holds two stages of one 64-deep K tile each (the
+// 16 x 16 x 32 form: a ring of five half stages), rows of 128 bytes (measured free of bank
 // conflicts for both the fragment reads and the staging stores).
 //
 // B_KN: B is stored [K, N] (N contiguous) instead of [N, K].  Its K tile is then staged as it
@@ -86,6 +86,7 @@ struct GemmTile4W {
   static_assert(!B_KN_ || BN_ != 192, "a [K, N] row of 192 elements does not split evenly over the loading lanes");
   static_assert(!DIRECT_ || !B_KN_, "the direct-to-LDS staging is written for [N, K] operands");
   static_assert(!X16_ || DIRECT_, "the 16 x 16 x 32 loop is written for the direct-to-LDS staging");
+  static_assert(!X16_ || BM_ == BN_, "the 16 x 16 x 32 loop keeps A and B parts in one ring of equal pieces");
   static constexpr bool B_KN = B_KN_;
   static constexpr bool DIRECT = DIRECT_;   // operands go from global memory straight into LDS (no staging registers)
   static constexpr bool X16 = X16_;
@@ -96,7 +97,8 @@ struct GemmTile4W {
   static constexpr int PB = BN * 2 + 64;                      // B_KN: bytes between two k rows of the staged B tile
   static constexpr int A_BYTES = BM * ROW_BYTES, B_BYTES = B_KN ? BK * PB : BN * ROW_BYTES;
   static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
-  static constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
+  // X16: a ring of five operand pieces (the A part and the B part of a K tile are pieces of their own), all of the LDS
+  static constexpr int LDS_BYTES = X16_ ? 5 * A_BYTES : NSTAGE * STAGE_BYTES;
   static constexpr int ROWS_PER_PASS = THREADS / 8;           // 32 rows per pass of 16-byte loads
   static constexpr int A_LOADS = BM / ROWS_PER_PASS, B_LOADS = BN / ROWS_PER_PASS, LOADS = A_LOADS + B_LOADS;
   // The K loop is written as slots of two MFMAs (one B fragment, two A fragments).
@@ -284,13 +286,15 @@ struct Frags16 {
   bf16x8_t b[T::NB];
 };
 
-// Fragment read J of the 32-deep step KS (0 or 1) of the K tile staged at `st`, in the order the slots
-// below consume them: b0, a0 .. a[MB-1], b1 .. b[NB-1].  koff[KS]: the lane's swizzled chunk offset.
+// Fragment read J of the 32-deep step KS (0 or 1) of the K tile whose A part is staged at `pa` and whose B part
+// at `pb`, in the order the slots below consume them: b0, a0 .. a[MB-1], b1 .. b[NB-1].  koff[KS]: the lane's
+// swizzled chunk offset.
 template <class T, int KS, int J>
-__device__ __forceinline__ void read_one16(Frags16<T>& f, const char* st, int a_off, int b_off, const int (&koff)[2]) {
-  if constexpr (J == 0) f.b[0] = *(const bf16x8_t*)(st + b_off + koff[KS]);
-  else if constexpr (J <= T::MB) f.a[J - 1] = *(const bf16x8_t*)(st + a_off + (J - 1) * 16 * 128 + koff[KS]);
-  else f.b[J - T::MB] = *(const bf16x8_t*)(st + b_off + (J - T::MB) * 16 * 128 + koff[KS]);
+__device__ __forceinline__ void read_one16(Frags16<T>& f, const char* pa, const char* pb, int a_off, int b_off,
+                                            const int (&koff)[2]) {
+  if constexpr (J == 0) f.b[0] = *(const bf16x8_t*)(pb + b_off + koff[KS]);
+  else if constexpr (J <= T::MB) f.a[J - 1] = *(const bf16x8_t*)(pa + a_off + (J - 1) * 16 * 128 + koff[KS]);
+  else f.b[J - T::MB] = *(const bf16x8_t*)(pb + b_off + (J - T::MB) * 16 * 128 + koff[KS]);
 }
 
 // MFMA I (0..3) of slot S of a step: column block S / (MB / 4), row block 4 (S % (MB / 4)) + I.
@@ -300,32 +304,38 @@ __device__ __forceinline__ void mma_one16(typename T::Acc16& acc, const Frags16<
   acc[nb][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.b[nb], f.a[mb], acc[nb][mb], 0, 0, 0);
 }
 
-// K loop of the 16 x 16 x 32 form, operands loaded straight into two LDS stages; K must be a whole number of
-// 64-deep K tiles (the loads carry no range test).  A K tile is two 32-deep steps of MB x NB MFMAs each, written
-// as slots of four MFMAs plus one fragment read and at most one load.  All fragments of a step are read during
-// the step before it, so the K tile's stage is no longer read once its second step starts: the barrier sits
-// between the two steps.
-//   step 0 of tile kt : fragment reads of step 1 (same stage)
-//   barrier           : every wave's part of tile kt+1 has landed, nobody reads tile kt's stage any more
-//   step 1 of tile kt : fragment reads of step 0 of tile kt+1 (other stage); loads of tile kt+2 into the
-//                       stage just freed, which have the whole of the next step 0 to land
+// K loop of the 16 x 16 x 32 form, operands loaded straight into LDS; K must be a whole number of 64-deep K
+// tiles (the loads carry no range test).  A K tile is two 32-deep steps of MB x NB MFMAs each, written as slots of
+// four MFMAs plus one fragment read and at most one load.  All fragments of a step are read during the step
+// before it, so a K tile's operands are no longer read once its second step starts: the barrier sits between
+// the two steps.  LDS is a ring of five pieces of 32 KiB; the A part of K tile j lives in piece 2j mod 5 and
+// its B part in piece (2j + 1) mod 5, so two and a half K tiles are resident:
+//   step 0 of tile kt : fragment reads of step 1; loads of A(kt+2) into the piece idle since the last barrier
+//   barrier           : every wave's part of tile kt+1 has landed, nobody reads tile kt any more
+//   step 1 of tile kt : fragment reads of step 0 of tile kt+1; loads of B(kt+2) into the piece of A(kt)
+// The loads go out one per two slots over the whole K tile and have one to three steps to land (with two
+// whole-tile stages all of them went out during step 1 and had one to two: at operands that are not in the
+// caches, cfg 2 and cfg 3 shapes beside the vendor GEMM, the ring takes 8-10 % less time; with operands that
+// are, the same).
 // An MFMA of this form holds the matrix pipe for 16 cycles and the wave is alone on its SIMD, so whatever is
 // issued between two MFMAs has to fit into the 12 cycles the first one leaves: the read and the load of a slot
 // go behind different MFMAs, each MFMA fenced so that the compiler keeps them there (measured: with both behind
 // the slot's last MFMA the loads cost ~300 and the reads ~150 cycles of a K tile's 2048; spread like this the
 // cfg 2 GEMM takes 4 % less time).
-// On entry the LDS stages must be idle; on exit no load is in flight.
+// On entry the LDS must be idle; on exit no load is in flight.
 template <class T, class ARow, class BRow>
 __device__ __forceinline__ void gemm_mainloop_x16(typename T::Acc16& acc, const char* a_base, ARow a_row,
                                                      const char* b_base, BRow b_row, int K, char* lds) {
-  constexpr int MB = T::MB, NB = T::NB, READS = MB + NB, LOADS = T::LOADS;
+  constexpr int MB = T::MB, NB = T::NB, READS = MB + NB, AL = T::A_LOADS, BL = T::B_LOADS;
   constexpr int SLOTS = MB * NB / 4;   // per step
-  static_assert(MB % 4 == 0 && READS <= SLOTS && LOADS <= SLOTS, "one read and at most one load per slot");
+  constexpr int PIECE = T::A_BYTES;
+  static_assert(MB % 4 == 0 && READS <= SLOTS && 2 * AL <= SLOTS && 2 * BL <= SLOTS && T::A_BYTES == T::B_BYTES,
+                "one read per slot, one load per two slots, equal pieces");
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int wm = wave / 2, wn = wave % 2;
   const int lr = lane & 15, lq = lane >> 4;
   const int a_off = (wm * T::WTM + lr) * T::ROW_BYTES;
-  const int b_off = T::A_BYTES + (wn * T::WTN + lr) * T::ROW_BYTES;
+  const int b_off = (wn * T::WTN + lr) * T::ROW_BYTES;
   int koff[2];
 #pragma unroll
   for (int ks = 0; ks < 2; ++ks) koff[ks] = ((ks * 4 + lq) ^ swz128_x16(lr)) * 16;
@@ -340,44 +350,57 @@ __device__ __forceinline__ void gemm_mainloop_x16(typename T::Acc16& acc, const 
   const int kt_last = kt_all - 1;
   Stager4W<T> st;
   st.init(a_base, a_row, b_base, b_row);
-  static_for<0, LOADS>([&](auto i) { st.template issue_one<decltype(i)::value, true>(0, K, lds); });
-  static_for<0, LOADS>([&](auto i) { st.template issue_one<decltype(i)::value, true>(min(1, kt_last), K, lds + T::STAGE_BYTES); });
-  wait_vmcnt<LOADS>();
+  auto wrap = [](int x) { return x >= 5 ? x - 5 : x; };
+  // load I of K tile kt into the piece at `piece` (the stager puts B loads T::A_BYTES behind the address it is given)
+  auto load_a = [&](auto i, int kt, char* piece) { st.template issue_one<decltype(i)::value, true>(kt, K, piece); };
+  auto load_b = [&](auto i, int kt, char* piece) { st.template issue_one<AL + decltype(i)::value, true>(kt, K, piece - T::A_BYTES); };
+  static_for<0, AL>([&](auto i) { load_a(i, 0, lds); });
+  static_for<0, BL>([&](auto i) { load_b(i, 0, lds + PIECE); });
+  static_for<0, AL>([&](auto i) { load_a(i, min(1, kt_last), lds + 2 * PIECE); });
+  static_for<0, BL>([&](auto i) { load_b(i, min(1, kt_last), lds + 3 * PIECE); });
+  wait_vmcnt<AL + BL>();
   barrier_no_drain();
   Frags16<T> f0, f1;
-  static_for<0, READS>([&](auto j) { read_one16<T, 0, decltype(j)::value>(f0, lds, a_off, b_off, koff); });
+  static_for<0, READS>([&](auto j) { read_one16<T, 0, decltype(j)::value>(f0, lds, lds + PIECE, a_off, b_off, koff); });
+  int ia = 0;   // piece of A(kt)
   for (int kt = 0; kt < kt_all; ++kt) {
-    char* cur = lds + (kt & 1) * T::STAGE_BYTES;
-    const char* nxt = lds + ((kt + 1) & 1) * T::STAGE_BYTES;
-    const int kf = min(kt + 2, kt_last);
+    const char* cur_a = lds + ia * PIECE;
+    const char* cur_b = lds + wrap(ia + 1) * PIECE;
+    const char* nxt_a = lds + wrap(ia + 2) * PIECE;
+    const char* nxt_b = lds + wrap(ia + 3) * PIECE;
+    char* free_a = lds + wrap(ia + 4) * PIECE;   // held B(kt-1): nobody has read it since the last barrier
+    char* free_b = lds + ia * PIECE;             // A(kt): free after this iteration's barrier
+    const int kf = min(kt + 2, kt_last);   // past the end the last K tile is requested again, into pieces nobody reads
     static_for<0, SLOTS>([&](auto sl) {
       constexpr int S = decltype(sl)::value;
       mma_one16<T, S, 0>(acc, f0);
-      if constexpr (S < READS) read_one16<T, 1, S>(f1, cur, a_off, b_off, koff);
+      if constexpr (S < READS) read_one16<T, 1, S>(f1, cur_a, cur_b, a_off, b_off, koff);
       __builtin_amdgcn_sched_barrier(0);
       mma_one16<T, S, 1>(acc, f0);
       __builtin_amdgcn_sched_barrier(0);
       mma_one16<T, S, 2>(acc, f0);
+      if constexpr (S % 2 == 0 && S / 2 < AL) load_a(std::integral_constant<int, S / 2>{}, kf, free_a);
       __builtin_amdgcn_sched_barrier(0);
       mma_one16<T, S, 3>(acc, f0);
       __builtin_amdgcn_sched_barrier(0);
     });
-    wait_vmcnt0();     // this wave's part of tile kt+1 has landed
-    wait_lgkmcnt0();   // every read of tile kt has returned
+    wait_vmcnt<AL>();   // this wave's part of tile kt+1 has landed (loads return in order); A(kt+2) may be in flight
+    wait_lgkmcnt0();    // every read of tile kt has returned
     barrier_no_drain();
     static_for<0, SLOTS>([&](auto sl) {
       constexpr int S = decltype(sl)::value;
       mma_one16<T, S, 0>(acc, f1);
-      if constexpr (S < READS) read_one16<T, 0, S>(f0, nxt, a_off, b_off, koff);
+      if constexpr (S < READS) read_one16<T, 0, S>(f0, nxt_a, nxt_b, a_off, b_off, koff);
       __builtin_amdgcn_sched_barrier(0);
       mma_one16<T, S, 1>(acc, f1);
       __builtin_amdgcn_sched_barrier(0);
       mma_one16<T, S, 2>(acc, f1);
-      if constexpr (S < LOADS) st.template issue_one<S, true>(kf, K, cur);
+      if constexpr (S % 2 == 0 && S / 2 < BL) load_b(std::integral_constant<int, S / 2>{}, kf, free_b);
       __builtin_amdgcn_sched_barrier(0);
       mma_one16<T, S, 3>(acc, f1);
       __builtin_amdgcn_sched_barrier(0);
     });
+    ia = wrap(ia + 2);
   }
   wait_vmcnt0();   // the last iteration's requests (the last K tile once more) are not left in flight
 }

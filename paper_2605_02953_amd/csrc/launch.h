@@ -12,12 +12,12 @@ namespace ditron {
 
 // 256x256 output tile: 128x128 per wave, 128 KiB of LDS.
 typedef GemmTile4W<256, 256> TileBig;
-// The same tile with operands loaded straight into LDS and the 16 x 16 x 32 MFMA form, and the contraction
-// lengths for which that is the faster one (measured against the tile above: 6-7 % faster at 3584 and 8192, 3 %
-// faster at 10240 and 12288, 1-2 % slower at 14336, 16320 and 16448, 8 % slower at 16384, whose rows are 32 KiB
-// apart; 7 % slower when the last K tile is ragged).
+// The same tile with operands loaded straight into a ring of five LDS pieces and the 16 x 16 x 32 MFMA form, taken
+// whenever the contraction is a whole number of K tiles (measured against the tile above with emulated peers:
+// 5-9 % faster at K 3584 and 8192, 12 % faster at 16384; its loads carry no range test, so a ragged last K tile
+// stays with the register staging).
 typedef GemmTile4W<256, 256, false, true, true> TileBigDirect;
-inline bool use_direct_staging(int k) { return k % 64 == 0 && k <= 12288; }
+inline bool use_direct_staging(int k) { return k % 64 == 0; }
 // 128x128 output tile: 64x64 per wave, 64 KiB of LDS; for problems with too few 256x256 tiles
 // to fill the chip.
 typedef GemmTile4W<128, 128> TileSmall;
