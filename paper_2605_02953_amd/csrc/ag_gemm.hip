@@ -156,7 +156,6 @@ extern "C" ditron_status_t ditron_ag_gemm(const void* const* a_shards, const voi
     if (tc.big) return launch_ag<TileBigKN>(p, (hipStream_t)stream);
     return launch_ag<TileSmallKN>(p, (hipStream_t)stream);
   }
-  if (tc.big && use_direct_staging(k)) return launch_ag<TileBigDirect>(p, (hipStream_t)stream);
-  if (tc.big) return launch_ag<TileBig>(p, (hipStream_t)stream);
+  if (tc.big) return launch_ag<TileBigDirect>(p, (hipStream_t)stream);
   return launch_ag<TileSmall>(p, (hipStream_t)stream);
 }

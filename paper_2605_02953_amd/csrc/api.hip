@@ -69,8 +69,8 @@ extern "C" ditron_status_t ditron_tile_config(int op, int m, int n, int k, int d
   out[4] = t.per_xcd;
   out[5] = t.block_n ? cdiv(m, t.block_m) * cdiv(n, t.block_n) : 0;
   out[6] = t.threads;
-  // operand staging of the tile engine: 1 = straight into LDS (256 x 256 tiles, B stored [n, k], whole K tiles)
-  out[7] = (!decode && op != 2 && op != 4 && t.big && use_direct_staging(k)) ? 1 : 0;
+  // operand staging of the tile engine: 1 = straight into LDS (256 x 256 tiles, B stored [n, k])
+  out[7] = (!decode && op != 2 && op != 4 && t.big) ? 1 : 0;
   out[8] = splits;
   out[9] = 0;
   return DITRON_OK;

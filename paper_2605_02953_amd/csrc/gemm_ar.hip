@@ -391,7 +391,7 @@ static ditron_status_t gemm_ar_impl(const void* a, const void* b, int b_layout, 
   const hipStream_t s = (hipStream_t)stream;
   if (b_layout == DITRON_B_KN) return tc.big ? launch_ar<TileBigKN>(p, units, two_shot, s) : launch_ar<TileSmallKN>(p, units, two_shot, s);
   if (!tc.big) return launch_ar<TileSmall>(p, units, two_shot, s);
-  return use_direct_staging(k_local) ? launch_ar<TileBigDirect>(p, units, two_shot, s) : launch_ar<TileBig>(p, units, two_shot, s);
+  return launch_ar<TileBigDirect>(p, units, two_shot, s);
 }
 
 extern "C" ditron_status_t ditron_gemm_ar(const void* a, const void* b, int b_layout, void* gemm_out,

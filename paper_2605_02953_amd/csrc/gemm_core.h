@@ -304,8 +304,9 @@ __device__ __forceinline__ void mma_one16(typename T::Acc16& acc, const Frags16<
   acc[nb][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.b[nb], f.a[mb], acc[nb][mb], 0, 0, 0);
 }
 
-// K loop of the 16 x 16 x 32 form, operands loaded straight into LDS; K must be a whole number of 64-deep K
-// tiles (the loads carry no range test).  A K tile is two 32-deep steps of MB x NB MFMAs each, written as slots of
+// K loop of the 16 x 16 x 32 form, operands loaded straight into LDS.  WHOLE: K is a whole number of 64-deep K
+// tiles and the loads carry no range test; otherwise the chunks of the last K tile that lie past K are written
+// as zeros (their offsets are pushed out of the buffer's range).  A K tile is two 32-deep steps of MB x NB MFMAs each, written as slots of
 // four MFMAs plus one fragment read and at most one load.  All fragments of a step are read during the step
 // before it, so a K tile's operands are no longer read once its second step starts: the barrier sits between
 // the two steps.  LDS is a ring of five pieces of 32 KiB; the A part of K tile j lives in piece 2j mod 5 and
@@ -323,7 +324,7 @@ __device__ __forceinline__ void mma_one16(typename T::Acc16& acc, const Frags16<
 // the slot's last MFMA the loads cost ~300 and the reads ~150 cycles of a K tile's 2048; spread like this the
 // cfg 2 GEMM takes 4 % less time).
 // On entry the LDS must be idle; on exit no load is in flight.
-template <class T, class ARow, class BRow>
+template <class T, bool WHOLE, class ARow, class BRow>
 __device__ __forceinline__ void gemm_mainloop_x16(typename T::Acc16& acc, const char* a_base, ARow a_row,
                                                      const char* b_base, BRow b_row, int K, char* lds) {
   constexpr int MB = T::MB, NB = T::NB, READS = MB + NB, AL = T::A_LOADS, BL = T::B_LOADS;
@@ -352,8 +353,8 @@ __device__ __forceinline__ void gemm_mainloop_x16(typename T::Acc16& acc, const 
   st.init(a_base, a_row, b_base, b_row);
   auto wrap = [](int x) { return x >= 5 ? x - 5 : x; };
   // load I of K tile kt into the piece at `piece` (the stager puts B loads T::A_BYTES behind the address it is given)
-  auto load_a = [&](auto i, int kt, char* piece) { st.template issue_one<decltype(i)::value, true>(kt, K, piece); };
-  auto load_b = [&](auto i, int kt, char* piece) { st.template issue_one<AL + decltype(i)::value, true>(kt, K, piece - T::A_BYTES); };
+  auto load_a = [&](auto i, int kt, char* piece) { st.template issue_one<decltype(i)::value, WHOLE>(kt, K, piece); };
+  auto load_b = [&](auto i, int kt, char* piece) { st.template issue_one<AL + decltype(i)::value, WHOLE>(kt, K, piece - T::A_BYTES); };
   static_for<0, AL>([&](auto i) { load_a(i, 0, lds); });
   static_for<0, BL>([&](auto i) { load_b(i, 0, lds + PIECE); });
   static_for<0, AL>([&](auto i) { load_a(i, min(1, kt_last), lds + 2 * PIECE); });
@@ -423,7 +424,9 @@ template <class T, class ARow, class BRow>
 __device__ __forceinline__ void gemm_mainloop(typename T::Acc& acc, const char* a_base, ARow a_row,
                                                  const char* b_base, BRow b_row, int K, char* lds) {
   if constexpr (T::X16) {
-    gemm_mainloop_x16<T>(acc, a_base, a_row, b_base, b_row, K, lds);
+    // two copies of the loop: the per-load range test of a ragged last K tile costs the others 0.8 %
+    if (K % 64 == 0) gemm_mainloop_x16<T, true>(acc, a_base, a_row, b_base, b_row, K, lds);
+    else gemm_mainloop_x16<T, false>(acc, a_base, a_row, b_base, b_row, K, lds);
     return;
   } else {
   constexpr int PAIRS = T::PAIRS, SLOTS = T::SLOTS, READS = T::READS, LOADS = T::LOADS;

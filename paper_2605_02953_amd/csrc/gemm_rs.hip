@@ -336,9 +336,7 @@ static ditron_status_t gemm_rs_impl(const void* a, const void* b, int b_layout, 
   if (b_layout == DITRON_B_KN) {
     st = tc.big ? launch_rs<TileBigKN>(p, (hipStream_t)stream) : launch_rs<TileSmallKN>(p, (hipStream_t)stream);
   } else {
-    st = !tc.big                 ? launch_rs<TileSmall>(p, (hipStream_t)stream)
-         : use_direct_staging(k_local) ? launch_rs<TileBigDirect>(p, (hipStream_t)stream)
-                                 : launch_rs<TileBig>(p, (hipStream_t)stream);
+    st = tc.big ? launch_rs<TileBigDirect>(p, (hipStream_t)stream) : launch_rs<TileSmall>(p, (hipStream_t)stream);
   }
   if (st != DITRON_OK) return st;
 

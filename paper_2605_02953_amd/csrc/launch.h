@@ -10,18 +10,15 @@
 
 namespace ditron {
 
-// 256x256 output tile: 128x128 per wave, 128 KiB of LDS.
-typedef GemmTile4W<256, 256> TileBig;
-// The same tile with operands loaded straight into a ring of five LDS pieces and the 16 x 16 x 32 MFMA form, taken
-// whenever the contraction is a whole number of K tiles (measured against the tile above with emulated peers:
-// 5-9 % faster at K 3584 and 8192, 12 % faster at 16384; its loads carry no range test, so a ragged last K tile
-// stays with the register staging).
+// 256x256 output tile for B stored [N, K]: 128x128 per wave, operands loaded straight into a ring of five LDS
+// pieces (160 KiB), 16 x 16 x 32 MFMA.  (Measured with emulated peers against the same tile with register
+// staging, two LDS stages and 32 x 32 x 16 MFMA, which it replaced: 5-9 % faster at K 3584 and 8192, 12 % faster at
+// 16384, 6 % faster at 3696, whose last K tile is ragged.)
 typedef GemmTile4W<256, 256, false, true, true> TileBigDirect;
-inline bool use_direct_staging(int k) { return k % 64 == 0; }
 // 128x128 output tile: 64x64 per wave, 64 KiB of LDS; for problems with too few 256x256 tiles
 // to fill the chip.
 typedef GemmTile4W<128, 128> TileSmall;
-// The same two for B stored [K, N].
+// The same two sizes for B stored [K, N] (register staging, two LDS stages, 32 x 32 x 16 MFMA, as the 128x128 tile).
 typedef GemmTile4W<256, 256, true> TileBigKN;
 typedef GemmTile4W<128, 128, true> TileSmallKN;
 // The MoE grouped GEMM: 4 waves as 2 x 2.  An expert's rows are padded to whole row tiles, so the row
@@ -83,7 +80,7 @@ inline TileChoice choose_tile(int m, int n, int /*k*/) {
   const long tiles_big = (long)cdiv(m, 256) * cdiv(n, 256);
   t.big = tiles_big >= 192;
   t.block_m = t.block_n = t.big ? 256 : 128;
-  t.threads = t.big ? TileBig::THREADS : TileSmall::THREADS;
+  t.threads = t.big ? TileBigDirect::THREADS : TileSmall::THREADS;
   t.group_m = 4;
   t.num_xcd = 8;
   t.per_xcd = 32;

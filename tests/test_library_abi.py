@@ -64,13 +64,13 @@ def test_tile_config(B):
 
 
 def test_operand_staging_choice(B):
-    """256 x 256 tiles of [n, k] operands take the direct-to-LDS staging for contractions of whole K tiles."""
+    """256 x 256 tiles of [n, k] operands take the direct-to-LDS staging, whatever the contraction length."""
     assert B.tile_config(0, 8192, 3584, 8192)[1]["direct_staging"] == 1      # cfg 2
     assert B.tile_config(1, 8192, 8192, 3584)[1]["direct_staging"] == 1      # cfg 3
     assert B.tile_config(3, 8192, 8192, 3584)[1]["direct_staging"] == 1
     assert B.tile_config(0, 8192, 6656, 16384)[1]["direct_staging"] == 1     # long contraction
-    assert B.tile_config(0, 8192, 6656, 12288)[1]["direct_staging"] == 1 and B.tile_config(0, 8192, 6656, 12360)[1]["direct_staging"] == 0
-    assert B.tile_config(1, 8192, 8192, 3696)[1]["direct_staging"] == 0      # ragged last K tile
+    assert B.tile_config(0, 8192, 6656, 12288)[1]["direct_staging"] == 1 and B.tile_config(0, 8192, 6656, 12360)[1]["direct_staging"] == 1
+    assert B.tile_config(1, 8192, 8192, 3696)[1]["direct_staging"] == 1      # ragged last K tile
     assert B.tile_config(4, 8192, 3584, 8192)[1]["direct_staging"] == 0      # B stored [k, n]
     assert B.tile_config(0, 2048, 2048, 256)[1]["direct_staging"] == 0       # 128 x 128 tiles
     assert B.tile_config(0, 128, 8192, 8192, B.FP8_E4M3)[1]["direct_staging"] == 0
