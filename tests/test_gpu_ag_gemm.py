@@ -235,6 +235,20 @@ def test_long_contraction_on_256_tiles_is_bit_exact(B, k, kn):
     assert np.array_equal(c, want)
 
 
+@pytest.mark.parametrize("k", [8, 40, 64, 72, 128, 136, 200, 320])
+def test_short_contraction_on_256_tiles_is_bit_exact(B, k):
+    """The 256 x 256 direct-to-LDS loop at the short end: one, two, three and five K tiles, with and without a
+    ragged last one (fewer K tiles than the ring of operand pieces holds; past the end the last K tile is requested
+    again), ragged tile rows and columns, small-integer inputs, bit for bit."""
+    cfg = synth.CONFIGS[2].scaled(world=8, m_per_rank=505, n=3080, k=k, rank=5)
+    st, tc = B.tile_config(0, cfg.m, cfg.n, cfg.k)
+    assert (tc["block_m"], tc["block_n"], tc["direct_staging"]) == (256, 256, 1)
+    shards, b = synth.ag_gemm_inputs(cfg, integer=True)
+    c, ws, _, _ = _run(B, cfg, shards, b)
+    want = formats.encode_bf16_rne(oag.ag_gemm(shards, b).astype(np.float32))
+    assert np.array_equal(c, want)
+
+
 def test_cfg2_full_size_other_rank_and_layout(B):
     """cfg 2 at full size from the view of rank 5, B stored [n, k] and [k, n]; every 16th row plus the
     rows around every shard boundary against the oracle, the schedule bit for bit."""
