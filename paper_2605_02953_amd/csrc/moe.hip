@@ -575,7 +575,7 @@ extern "C" ditron_status_t ditron_moe_ag_grouped_gemm(
   }
   if (mt.block_m == 256) {
     if (mt.block_n == 128) return launch_moe_gemm<GemmTile4W<256, 128>>(g, max_tiles, s);
-    return launch_moe_gemm<GemmTile4W<256, 256>>(g, max_tiles, s);
+    return launch_moe_gemm<TileBigDirect>(g, max_tiles, s);
   }
   // 128-row tiles: their operands are streamed (an expert's weights are read by one or two row tiles), so
   // they go through as deep a ring of LDS stages as fits
@@ -822,7 +822,7 @@ extern "C" ditron_status_t ditron_moe_grouped_gemm_rs(
     if (mt.block_m == 256) st = wide ? launch_moe_gemm<GemmTile4W<256, 256, true>>(g, max_tiles, s) : launch_moe_gemm<GemmTile4W<256, 128, true>>(g, max_tiles, s);
     else st = wide ? launch_moe_gemm<GemmTile4W<128, 256, true>>(g, max_tiles, s) : launch_moe_gemm<GemmTile4W<128, 128, true>>(g, max_tiles, s);
   } else if (mt.block_m == 256) {
-    st = mt.block_n == 128 ? launch_moe_gemm<GemmTile4W<256, 128>>(g, max_tiles, s) : launch_moe_gemm<GemmTile4W<256, 256>>(g, max_tiles, s);
+    st = mt.block_n == 128 ? launch_moe_gemm<GemmTile4W<256, 128>>(g, max_tiles, s) : launch_moe_gemm<TileBigDirect>(g, max_tiles, s);
   } else {
     // A contraction of a few K tiles: a tile is over before the ring of stages is full and costs about what a
     // work-group start costs, so 128 x 128 tiles on the two-stage loop (two work-groups fit a unit) and as many
