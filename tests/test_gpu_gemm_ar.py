@@ -46,6 +46,7 @@ def _check_schedule(run, cfg, sched):
     (4, 100, 264, 72, True),       # ragged rows, columns and contraction tail
     (8, 505, 3080, 200, True),     # 256x256 tiles with ragged edges, a single round: all tiles, then the consumers
     (8, 505, 3080, 192, True),     # the same with whole K tiles: operands staged straight into LDS
+    (8, 505, 3080, 1096, True),    # 17 K tiles and a ragged 18th: several turns of the ring of operand pieces
     (8, 315, 2600, 64, True),      # 420 tiles of 128x128: more than one round, consumers behind the first one
     (2, 192, 384, 512, False),
     (1, 256, 256, 128, True),      # world 1: the all-reduce is a copy of the partial

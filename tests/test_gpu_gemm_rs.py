@@ -79,6 +79,7 @@ def _check_schedule(B, cfg, rank, sched):
     (8, 505, 3080, 200, 5, True),     # 256x256 tiles, ragged edges
     (8, 505, 3080, 192, 5, True),     # the same with whole K tiles: operands staged straight into LDS
     (8, 505, 3080, 64, 5, True),      # ... a single K tile
+    (8, 505, 3080, 1096, 5, True),    # ... 17 K tiles and a ragged 18th: several turns of the ring of operand pieces
     (2, 192, 384, 512, 3, False),
     (1, 256, 256, 128, 1, True),      # world 1: plain GEMM
 ])
