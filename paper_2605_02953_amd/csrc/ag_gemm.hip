@@ -143,7 +143,7 @@ extern "C" ditron_status_t ditron_ag_gemm(const void* const* a_shards, const voi
   p.epoch = epoch;
   p.spin_limit = tune.spin_limit;
   p.wait = mode != Mode::kPreset;
-  TileChoice tc = choose_tile(p.m, n, k);
+  TileChoice tc = choose_tile(p.m, n, k, b_layout == DITRON_B_NK);
   if (p.nnodes > 1 && !node_order_is_bijection(p.m, tc.block_m, world, p.nnodes, rank, kOrderGather))
     return DITRON_ERR_UNSUPPORTED;
   p.tiling.group_m = tc.group_m;
@@ -156,6 +156,6 @@ extern "C" ditron_status_t ditron_ag_gemm(const void* const* a_shards, const voi
     if (tc.big) return launch_ag<TileBigKN>(p, (hipStream_t)stream);
     return launch_ag<TileSmallKN>(p, (hipStream_t)stream);
   }
-  if (tc.big) return launch_ag<TileBigDirect>(p, (hipStream_t)stream);
+  if (tc.big) return tc.block_n == 224 ? launch_ag<TileBigDirect224>(p, (hipStream_t)stream) : launch_ag<TileBigDirect>(p, (hipStream_t)stream);
   return launch_ag<TileSmall>(p, (hipStream_t)stream);
 }

@@ -47,7 +47,7 @@ extern "C" ditron_status_t ditron_tile_config(int op, int m, int n, int k, int d
   const Tuning tune = resolve_tuning(tuning, 1);
   if (!tune.valid) return DITRON_ERR_INVALID_ARG;
   const bool decode = dtype == DITRON_FP8_E4M3 || (op == 0 && bf16_ag_is_decode_shaped(m, n));
-  TileChoice t = decode ? choose_tile_decode(m, n, k) : choose_tile(m, n, k);
+  TileChoice t = decode ? choose_tile_decode(m, n, k) : choose_tile(m, n, k, op == 0);
   int splits = 1;
   if (decode) {
     const DecodePlan plan = plan_decode(m, n, k * (dtype == DITRON_BF16 ? 2 : 1), tune.decode_variant);
@@ -110,7 +110,7 @@ extern "C" ditron_status_t ditron_schedule_dump(int op, int m, int n, int k, int
   const Tuning tune = resolve_tuning(tuning, op == 3 ? 1 : world);
   if (!tune.valid) return DITRON_ERR_INVALID_ARG;
   const bool decode = op == 0 && (dtype == DITRON_FP8_E4M3 || (b_layout == DITRON_B_NK && bf16_ag_is_decode_shaped(m, n)));
-  TileChoice tc = decode ? choose_tile_decode(m, n, k) : choose_tile(m, n, k);
+  TileChoice tc = decode ? choose_tile_decode(m, n, k) : choose_tile(m, n, k, op == 0 && b_layout == DITRON_B_NK);
   int splits = 1;
   if (decode) {
     const DecodePlan plan = plan_decode(m, n, k * (dtype == DITRON_BF16 ? 2 : 1), tune.decode_variant);

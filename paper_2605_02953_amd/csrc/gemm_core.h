@@ -82,11 +82,11 @@ __device__ __forceinline__ void barrier_no_drain() {
 // moves a quarter of the accumulator registers per unit of matrix work.
 template <int BM_, int BN_, bool B_KN_ = false, bool DIRECT_ = false, bool X16_ = false>
 struct GemmTile4W {
-  static_assert((BM_ == 256 || BM_ == 128) && (BN_ == 256 || BN_ == 192 || BN_ == 128), "supported tile sides");
+  static_assert((BM_ == 256 || BM_ == 128) && (BN_ == 256 || BN_ == 192 || BN_ == 128 || (X16_ && BN_ == 224)), "supported tile sides");
   static_assert(!B_KN_ || BN_ != 192, "a [K, N] row of 192 elements does not split evenly over the loading lanes");
   static_assert(!DIRECT_ || !B_KN_, "the direct-to-LDS staging is written for [N, K] operands");
   static_assert(!X16_ || DIRECT_, "the 16 x 16 x 32 loop is written for the direct-to-LDS staging");
-  static_assert(!X16_ || BM_ == BN_, "the 16 x 16 x 32 loop keeps A and B parts in one ring of equal pieces");
+  static_assert(!X16_ || (BN_ <= BM_ && BN_ % 32 == 0), "the 16 x 16 x 32 loop keeps A and B parts in one ring of pieces the size of the A part");
   static constexpr bool B_KN = B_KN_;
   static constexpr bool DIRECT = DIRECT_;   // operands go from global memory straight into LDS (no staging registers)
   static constexpr bool X16 = X16_;
@@ -304,6 +304,14 @@ __device__ __forceinline__ void mma_one16(typename T::Acc16& acc, const Frags16<
   acc[nb][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.b[nb], f.a[mb], acc[nb][mb], 0, 0, 0);
 }
 
+// The `n` loads of a step are spread evenly over its `slots` slots: load i goes into slot i * slots / n.  Which load
+// (or none, -1) belongs to slot s.
+constexpr int load_in_slot(int s, int n, int slots) {
+  for (int i = 0; i < n; ++i)
+    if (i * slots / n == s) return i;
+  return -1;
+}
+
 // K loop of the 16 x 16 x 32 form, operands loaded straight into LDS.  WHOLE: K is a whole number of 64-deep K
 // tiles and the loads carry no range test; otherwise the chunks of the last K tile that lie past K are written
 // as zeros (their offsets are pushed out of the buffer's range).  A K tile is two 32-deep steps of MB x NB MFMAs each, written as slots of
@@ -330,8 +338,8 @@ __device__ __forceinline__ void gemm_mainloop_x16(typename T::Acc16& acc, const 
   constexpr int MB = T::MB, NB = T::NB, READS = MB + NB, AL = T::A_LOADS, BL = T::B_LOADS;
   constexpr int SLOTS = MB * NB / 4;   // per step
   constexpr int PIECE = T::A_BYTES;
-  static_assert(MB % 4 == 0 && READS <= SLOTS && 2 * AL <= SLOTS && 2 * BL <= SLOTS && T::A_BYTES == T::B_BYTES,
-                "one read per slot, one load per two slots, equal pieces");
+  static_assert(MB % 4 == 0 && READS <= 2 * SLOTS && AL <= SLOTS && BL <= SLOTS && T::B_BYTES <= T::A_BYTES,
+                "at most two reads and one load per slot; a B part fits in a piece");
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int wm = wave / 2, wn = wave % 2;
   const int lr = lane & 15, lq = lane >> 4;
@@ -378,9 +386,10 @@ __device__ __forceinline__ void gemm_mainloop_x16(typename T::Acc16& acc, const 
       if constexpr (S < READS) read_one16<T, 1, S>(f1, cur_a, cur_b, a_off, b_off, koff);
       __builtin_amdgcn_sched_barrier(0);
       mma_one16<T, S, 1>(acc, f0);
+      if constexpr (SLOTS + S < READS) read_one16<T, 1, SLOTS + S>(f1, cur_a, cur_b, a_off, b_off, koff);
       __builtin_amdgcn_sched_barrier(0);
       mma_one16<T, S, 2>(acc, f0);
-      if constexpr (S % 2 == 0 && S / 2 < AL) load_a(std::integral_constant<int, S / 2>{}, kf, free_a);
+      if constexpr (load_in_slot(S, AL, SLOTS) >= 0) load_a(std::integral_constant<int, load_in_slot(S, AL, SLOTS)>{}, kf, free_a);
       __builtin_amdgcn_sched_barrier(0);
       mma_one16<T, S, 3>(acc, f0);
       __builtin_amdgcn_sched_barrier(0);
@@ -394,9 +403,10 @@ __device__ __forceinline__ void gemm_mainloop_x16(typename T::Acc16& acc, const 
       if constexpr (S < READS) read_one16<T, 0, S>(f0, nxt_a, nxt_b, a_off, b_off, koff);
       __builtin_amdgcn_sched_barrier(0);
       mma_one16<T, S, 1>(acc, f1);
+      if constexpr (SLOTS + S < READS) read_one16<T, 0, SLOTS + S>(f0, nxt_a, nxt_b, a_off, b_off, koff);
       __builtin_amdgcn_sched_barrier(0);
       mma_one16<T, S, 2>(acc, f1);
-      if constexpr (S % 2 == 0 && S / 2 < BL) load_b(std::integral_constant<int, S / 2>{}, kf, free_b);
+      if constexpr (load_in_slot(S, BL, SLOTS) >= 0) load_b(std::integral_constant<int, load_in_slot(S, BL, SLOTS)>{}, kf, free_b);
       __builtin_amdgcn_sched_barrier(0);
       mma_one16<T, S, 3>(acc, f1);
       __builtin_amdgcn_sched_barrier(0);

@@ -228,7 +228,7 @@ def test_long_contraction_on_256_tiles_is_bit_exact(B, k, kn):
     go straight into LDS, [k, n] operands through the register-staged loop."""
     cfg = synth.CONFIGS[2].scaled(world=8, m_per_rank=505, n=3080, k=k, rank=3)
     st, tc = B.tile_config(4 if kn else 0, cfg.m, cfg.n, cfg.k)
-    assert (tc["block_m"], tc["block_n"], tc["direct_staging"]) == (256, 256, 0 if kn else 1)
+    assert (tc["block_m"], tc["block_n"], tc["direct_staging"]) == (256, 256, 0) if kn else (256, 224, 1)   # 16 x 14 tiles of 224 columns fill more of the last round than 16 x 13 of 256
     shards, b = synth.ag_gemm_inputs(cfg, integer=True)
     c, ws, _, _ = _run(B, cfg, shards, b, kn=kn)
     want = formats.encode_bf16_rne(oag.ag_gemm(shards, b).astype(np.float32))
@@ -237,12 +237,12 @@ def test_long_contraction_on_256_tiles_is_bit_exact(B, k, kn):
 
 @pytest.mark.parametrize("k", [8, 40, 64, 72, 128, 136, 200, 320])
 def test_short_contraction_on_256_tiles_is_bit_exact(B, k):
-    """The 256 x 256 direct-to-LDS loop at the short end: one, two, three and five K tiles, with and without a
+    """The direct-to-LDS loop of the 256-row tiles (256 and 224 columns) at the short end: one, two, three and five K tiles, with and without a
     ragged last one (fewer K tiles than the ring of operand pieces holds; past the end the last K tile is requested
     again), ragged tile rows and columns, small-integer inputs, bit for bit."""
-    cfg = synth.CONFIGS[2].scaled(world=8, m_per_rank=505, n=3080, k=k, rank=5)
+    cfg = synth.CONFIGS[2].scaled(world=8, m_per_rank=505, n=3080 if k % 16 else 4096, k=k, rank=5)
     st, tc = B.tile_config(0, cfg.m, cfg.n, cfg.k)
-    assert (tc["block_m"], tc["block_n"], tc["direct_staging"]) == (256, 256, 1)
+    assert (tc["block_m"], tc["block_n"], tc["direct_staging"]) == (256, 224 if cfg.n == 3080 else 256, 1)   # both tile widths
     shards, b = synth.ag_gemm_inputs(cfg, integer=True)
     c, ws, _, _ = _run(B, cfg, shards, b)
     want = formats.encode_bf16_rne(oag.ag_gemm(shards, b).astype(np.float32))

@@ -45,7 +45,7 @@ def test_sizes_and_strings(B):
 
 def test_tile_config(B):
     st, tc = B.tile_config(0, 8192, 3584, 8192)
-    assert st == B.OK and (tc["block_m"], tc["block_n"], tc["ntiles"]) == (256, 256, 448)
+    assert st == B.OK and (tc["block_m"], tc["block_n"], tc["ntiles"]) == (256, 224, 512)   # two whole rounds instead of 1.75
     st, tc = B.tile_config(0, 256, 256, 256)           # few tiles, B stored [n, k]: the decode kernel's 128 x 128 tile
     assert st == B.OK and (tc["block_m"], tc["block_n"], tc["ntiles"], tc["splits"]) == (128, 128, 4, 1)
     st, tc = B.tile_config(0, 256, 256, 256, tuning=B.tuning(decode_variant=1))
@@ -60,6 +60,14 @@ def test_tile_config(B):
     assert st == B.OK and (tc["block_m"], tc["block_n"], tc["ntiles"], tc["splits"]) == (128, 64, 128, 2)
     st, tc = B.tile_config(0, 128, 8192, 8192, B.FP8_E4M3, B.tuning(decode_variant=4))     # one tile per shard and column block
     assert st == B.OK and (tc["block_m"], tc["block_n"], tc["ntiles"], tc["splits"]) == (16, 128, 512, 1)
+    # the column count of the 256-row tile: 224 where that fills the last round of 256 units better (AllGather-GEMM with B
+    # stored [n, k] only), 256 otherwise
+    assert B.tile_config(0, 8192, 8192, 3584)[1]["block_n"] == 256      # four whole rounds of 256-column tiles
+    assert B.tile_config(0, 8192, 3696, 8192)[1]["block_n"] == 256      # 480 tiles of 256 columns against 544 of 224
+    assert B.tile_config(0, 8192, 6656, 16384)[1]["block_n"] == 224     # 3.75 rounds of 224-column tiles against 3.25 of 256
+    assert B.tile_config(0, 8192, 1792, 4096)[1]["block_n"] == 224      # 8 x 224 columns: one whole round
+    assert B.tile_config(4, 8192, 3584, 8192)[1]["block_n"] == 256      # B stored [k, n]
+    assert B.tile_config(1, 8192, 3584, 8192)[1]["block_n"] == 256 and B.tile_config(3, 8192, 3584, 8192)[1]["block_n"] == 256
     assert B.tile_config(7, 1, 1, 1)[0] == B.ERR_INVALID_ARG
 
 
@@ -226,7 +234,7 @@ def test_schedule_dump_on_the_host(B):
     cnt = C.c_int(0)
     out = (C.c_int32 * 4)()
     assert B.lib.ditron_schedule_dump(0, 8192, 3584, 8192, 8, 0, B.BF16, B.B_NK, None, out, 1, C.byref(cnt)) == B.ERR_WORKSPACE
-    assert cnt.value == 448
+    assert cnt.value == 512
     assert B.lib.ditron_schedule_dump(2, 8192, 3584, 8192, 8, 0, B.BF16, B.B_NK, None, out, 1, C.byref(cnt)) == B.ERR_INVALID_ARG
     assert B.lib.ditron_schedule_dump(0, 8192, 3584, 8192, 8, 8, B.BF16, B.B_NK, None, out, 1, C.byref(cnt)) == B.ERR_INVALID_ARG
 
