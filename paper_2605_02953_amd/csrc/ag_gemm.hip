@@ -156,6 +156,10 @@ extern "C" ditron_status_t ditron_ag_gemm(const void* const* a_shards, const voi
     if (tc.big) return launch_ag<TileBigKN>(p, (hipStream_t)stream);
     return launch_ag<TileSmallKN>(p, (hipStream_t)stream);
   }
-  if (tc.big) return tc.block_n == 224 ? launch_ag<TileBigDirect224>(p, (hipStream_t)stream) : launch_ag<TileBigDirect>(p, (hipStream_t)stream);
+  if (tc.big) {
+    if (tc.block_n == 224) return launch_ag<TileBigDirect224>(p, (hipStream_t)stream);
+    if (tc.block_n == 192) return launch_ag<TileBigDirect192>(p, (hipStream_t)stream);
+    return launch_ag<TileBigDirect>(p, (hipStream_t)stream);
+  }
   return launch_ag<TileSmall>(p, (hipStream_t)stream);
 }

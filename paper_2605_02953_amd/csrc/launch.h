@@ -15,9 +15,10 @@ namespace ditron {
 // staging, two LDS stages and 32 x 32 x 16 MFMA, which it replaced: 5-9 % faster at K 3584 and 8192, 12 % faster at
 // 16384, 6 % faster at 3696, whose last K tile is ragged.)
 typedef GemmTile4W<256, 256, false, true, true> TileBigDirect;
-// The same with 224 columns: fewer columns per tile for problems whose 256-column tiling leaves the last round
+// The same with 224 and 192 columns: fewer columns per tile for problems whose 256-column tiling leaves the last round
 // of 256 units partly empty (choose_tile).
 typedef GemmTile4W<256, 224, false, true, true> TileBigDirect224;
+typedef GemmTile4W<256, 192, false, true, true> TileBigDirect192;
 // 128x128 output tile: 64x64 per wave, 64 KiB of LDS; for problems with too few 256x256 tiles
 // to fill the chip.
 typedef GemmTile4W<128, 128> TileSmall;
@@ -81,9 +82,9 @@ struct TileChoice {
 // What a launch of `tiles` tiles of 256 x block_n costs, in units of a full round of 256 x 256 tiles: the work of a
 // tile times the rounds, a last round that fills the fraction x of the chip counting 0.55 + 0.45 x (measured: the
 // 192 tiles of cfg 2's second round take 0.886 of the time of the 256 of its first, the chip being power-limited);
-// a 224-column tile loads 3 % more bytes per flop.
+// a 224-column tile loads 3 % more bytes per flop, a 192-column tile 7 %.
 inline double tiling_cost(long tiles, int block_n) {
-  const double work = block_n / 256.0 * (block_n == 256 ? 1.0 : 1.03);
+  const double work = block_n / 256.0 * (block_n == 256 ? 1.0 : block_n == 224 ? 1.03 : 1.07);
   const long full = tiles / 256, rest = tiles % 256;
   return work * ((double)full + (rest ? 0.55 + 0.45 * (double)rest / 256.0 : 0.0));
 }
@@ -95,7 +96,13 @@ inline TileChoice choose_tile(int m, int n, int /*k*/, bool narrow_ok = false) {
   const long tiles_big = (long)cdiv(m, 256) * cdiv(n, 256);
   t.big = tiles_big >= 192;
   t.block_m = t.block_n = t.big ? 256 : 128;
-  if (t.big && narrow_ok && tiling_cost((long)cdiv(m, 256) * cdiv(n, 224), 224) < 0.98 * tiling_cost(tiles_big, 256)) t.block_n = 224;
+  if (t.big && narrow_ok) {
+    double best = 0.98 * tiling_cost(tiles_big, 256);
+    for (int bn : {224, 192}) {
+      const double c = tiling_cost((long)cdiv(m, 256) * cdiv(n, bn), bn);
+      if (c < best) { best = c; t.block_n = bn; }
+    }
+  }
   t.threads = t.big ? TileBigDirect::THREADS : TileSmall::THREADS;
   t.group_m = 4;
   t.num_xcd = 8;

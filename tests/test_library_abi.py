@@ -60,12 +60,13 @@ def test_tile_config(B):
     assert st == B.OK and (tc["block_m"], tc["block_n"], tc["ntiles"], tc["splits"]) == (128, 64, 128, 2)
     st, tc = B.tile_config(0, 128, 8192, 8192, B.FP8_E4M3, B.tuning(decode_variant=4))     # one tile per shard and column block
     assert st == B.OK and (tc["block_m"], tc["block_n"], tc["ntiles"], tc["splits"]) == (16, 128, 512, 1)
-    # the column count of the 256-row tile: 224 where that fills the last round of 256 units better (AllGather-GEMM with B
+    # the column count of the 256-row tile: 224 or 192 where that fills the last round of 256 units better (AllGather-GEMM with B
     # stored [n, k] only), 256 otherwise
     assert B.tile_config(0, 8192, 8192, 3584)[1]["block_n"] == 256      # four whole rounds of 256-column tiles
     assert B.tile_config(0, 8192, 3696, 8192)[1]["block_n"] == 256      # 480 tiles of 256 columns against 544 of 224
     assert B.tile_config(0, 8192, 6656, 16384)[1]["block_n"] == 224     # 3.75 rounds of 224-column tiles against 3.25 of 256
     assert B.tile_config(0, 8192, 1792, 4096)[1]["block_n"] == 224      # 8 x 224 columns: one whole round
+    assert B.tile_config(0, 8192, 1376, 4096)[1]["block_n"] == 192      # 8 x 192 columns: one whole round against 0.75 (256) or 0.875 (224)
     assert B.tile_config(4, 8192, 3584, 8192)[1]["block_n"] == 256      # B stored [k, n]
     assert B.tile_config(1, 8192, 3584, 8192)[1]["block_n"] == 256 and B.tile_config(3, 8192, 3584, 8192)[1]["block_n"] == 256
     assert B.tile_config(7, 1, 1, 1)[0] == B.ERR_INVALID_ARG
