@@ -249,6 +249,19 @@ def test_short_contraction_on_256_tiles_is_bit_exact(B, k):
     assert np.array_equal(c, want)
 
 
+@pytest.mark.parametrize("k", [72, 192])
+def test_192_column_tiles_are_bit_exact(B, k):
+    """1376 columns (the LLaMA-7B share) go to 256 x 192 tiles: eight column blocks, the last one 32 columns wide."""
+    cfg = synth.CONFIGS[2].scaled(world=8, m_per_rank=1024, n=1376, k=k, rank=2)
+    st, tc = B.tile_config(0, cfg.m, cfg.n, cfg.k)
+    assert (tc["block_m"], tc["block_n"], tc["ntiles"], tc["direct_staging"]) == (256, 192, 256, 1)
+    shards, b = synth.ag_gemm_inputs(cfg, integer=True)
+    c, ws, sched, _ = _run(B, cfg, shards, b, want_schedule=True)
+    want = formats.encode_bf16_rne(oag.ag_gemm(shards, b).astype(np.float32))
+    assert np.array_equal(c, want)
+    _check_schedule(B, cfg, cfg.rank, sched)
+
+
 def test_cfg2_full_size_other_rank_and_layout(B):
     """cfg 2 at full size from the view of rank 5, B stored [n, k] and [k, n]; every 16th row plus the
     rows around every shard boundary against the oracle, the schedule bit for bit."""
